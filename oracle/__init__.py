@@ -1,0 +1,275 @@
+"""CPU oracle for the factorized-layer forward/backward -- TEST INFRASTRUCTURE.
+
+A thin ctypes wrapper over ``pf_oracle.c`` (plain double-precision nested
+loops written from the paper's layer definitions).  Only the tests, the
+smoke check and the benchmark's CPU-baseline leg may import this package; the
+GPU library never does, and this package never imports the GPU library.
+
+All arrays are C-contiguous ``float64`` numpy arrays.  Shapes follow the
+paper's layers: Section 2.1 (fully connected), Section 2.2 (convolution),
+Section 2.3 eq. (1)/(2) (LSTM), Algorithm 1 (SVD split).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pf_oracle.c")
+_LIB = os.path.join(_HERE, "libpf_oracle.so")
+
+_c_double_p = ctypes.POINTER(ctypes.c_double)
+_i64 = ctypes.c_int64
+
+
+def build(force=False):
+    """Compile pf_oracle.c with gcc -O2 (OpenMP on the outer loops)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.pfo_num_threads.restype = ctypes.c_int
+        _lib.pfo_conv_out_dim.restype = _i64
+        _lib.pfo_conv_out_dim.argtypes = [_i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        _lib.pfo_svd_split.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads():
+    return int(lib().pfo_num_threads())
+
+
+def set_num_threads(n):
+    lib().pfo_set_num_threads(ctypes.c_int(int(n)))
+
+
+def _in(a, shape=None):
+    """float64 C-contiguous view/copy of an input (None -> NULL)."""
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if shape is not None:
+        assert tuple(a.shape) == tuple(shape), (a.shape, shape)
+    return a, a.ctypes.data_as(_c_double_p)
+
+
+def _out(shape):
+    a = np.zeros(shape, dtype=np.float64)
+    return a, a.ctypes.data_as(_c_double_p)
+
+
+def conv_out_dim(H, k, s, p):
+    return (H + 2 * p - k) // s + 1
+
+
+# ---------------------------------------------------------------- linear
+
+def dense_linear_fwd(X, W, bias=None):
+    M, n_in = X.shape
+    n_out = W.shape[0]
+    X, pX = _in(X)
+    W, pW = _in(W, (n_out, n_in))
+    bias, pb = _in(bias, (n_out,)) if bias is not None else (None, None)
+    Y, pY = _out((M, n_out))
+    lib().pfo_dense_linear_fwd(_i64(M), _i64(n_in), _i64(n_out), pX, pW, pb, pY)
+    return Y
+
+
+def lowrank_linear_fwd(X, V, U, bias=None):
+    """Y = (X V) U^T + b; returns (Y, T) with T = X V."""
+    M, n_in = X.shape
+    n_out, r = U.shape
+    X, pX = _in(X)
+    V, pV = _in(V, (n_in, r))
+    U, pU = _in(U)
+    bias, pb = _in(bias, (n_out,)) if bias is not None else (None, None)
+    Y, pY = _out((M, n_out))
+    T, pT = _out((M, r))
+    lib().pfo_lowrank_linear_fwd(_i64(M), _i64(n_in), _i64(n_out), _i64(r), pX, pV, pU, pb, pY, pT)
+    return Y, T
+
+
+def lowrank_linear_bwd(X, V, U, dY):
+    """Returns (dX, dU, dV, db)."""
+    M, n_in = X.shape
+    n_out, r = U.shape
+    X, pX = _in(X)
+    V, pV = _in(V, (n_in, r))
+    U, pU = _in(U)
+    dY, pdY = _in(dY, (M, n_out))
+    dX, pdX = _out((M, n_in))
+    dU, pdU = _out((n_out, r))
+    dV, pdV = _out((n_in, r))
+    db, pdb = _out((n_out,))
+    lib().pfo_lowrank_linear_bwd(_i64(M), _i64(n_in), _i64(n_out), _i64(r), pX, pV, pU, pdY,
+                                 pdX, pdU, pdV, pdb)
+    return dX, dU, dV, db
+
+
+# ------------------------------------------------------------------ conv
+
+def dense_conv_fwd(X, Wd, stride=1, pad=0):
+    N, C, H, W = X.shape
+    Cout, _, k, _ = Wd.shape
+    Ho, Wo = conv_out_dim(H, k, stride, pad), conv_out_dim(W, k, stride, pad)
+    X, pX = _in(X)
+    Wd, pW = _in(Wd, (Cout, C, k, k))
+    Y, pY = _out((N, Cout, Ho, Wo))
+    lib().pfo_dense_conv_fwd(_i64(N), _i64(C), _i64(H), _i64(W), _i64(Cout), ctypes.c_int(k),
+                             ctypes.c_int(stride), ctypes.c_int(pad), pX, pW, pY)
+    return Y
+
+
+def lowrank_conv_fwd(X, Uk, Vp, stride=1, pad=0):
+    """Thin k x k conv (Uk[r,C,k,k]) then 1x1 conv (Vp[Cout,r]); returns (Y, T)."""
+    N, C, H, W = X.shape
+    r, _, k, _ = Uk.shape
+    Cout = Vp.shape[0]
+    Ho, Wo = conv_out_dim(H, k, stride, pad), conv_out_dim(W, k, stride, pad)
+    X, pX = _in(X)
+    Uk, pU = _in(Uk, (r, C, k, k))
+    Vp, pV = _in(Vp, (Cout, r))
+    Y, pY = _out((N, Cout, Ho, Wo))
+    T, pT = _out((N, r, Ho, Wo))
+    lib().pfo_lowrank_conv_fwd(_i64(N), _i64(C), _i64(H), _i64(W), _i64(Cout), _i64(r),
+                               ctypes.c_int(k), ctypes.c_int(stride), ctypes.c_int(pad),
+                               pX, pU, pV, pY, pT)
+    return Y, T
+
+
+def lowrank_conv_bwd(X, Uk, Vp, dY, stride=1, pad=0):
+    """Returns (dX, dUk, dVp)."""
+    N, C, H, W = X.shape
+    r, _, k, _ = Uk.shape
+    Cout = Vp.shape[0]
+    Ho, Wo = conv_out_dim(H, k, stride, pad), conv_out_dim(W, k, stride, pad)
+    X, pX = _in(X)
+    Uk, pU = _in(Uk, (r, C, k, k))
+    Vp, pV = _in(Vp, (Cout, r))
+    dY, pdY = _in(dY, (N, Cout, Ho, Wo))
+    dX, pdX = _out((N, C, H, W))
+    dUk, pdU = _out((r, C, k, k))
+    dVp, pdV = _out((Cout, r))
+    lib().pfo_lowrank_conv_bwd(_i64(N), _i64(C), _i64(H), _i64(W), _i64(Cout), _i64(r),
+                               ctypes.c_int(k), ctypes.c_int(stride), ctypes.c_int(pad),
+                               pX, pU, pV, pdY, pdX, pdU, pdV)
+    return dX, dUk, dVp
+
+
+# ------------------------------------------------------------------ LSTM
+
+def dense_lstm_cell_fwd(x, hprev, cprev, Wx, Wh, bias=None):
+    """Eq. (1): returns (h, c)."""
+    B, d = x.shape
+    h = hprev.shape[1]
+    x, px = _in(x)
+    hprev, ph = _in(hprev, (B, h))
+    cprev, pc = _in(cprev, (B, h))
+    Wx, pWx = _in(Wx, (4 * h, d))
+    Wh, pWh = _in(Wh, (4 * h, h))
+    bias, pb = _in(bias, (4 * h,)) if bias is not None else (None, None)
+    ho, pho = _out((B, h))
+    co, pco = _out((B, h))
+    lib().pfo_dense_lstm_cell_fwd(_i64(B), _i64(d), _i64(h), px, ph, pc, pWx, pWh, pb, pho, pco)
+    return ho, co
+
+
+def lowrank_lstm_cell_fwd(x, hprev, cprev, Vx, Ux, Vh, Uh, bias=None, groups=1):
+    """Eq. (2): returns (h, c, gates, Tx, Th)."""
+    B, d = x.shape
+    h = hprev.shape[1]
+    r = Ux.shape[1]
+    gr = groups * r
+    x, px = _in(x)
+    hprev, ph = _in(hprev, (B, h))
+    cprev, pc = _in(cprev, (B, h))
+    Vx, pVx = _in(Vx, (d, gr))
+    Ux, pUx = _in(Ux, (4 * h, r))
+    Vh, pVh = _in(Vh, (h, gr))
+    Uh, pUh = _in(Uh, (4 * h, r))
+    bias, pb = _in(bias, (4 * h,)) if bias is not None else (None, None)
+    ho, pho = _out((B, h))
+    co, pco = _out((B, h))
+    gates, pg = _out((B, 4 * h))
+    Tx, pTx = _out((B, gr))
+    Th, pTh = _out((B, gr))
+    lib().pfo_lowrank_lstm_cell_fwd(_i64(B), _i64(d), _i64(h), _i64(r), ctypes.c_int(groups),
+                                    px, ph, pc, pVx, pUx, pVh, pUh, pb, pho, pco, pg, pTx, pTh)
+    return ho, co, gates, Tx, Th
+
+
+def lowrank_lstm_cell_bwd(x, hprev, cprev, c_out, gates, Tx, Th, Vx, Ux, Vh, Uh, dh,
+                          dc_next=None, groups=1, grads=None):
+    """Returns (dx, dh_prev, dc_prev, grads) with grads = dict(dVx, dUx, dVh, dUh, dbias).
+
+    If ``grads`` is given the parameter gradients are accumulated into it.
+    """
+    B, d = x.shape
+    h = hprev.shape[1]
+    r = Ux.shape[1]
+    gr = groups * r
+    x, px = _in(x)
+    hprev, ph = _in(hprev, (B, h))
+    cprev, pc = _in(cprev, (B, h))
+    c_out, pco = _in(c_out, (B, h))
+    gates, pg = _in(gates, (B, 4 * h))
+    Tx, pTx = _in(Tx, (B, gr))
+    Th, pTh = _in(Th, (B, gr))
+    Vx, pVx = _in(Vx, (d, gr))
+    Ux, pUx = _in(Ux, (4 * h, r))
+    Vh, pVh = _in(Vh, (h, gr))
+    Uh, pUh = _in(Uh, (4 * h, r))
+    dh, pdh = _in(dh, (B, h))
+    dc_next, pdc = _in(dc_next, (B, h)) if dc_next is not None else (None, None)
+    dx, pdx = _out((B, d))
+    dhp, pdhp = _out((B, h))
+    dcp, pdcp = _out((B, h))
+    accumulate = grads is not None
+    if grads is None:
+        grads = dict(dVx=np.zeros((d, gr)), dUx=np.zeros((4 * h, r)), dVh=np.zeros((h, gr)),
+                     dUh=np.zeros((4 * h, r)), dbias=np.zeros((4 * h,)))
+    ptr = {k: v.ctypes.data_as(_c_double_p) for k, v in grads.items()}
+    lib().pfo_lowrank_lstm_cell_bwd(_i64(B), _i64(d), _i64(h), _i64(r), ctypes.c_int(groups),
+                                    px, ph, pc, pco, pg, pTx, pTh, pVx, pUx, pVh, pUh, pdh, pdc,
+                                    pdx, pdhp, pdcp, ptr["dVx"], ptr["dUx"], ptr["dVh"],
+                                    ptr["dUh"], ptr["dbias"], ctypes.c_int(1 if accumulate else 0))
+    return dx, dhp, dcp, grads
+
+
+# ------------------------------------------------------------------- SVD
+
+def svd_split(W, r):
+    """Algorithm 1's SVD step: returns (U[m x r], V[n x r], sigma[min(m,n)]),
+    U = Ut_r S_r^(1/2), V = Vt_r S_r^(1/2), so U V^T is the rank-r truncation."""
+    m, n = W.shape
+    W, pW = _in(W)
+    U, pU = _out((m, r))
+    V, pV = _out((n, r))
+    sigma, ps = _out((min(m, n),))
+    sweeps = lib().pfo_svd_split(_i64(m), _i64(n), _i64(r), pW, pU, pV, ps)
+    if sweeps < 0:
+        raise RuntimeError("Jacobi SVD did not converge")
+    return U, V, sigma
+
+
+def svd_split_conv(Wd, r):
+    """Section 2.2 / Section 3: unroll Wd[Cout,C,k,k] to [C k^2, Cout] (column =
+    one vectorised filter, row index c k^2 + i k + j), split at rank r, reshape
+    the factors back to Uk[r,C,k,k] and Vp[Cout,r]."""
+    Cout, C, k, _ = Wd.shape
+    unrolled = np.ascontiguousarray(Wd.reshape(Cout, C * k * k).T)
+    U, V, sigma = svd_split(unrolled, r)
+    Uk = np.ascontiguousarray(U.T).reshape(r, C, k, k)
+    return Uk, V, sigma
