@@ -1,0 +1,210 @@
+/*
+ * pufferfish.h -- C ABI of the MI355X (gfx950) library for Pufferfish's
+ * pre-factorized low-rank layers: forward and backward of a dense weight W
+ * replaced by rank-r factors U V^T.
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or synchronises; work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - Descriptors are small HOST structs passed by pointer.
+ *   - Arrays are dense row-major, last index fastest.
+ *   - `dtype` PF_F32: all tensors float.  PF_BF16: activations and factors are
+ *     bfloat16, products accumulate in float, activation outputs (Y, dX, T_save)
+ *     are rounded to bfloat16.  Parameter gradients (dU, dV, dbias, ...) are
+ *     ALWAYS float.
+ *   - `accumulate` != 0 adds parameter gradients to what the buffers hold
+ *     (gradient accumulation, back-propagation through time); 0 overwrites.
+ *   - Scratch memory comes from the caller: ask pf_*_workspace_bytes(desc),
+ *     pass at least that many bytes, 256-byte aligned.  A NULL workspace is
+ *     accepted when the query returns 0.
+ *   - Every call returns a pf_status.  Arguments are validated on the host
+ *     before anything is launched: PF_ERR_NULL (a required pointer is NULL),
+ *     PF_ERR_SHAPE (a dimension is not positive, or a convolution has no
+ *     output pixel), PF_ERR_UNSUPPORTED (dtype/layout/groups value not built),
+ *     PF_ERR_WORKSPACE (workspace too small or NULL), PF_ERR_LAUNCH (HIP
+ *     reported an error; see pf_last_hip_error()).  A batch of zero rows
+ *     (M, N or B equal to 0) is legal: activation outputs are empty and
+ *     non-accumulated parameter gradients are set to zero.
+ */
+#ifndef PUFFERFISH_H
+#define PUFFERFISH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PF_OK = 0,
+    PF_ERR_NULL = 1,
+    PF_ERR_SHAPE = 2,
+    PF_ERR_UNSUPPORTED = 3,
+    PF_ERR_WORKSPACE = 4,
+    PF_ERR_LAUNCH = 5
+} pf_status;
+
+typedef enum { PF_F32 = 0, PF_BF16 = 1 } pf_dtype;
+
+const char *pf_status_string(int status);
+/* hipError_t of the last failed launch on the calling thread (0 = none). */
+int pf_last_hip_error(void);
+/* Library version, major * 100 + minor. */
+int pf_version(void);
+
+/* ------------------------------------------------------------------ */
+/* Fully connected layer (paper Section 2.1; Appendix B "FC layer";     */
+/* Transformer projections and FFN matrices of Section 2.4 are this     */
+/* layer with M = number of tokens).                                   */
+/*   X[M x in], V[in x r] input-side factor, U[out x r] output-side     */
+/*   factor, W = U V^T (out x in), T = X V (M x r), Y = T U^T + bias.   */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t M, in, out, r;
+    int dtype;    /* pf_dtype */
+    int has_bias; /* bias[out] is read (fwd) / dbias[out] is written (bwd) */
+} pf_linear_desc;
+
+size_t pf_lowrank_linear_fwd_workspace_bytes(const pf_linear_desc *d);
+size_t pf_lowrank_linear_bwd_workspace_bytes(const pf_linear_desc *d);
+
+/* Y = (X V) U^T + bias.  T_save (nullable, [M x r], dtype) receives T for
+ * the backward pass; when NULL, T never leaves the chip. */
+int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V,
+                          const void *U, const void *bias /* nullable */,
+                          void *Y, void *T_save /* nullable */,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Given dY[M x out]:  dT = dY U,  dX = dT V^T,  dU = dY^T T,  dV = X^T dT,
+ * dbias = column sums of dY.  T_saved (nullable) is the forward pass's
+ * T_save; when NULL, T is recomputed from X and V.  dX, dU, dV, dbias are
+ * each nullable (skipped); dU, dV, dbias are float. */
+int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
+                          const void *U, const void *dY,
+                          const void *T_saved /* nullable */,
+                          void *dX, void *dU, void *dV, void *dbias,
+                          int accumulate, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ */
+/* Convolution layer (paper Section 2.2 "Factorizing a convolution      */
+/* layer"; Appendix B "Convolution layer").                            */
+/*   X[N,Cin,H,W] (NCHW); Uk[r,Cin,k,k] = the r thin k x k basis        */
+/*   filters (conv_u; stride and zero padding of the original layer);   */
+/*   Vp[Cout,r] = the 1x1 convolution (conv_v; stride 1, no padding);   */
+/*   T[N,r,Ho,Wo]; Y[N,Cout,Ho,Wo]; Ho = (H + 2 pad - k) / stride + 1.   */
+/*   Cross-correlation (no kernel flip); nothing between the stages.    */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t N, Cin, H, W, Cout, r;
+    int k, stride, pad;
+    int dtype; /* pf_dtype */
+} pf_conv_desc;
+
+size_t pf_lowrank_conv_fwd_workspace_bytes(const pf_conv_desc *d);
+size_t pf_lowrank_conv_bwd_workspace_bytes(const pf_conv_desc *d);
+
+/* T = Uk * X (k x k, stride, pad), Y = Vp * T (1x1).  T_save nullable. */
+int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk,
+                        const void *Vp, void *Y, void *T_save /* nullable */,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Given dY[N,Cout,Ho,Wo]:  dT = Vp^T dY (1x1),  dVp[o,q] = sum dY T,
+ * dX = transposed k x k convolution of dT with Uk,
+ * dUk[q,c,i,j] = sum dT[n,q,y,x] Xpad[n,c,y s+i-p,x s+j-p].
+ * T_saved nullable (recomputed).  dX, dUk, dVp each nullable; dUk, dVp float. */
+int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk,
+                        const void *Vp, const void *dY,
+                        const void *T_saved /* nullable */, void *dX,
+                        void *dUk, void *dVp, int accumulate, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ */
+/* LSTM cell (paper Section 2.3, eq. (2); architecture table of the     */
+/* low-rank LSTM in Appendix D).  One time step for a batch of B rows:  */
+/*   Tx = x Vx, Th = h_prev Vh,                                        */
+/*   z = Tx Ux^T + Th Uh^T + bias   (z[B x 4h], gate blocks i|f|g|o),   */
+/*   i,f,o = sigmoid(z), g = tanh(z), c = f c_prev + i g, h = o tanh(c).*/
+/*   groups == 4: one factor pair per gate, as eq. (2) has it:          */
+/*     Vx[d_in x 4r], gate g reads columns g r..(g+1) r-1 of Tx;        */
+/*   groups == 1: the stacked 4h x d_in matrix is one rank-r product:   */
+/*     Vx[d_in x r] shared by the gates.                                */
+/*   Ux, Uh are [4h x r] in both cases; bias[4h] is the sum of the      */
+/*   equation's two bias vectors.  dtype must be PF_F32.                */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t B, d_in, h, r;
+    int groups;   /* 1 or 4 */
+    int dtype;    /* PF_F32 */
+    int has_bias;
+} pf_lstm_desc;
+
+size_t pf_lowrank_lstm_cell_fwd_workspace_bytes(const pf_lstm_desc *d);
+size_t pf_lowrank_lstm_cell_bwd_workspace_bytes(const pf_lstm_desc *d);
+
+/* Outputs h_out[B x h], c_out[B x h]; saved for backward: gates_save[B x 4h]
+ * (activated i|f|g|o), Tx_save, Th_save [B x groups r] -- all three required. */
+int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x,
+                             const void *h_prev, const void *c_prev,
+                             const void *Vx, const void *Ux, const void *Vh,
+                             const void *Uh, const void *bias /* nullable */,
+                             void *h_out, void *c_out, void *gates_save,
+                             void *Tx_save, void *Th_save, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* One step of back-propagation through time.  dh = dL/dh_t (from the layer
+ * above plus from step t+1), dc_next = dL/dc_t from step t+1 (NULL = 0).
+ * Outputs dx (nullable), dh_prev, dc_prev and the float parameter gradients
+ * dVx, dUx, dVh, dUh, dbias (dbias nullable), overwritten or accumulated. */
+int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x,
+                             const void *h_prev, const void *c_prev,
+                             const void *c_out, const void *gates_saved,
+                             const void *Tx_saved, const void *Th_saved,
+                             const void *Vx, const void *Ux, const void *Vh,
+                             const void *Uh, const void *dh,
+                             const void *dc_next /* nullable */,
+                             void *dx /* nullable */, void *dh_prev,
+                             void *dc_prev, void *dVx, void *dUx, void *dVh,
+                             void *dUh, void *dbias /* nullable */,
+                             int accumulate, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ */
+/* Dense (un-factorized) comparators, for benchmarks only: the layers   */
+/* of Section 2.1 / 2.2 before factorization, on the same tiling code.  */
+/*   linear: W[out x in];  conv: Wd[Cout,Cin,k,k].                      */
+/* ------------------------------------------------------------------ */
+size_t pf_dense_linear_workspace_bytes(const pf_linear_desc *d);
+int pf_dense_linear_fwd(const pf_linear_desc *d, const void *X, const void *W,
+                        const void *bias, void *Y, void *workspace,
+                        size_t workspace_bytes, void *stream);
+int pf_dense_linear_bwd(const pf_linear_desc *d, const void *X, const void *W,
+                        const void *dY, void *dX, void *dW, void *dbias,
+                        int accumulate, void *workspace, size_t workspace_bytes,
+                        void *stream);
+size_t pf_dense_conv_workspace_bytes(const pf_conv_desc *d);
+int pf_dense_conv_fwd(const pf_conv_desc *d, const void *X, const void *Wd,
+                      void *Y, void *workspace, size_t workspace_bytes,
+                      void *stream);
+int pf_dense_conv_bwd(const pf_conv_desc *d, const void *X, const void *Wd,
+                      const void *dY, void *dX, void *dWd, int accumulate,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ */
+/* Per-kernel timing (HIP events recorded around every kernel launch on */
+/* the launch stream while enabled).  Not thread-safe; for benchmarks.  */
+/* ------------------------------------------------------------------ */
+void pf_timing_enable(int on);
+/* Synchronises the recorded events, adds them to the totals and returns the
+ * number of distinct kernels seen so far. */
+int pf_timing_collect(void);
+/* Entry i of the totals: name (static string), launches, total milliseconds. */
+int pf_timing_entry(int i, const char **name, int64_t *launches, double *total_ms);
+void pf_timing_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PUFFERFISH_H */

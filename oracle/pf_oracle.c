@@ -414,6 +414,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
     double *dTx = (double *)malloc(sizeof(double) * (size_t)(B * gr + 1));
     double *dTh = (double *)malloc(sizeof(double) * (size_t)(B * gr + 1));
     /* gate derivatives */
+#pragma omp parallel for schedule(static)
     for (i64 b = 0; b < B; ++b)
         for (i64 j = 0; j < h; ++j) {
             double ig = gates[b * 4 * h + 0 * h + j], fg = gates[b * 4 * h + 1 * h + j];
@@ -429,6 +430,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
             dz[b * 4 * h + 3 * h + j] = d_o * og * (1.0 - og);
         }
     /* dTx = dz Ux, dTh = dz Uh (per gate group when groups == 4) */
+#pragma omp parallel for collapse(2) schedule(static)
     for (i64 b = 0; b < B; ++b)
         for (i64 q = 0; q < gr; ++q) {
             double ax = 0.0, ah = 0.0;
@@ -445,6 +447,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
             dTh[b * gr + q] = ah;
         }
     if (dx)
+#pragma omp parallel for collapse(2) schedule(static)
         for (i64 b = 0; b < B; ++b)
             for (i64 i = 0; i < d; ++i) {
                 double acc = 0.0;
@@ -452,6 +455,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
                 dx[b * d + i] = acc;
             }
     if (dh_prev)
+#pragma omp parallel for collapse(2) schedule(static)
         for (i64 b = 0; b < B; ++b)
             for (i64 i = 0; i < h; ++i) {
                 double acc = 0.0;
@@ -459,6 +463,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
                 dh_prev[b * h + i] = acc;
             }
     /* parameter gradients */
+#pragma omp parallel for schedule(static)
     for (i64 row = 0; row < 4 * h; ++row) {
         i64 off = (groups == 4) ? (row / h) * r : 0;
         for (i64 q = 0; q < r; ++q) {
@@ -477,6 +482,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
         }
     }
     if (dVx)
+#pragma omp parallel for schedule(static)
         for (i64 i = 0; i < d; ++i)
             for (i64 q = 0; q < gr; ++q) {
                 double acc = 0.0;
@@ -484,6 +490,7 @@ void pfo_lowrank_lstm_cell_bwd(i64 B, i64 d, i64 h, i64 r, int groups,
                 dVx[i * gr + q] = (accumulate ? dVx[i * gr + q] : 0.0) + acc;
             }
     if (dVh)
+#pragma omp parallel for schedule(static)
         for (i64 i = 0; i < h; ++i)
             for (i64 q = 0; q < gr; ++q) {
                 double acc = 0.0;

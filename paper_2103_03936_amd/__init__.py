@@ -1,0 +1,319 @@
+"""Python binding of libpufferfish.so (HIP kernels for gfx950).
+
+Argument marshalling only: every function takes torch tensors that live on the
+GPU, passes their device pointers and torch's current HIP stream through the
+C ABI declared in include/pufferfish.h, and returns the output tensors.  torch
+is used for device memory and streams; nothing here computes.  There is no
+CPU fallback: importing without the built library, or calling with CPU
+tensors, raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpufferfish.so")
+
+PF_F32, PF_BF16 = 0, 1
+
+
+class PfError(RuntimeError):
+    pass
+
+
+class pf_linear_desc(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("n_in", ctypes.c_int64), ("n_out", ctypes.c_int64), ("r", ctypes.c_int64),
+                ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
+
+
+class pf_conv_desc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("Cin", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
+                ("Cout", ctypes.c_int64), ("r", ctypes.c_int64), ("k", ctypes.c_int), ("stride", ctypes.c_int),
+                ("pad", ctypes.c_int), ("dtype", ctypes.c_int)]
+
+
+class pf_lstm_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int64), ("d_in", ctypes.c_int64), ("h", ctypes.c_int64), ("r", ctypes.c_int64),
+                ("groups", ctypes.c_int), ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
+
+
+EXPORTS = [
+    "pf_status_string", "pf_last_hip_error", "pf_version",
+    "pf_lowrank_linear_fwd_workspace_bytes", "pf_lowrank_linear_bwd_workspace_bytes",
+    "pf_lowrank_linear_fwd", "pf_lowrank_linear_bwd",
+    "pf_lowrank_conv_fwd_workspace_bytes", "pf_lowrank_conv_bwd_workspace_bytes",
+    "pf_lowrank_conv_fwd", "pf_lowrank_conv_bwd",
+    "pf_lowrank_lstm_cell_fwd_workspace_bytes", "pf_lowrank_lstm_cell_bwd_workspace_bytes",
+    "pf_lowrank_lstm_cell_fwd", "pf_lowrank_lstm_cell_bwd",
+    "pf_dense_linear_workspace_bytes", "pf_dense_linear_fwd", "pf_dense_linear_bwd",
+    "pf_dense_conv_workspace_bytes", "pf_dense_conv_fwd", "pf_dense_conv_bwd",
+    "pf_timing_enable", "pf_timing_collect", "pf_timing_entry", "pf_timing_reset",
+]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'); "
+        "there is no fallback path")
+
+lib = ctypes.CDLL(LIB_PATH)
+lib.pf_status_string.restype = ctypes.c_char_p
+for _n in EXPORTS:
+    if _n.endswith("workspace_bytes"):
+        getattr(lib, _n).restype = ctypes.c_size_t
+
+
+def _check(status, what):
+    if status != 0:
+        msg = lib.pf_status_string(int(status)).decode()
+        raise PfError(f"{what}: status {status} ({msg}), hip error {lib.pf_last_hip_error()}")
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return PF_F32
+    if t.dtype == torch.bfloat16:
+        return PF_BF16
+    raise PfError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t, dtype=None, allow_none=True):
+    if t is None:
+        if not allow_none:
+            raise PfError("required tensor is None")
+        return ctypes.c_void_p(0)
+    if not t.is_cuda:
+        raise PfError("tensors must live on the GPU; there is no CPU path")
+    if not t.is_contiguous():
+        raise PfError("tensors must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise PfError(f"expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+_ws_cache = {}
+
+
+def _workspace(nbytes, device):
+    """A reusable byte buffer of at least nbytes on `device` (grown, never shrunk)."""
+    key = (device.type, device.index)
+    buf = _ws_cache.get(key)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        _ws_cache[key] = buf
+    return buf
+
+
+# ------------------------------------------------------------------ linear
+
+def _linear_desc(X, U, bias_flag):
+    M, n_in = X.shape
+    n_out, r = U.shape
+    return pf_linear_desc(M, n_in, n_out, r, _dtype_code(X), 1 if bias_flag else 0)
+
+
+def pf_lowrank_linear_fwd(X, V, U, bias=None, save_T=True):
+    """Y = (X V) U^T + bias.  Returns (Y, T) with T = X V saved for backward (None if not saved)."""
+    d = _linear_desc(X, U, bias is not None)
+    dt = X.dtype
+    Y = torch.empty((d.M, d.n_out), dtype=dt, device=X.device)
+    T = torch.empty((d.M, d.r), dtype=dt, device=X.device) if save_T else None
+    n = lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(d))
+    ws = _workspace(n, X.device)
+    _check(lib.pf_lowrank_linear_fwd(ctypes.byref(d), _ptr(X, dt), _ptr(V, dt), _ptr(U, dt), _ptr(bias, dt),
+                                     _ptr(Y), _ptr(T), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "pf_lowrank_linear_fwd")
+    return Y, T
+
+
+def pf_lowrank_linear_bwd(X, V, U, dY, T_saved=None, need_dX=True, has_bias=False, grads=None):
+    """Returns (dX, dU, dV, dbias); dU, dV, dbias are float32.  If `grads` = (dU, dV, dbias) is given the
+    parameter gradients are accumulated into those tensors."""
+    d = _linear_desc(X, U, has_bias)
+    dt = X.dtype
+    dX = torch.empty_like(X) if need_dX else None
+    accumulate = grads is not None
+    if grads is None:
+        dU = torch.empty((d.n_out, d.r), dtype=torch.float32, device=X.device)
+        dV = torch.empty((d.n_in, d.r), dtype=torch.float32, device=X.device)
+        db = torch.empty((d.n_out,), dtype=torch.float32, device=X.device) if has_bias else None
+    else:
+        dU, dV, db = grads
+    n = lib.pf_lowrank_linear_bwd_workspace_bytes(ctypes.byref(d))
+    ws = _workspace(n, X.device)
+    _check(lib.pf_lowrank_linear_bwd(ctypes.byref(d), _ptr(X, dt), _ptr(V, dt), _ptr(U, dt), _ptr(dY, dt),
+                                     _ptr(T_saved, dt), _ptr(dX), _ptr(dU, torch.float32), _ptr(dV, torch.float32),
+                                     _ptr(db, torch.float32), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
+                                     ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_linear_bwd")
+    return dX, dU, dV, db
+
+
+def pf_dense_linear_fwd(X, W, bias=None):
+    M, n_in = X.shape
+    n_out = W.shape[0]
+    d = pf_linear_desc(M, n_in, n_out, 1, _dtype_code(X), 1 if bias is not None else 0)
+    Y = torch.empty((M, n_out), dtype=X.dtype, device=X.device)
+    ws = _workspace(256, X.device)
+    _check(lib.pf_dense_linear_fwd(ctypes.byref(d), _ptr(X), _ptr(W, X.dtype), _ptr(bias, X.dtype), _ptr(Y),
+                                   _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()), "pf_dense_linear_fwd")
+    return Y
+
+
+def pf_dense_linear_bwd(X, W, dY, has_bias=False):
+    M, n_in = X.shape
+    n_out = W.shape[0]
+    d = pf_linear_desc(M, n_in, n_out, 1, _dtype_code(X), 1 if has_bias else 0)
+    dX = torch.empty_like(X)
+    dW = torch.empty((n_out, n_in), dtype=torch.float32, device=X.device)
+    db = torch.empty((n_out,), dtype=torch.float32, device=X.device) if has_bias else None
+    ws = _workspace(lib.pf_dense_linear_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_dense_linear_bwd(ctypes.byref(d), _ptr(X), _ptr(W, X.dtype), _ptr(dY, X.dtype), _ptr(dX),
+                                   _ptr(dW), _ptr(db), ctypes.c_int(0), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                                   _stream()), "pf_dense_linear_bwd")
+    return dX, dW, db
+
+
+# -------------------------------------------------------------------- conv
+
+def _conv_desc(X, Uk, Vp, stride, pad):
+    N, C, H, W = X.shape
+    r, _, k, _ = Uk.shape
+    return pf_conv_desc(N, C, H, W, Vp.shape[0], r, k, stride, pad, _dtype_code(X))
+
+
+def conv_out_hw(d):
+    return (d.H + 2 * d.pad - d.k) // d.stride + 1, (d.W + 2 * d.pad - d.k) // d.stride + 1
+
+
+def pf_lowrank_conv_fwd(X, Uk, Vp, stride=1, pad=0, save_T=True):
+    """Thin k x k conv (Uk[r,C,k,k]) then 1x1 conv (Vp[Cout,r]).  Returns (Y, T)."""
+    d = _conv_desc(X, Uk, Vp, stride, pad)
+    Ho, Wo = conv_out_hw(d)
+    dt = X.dtype
+    Y = torch.empty((d.N, d.Cout, Ho, Wo), dtype=dt, device=X.device)
+    T = torch.empty((d.N, d.r, Ho, Wo), dtype=dt, device=X.device) if save_T else None
+    ws = _workspace(lib.pf_lowrank_conv_fwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_conv_fwd(ctypes.byref(d), _ptr(X), _ptr(Uk, dt), _ptr(Vp, dt), _ptr(Y), _ptr(T),
+                                   _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_conv_fwd")
+    return Y, T
+
+
+def pf_lowrank_conv_bwd(X, Uk, Vp, dY, T_saved=None, stride=1, pad=0, need_dX=True, grads=None):
+    """Returns (dX, dUk, dVp); dUk, dVp are float32 (accumulated into `grads` = (dUk, dVp) if given)."""
+    d = _conv_desc(X, Uk, Vp, stride, pad)
+    dt = X.dtype
+    dX = torch.empty_like(X) if need_dX else None
+    accumulate = grads is not None
+    if grads is None:
+        dUk = torch.empty(Uk.shape, dtype=torch.float32, device=X.device)
+        dVp = torch.empty(Vp.shape, dtype=torch.float32, device=X.device)
+    else:
+        dUk, dVp = grads
+    ws = _workspace(lib.pf_lowrank_conv_bwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_conv_bwd(ctypes.byref(d), _ptr(X), _ptr(Uk, dt), _ptr(Vp, dt), _ptr(dY, dt),
+                                   _ptr(T_saved, dt), _ptr(dX), _ptr(dUk, torch.float32), _ptr(dVp, torch.float32),
+                                   ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                                   _stream()), "pf_lowrank_conv_bwd")
+    return dX, dUk, dVp
+
+
+def pf_dense_conv_fwd(X, Wd, stride=1, pad=0):
+    N, C, H, W = X.shape
+    Cout, _, k, _ = Wd.shape
+    d = pf_conv_desc(N, C, H, W, Cout, 1, k, stride, pad, _dtype_code(X))
+    Ho, Wo = conv_out_hw(d)
+    Y = torch.empty((N, Cout, Ho, Wo), dtype=X.dtype, device=X.device)
+    ws = _workspace(lib.pf_dense_conv_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_dense_conv_fwd(ctypes.byref(d), _ptr(X), _ptr(Wd, X.dtype), _ptr(Y), _ptr(ws),
+                                 ctypes.c_size_t(ws.numel()), _stream()), "pf_dense_conv_fwd")
+    return Y
+
+
+def pf_dense_conv_bwd(X, Wd, dY, stride=1, pad=0):
+    N, C, H, W = X.shape
+    Cout, _, k, _ = Wd.shape
+    d = pf_conv_desc(N, C, H, W, Cout, 1, k, stride, pad, _dtype_code(X))
+    dX = torch.empty_like(X)
+    dW = torch.empty(Wd.shape, dtype=torch.float32, device=X.device)
+    ws = _workspace(lib.pf_dense_conv_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_dense_conv_bwd(ctypes.byref(d), _ptr(X), _ptr(Wd, X.dtype), _ptr(dY, X.dtype), _ptr(dX), _ptr(dW),
+                                 ctypes.c_int(0), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "pf_dense_conv_bwd")
+    return dX, dW
+
+
+# -------------------------------------------------------------------- LSTM
+
+def _lstm_desc(x, h_prev, Ux, groups, has_bias):
+    B, d_in = x.shape
+    return pf_lstm_desc(B, d_in, h_prev.shape[1], Ux.shape[1], groups, _dtype_code(x), 1 if has_bias else 0)
+
+
+def pf_lowrank_lstm_cell_fwd(x, h_prev, c_prev, Vx, Ux, Vh, Uh, bias=None, groups=1):
+    """One factorized LSTM step.  Returns (h, c, gates, Tx, Th); the last three are saved for backward."""
+    d = _lstm_desc(x, h_prev, Ux, groups, bias is not None)
+    f32 = torch.float32
+    dev = x.device
+    h_out = torch.empty((d.B, d.h), dtype=f32, device=dev)
+    c_out = torch.empty((d.B, d.h), dtype=f32, device=dev)
+    gates = torch.empty((d.B, 4 * d.h), dtype=f32, device=dev)
+    Tx = torch.empty((d.B, groups * d.r), dtype=f32, device=dev)
+    Th = torch.empty((d.B, groups * d.r), dtype=f32, device=dev)
+    ws = _workspace(lib.pf_lowrank_lstm_cell_fwd_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_lowrank_lstm_cell_fwd(ctypes.byref(d), _ptr(x, f32), _ptr(h_prev, f32), _ptr(c_prev, f32),
+                                        _ptr(Vx, f32), _ptr(Ux, f32), _ptr(Vh, f32), _ptr(Uh, f32), _ptr(bias, f32),
+                                        _ptr(h_out), _ptr(c_out), _ptr(gates), _ptr(Tx), _ptr(Th), _ptr(ws),
+                                        ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_lstm_cell_fwd")
+    return h_out, c_out, gates, Tx, Th
+
+
+def pf_lowrank_lstm_cell_bwd(x, h_prev, c_prev, c_out, gates, Tx, Th, Vx, Ux, Vh, Uh, dh, dc_next=None, groups=1,
+                             need_dx=True, grads=None):
+    """One BPTT step.  Returns (dx, dh_prev, dc_prev, grads) with grads = dict(dVx, dUx, dVh, dUh, dbias) in
+    float32; if `grads` is given the parameter gradients are accumulated into it."""
+    d = _lstm_desc(x, h_prev, Ux, groups, True)
+    f32 = torch.float32
+    dev = x.device
+    dx = torch.empty_like(x) if need_dx else None
+    dh_prev = torch.empty_like(h_prev)
+    dc_prev = torch.empty_like(c_prev)
+    accumulate = grads is not None
+    if grads is None:
+        grads = dict(dVx=torch.empty_like(Vx), dUx=torch.empty_like(Ux), dVh=torch.empty_like(Vh),
+                     dUh=torch.empty_like(Uh), dbias=torch.empty((4 * d.h,), dtype=f32, device=dev))
+    ws = _workspace(lib.pf_lowrank_lstm_cell_bwd_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_lowrank_lstm_cell_bwd(
+        ctypes.byref(d), _ptr(x, f32), _ptr(h_prev, f32), _ptr(c_prev, f32), _ptr(c_out, f32), _ptr(gates, f32),
+        _ptr(Tx, f32), _ptr(Th, f32), _ptr(Vx, f32), _ptr(Ux, f32), _ptr(Vh, f32), _ptr(Uh, f32), _ptr(dh, f32),
+        _ptr(dc_next, f32), _ptr(dx), _ptr(dh_prev), _ptr(dc_prev), _ptr(grads["dVx"], f32), _ptr(grads["dUx"], f32),
+        _ptr(grads["dVh"], f32), _ptr(grads["dUh"], f32), _ptr(grads["dbias"], f32),
+        ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
+        "pf_lowrank_lstm_cell_bwd")
+    return dx, dh_prev, dc_prev, grads
+
+
+# ------------------------------------------------------------------ timing
+
+def timing_enable(on=True):
+    lib.pf_timing_enable(ctypes.c_int(1 if on else 0))
+
+
+def timing_reset():
+    lib.pf_timing_reset()
+
+
+def timing_collect():
+    """{kernel name: (launches, total_ms)} of everything recorded while timing was enabled."""
+    n = lib.pf_timing_collect()
+    out = {}
+    for i in range(n):
+        name = ctypes.c_char_p()
+        launches = ctypes.c_int64()
+        ms = ctypes.c_double()
+        lib.pf_timing_entry(ctypes.c_int(i), ctypes.byref(name), ctypes.byref(launches), ctypes.byref(ms))
+        out[name.value.decode()] = (int(launches.value), float(ms.value))
+    return out

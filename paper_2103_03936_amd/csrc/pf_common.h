@@ -1,0 +1,87 @@
+// Shared host/device helpers for the gfx950 low-rank layer kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pufferfish.h"
+
+namespace pf {
+
+typedef long long i64;
+
+// ------------------------------------------------------------------ types
+struct bf16_t {
+    uint16_t v;
+};
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return bf16_bits_to_float(x.v); }
+
+template <typename T>
+__device__ __forceinline__ T from_float(float f);
+template <>
+__device__ __forceinline__ float from_float<float>(float f) { return f; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float f)
+{
+    bf16_t r;
+    r.v = float_to_bf16_bits(f);
+    return r;
+}
+
+// ------------------------------------------------------------ host helpers
+int set_hip_error(hipError_t e); // records e for pf_last_hip_error(), returns PF_ERR_LAUNCH
+
+struct TimingScope {
+    TimingScope(const char *name, hipStream_t s);
+    ~TimingScope();
+    int slot;
+    hipStream_t stream;
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Bump allocator over the caller's workspace.
+struct Workspace {
+    char *base;
+    size_t size, used;
+    Workspace(void *p, size_t n) : base((char *)p), size(n), used(0) {}
+    template <typename T>
+    T *take(size_t count)
+    {
+        size_t bytes = align_up(count * sizeof(T));
+        T *r = (T *)(base + used);
+        used += bytes;
+        return r;
+    }
+};
+
+} // namespace pf
+
+// Launch `kernel` on `stream`, bracketed by timing events when enabled.  Evaluates to a
+// pf_status in `status_var` (PF_OK or PF_ERR_LAUNCH).
+#define PF_LAUNCH(status_var, name, kernel, grid, block, stream, ...)                    \
+    do {                                                                                  \
+        if ((status_var) == PF_OK) {                                                      \
+            pf::TimingScope pf_ts_(name, stream);                                         \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);              \
+            hipError_t pf_e_ = hipGetLastError();                                         \
+            if (pf_e_ != hipSuccess) (status_var) = pf::set_hip_error(pf_e_);             \
+        }                                                                                 \
+    } while (0)

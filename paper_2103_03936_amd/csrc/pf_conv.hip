@@ -1,0 +1,386 @@
+// Factorized convolution (paper Section 2.2): thin k x k convolution into r channels
+// followed by a 1x1 convolution, forward and backward, plus the dense comparator.
+// Host-side validation, workspace planning and dispatch; the any-shape path runs every
+// stage as an implicit GEMM (operands gathered by functors) on the guarded tile GEMM.
+#include "pf_gemm.h"
+
+namespace pf {
+
+struct ConvGeom {
+    int N, C, H, W, Cout, r, k, s, p, Ho, Wo;
+};
+
+// B(kidx = (c,i,j), n = (img,y,x)) = Xpad[img, c, y s + i - p, x s + j - p]
+template <typename T>
+struct OpB_Im2col {
+    const T *X;
+    ConvGeom g;
+    __device__ __forceinline__ float at(int kidx, int n) const
+    {
+        const int kk = g.k * g.k;
+        const int c = kidx / kk, t = kidx % kk, i = t / g.k, j = t % g.k;
+        const int hw = g.Ho * g.Wo;
+        const int img = n / hw, pix = n % hw, y = pix / g.Wo, x = pix % g.Wo;
+        const int yy = y * g.s + i - g.p, xx = x * g.s + j - g.p;
+        if (yy < 0 || yy >= g.H || xx < 0 || xx >= g.W) return 0.f;
+        return to_float(X[(((i64)img * g.C + c) * g.H + yy) * g.W + xx]);
+    }
+    __device__ __forceinline__ float operator()(int k, int n, int) const { return at(k, n); }
+};
+// B(k = (img,y,x), n = (c,i,j)): the same view with the roles swapped (weight gradient)
+template <typename T>
+struct OpB_Im2colT {
+    OpB_Im2col<T> v;
+    __device__ __forceinline__ float operator()(int k, int n, int) const { return v.at(n, k); }
+};
+
+// Tensor P[img, ch, pix] (NCHW with HW flattened) seen as a matrix over (channel, pixel).
+template <typename T>
+struct OpB_NCHW { // B(k = ch, n = (img,pix))
+    const T *p;
+    int CH, HW;
+    __device__ __forceinline__ float operator()(int k, int n, int) const
+    {
+        const int img = n / HW, pix = n % HW;
+        return to_float(p[((i64)img * CH + k) * HW + pix]);
+    }
+};
+template <typename T>
+struct OpB_NCHW_T { // B(k = (img,pix), n = ch)
+    const T *p;
+    int CH, HW;
+    __device__ __forceinline__ float operator()(int k, int n, int) const
+    {
+        const int img = k / HW, pix = k % HW;
+        return to_float(p[((i64)img * CH + n) * HW + pix]);
+    }
+};
+template <typename T>
+struct OpA_NCHW { // A(m = ch, k = (img,pix))
+    const T *p;
+    int CH, HW;
+    __device__ __forceinline__ float operator()(int m, int k, int) const
+    {
+        const int img = k / HW, pix = k % HW;
+        return to_float(p[((i64)img * CH + m) * HW + pix]);
+    }
+};
+
+// A(m = c, kidx = (q,i,j)) = Uk[q, c, i, j]
+template <typename T>
+struct OpA_FilterT {
+    const T *Uk;
+    int C, kk;
+    __device__ __forceinline__ float operator()(int m, int kidx, int) const
+    {
+        const int q = kidx / kk, t = kidx % kk;
+        return to_float(Uk[((i64)q * C + m) * kk + t]);
+    }
+};
+
+// B(kidx = (q,i,j), n = (img,yy,xx)) = dT[img, q, y, x] where y s + i - p = yy, x s + j - p = xx
+template <typename T>
+struct OpB_Col2im {
+    const T *dT;
+    ConvGeom g;
+    int CH; // channels of dT
+    __device__ __forceinline__ float operator()(int kidx, int n, int) const
+    {
+        const int kk = g.k * g.k;
+        const int q = kidx / kk, t = kidx % kk, i = t / g.k, j = t % g.k;
+        const int hw = g.H * g.W;
+        const int img = n / hw, pix = n % hw, yy = pix / g.W, xx = pix % g.W;
+        const int ys = yy + g.p - i, xs = xx + g.p - j;
+        if (ys < 0 || xs < 0 || ys % g.s || xs % g.s) return 0.f;
+        const int y = ys / g.s, x = xs / g.s;
+        if (y >= g.Ho || x >= g.Wo) return 0.f;
+        return to_float(dT[(((i64)img * CH + q) * g.Ho + y) * g.Wo + x]);
+    }
+};
+
+// C(m = ch, n = (img,pix)) -> P[img, ch, pix], optionally to a second buffer
+template <typename T1, typename T2>
+struct EpiNCHW {
+    T1 *c1;
+    T2 *c2;
+    int CH, HW;
+    __device__ __forceinline__ void operator()(int m, int n, float acc, int, int) const
+    {
+        const int img = n / HW, pix = n % HW;
+        const i64 off = ((i64)img * CH + m) * HW + pix;
+        if (c1) c1[off] = from_float<T1>(acc);
+        if (c2) c2[off] = from_float<T2>(acc);
+    }
+};
+
+// ------------------------------------------------------------ validation
+static int check_conv_desc(const pf_conv_desc *d, ConvGeom *g)
+{
+    if (!d) return PF_ERR_NULL;
+    if (d->dtype != PF_F32 && d->dtype != PF_BF16) return PF_ERR_UNSUPPORTED;
+    if (d->N < 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->Cout <= 0 || d->r <= 0) return PF_ERR_SHAPE;
+    if (d->k <= 0 || d->stride <= 0 || d->pad < 0 || d->k > 15) return PF_ERR_SHAPE;
+    const i64 Ho = (d->H + 2 * (i64)d->pad - d->k) / d->stride + 1, Wo = (d->W + 2 * (i64)d->pad - d->k) / d->stride + 1;
+    if (d->H + 2 * (i64)d->pad < d->k || d->W + 2 * (i64)d->pad < d->k || Ho <= 0 || Wo <= 0) return PF_ERR_SHAPE;
+    const i64 lim = 0x7fffffffLL;
+    if (d->N * d->H * d->W > lim || d->N * Ho * Wo > lim || d->Cin * d->k * d->k > lim || d->r * d->k * d->k > lim ||
+        d->Cout > lim || d->r > lim)
+        return PF_ERR_SHAPE;
+    if (d->N * d->Cin * d->H * d->W > (lim << 4) || d->N * d->Cout * Ho * Wo > (lim << 4)) return PF_ERR_SHAPE;
+    if (g) *g = ConvGeom{(int)d->N, (int)d->Cin, (int)d->H, (int)d->W, (int)d->Cout, (int)d->r,
+                         d->k,      d->stride,   d->pad,    (int)Ho,   (int)Wo};
+    return PF_OK;
+}
+
+struct ConvPlan {
+    int ks_dVp, ks_dUk;
+    size_t n_T, n_part, fwd_bytes, bwd_bytes;
+};
+
+static ConvPlan plan_conv(const ConvGeom &g)
+{
+    ConvPlan p;
+    const i64 npix = (i64)g.N * g.Ho * g.Wo;
+    p.ks_dVp = choose_ksplit(g.Cout, g.r, npix);
+    p.ks_dUk = choose_ksplit(g.r, (i64)g.C * g.k * g.k, npix);
+    p.n_T = (size_t)(npix * g.r);
+    size_t a = (size_t)p.ks_dVp * g.Cout * g.r, b = (size_t)p.ks_dUk * g.r * g.C * g.k * g.k;
+    p.n_part = a > b ? a : b;
+    p.fwd_bytes = align_up(p.n_T * sizeof(float));
+    p.bwd_bytes = 2 * align_up(p.n_T * sizeof(float)) + align_up(p.n_part * sizeof(float));
+    return p;
+}
+
+// ------------------------------------------------------------- any-shape
+template <typename T>
+static int conv_T_generic(const ConvGeom &g, const T *X, const T *Uk, float *Tws, T *T_save, hipStream_t s)
+{
+    const int npix = g.N * g.Ho * g.Wo, K = g.C * g.k * g.k;
+    return launch_gemm_generic<T, true, false>("conv_T=Uk*X", s, GemmShape{g.r, npix, K, 1, 1},
+                                               OpA_RowMajor<T>{Uk, K, 0}, OpB_Im2col<T>{X, g},
+                                               EpiNCHW<float, T>{Tws, T_save, g.r, g.Ho * g.Wo});
+}
+
+template <typename T>
+static int conv_fwd_generic(const ConvGeom &g, const T *X, const T *Uk, const T *Vp, T *Y, T *T_save, Workspace &ws,
+                            hipStream_t s)
+{
+    const int npix = g.N * g.Ho * g.Wo;
+    float *Tws = ws.take<float>((size_t)npix * g.r);
+    int st = conv_T_generic<T>(g, X, Uk, Tws, T_save, s);
+    if (st != PF_OK) return st;
+    return launch_gemm_generic<T, true, false>("conv_Y=Vp*T", s, GemmShape{g.Cout, npix, g.r, 1, 1},
+                                               OpA_RowMajor<T>{Vp, g.r, 0}, OpB_NCHW<float>{Tws, g.r, g.Ho * g.Wo},
+                                               EpiNCHW<T, T>{Y, nullptr, g.Cout, g.Ho * g.Wo});
+}
+
+template <typename T>
+static int conv_bwd_generic(const ConvGeom &g, const T *X, const T *Uk, const T *Vp, const T *dY, const T *T_saved,
+                            T *dX, float *dUk, float *dVp, int accumulate, Workspace &ws, hipStream_t s)
+{
+    const ConvPlan p = plan_conv(g);
+    const int npix = g.N * g.Ho * g.Wo, HW = g.Ho * g.Wo, kk = g.k * g.k;
+    float *Tws = ws.take<float>(p.n_T);
+    float *dTws = ws.take<float>(p.n_T);
+    float *part = ws.take<float>(p.n_part);
+    int st = PF_OK;
+    if (g.N == 0) {
+        if (!accumulate) {
+            st = launch_zero_f32(s, dUk, (i64)g.r * g.C * kk);
+            if (st == PF_OK) st = launch_zero_f32(s, dVp, (i64)g.Cout * g.r);
+        }
+        return st;
+    }
+    if (dVp && !T_saved) {
+        st = conv_T_generic<T>(g, X, Uk, Tws, nullptr, s);
+        if (st != PF_OK) return st;
+    }
+    if (dX || dUk) { // dT[q, pixel] = sum_o Vp[o,q] dY[o, pixel]
+        st = launch_gemm_generic<T, false, false>("conv_dT=Vpt*dY", s, GemmShape{g.r, npix, g.Cout, 1, 1},
+                                                  OpA_ColMajor<T>{Vp, g.r, 0}, OpB_NCHW<T>{dY, g.Cout, HW},
+                                                  EpiNCHW<float, float>{dTws, nullptr, g.r, HW});
+        if (st != PF_OK) return st;
+    }
+    if (dVp) { // dVp[o,q] = sum_pixel dY[o,pixel] T[q,pixel]
+        const GemmShape gs{g.Cout, g.r, npix, 1, p.ks_dVp};
+        const EpiPartial epi{part, g.r, (i64)g.Cout * g.r};
+        if (T_saved)
+            st = launch_gemm_generic<T, true, true>("conv_dVp=dY*Tt", s, gs, OpA_NCHW<T>{dY, g.Cout, HW},
+                                                    OpB_NCHW_T<T>{T_saved, g.r, HW}, epi);
+        else
+            st = launch_gemm_generic<T, true, true>("conv_dVp=dY*Tt", s, gs, OpA_NCHW<T>{dY, g.Cout, HW},
+                                                    OpB_NCHW_T<float>{Tws, g.r, HW}, epi);
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dVp, (i64)g.Cout * g.r, p.ks_dVp, accumulate);
+        if (st != PF_OK) return st;
+    }
+    if (dX) { // dX[c, in-pixel] = sum_{q,i,j} Uk[q,c,i,j] dT[q, out-pixel(in-pixel,i,j)]
+        st = launch_gemm_generic<T, true, false>("conv_dX=Ukt*dT", s, GemmShape{g.C, g.N * g.H * g.W, g.r * kk, 1, 1},
+                                                 OpA_FilterT<T>{Uk, g.C, kk}, OpB_Col2im<float>{dTws, g, g.r},
+                                                 EpiNCHW<T, T>{dX, nullptr, g.C, g.H * g.W});
+        if (st != PF_OK) return st;
+    }
+    if (dUk) { // dUk[q,(c,i,j)] = sum_pixel dT[q,pixel] Xcol[(c,i,j),pixel]
+        st = launch_gemm_generic<T, true, true>("conv_dUk=dT*Xcolt", s, GemmShape{g.r, g.C * kk, npix, 1, p.ks_dUk},
+                                                OpA_NCHW<float>{dTws, g.r, HW},
+                                                OpB_Im2colT<T>{OpB_Im2col<T>{X, g}},
+                                                EpiPartial{part, (i64)g.C * kk, (i64)g.r * g.C * kk});
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dUk, (i64)g.r * g.C * kk, p.ks_dUk, accumulate);
+    }
+    return st;
+}
+
+// ------------------------------------------------------------------ dense
+struct DenseConvPlan {
+    int ks;
+    size_t n_part, bytes;
+};
+static DenseConvPlan plan_dense_conv(const ConvGeom &g)
+{
+    DenseConvPlan p;
+    const i64 npix = (i64)g.N * g.Ho * g.Wo;
+    p.ks = choose_ksplit(g.Cout, (i64)g.C * g.k * g.k, npix);
+    p.n_part = (size_t)p.ks * g.Cout * g.C * g.k * g.k;
+    p.bytes = align_up(p.n_part * sizeof(float));
+    return p;
+}
+
+template <typename T>
+static int dense_conv_fwd_t(const ConvGeom &g, const T *X, const T *Wd, T *Y, hipStream_t s)
+{
+    const int npix = g.N * g.Ho * g.Wo, K = g.C * g.k * g.k;
+    return launch_gemm_generic<T, true, false>("dense_conv_Y=W*X", s, GemmShape{g.Cout, npix, K, 1, 1},
+                                               OpA_RowMajor<T>{Wd, K, 0}, OpB_Im2col<T>{X, g},
+                                               EpiNCHW<T, T>{Y, nullptr, g.Cout, g.Ho * g.Wo});
+}
+
+template <typename T>
+static int dense_conv_bwd_t(const ConvGeom &g, const T *X, const T *Wd, const T *dY, T *dX, float *dW, int accumulate,
+                            Workspace &ws, hipStream_t s)
+{
+    const DenseConvPlan p = plan_dense_conv(g);
+    const int npix = g.N * g.Ho * g.Wo, HW = g.Ho * g.Wo, kk = g.k * g.k;
+    float *part = ws.take<float>(p.n_part);
+    int st = PF_OK;
+    if (g.N == 0) return accumulate ? st : launch_zero_f32(s, dW, (i64)g.Cout * g.C * kk);
+    if (dX) {
+        // the transposed convolution of the dense layer: the same gather with Cout in place of r
+        st = launch_gemm_generic<T, true, false>("dense_conv_dX=Wt*dY", s,
+                                                 GemmShape{g.C, g.N * g.H * g.W, g.Cout * kk, 1, 1},
+                                                 OpA_FilterT<T>{Wd, g.C, kk}, OpB_Col2im<T>{dY, g, g.Cout},
+                                                 EpiNCHW<T, T>{dX, nullptr, g.C, g.H * g.W});
+        if (st != PF_OK) return st;
+    }
+    if (dW) {
+        st = launch_gemm_generic<T, true, true>("dense_conv_dW=dY*Xcolt", s, GemmShape{g.Cout, g.C * kk, npix, 1, p.ks},
+                                                OpA_NCHW<T>{dY, g.Cout, HW}, OpB_Im2colT<T>{OpB_Im2col<T>{X, g}},
+                                                EpiPartial{part, (i64)g.C * kk, (i64)g.Cout * g.C * kk});
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dW, (i64)g.Cout * g.C * kk, p.ks, accumulate);
+    }
+    return st;
+}
+
+} // namespace pf
+
+using namespace pf;
+
+extern "C" {
+
+size_t pf_lowrank_conv_fwd_workspace_bytes(const pf_conv_desc *d)
+{
+    ConvGeom g;
+    if (check_conv_desc(d, &g) != PF_OK) return 0;
+    return plan_conv(g).fwd_bytes;
+}
+
+size_t pf_lowrank_conv_bwd_workspace_bytes(const pf_conv_desc *d)
+{
+    ConvGeom g;
+    if (check_conv_desc(d, &g) != PF_OK) return 0;
+    return plan_conv(g).bwd_bytes;
+}
+
+int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, void *Y, void *T_save,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    ConvGeom g;
+    int st = check_conv_desc(d, &g);
+    if (st != PF_OK) return st;
+    if (!Uk || !Vp) return PF_ERR_NULL;
+    if (g.N > 0 && (!X || !Y)) return PF_ERR_NULL;
+    const size_t need = plan_conv(g).fwd_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    if (g.N == 0) return PF_OK;
+    Workspace ws(workspace, workspace_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32)
+        return conv_fwd_generic<float>(g, (const float *)X, (const float *)Uk, (const float *)Vp, (float *)Y,
+                                       (float *)T_save, ws, s);
+    return conv_fwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
+                                    (bf16_t *)T_save, ws, s);
+}
+
+int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dY,
+                        const void *T_saved, void *dX, void *dUk, void *dVp, int accumulate, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    ConvGeom g;
+    int st = check_conv_desc(d, &g);
+    if (st != PF_OK) return st;
+    if (!Uk || !Vp) return PF_ERR_NULL;
+    if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
+    const size_t need = plan_conv(g).bwd_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    Workspace ws(workspace, workspace_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32)
+        return conv_bwd_generic<float>(g, (const float *)X, (const float *)Uk, (const float *)Vp, (const float *)dY,
+                                       (const float *)T_saved, (float *)dX, (float *)dUk, (float *)dVp, accumulate, ws,
+                                       s);
+    return conv_bwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
+                                    (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk, (float *)dVp, accumulate, ws,
+                                    s);
+}
+
+size_t pf_dense_conv_workspace_bytes(const pf_conv_desc *d)
+{
+    ConvGeom g;
+    if (check_conv_desc(d, &g) != PF_OK) return 0;
+    return plan_dense_conv(g).bytes;
+}
+
+int pf_dense_conv_fwd(const pf_conv_desc *d, const void *X, const void *Wd, void *Y, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    ConvGeom g;
+    int st = check_conv_desc(d, &g);
+    if (st != PF_OK) return st;
+    if (!Wd) return PF_ERR_NULL;
+    if (g.N == 0) return PF_OK;
+    if (!X || !Y) return PF_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32) return dense_conv_fwd_t<float>(g, (const float *)X, (const float *)Wd, (float *)Y, s);
+    return dense_conv_fwd_t<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Wd, (bf16_t *)Y, s);
+}
+
+int pf_dense_conv_bwd(const pf_conv_desc *d, const void *X, const void *Wd, const void *dY, void *dX, void *dWd,
+                      int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ConvGeom g;
+    int st = check_conv_desc(d, &g);
+    if (st != PF_OK) return st;
+    if (!Wd) return PF_ERR_NULL;
+    if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
+    const size_t need = plan_dense_conv(g).bytes;
+    if (!workspace || workspace_bytes < need) return PF_ERR_WORKSPACE;
+    Workspace ws(workspace, workspace_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32)
+        return dense_conv_bwd_t<float>(g, (const float *)X, (const float *)Wd, (const float *)dY, (float *)dX,
+                                       (float *)dWd, accumulate, ws, s);
+    return dense_conv_bwd_t<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Wd, (const bf16_t *)dY, (bf16_t *)dX,
+                                    (float *)dWd, accumulate, ws, s);
+}
+
+} // extern "C"

@@ -1,0 +1,260 @@
+// Factorized LSTM cell (paper Section 2.3, eq. (2)): one time step forward and one step of
+// back-propagation through time.  Host-side validation, workspace planning and dispatch;
+// the any-shape path composes the guarded tile GEMM with two pointwise kernels.
+#include "pf_gemm.h"
+
+namespace pf {
+
+__device__ __forceinline__ float sigmoidf_acc(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+// z[B x 4h] pre-activations (i|f|g|o) -> gates, c, h
+__global__ __launch_bounds__(256) void lstm_pointwise_fwd_kernel(const float *z, const float *c_prev, float *h_out,
+                                                                  float *c_out, float *gates, int B, int h)
+{
+    const i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (i64)B * h) return;
+    const int b = (int)(idx / h), j = (int)(idx % h);
+    const i64 base = (i64)b * 4 * h + j;
+    const float ig = sigmoidf_acc(z[base]), fg = sigmoidf_acc(z[base + h]);
+    const float gg = tanhf(z[base + 2 * (i64)h]), og = sigmoidf_acc(z[base + 3 * (i64)h]);
+    const float c = fg * c_prev[idx] + ig * gg;
+    gates[base] = ig;
+    gates[base + h] = fg;
+    gates[base + 2 * (i64)h] = gg;
+    gates[base + 3 * (i64)h] = og;
+    c_out[idx] = c;
+    h_out[idx] = og * tanhf(c);
+}
+
+// dh, dc_next -> dz[B x 4h] (gradient at the pre-activations), dc_prev
+__global__ __launch_bounds__(256) void lstm_pointwise_bwd_kernel(const float *gates, const float *c_prev,
+                                                                  const float *c_out, const float *dh,
+                                                                  const float *dc_next, float *dz, float *dc_prev, int B,
+                                                                  int h)
+{
+    const i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (i64)B * h) return;
+    const int b = (int)(idx / h), j = (int)(idx % h);
+    const i64 base = (i64)b * 4 * h + j;
+    const float ig = gates[base], fg = gates[base + h], gg = gates[base + 2 * (i64)h], og = gates[base + 3 * (i64)h];
+    const float tc = tanhf(c_out[idx]);
+    const float dhv = dh[idx];
+    const float dc = (dc_next ? dc_next[idx] : 0.f) + dhv * og * (1.f - tc * tc);
+    dc_prev[idx] = dc * fg;
+    dz[base] = dc * gg * ig * (1.f - ig);
+    dz[base + h] = dc * c_prev[idx] * fg * (1.f - fg);
+    dz[base + 2 * (i64)h] = dc * ig * (1.f - gg * gg);
+    dz[base + 3 * (i64)h] = dhv * tc * og * (1.f - og);
+}
+
+// A(m, k, gate): [Tx | Th] of the gate's group, k in [0, 2r)
+struct OpA_LstmT {
+    const float *Tx, *Th;
+    int r, gr, goff; // goff = r for groups == 4, 0 for groups == 1
+    __device__ __forceinline__ float operator()(int m, int k, int gate) const
+    {
+        const i64 base = (i64)m * gr + (i64)gate * goff;
+        return k < r ? Tx[base + k] : Th[base + k - r];
+    }
+};
+// B(k, n, gate): [Ux | Uh] row gate * h + n
+struct OpB_LstmU {
+    const float *Ux, *Uh;
+    int r, h;
+    __device__ __forceinline__ float operator()(int k, int n, int gate) const
+    {
+        const i64 row = (i64)gate * h + n;
+        return k < r ? Ux[row * r + k] : Uh[row * r + k - r];
+    }
+};
+
+static int check_lstm_desc(const pf_lstm_desc *d)
+{
+    if (!d) return PF_ERR_NULL;
+    if (d->dtype != PF_F32) return PF_ERR_UNSUPPORTED;
+    if (d->groups != 1 && d->groups != 4) return PF_ERR_UNSUPPORTED;
+    if (d->B < 0 || d->d_in <= 0 || d->h <= 0 || d->r <= 0) return PF_ERR_SHAPE;
+    const i64 lim = 0x7fffffffLL;
+    if (d->B > lim || d->d_in > lim || d->h * 4 > lim || d->r * 4 > lim) return PF_ERR_SHAPE;
+    if (d->B * d->h * 4 > lim || d->B * d->d_in > lim) return PF_ERR_SHAPE;
+    return PF_OK;
+}
+
+struct LstmPlan {
+    size_t n_z, n_dT, fwd_bytes, bwd_bytes, n_part;
+};
+static LstmPlan plan_lstm(const pf_lstm_desc *d)
+{
+    LstmPlan p;
+    p.n_z = (size_t)(d->B * 4 * d->h);
+    p.n_dT = (size_t)(d->B * d->groups * d->r);
+    p.n_part = (size_t)colsum_chunks(d->B) * 4 * d->h;
+    p.fwd_bytes = align_up(p.n_z * sizeof(float));
+    p.bwd_bytes = align_up(p.n_z * sizeof(float)) + 2 * align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
+    return p;
+}
+
+static int lstm_fwd_generic(const pf_lstm_desc *d, const float *x, const float *h_prev, const float *c_prev,
+                            const float *Vx, const float *Ux, const float *Vh, const float *Uh, const float *bias,
+                            float *h_out, float *c_out, float *gates, float *Tx, float *Th, Workspace &ws,
+                            hipStream_t s)
+{
+    const int B = (int)d->B, din = (int)d->d_in, h = (int)d->h, r = (int)d->r, gr = d->groups * r;
+    float *z = ws.take<float>((size_t)B * 4 * h);
+    int st = launch_gemm_generic<float, true, false>("lstm_Tx=x*Vx", s, GemmShape{B, gr, din, 1, 1},
+                                                     OpA_RowMajor<float>{x, din, 0}, OpB_KN<float>{Vx, gr, 0, 0},
+                                                     EpiRowMajor<float, float>{Tx, nullptr, gr, nullptr, 0});
+    if (st != PF_OK) return st;
+    st = launch_gemm_generic<float, true, false>("lstm_Th=h*Vh", s, GemmShape{B, gr, h, 1, 1},
+                                                 OpA_RowMajor<float>{h_prev, h, 0}, OpB_KN<float>{Vh, gr, 0, 0},
+                                                 EpiRowMajor<float, float>{Th, nullptr, gr, nullptr, 0});
+    if (st != PF_OK) return st;
+    st = launch_gemm_generic<float, true, true>(
+        "lstm_z=[Tx|Th]*[Ux|Uh]t", s, GemmShape{B, h, 2 * r, 4, 1},
+        OpA_LstmT{Tx, Th, r, gr, d->groups == 4 ? r : 0}, OpB_LstmU{Ux, Uh, r, h},
+        EpiRowMajor<float, float>{z, nullptr, 4 * (i64)h, d->has_bias ? bias : nullptr, h});
+    if (st != PF_OK) return st;
+    dim3 grid((unsigned)(((i64)B * h + 255) / 256));
+    PF_LAUNCH(st, "lstm_pointwise_fwd", lstm_pointwise_fwd_kernel, grid, dim3(256), s, z, c_prev, h_out, c_out, gates,
+              B, h);
+    return st;
+}
+
+static int lstm_bwd_generic(const pf_lstm_desc *d, const float *x, const float *h_prev, const float *c_prev,
+                            const float *c_out, const float *gates, const float *Tx, const float *Th, const float *Vx,
+                            const float *Ux, const float *Vh, const float *Uh, const float *dh, const float *dc_next,
+                            float *dx, float *dh_prev, float *dc_prev, float *dVx, float *dUx, float *dVh, float *dUh,
+                            float *dbias, int accumulate, Workspace &ws, hipStream_t s)
+{
+    const int B = (int)d->B, din = (int)d->d_in, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
+    const LstmPlan p = plan_lstm(d);
+    float *dz = ws.take<float>(p.n_z);
+    float *dTx = ws.take<float>(p.n_dT);
+    float *dTh = ws.take<float>(p.n_dT);
+    float *part = ws.take<float>(p.n_part);
+    int st = PF_OK;
+    if (B == 0) {
+        if (!accumulate) {
+            st = launch_zero_f32(s, dVx, (i64)din * gr);
+            if (st == PF_OK) st = launch_zero_f32(s, dVh, (i64)h * gr);
+            if (st == PF_OK) st = launch_zero_f32(s, dUx, (i64)4 * h * r);
+            if (st == PF_OK) st = launch_zero_f32(s, dUh, (i64)4 * h * r);
+            if (st == PF_OK) st = launch_zero_f32(s, dbias, (i64)4 * h);
+        }
+        return st;
+    }
+    dim3 grid((unsigned)(((i64)B * h + 255) / 256));
+    PF_LAUNCH(st, "lstm_pointwise_bwd", lstm_pointwise_bwd_kernel, grid, dim3(256), s, gates, c_prev, c_out, dh,
+              dc_next, dz, dc_prev, B, h);
+    if (st != PF_OK) return st;
+    // dT = dz U: one product over all 4h rows (groups == 1) or one per gate block (groups == 4)
+    const int nb = G == 4 ? 4 : 1, Kz = G == 4 ? h : 4 * h;
+    for (int path = 0; path < 2; ++path) {
+        const float *U = path ? Uh : Ux;
+        float *dT = path ? dTh : dTx;
+        st = launch_gemm_generic<float, true, false>(path ? "lstm_dTh=dz*Uh" : "lstm_dTx=dz*Ux", s,
+                                                     GemmShape{B, r, Kz, nb, 1}, OpA_RowMajor<float>{dz, 4 * (i64)h, h},
+                                                     OpB_KN<float>{U, r, h, 0},
+                                                     EpiRowMajor<float, float>{dT, nullptr, gr, nullptr, r});
+        if (st != PF_OK) return st;
+    }
+    if (dx) {
+        st = launch_gemm_generic<float, true, true>("lstm_dx=dTx*Vxt", s, GemmShape{B, din, gr, 1, 1},
+                                                    OpA_RowMajor<float>{dTx, gr, 0}, OpB_NK<float>{Vx, gr, 0},
+                                                    EpiRowMajor<float, float>{dx, nullptr, din, nullptr, 0});
+        if (st != PF_OK) return st;
+    }
+    st = launch_gemm_generic<float, true, true>("lstm_dh=dTh*Vht", s, GemmShape{B, h, gr, 1, 1},
+                                                OpA_RowMajor<float>{dTh, gr, 0}, OpB_NK<float>{Vh, gr, 0},
+                                                EpiRowMajor<float, float>{dh_prev, nullptr, h, nullptr, 0});
+    if (st != PF_OK) return st;
+    // dU[gate rows, :] (+)= dz[:, gate rows]^T T[:, gate's group]
+    for (int path = 0; path < 2; ++path) {
+        const float *T = path ? Th : Tx;
+        float *dU = path ? dUh : dUx;
+        if (!dU) continue;
+        st = launch_gemm_generic<float, false, false>(path ? "lstm_dUh=dzt*Th" : "lstm_dUx=dzt*Tx", s,
+                                                      GemmShape{h, r, B, 4, 1}, OpA_ColMajor<float>{dz, 4 * (i64)h, h},
+                                                      OpB_KN<float>{T, gr, 0, G == 4 ? r : 0},
+                                                      EpiGrad{dU, r, h, 0, accumulate});
+        if (st != PF_OK) return st;
+    }
+    if (dVx) {
+        st = launch_gemm_generic<float, false, false>("lstm_dVx=xt*dTx", s, GemmShape{din, gr, B, 1, 1},
+                                                      OpA_ColMajor<float>{x, din, 0}, OpB_KN<float>{dTx, gr, 0, 0},
+                                                      EpiGrad{dVx, gr, 0, 0, accumulate});
+        if (st != PF_OK) return st;
+    }
+    if (dVh) {
+        st = launch_gemm_generic<float, false, false>("lstm_dVh=ht*dTh", s, GemmShape{h, gr, B, 1, 1},
+                                                      OpA_ColMajor<float>{h_prev, h, 0}, OpB_KN<float>{dTh, gr, 0, 0},
+                                                      EpiGrad{dVh, gr, 0, 0, accumulate});
+        if (st != PF_OK) return st;
+    }
+    if (dbias) st = launch_colsum<float>(s, dz, part, dbias, B, 4 * (i64)h, 4 * (i64)h, accumulate);
+    return st;
+}
+
+} // namespace pf
+
+using namespace pf;
+
+extern "C" {
+
+size_t pf_lowrank_lstm_cell_fwd_workspace_bytes(const pf_lstm_desc *d)
+{
+    if (check_lstm_desc(d) != PF_OK) return 0;
+    return plan_lstm(d).fwd_bytes;
+}
+
+size_t pf_lowrank_lstm_cell_bwd_workspace_bytes(const pf_lstm_desc *d)
+{
+    if (check_lstm_desc(d) != PF_OK) return 0;
+    return plan_lstm(d).bwd_bytes;
+}
+
+int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x, const void *h_prev, const void *c_prev,
+                             const void *Vx, const void *Ux, const void *Vh, const void *Uh, const void *bias,
+                             void *h_out, void *c_out, void *gates_save, void *Tx_save, void *Th_save, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    int st = check_lstm_desc(d);
+    if (st != PF_OK) return st;
+    if (!Vx || !Ux || !Vh || !Uh || (d->has_bias && !bias)) return PF_ERR_NULL;
+    if (d->B > 0 && (!x || !h_prev || !c_prev || !h_out || !c_out || !gates_save || !Tx_save || !Th_save))
+        return PF_ERR_NULL;
+    const size_t need = plan_lstm(d).fwd_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    if (d->B == 0) return PF_OK;
+    Workspace ws(workspace, workspace_bytes);
+    return lstm_fwd_generic(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)Vx,
+                            (const float *)Ux, (const float *)Vh, (const float *)Uh, (const float *)bias,
+                            (float *)h_out, (float *)c_out, (float *)gates_save, (float *)Tx_save, (float *)Th_save, ws,
+                            (hipStream_t)stream);
+}
+
+int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x, const void *h_prev, const void *c_prev,
+                             const void *c_out, const void *gates_saved, const void *Tx_saved, const void *Th_saved,
+                             const void *Vx, const void *Ux, const void *Vh, const void *Uh, const void *dh,
+                             const void *dc_next, void *dx, void *dh_prev, void *dc_prev, void *dVx, void *dUx,
+                             void *dVh, void *dUh, void *dbias, int accumulate, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    int st = check_lstm_desc(d);
+    if (st != PF_OK) return st;
+    if (!Vx || !Ux || !Vh || !Uh || !dVx || !dUx || !dVh || !dUh) return PF_ERR_NULL;
+    if (d->B > 0 && (!x || !h_prev || !c_prev || !c_out || !gates_saved || !Tx_saved || !Th_saved || !dh || !dh_prev ||
+                     !dc_prev))
+        return PF_ERR_NULL;
+    const size_t need = plan_lstm(d).bwd_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    Workspace ws(workspace, workspace_bytes);
+    return lstm_bwd_generic(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)c_out,
+                            (const float *)gates_saved, (const float *)Tx_saved, (const float *)Th_saved,
+                            (const float *)Vx, (const float *)Ux, (const float *)Vh, (const float *)Uh,
+                            (const float *)dh, (const float *)dc_next, (float *)dx, (float *)dh_prev, (float *)dc_prev,
+                            (float *)dVx, (float *)dUx, (float *)dVh, (float *)dUh, (float *)dbias, accumulate, ws,
+                            (hipStream_t)stream);
+}
+
+} // extern "C"

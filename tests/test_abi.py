@@ -1,0 +1,103 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import paper_2103_03936_amd as pf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = ctypes.c_void_p
+FAKE = P(256)  # never dereferenced: validation fails before any launch in these calls
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pufferfish.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_symbols()
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(pf.lib, n), n
+    assert set(names) == set(pf.EXPORTS)
+
+
+def test_status_strings():
+    assert pf.lib.pf_status_string(0) == b"ok"
+    for s in range(1, 6):
+        assert len(pf.lib.pf_status_string(s)) > 3
+    assert pf.lib.pf_version() >= 1
+
+
+def _lin(M=4, n_in=5, n_out=3, r=2, dtype=0, bias=0):
+    return pf.pf_linear_desc(M, n_in, n_out, r, dtype, bias)
+
+
+def test_linear_validation():
+    f = pf.lib.pf_lowrank_linear_fwd
+    z = ctypes.c_size_t(0)
+    assert f(None, FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
+    assert f(ctypes.byref(_lin(n_in=0)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(_lin(r=-1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(_lin(M=-1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(_lin(dtype=7)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 3
+    assert f(ctypes.byref(_lin()), None, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
+    assert f(ctypes.byref(_lin(bias=1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
+    # workspace too small / missing
+    d = _lin()
+    need = pf.lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(d))
+    if need:
+        assert f(ctypes.byref(d), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 4
+        assert f(ctypes.byref(d), FAKE, FAKE, FAKE, None, FAKE, None, FAKE, ctypes.c_size_t(need - 1), None) == 4
+    # an empty batch is legal and launches nothing
+    assert f(ctypes.byref(_lin(M=0)), None, FAKE, FAKE, None, None, None, None, z, None) == 0
+    b = pf.lib.pf_lowrank_linear_bwd
+    assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 1
+    assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 4
+    # full rank and beyond is legal
+    assert pf.lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(_lin(r=64))) >= 0
+
+
+def _conv(N=2, C=3, H=5, W=5, Cout=4, r=2, k=3, s=1, p=1, dtype=0):
+    return pf.pf_conv_desc(N, C, H, W, Cout, r, k, s, p, dtype)
+
+
+def test_conv_validation():
+    f = pf.lib.pf_lowrank_conv_fwd
+    z = ctypes.c_size_t(0)
+    assert f(None, FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 1
+    assert f(ctypes.byref(_conv(C=0)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(_conv(s=0)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(_conv(H=2, W=2, k=5, p=0)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(_conv(dtype=9)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 3
+    assert f(ctypes.byref(_conv()), FAKE, None, FAKE, FAKE, None, None, z, None) == 1
+    d = _conv()
+    need = pf.lib.pf_lowrank_conv_fwd_workspace_bytes(ctypes.byref(d))
+    if need:
+        assert f(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 4
+    assert f(ctypes.byref(_conv(N=0)), None, FAKE, FAKE, None, None, None, z, None) == 0
+    b = pf.lib.pf_lowrank_conv_bwd
+    assert b(ctypes.byref(_conv()), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, 0, None, z, None) == 1
+    assert b(ctypes.byref(_conv()), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 0, None, z, None) == 4
+
+
+def _lstm(B=2, d=3, h=4, r=2, groups=1, dtype=0, bias=1):
+    return pf.pf_lstm_desc(B, d, h, r, groups, dtype, bias)
+
+
+def test_lstm_validation():
+    f = pf.lib.pf_lowrank_lstm_cell_fwd
+    z = ctypes.c_size_t(0)
+    args = [FAKE] * 13
+    assert f(None, *args, None, z, None) == 1
+    assert f(ctypes.byref(_lstm(groups=2)), *args, None, z, None) == 3
+    assert f(ctypes.byref(_lstm(dtype=1)), *args, None, z, None) == 3
+    assert f(ctypes.byref(_lstm(h=0)), *args, None, z, None) == 2
+    bad = list(args)
+    bad[3] = None  # Vx
+    assert f(ctypes.byref(_lstm()), *bad, None, z, None) == 1
+    assert f(ctypes.byref(_lstm()), *args, None, z, None) == 4
+    assert f(ctypes.byref(_lstm(B=0)), *args, None, z, None) == 0

@@ -1,0 +1,178 @@
+"""GPU parity of pf_lowrank_lstm_cell_fwd/bwd (through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from parity import assert_close, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+CELLS = [
+    # B, d, h, r
+    (1, 1, 1, 1),
+    (3, 5, 4, 2),
+    (20, 70, 50, 13),
+    (33, 96, 128, 32),
+    (20, 1500, 1500, 375),  # the language model's layer shape (Appendix D)
+]
+
+
+def _cell(B, d, h, r, groups, seed=0, bias=True):
+    import paper_2103_03936_amd as pf
+    a = workloads.lstm_cell_inputs(B, d, h, r, groups=groups, seed=seed, bias=bias)
+    ho, co, gates_o, Txo, Tho = oracle.lowrank_lstm_cell_fwd(a["x"], a["h_prev"], a["c_prev"], a["Vx"], a["Ux"],
+                                                             a["Vh"], a["Uh"], a["bias"], groups)
+    dxo, dhpo, dcpo, go = oracle.lowrank_lstm_cell_bwd(a["x"], a["h_prev"], a["c_prev"], co, gates_o, Txo, Tho,
+                                                       a["Vx"], a["Ux"], a["Vh"], a["Uh"], a["dh"], a["dc"], groups)
+    g = {k: to_gpu(v) for k, v in a.items()}
+    h_out, c_out, gates, Tx, Th = pf.pf_lowrank_lstm_cell_fwd(g["x"], g["h_prev"], g["c_prev"], g["Vx"], g["Ux"],
+                                                              g["Vh"], g["Uh"], g["bias"], groups)
+    dx, dhp, dcp, gr = pf.pf_lowrank_lstm_cell_bwd(g["x"], g["h_prev"], g["c_prev"], c_out, gates, Tx, Th, g["Vx"],
+                                                   g["Ux"], g["Vh"], g["Uh"], g["dh"], g["dc"], groups)
+    torch.cuda.synchronize()
+    tag = f"lstm[{B},{d},{h},{r},g{groups}]"
+    assert_close(h_out, ho, "f32", tag + " h")
+    assert_close(c_out, co, "f32", tag + " c")
+    assert_close(gates, gates_o, "f32", tag + " gates")
+    assert_close(Tx, Txo, "f32", tag + " Tx")
+    assert_close(Th, Tho, "f32", tag + " Th")
+    assert_close(dx, dxo, "f32", tag + " dx")
+    assert_close(dhp, dhpo, "f32", tag + " dh_prev")
+    assert_close(dcp, dcpo, "f32", tag + " dc_prev")
+    for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+        assert_close(gr[k], go[k], "f32", tag + " " + k)
+    return a, g, (h_out, c_out, gates, Tx, Th), gr
+
+
+@pytest.mark.parametrize("groups", [1, 4])
+@pytest.mark.parametrize("shape", CELLS)
+def test_cell_parity(shape, groups):
+    _cell(*shape, groups=groups)
+
+
+def test_cell_no_bias_no_dc_and_accumulate():
+    import paper_2103_03936_amd as pf
+    B, d, h, r, groups = 7, 19, 23, 5, 4
+    a = workloads.lstm_cell_inputs(B, d, h, r, groups=groups, seed=11, bias=False)
+    ho, co, gates_o, Txo, Tho = oracle.lowrank_lstm_cell_fwd(a["x"], a["h_prev"], a["c_prev"], a["Vx"], a["Ux"],
+                                                             a["Vh"], a["Uh"], None, groups)
+    _, _, _, go = oracle.lowrank_lstm_cell_bwd(a["x"], a["h_prev"], a["c_prev"], co, gates_o, Txo, Tho, a["Vx"],
+                                               a["Ux"], a["Vh"], a["Uh"], a["dh"], None, groups)
+    g = {k: to_gpu(v) for k, v in a.items()}
+    h_out, c_out, gates, Tx, Th = pf.pf_lowrank_lstm_cell_fwd(g["x"], g["h_prev"], g["c_prev"], g["Vx"], g["Ux"],
+                                                              g["Vh"], g["Uh"], None, groups)
+    assert_close(h_out, ho, "f32", "h without bias")
+    _, _, _, gr = pf.pf_lowrank_lstm_cell_bwd(g["x"], g["h_prev"], g["c_prev"], c_out, gates, Tx, Th, g["Vx"],
+                                              g["Ux"], g["Vh"], g["Uh"], g["dh"], None, groups)
+    _, _, _, gr = pf.pf_lowrank_lstm_cell_bwd(g["x"], g["h_prev"], g["c_prev"], c_out, gates, Tx, Th, g["Vx"],
+                                              g["Ux"], g["Vh"], g["Uh"], g["dh"], None, groups, grads=gr)
+    for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+        assert_close(gr[k], 2 * go[k], "f32", "accumulated " + k)
+
+
+def lm_oracle(inp, groups):
+    """Forward and BPTT of the stacked LSTM on the CPU oracle; returns top-layer h and all gradients."""
+    T, B = inp["tokens"].shape
+    L = len(inp["layers"])
+    h_dim = inp["layers"][0]["Uh"].shape[0] // 4
+    xs = [inp["E"][inp["tokens"][t]].astype(np.float64) for t in range(T)]
+    hs = [np.zeros((B, h_dim)) for _ in range(L)]
+    cs = [np.zeros((B, h_dim)) for _ in range(L)]
+    saved = [[None] * T for _ in range(L)]
+    top = []
+    for t in range(T):
+        x = xs[t]
+        for l, p in enumerate(inp["layers"]):
+            ho, co, gates, Tx, Th = oracle.lowrank_lstm_cell_fwd(x, hs[l], cs[l], p["Vx"], p["Ux"], p["Vh"], p["Uh"],
+                                                                 p["bias"], groups)
+            saved[l][t] = (x, hs[l], cs[l], co, gates, Tx, Th)
+            hs[l], cs[l] = ho, co
+            x = ho
+        top.append(x)
+    grads = [None] * L
+    dE_rows = [None] * T
+    dh_next = [np.zeros((B, h_dim)) for _ in range(L)]
+    dc_next = [np.zeros((B, h_dim)) for _ in range(L)]
+    for t in reversed(range(T)):
+        d_from_above = inp["dH_top"][t].astype(np.float64)
+        for l in reversed(range(L)):
+            p = inp["layers"][l]
+            x, hp, cp, co, gates, Tx, Th = saved[l][t]
+            dx, dhp, dcp, grads[l] = oracle.lowrank_lstm_cell_bwd(x, hp, cp, co, gates, Tx, Th, p["Vx"], p["Ux"],
+                                                                  p["Vh"], p["Uh"], d_from_above + dh_next[l],
+                                                                  dc_next[l], groups, grads=grads[l])
+            dh_next[l], dc_next[l] = dhp, dcp
+            d_from_above = dx
+        dE_rows[t] = d_from_above
+    return np.stack(top), grads, np.stack(dE_rows)
+
+
+def lm_gpu(inp, groups):
+    """The same sequence through the C ABI, one cell call per (step, layer)."""
+    import paper_2103_03936_amd as pf
+    T, B = inp["tokens"].shape
+    L = len(inp["layers"])
+    h_dim = inp["layers"][0]["Uh"].shape[0] // 4
+    E = to_gpu(inp["E"])
+    tok = torch.from_numpy(inp["tokens"]).cuda()
+    P = [{k: to_gpu(v) for k, v in p.items()} for p in inp["layers"]]
+    dH = to_gpu(inp["dH_top"])
+    zeros = torch.zeros((B, h_dim), device="cuda")
+    hs, cs = [zeros] * L, [zeros] * L
+    saved = [[None] * T for _ in range(L)]
+    top = []
+    for t in range(T):
+        x = E[tok[t]].contiguous()  # embedding lookup: a gather, not part of the factorized path
+        for l, p in enumerate(P):
+            ho, co, gates, Tx, Th = pf.pf_lowrank_lstm_cell_fwd(x, hs[l], cs[l], p["Vx"], p["Ux"], p["Vh"], p["Uh"],
+                                                                p["bias"], groups)
+            saved[l][t] = (x, hs[l], cs[l], co, gates, Tx, Th)
+            hs[l], cs[l] = ho, co
+            x = ho
+        top.append(x)
+    grads = [None] * L
+    dE_rows = [None] * T
+    dh_next, dc_next = [zeros] * L, [zeros] * L
+    for t in reversed(range(T)):
+        d_from_above = dH[t]
+        for l in reversed(range(L)):
+            p = P[l]
+            x, hp, cp, co, gates, Tx, Th = saved[l][t]
+            dh_total = (d_from_above + dh_next[l]).contiguous()  # gradient fan-in, outside the cell
+            dx, dhp, dcp, grads[l] = pf.pf_lowrank_lstm_cell_bwd(x, hp, cp, co, gates, Tx, Th, p["Vx"], p["Ux"],
+                                                                 p["Vh"], p["Uh"], dh_total, dc_next[l], groups,
+                                                                 grads=grads[l])
+            dh_next[l], dc_next[l] = dhp, dcp
+            d_from_above = dx
+        dE_rows[t] = d_from_above
+    torch.cuda.synchronize()
+    return torch.stack(top), grads, torch.stack(dE_rows)
+
+
+@pytest.mark.parametrize("groups", [1, 4])
+def test_stacked_sequence_small(groups):
+    inp = workloads.lstm_lm_inputs(vocab=50, d=40, h=40, r=10, layers=2, T=6, B=5, groups=groups, seed=21, scale=0.3)
+    top_o, grads_o, dE_o = lm_oracle(inp, groups)
+    top, grads, dE = lm_gpu(inp, groups)
+    assert_close(top, top_o, "f32", "top h")
+    assert_close(dE, dE_o, "f32", "d embedding rows")
+    for l in range(2):
+        for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+            assert_close(grads[l][k], grads_o[l][k], "f32", f"layer {l} {k}")
+
+
+def test_language_model_full_size():
+    # the 2-layer LSTM language model of Appendix D: d = h = 1500, r = 375, sequence 35, batch 20;
+    # one shared rank-375 pair per path (groups = 1), forward and back-propagation through time
+    c = workloads.CONFIGS["lstm_lm_f32"]
+    inp = workloads.lstm_lm_inputs(c["vocab"], c["d"], c["h"], c["r"], c["layers"], c["T"], c["B"], groups=1,
+                                   seed=c["seed"])
+    top_o, grads_o, dE_o = lm_oracle(inp, 1)
+    top, grads, dE = lm_gpu(inp, 1)
+    assert_close(top, top_o, "f32", "top h")
+    assert_close(dE, dE_o, "f32", "d embedding rows")
+    for l in range(2):
+        for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+            assert_close(grads[l][k], grads_o[l][k], "f32", f"layer {l} {k}")
