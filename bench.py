@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the factorized-layer forward+backward path on one MI355X.
+
+A step is one forward (T saved) plus one backward (dX, both factor gradients) of the
+workload's factorized layer(s) on synthetic inputs that are already resident in HBM.  The
+default workload is the CIFAR ResNet-18 conv4_x factorized 3x3 convolution at batch 128
+(bf16 inputs, fp32 accumulation).  Steps rotate over enough distinct buffer sets to exceed
+the 256 MB last-level cache, so every step reads its activations from HBM.
+
+Prints ONE JSON line: throughput in algorithmic TFLOP/s (6 M r (C k^2 + Cout) per
+factorized layer), the roofline figures of the kernel that takes the most time (timed
+live with HIP events around every launch), the dense un-factorized layer on the same
+tiling code, and the CPU oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "factorized-layer fwd+bwd TFLOP/s and % of MFMA peak vs dense layer, 1 MI355X"
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+HBM_GBS = 8000.0
+
+
+# ----------------------------------------------------------------- workloads
+class ConvWorkload:
+    """One or more factorized convolutions (Section 2.2 shapes from Appendix D)."""
+
+    def __init__(self, name, cfg):
+        self.name, self.dtype = name, cfg["dtype"]
+        if cfg["kind"] == "conv":
+            self.layers = {"conv": (cfg["C"], cfg["Cout"], cfg["r"], cfg["k"], cfg["pad"])}
+        else:
+            self.layers = cfg["layers"]
+        self.N, self.H, self.W, self.seed = cfg["N"], cfg["H"], cfg["W"], cfg["seed"]
+
+    def describe(self):
+        return {"workload": self.name, "batch": self.N, "hw": [self.H, self.W],
+                "layers": {k: {"Cin": v[0], "Cout": v[1], "r": v[2], "k": v[3]} for k, v in self.layers.items()}}
+
+    def flops(self):
+        return sum(6.0 * self.N * self.H * self.W * r * (C * k * k + Co) for C, Co, r, k, p in self.layers.values())
+
+    def dense_flops(self):
+        return sum(6.0 * self.N * self.H * self.W * C * k * k * Co for C, Co, r, k, p in self.layers.values())
+
+    def make_set(self, i, torch, workloads):
+        sets = {}
+        for lname, (C, Co, r, k, p) in self.layers.items():
+            a = workloads.conv_inputs(self.N, C, self.H, self.W, Co, r, k, 1, p, dtype=self.dtype,
+                                      seed=self.seed * 1000 + i)
+            td = torch.bfloat16 if self.dtype == "bf16" else torch.float32
+            sets[lname] = {n: torch.from_numpy(v).to(td).cuda().contiguous() for n, v in a.items()}
+            sets[lname]["pad"] = p
+        return sets
+
+    def step(self, pf, s):
+        for g in s.values():
+            Y, T = pf.pf_lowrank_conv_fwd(g["X"], g["Uk"], g["Vp"], 1, g["pad"], save_T=True)
+            pf.pf_lowrank_conv_bwd(g["X"], g["Uk"], g["Vp"], g["dY"], T_saved=T, stride=1, pad=g["pad"])
+
+    def dense_prepare(self, s, torch):
+        for g in s.values():
+            if "Wd" not in g:
+                g["Wd"] = torch.einsum("oq,qcij->ocij", g["Vp"].float(), g["Uk"].float()).to(g["X"].dtype).contiguous()
+
+    def dense_step(self, pf, s):
+        for g in s.values():
+            pf.pf_dense_conv_fwd(g["X"], g["Wd"], 1, g["pad"])
+            pf.pf_dense_conv_bwd(g["X"], g["Wd"], g["dY"], 1, g["pad"])
+
+    def kernel_work(self):
+        """{kernel name: (algorithmic flops per launch, algorithmic bytes per launch)} for single-layer workloads."""
+        if len(self.layers) != 1:
+            return {}
+        (C, Co, r, k, p), = self.layers.values()
+        s = 2 if self.dtype == "bf16" else 4
+        npix, K = self.N * self.H * self.W, C * k * k
+        return {
+            "conv_T=Uk*X": (2.0 * npix * r * K, s * (npix * C + r * K + npix * r)),
+            "conv_Y=Vp*T": (2.0 * npix * r * Co, s * (npix * r + Co * r + npix * Co)),
+            "conv_dT=Vpt*dY": (2.0 * npix * r * Co, s * (npix * Co + Co * r) + 4 * npix * r),
+            "conv_dVp=dY*Tt": (2.0 * npix * r * Co, s * (npix * Co + npix * r) + 4 * Co * r),
+            "conv_dX=Ukt*dT": (2.0 * npix * r * K, s * (r * K + npix * C) + 4 * npix * r),
+            "conv_dUk=dT*Xcolt": (2.0 * npix * r * K, s * npix * C + 4 * (npix * r + r * K)),
+            "conv_fwd_fused": (2.0 * npix * r * (K + Co), s * (npix * C + r * K + Co * r + npix * Co + npix * r)),
+        }
+
+    def cpu_baseline(self, oracle, workloads, reps=3):
+        inputs = [(workloads.conv_inputs(self.N, C, self.H, self.W, Co, r, k, 1, p, dtype=self.dtype, seed=self.seed), p)
+                  for C, Co, r, k, p in self.layers.values()]
+        times = []
+        for rep in range(reps):
+            t0 = time.perf_counter()
+            for a, p in inputs:
+                oracle.lowrank_conv_fwd(a["X"], a["Uk"], a["Vp"], 1, p)
+                oracle.lowrank_conv_bwd(a["X"], a["Uk"], a["Vp"], a["dY"], 1, p)
+            times.append(time.perf_counter() - t0)
+        return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
+
+
+class LinearWorkload:
+    """One or more factorized linear layers (Section 2.1 / 2.4 shapes from Appendix D)."""
+
+    def __init__(self, name, cfg):
+        self.name, self.dtype, self.M, self.seed = name, cfg["dtype"], cfg["M"], cfg["seed"]
+        self.layers = cfg["layers"] if cfg["kind"] == "linear_set" else {"fc": (cfg["n_in"], cfg["n_out"], cfg["r"])}
+
+    def describe(self):
+        return {"workload": self.name, "tokens": self.M,
+                "layers": {k: {"in": v[0], "out": v[1], "r": v[2]} for k, v in self.layers.items()}}
+
+    def flops(self):
+        return sum(6.0 * self.M * r * (i + o) for i, o, r in self.layers.values())
+
+    def dense_flops(self):
+        return sum(6.0 * self.M * i * o for i, o, r in self.layers.values())
+
+    def make_set(self, idx, torch, workloads):
+        td = torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        out = {}
+        for lname, (i, o, r) in self.layers.items():
+            a = workloads.linear_inputs(self.M, i, o, r, dtype=self.dtype, seed=self.seed * 1000 + idx, bias=True)
+            out[lname] = {n: torch.from_numpy(v).to(td).cuda().contiguous() for n, v in a.items()}
+        return out
+
+    def step(self, pf, s):
+        for g in s.values():
+            Y, T = pf.pf_lowrank_linear_fwd(g["X"], g["V"], g["U"], g["bias"], save_T=True)
+            pf.pf_lowrank_linear_bwd(g["X"], g["V"], g["U"], g["dY"], T_saved=T, has_bias=True)
+
+    def dense_prepare(self, s, torch):
+        for g in s.values():
+            if "W" not in g:
+                g["W"] = (g["U"].float() @ g["V"].float().T).to(g["X"].dtype).contiguous()
+
+    def dense_step(self, pf, s):
+        for g in s.values():
+            pf.pf_dense_linear_fwd(g["X"], g["W"], g["bias"])
+            pf.pf_dense_linear_bwd(g["X"], g["W"], g["dY"], has_bias=True)
+
+    def kernel_work(self):
+        if len(self.layers) != 1:
+            return {}
+        (i, o, r), = self.layers.values()
+        s = 2 if self.dtype == "bf16" else 4
+        M = self.M
+        return {
+            "linear_T=X*V": (2.0 * M * r * i, s * (M * i + i * r + M * r)),
+            "linear_Y=T*Ut": (2.0 * M * r * o, s * (M * r + o * r + M * o)),
+            "linear_dT=dY*U": (2.0 * M * r * o, s * (M * o + o * r) + 4 * M * r),
+            "linear_dX=dT*Vt": (2.0 * M * r * i, s * (i * r + M * i) + 4 * M * r),
+            "linear_dU=dYt*T": (2.0 * M * r * o, s * (M * o + M * r) + 4 * o * r),
+            "linear_dV=Xt*dT": (2.0 * M * r * i, s * M * i + 4 * (M * r + i * r)),
+        }
+
+    def cpu_baseline(self, oracle, workloads, reps=3):
+        inputs = [workloads.linear_inputs(self.M, i, o, r, dtype=self.dtype, seed=self.seed, bias=True)
+                  for i, o, r in self.layers.values()]
+        times = []
+        for rep in range(reps):
+            t0 = time.perf_counter()
+            for a in inputs:
+                oracle.lowrank_linear_fwd(a["X"], a["V"], a["U"], a["bias"])
+                oracle.lowrank_linear_bwd(a["X"], a["V"], a["U"], a["dY"])
+            times.append(time.perf_counter() - t0)
+        return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
+
+
+def make_workload(name):
+    import workloads
+    cfg = workloads.CONFIGS[name]
+    if cfg["kind"] in ("conv", "conv_set"):
+        return ConvWorkload(name, cfg)
+    if cfg["kind"] in ("linear", "linear_set"):
+        return LinearWorkload(name, cfg)
+    raise SystemExit(f"workload {name} is not a bench workload (the LSTM stack is measured by its parity test)")
+
+
+def time_steps(torch, fn, sets, steps, warmup):
+    for i in range(warmup):
+        fn(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(sets[i % len(sets)])
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet18_conv4_bf16")
+    ap.add_argument("--buffer-sets", type=int, default=0, help="distinct input/output sets to rotate over (0 = enough to exceed 256 MB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    import workloads
+    import paper_2103_03936_amd as pf
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: the HIP library has no CPU path")
+    torch.cuda.set_device(0)
+    wl = make_workload(args.workload)
+
+    one = wl.make_set(0, torch, workloads)
+    set_bytes = sum(t.numel() * t.element_size() for g in one.values() for t in g.values() if hasattr(t, "numel"))
+    nsets = args.buffer_sets or max(2, int(300e6 // max(set_bytes * 2, 1)) + 1)  # x2: outputs are as large as inputs
+    nsets = min(nsets, 64)
+    sets = [one] + [wl.make_set(i, torch, workloads) for i in range(1, nsets)]
+
+    ms = time_steps(torch, lambda s: wl.step(pf, s), sets, args.steps, args.warmup)
+    ms_resident = time_steps(torch, lambda s: wl.step(pf, s), sets[:1], args.steps, args.warmup)
+    flops = wl.flops()
+    value = flops / (ms * 1e-3) / 1e12
+
+    # per-kernel durations, HIP events around every launch on the launch stream
+    pf.timing_reset()
+    pf.timing_enable(True)
+    for i in range(min(args.steps, 50)):
+        wl.step(pf, sets[i % len(sets)])
+    torch.cuda.synchronize()
+    pf.timing_enable(False)
+    per_kernel = pf.timing_collect()
+    kernels = {k: {"launches": n, "avg_us": 1e3 * t / n} for k, (n, t) in sorted(per_kernel.items(), key=lambda kv: -kv[1][1])}
+    work = wl.kernel_work()
+    roofline = None
+    if kernels:
+        dom = next(iter(kernels))
+        avg_s = kernels[dom]["avg_us"] * 1e-6
+        if dom in work:
+            kflops, kbytes = work[dom]
+            peak = PEAK_TFLOPS[wl.dtype]
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": kflops / avg_s / 1e12, "peak": peak,
+                        "unit": "TFLOP/s", "frac": kflops / avg_s / 1e12 / peak, "traffic": None,
+                        "avg_us": kernels[dom]["avg_us"], "algorithmic_GBps": kbytes / avg_s / 1e9,
+                        "frac_of_hbm_peak": kbytes / avg_s / 1e9 / HBM_GBS}
+        else:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": None, "peak": PEAK_TFLOPS[wl.dtype],
+                        "unit": "TFLOP/s", "frac": None, "traffic": None, "avg_us": kernels[dom]["avg_us"]}
+
+    dense = None
+    if not args.no_dense:
+        for s in sets:
+            wl.dense_prepare(s, torch)
+        dms = time_steps(torch, lambda s: wl.dense_step(pf, s), sets, max(10, args.steps // 4), max(2, args.warmup // 4))
+        dense = {"ms_per_step": dms, "value": wl.dense_flops() / (dms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
+                 "speedup_of_factorized": dms / ms}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        secs, cflops, sample = wl.cpu_baseline(oracle, workloads)
+        cpu = {"value": cflops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": sample, "seconds": secs}
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic", "config": dict(wl.describe(), buffer_sets=nsets),
+        "frac_of_mfma_peak": value / PEAK_TFLOPS[wl.dtype],
+        "cache_resident": {"ms_per_step": ms_resident, "value": flops / (ms_resident * 1e-3) / 1e12},
+        "roofline": roofline, "cpu_baseline": cpu, "dense_layer": dense, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

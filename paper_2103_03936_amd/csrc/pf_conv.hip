@@ -2,6 +2,7 @@
 // followed by a 1x1 convolution, forward and backward, plus the dense comparator.
 // Host-side validation, workspace planning and dispatch; the any-shape path runs every
 // stage as an implicit GEMM (operands gathered by functors) on the guarded tile GEMM.
+#include "pf_conv_chain.h"
 #include "pf_gemm.h"
 
 namespace pf {
@@ -135,11 +136,19 @@ static int check_conv_desc(const pf_conv_desc *d, ConvGeom *g)
 struct ConvPlan {
     int ks_dVp, ks_dUk;
     size_t n_T, n_part, fwd_bytes, bwd_bytes;
+    bool chain;              // the fused small-image kernel applies (bf16 only)
+    size_t n_w1, n_w2;       // packed weight elements, forward direction
+    size_t n_w1b, n_w2b;     // packed weight elements, backward direction
 };
 
-static ConvPlan plan_conv(const ConvGeom &g)
+static ConvPlan plan_conv(const ConvGeom &g, int dtype)
 {
     ConvPlan p;
+    p.chain = dtype == PF_BF16 && chain_supported(g.C, g.Cout, g.r, g.H, g.W, g.k, g.s, g.p);
+    p.n_w1 = chain_w1_elems(g.C, g.r, g.k);
+    p.n_w2 = chain_w2_elems(g.Cout, g.r, 1);
+    p.n_w1b = chain_w1_elems(g.Cout, g.r, 1);
+    p.n_w2b = chain_w2_elems(g.C, g.r, g.k);
     const i64 npix = (i64)g.N * g.Ho * g.Wo;
     p.ks_dVp = choose_ksplit(g.Cout, g.r, npix);
     p.ks_dUk = choose_ksplit(g.r, (i64)g.C * g.k * g.k, npix);
@@ -148,6 +157,13 @@ static ConvPlan plan_conv(const ConvGeom &g)
     p.n_part = a > b ? a : b;
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
     p.bwd_bytes = 2 * align_up(p.n_T * sizeof(float)) + align_up(p.n_part * sizeof(float));
+    if (p.chain) { // the fused path needs packed weights instead of float copies of T (take the larger)
+        const size_t f = align_up(p.n_w1 * 2) + align_up(p.n_w2 * 2);
+        const size_t b = align_up(p.n_w1b * 2) + align_up(p.n_w2b * 2) + 2 * align_up(p.n_T * 2) +
+                         align_up(p.n_part * sizeof(float));
+        if (f > p.fwd_bytes) p.fwd_bytes = f;
+        if (b > p.bwd_bytes) p.bwd_bytes = b;
+    }
     return p;
 }
 
@@ -174,23 +190,39 @@ static int conv_fwd_generic(const ConvGeom &g, const T *X, const T *Uk, const T 
                                                EpiNCHW<T, T>{Y, nullptr, g.Cout, g.Ho * g.Wo});
 }
 
-template <typename T>
-static int conv_bwd_generic(const ConvGeom &g, const T *X, const T *Uk, const T *Vp, const T *dY, const T *T_saved,
-                            T *dX, float *dUk, float *dVp, int accumulate, Workspace &ws, hipStream_t s)
+// Filter gradients from the saved / recomputed T and from dT (both [N][r][pixels], any element type).
+template <typename T, typename TT, typename TD>
+static int conv_wgrads(const ConvGeom &g, const ConvPlan &p, const T *X, const T *dY, const TT *Tt, const TD *dT,
+                       float *dUk, float *dVp, int accumulate, float *part, hipStream_t s)
 {
-    const ConvPlan p = plan_conv(g);
+    const int npix = g.N * g.Ho * g.Wo, HW = g.Ho * g.Wo, kk = g.k * g.k;
+    int st = PF_OK;
+    if (dVp) { // dVp[o,q] = sum_pixel dY[o,pixel] T[q,pixel]
+        st = launch_gemm_generic<T, true, true>("conv_dVp=dY*Tt", s, GemmShape{g.Cout, g.r, npix, 1, p.ks_dVp},
+                                                OpA_NCHW<T>{dY, g.Cout, HW}, OpB_NCHW_T<TT>{Tt, g.r, HW},
+                                                EpiPartial{part, g.r, (i64)g.Cout * g.r});
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dVp, (i64)g.Cout * g.r, p.ks_dVp, accumulate);
+        if (st != PF_OK) return st;
+    }
+    if (dUk) { // dUk[q,(c,i,j)] = sum_pixel dT[q,pixel] Xcol[(c,i,j),pixel]
+        st = launch_gemm_generic<T, true, true>("conv_dUk=dT*Xcolt", s, GemmShape{g.r, g.C * kk, npix, 1, p.ks_dUk},
+                                                OpA_NCHW<TD>{dT, g.r, HW}, OpB_Im2colT<T>{OpB_Im2col<T>{X, g}},
+                                                EpiPartial{part, (i64)g.C * kk, (i64)g.r * g.C * kk});
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dUk, (i64)g.r * g.C * kk, p.ks_dUk, accumulate);
+    }
+    return st;
+}
+
+template <typename T>
+static int conv_bwd_generic(const ConvGeom &g, const ConvPlan &p, const T *X, const T *Uk, const T *Vp, const T *dY,
+                            const T *T_saved, T *dX, float *dUk, float *dVp, int accumulate, Workspace &ws,
+                            hipStream_t s)
+{
     const int npix = g.N * g.Ho * g.Wo, HW = g.Ho * g.Wo, kk = g.k * g.k;
     float *Tws = ws.take<float>(p.n_T);
     float *dTws = ws.take<float>(p.n_T);
     float *part = ws.take<float>(p.n_part);
     int st = PF_OK;
-    if (g.N == 0) {
-        if (!accumulate) {
-            st = launch_zero_f32(s, dUk, (i64)g.r * g.C * kk);
-            if (st == PF_OK) st = launch_zero_f32(s, dVp, (i64)g.Cout * g.r);
-        }
-        return st;
-    }
     if (dVp && !T_saved) {
         st = conv_T_generic<T>(g, X, Uk, Tws, nullptr, s);
         if (st != PF_OK) return st;
@@ -201,32 +233,59 @@ static int conv_bwd_generic(const ConvGeom &g, const T *X, const T *Uk, const T 
                                                   EpiNCHW<float, float>{dTws, nullptr, g.r, HW});
         if (st != PF_OK) return st;
     }
-    if (dVp) { // dVp[o,q] = sum_pixel dY[o,pixel] T[q,pixel]
-        const GemmShape gs{g.Cout, g.r, npix, 1, p.ks_dVp};
-        const EpiPartial epi{part, g.r, (i64)g.Cout * g.r};
-        if (T_saved)
-            st = launch_gemm_generic<T, true, true>("conv_dVp=dY*Tt", s, gs, OpA_NCHW<T>{dY, g.Cout, HW},
-                                                    OpB_NCHW_T<T>{T_saved, g.r, HW}, epi);
-        else
-            st = launch_gemm_generic<T, true, true>("conv_dVp=dY*Tt", s, gs, OpA_NCHW<T>{dY, g.Cout, HW},
-                                                    OpB_NCHW_T<float>{Tws, g.r, HW}, epi);
-        if (st == PF_OK) st = launch_splitk_reduce(s, part, dVp, (i64)g.Cout * g.r, p.ks_dVp, accumulate);
-        if (st != PF_OK) return st;
-    }
     if (dX) { // dX[c, in-pixel] = sum_{q,i,j} Uk[q,c,i,j] dT[q, out-pixel(in-pixel,i,j)]
         st = launch_gemm_generic<T, true, false>("conv_dX=Ukt*dT", s, GemmShape{g.C, g.N * g.H * g.W, g.r * kk, 1, 1},
                                                  OpA_FilterT<T>{Uk, g.C, kk}, OpB_Col2im<float>{dTws, g, g.r},
                                                  EpiNCHW<T, T>{dX, nullptr, g.C, g.H * g.W});
         if (st != PF_OK) return st;
     }
-    if (dUk) { // dUk[q,(c,i,j)] = sum_pixel dT[q,pixel] Xcol[(c,i,j),pixel]
-        st = launch_gemm_generic<T, true, true>("conv_dUk=dT*Xcolt", s, GemmShape{g.r, g.C * kk, npix, 1, p.ks_dUk},
-                                                OpA_NCHW<float>{dTws, g.r, HW},
-                                                OpB_Im2colT<T>{OpB_Im2col<T>{X, g}},
-                                                EpiPartial{part, (i64)g.C * kk, (i64)g.r * g.C * kk});
-        if (st == PF_OK) st = launch_splitk_reduce(s, part, dUk, (i64)g.r * g.C * kk, p.ks_dUk, accumulate);
+    if (T_saved) return conv_wgrads<T, T, float>(g, p, X, dY, T_saved, dTws, dUk, dVp, accumulate, part, s);
+    return conv_wgrads<T, float, float>(g, p, X, dY, Tws, dTws, dUk, dVp, accumulate, part, s);
+}
+
+// ----------------------------------------------------- fused small-image path (bf16)
+static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X, const bf16_t *Uk, const bf16_t *Vp,
+                          bf16_t *Y, bf16_t *T_save, Workspace &ws, hipStream_t s)
+{
+    const int T = g.k * g.k;
+    uint16_t *w1 = ws.take<uint16_t>(p.n_w1);
+    uint16_t *w2 = ws.take<uint16_t>(p.n_w2);
+    int st = launch_pack_chain_w1(s, (const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1);
+    if (st == PF_OK) st = launch_pack_chain_w2(s, (const uint16_t *)Vp, (uint4 *)w2, g.Cout, g.r, 1, 0, g.r, 1, 0);
+    if (st != PF_OK) return st;
+    ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, (const uint4 *)w2, (uint16_t *)Y, (uint16_t *)T_save,
+                g.C,                 g.Cout,            g.H,               g.W};
+    return launch_conv_chain(s, "conv_fwd_fused", a, g.N, g.k, 1, g.r);
+}
+
+static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X, const bf16_t *Uk, const bf16_t *Vp,
+                          const bf16_t *dY, const bf16_t *T_saved, bf16_t *dX, float *dUk, float *dVp, int accumulate,
+                          Workspace &ws, hipStream_t s)
+{
+    const int T = g.k * g.k;
+    uint16_t *w1 = ws.take<uint16_t>(p.n_w1b);
+    uint16_t *w2 = ws.take<uint16_t>(p.n_w2b);
+    bf16_t *dT16 = ws.take<bf16_t>(p.n_T);
+    bf16_t *T16 = ws.take<bf16_t>(p.n_T);
+    float *part = ws.take<float>(p.n_part);
+    int st = PF_OK;
+    if (dVp && !T_saved) { // T was not saved: recompute it (thin convolution only)
+        st = launch_gemm_generic<bf16_t, true, false>(
+            "conv_T=Uk*X", s, GemmShape{g.r, g.N * g.Ho * g.Wo, g.C * T, 1, 1}, OpA_RowMajor<bf16_t>{Uk, (i64)g.C * T, 0},
+            OpB_Im2col<bf16_t>{X, g}, EpiNCHW<bf16_t, bf16_t>{T16, nullptr, g.r, g.Ho * g.Wo});
+        if (st != PF_OK) return st;
     }
-    return st;
+    // stage 1: dT = Vp^T dY (1x1); stage 2: dX = flipped-Uk * dT (k x k)
+    st = launch_pack_chain_w1(s, (const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0);
+    if (st == PF_OK)
+        st = launch_pack_chain_w2(s, (const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1);
+    if (st != PF_OK) return st;
+    ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, (uint16_t *)dX, (uint16_t *)dT16,
+                g.Cout,               g.C,               g.H,               g.W};
+    st = launch_conv_chain(s, "conv_bwd_data_fused", a, g.N, 1, g.k, g.r);
+    if (st != PF_OK) return st;
+    return conv_wgrads<bf16_t, bf16_t, bf16_t>(g, p, X, dY, T_saved ? T_saved : T16, dT16, dUk, dVp, accumulate, part,
+                                               s);
 }
 
 // ------------------------------------------------------------------ dense
@@ -289,14 +348,14 @@ size_t pf_lowrank_conv_fwd_workspace_bytes(const pf_conv_desc *d)
 {
     ConvGeom g;
     if (check_conv_desc(d, &g) != PF_OK) return 0;
-    return plan_conv(g).fwd_bytes;
+    return plan_conv(g, d->dtype).fwd_bytes;
 }
 
 size_t pf_lowrank_conv_bwd_workspace_bytes(const pf_conv_desc *d)
 {
     ConvGeom g;
     if (check_conv_desc(d, &g) != PF_OK) return 0;
-    return plan_conv(g).bwd_bytes;
+    return plan_conv(g, d->dtype).bwd_bytes;
 }
 
 int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, void *Y, void *T_save,
@@ -307,14 +366,17 @@ int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, co
     if (st != PF_OK) return st;
     if (!Uk || !Vp) return PF_ERR_NULL;
     if (g.N > 0 && (!X || !Y)) return PF_ERR_NULL;
-    const size_t need = plan_conv(g).fwd_bytes;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    const ConvPlan p = plan_conv(g, d->dtype);
+    if (p.fwd_bytes > 0 && (!workspace || workspace_bytes < p.fwd_bytes)) return PF_ERR_WORKSPACE;
     if (g.N == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     if (d->dtype == PF_F32)
         return conv_fwd_generic<float>(g, (const float *)X, (const float *)Uk, (const float *)Vp, (float *)Y,
                                        (float *)T_save, ws, s);
+    if (p.chain)
+        return conv_fwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
+                              (bf16_t *)T_save, ws, s);
     return conv_fwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
                                     (bf16_t *)T_save, ws, s);
 }
@@ -328,17 +390,27 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, co
     if (st != PF_OK) return st;
     if (!Uk || !Vp) return PF_ERR_NULL;
     if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
-    const size_t need = plan_conv(g).bwd_bytes;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    const ConvPlan p = plan_conv(g, d->dtype);
+    if (p.bwd_bytes > 0 && (!workspace || workspace_bytes < p.bwd_bytes)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
+    if (g.N == 0) {
+        if (!accumulate) {
+            st = launch_zero_f32(s, (float *)dUk, (i64)g.r * g.C * g.k * g.k);
+            if (st == PF_OK) st = launch_zero_f32(s, (float *)dVp, (i64)g.Cout * g.r);
+        }
+        return st;
+    }
     if (d->dtype == PF_F32)
-        return conv_bwd_generic<float>(g, (const float *)X, (const float *)Uk, (const float *)Vp, (const float *)dY,
+        return conv_bwd_generic<float>(g, p, (const float *)X, (const float *)Uk, (const float *)Vp, (const float *)dY,
                                        (const float *)T_saved, (float *)dX, (float *)dUk, (float *)dVp, accumulate, ws,
                                        s);
-    return conv_bwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
-                                    (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk, (float *)dVp, accumulate, ws,
-                                    s);
+    if (p.chain && dX)
+        return conv_bwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
+                              (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk, (float *)dVp, accumulate, ws, s);
+    return conv_bwd_generic<bf16_t>(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp,
+                                    (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk,
+                                    (float *)dVp, accumulate, ws, s);
 }
 
 size_t pf_dense_conv_workspace_bytes(const pf_conv_desc *d)

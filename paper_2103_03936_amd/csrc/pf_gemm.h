@@ -107,7 +107,18 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(AF af, BF bf, EF ef, 
             Bs[nn * LDK + kk] = LdsTraits<CT>::cvt(v);
         }
         __syncthreads();
-        mma_32x32_k32(acc, &As[wm * 32 * LDK], &Bs[wn * 32 * LDK], lane);
+        if (sizeof(elem) == 4) {
+            // float path: sum each 32-deep k-chunk on its own and add it to the running total, so the
+            // rounding error grows with the number of chunks rather than with K
+            f32x16_t chunk;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) chunk[v] = 0.f;
+            mma_32x32_k32(chunk, &As[wm * 32 * LDK], &Bs[wn * 32 * LDK], lane);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] += chunk[v];
+        } else {
+            mma_32x32_k32(acc, &As[wm * 32 * LDK], &Bs[wn * 32 * LDK], lane);
+        }
         __syncthreads();
     }
 
