@@ -3,6 +3,7 @@
 // Host-side validation, workspace planning and dispatch; the any-shape path runs every
 // stage as an implicit GEMM (operands gathered by functors) on the guarded tile GEMM.
 #include "pf_conv_chain.h"
+#include "pf_conv_wgrad.h"
 #include "pf_gemm.h"
 
 namespace pf {
@@ -137,6 +138,8 @@ struct ConvPlan {
     int ks_dVp, ks_dUk;
     size_t n_T, n_part, fwd_bytes, bwd_bytes;
     bool chain;              // the fused small-image kernel applies (bf16 only)
+    bool wgrad;              // the small-image filter-gradient kernel applies (bf16 only)
+    int wg_groups, wg_ipg;   // image groups and images per group of that kernel
     size_t n_w1, n_w2;       // packed weight elements, forward direction
     size_t n_w1b, n_w2b;     // packed weight elements, backward direction
 };
@@ -149,12 +152,29 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
     p.n_w2 = chain_w2_elems(g.Cout, g.r, 1);
     p.n_w1b = chain_w1_elems(g.Cout, g.r, 1);
     p.n_w2b = chain_w2_elems(g.C, g.r, g.k);
+    p.wgrad = p.chain && wgrad_supported(g.r, g.C, g.H, g.W, g.k, g.s, g.p) &&
+              wgrad_supported(g.r, g.Cout, g.H, g.W, 1, 1, 0);
+    p.wg_groups = p.wg_ipg = 1;
+    if (p.wgrad) {
+        const int chunks = g.C / wgrad_nchunk(g.r, g.k);
+        int want = 256 / (chunks > 0 ? chunks : 1);
+        if (want < 1) want = 1;
+        if (want > g.N) want = g.N > 0 ? g.N : 1;
+        p.wg_ipg = (g.N + want - 1) / want;
+        if (p.wg_ipg < 1) p.wg_ipg = 1;
+        p.wg_groups = (g.N + p.wg_ipg - 1) / p.wg_ipg;
+        if (p.wg_groups < 1) p.wg_groups = 1;
+    }
     const i64 npix = (i64)g.N * g.Ho * g.Wo;
     p.ks_dVp = choose_ksplit(g.Cout, g.r, npix);
     p.ks_dUk = choose_ksplit(g.r, (i64)g.C * g.k * g.k, npix);
     p.n_T = (size_t)(npix * g.r);
     size_t a = (size_t)p.ks_dVp * g.Cout * g.r, b = (size_t)p.ks_dUk * g.r * g.C * g.k * g.k;
     p.n_part = a > b ? a : b;
+    if (p.wgrad) { // both partial sets live side by side
+        const size_t both = (size_t)p.wg_groups * ((size_t)g.Cout * g.r + (size_t)g.r * g.C * g.k * g.k);
+        if (both > p.n_part) p.n_part = both;
+    }
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
     p.bwd_bytes = 2 * align_up(p.n_T * sizeof(float)) + align_up(p.n_part * sizeof(float));
     if (p.chain) { // the fused path needs packed weights instead of float copies of T (take the larger)
@@ -284,8 +304,22 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
                 g.Cout,               g.C,               g.H,               g.W};
     st = launch_conv_chain(s, "conv_bwd_data_fused", a, g.N, 1, g.k, g.r);
     if (st != PF_OK) return st;
-    return conv_wgrads<bf16_t, bf16_t, bf16_t>(g, p, X, dY, T_saved ? T_saved : T16, dT16, dUk, dVp, accumulate, part,
-                                               s);
+    const bf16_t *Tt = T_saved ? T_saved : T16;
+    if (!p.wgrad) return conv_wgrads<bf16_t, bf16_t, bf16_t>(g, p, X, dY, Tt, dT16, dUk, dVp, accumulate, part, s);
+    float *part_dUk = part, *part_dVp = part + (size_t)p.wg_groups * g.r * g.C * T;
+    if (dUk) {
+        WgradArgs wa{(const uint16_t *)dT16, (const uint16_t *)X, part_dUk, g.r, g.C, g.H, g.W, g.N, p.wg_ipg};
+        st = launch_conv_wgrad(s, "conv_dUk_small", wa, g.k, p.wg_groups);
+        if (st != PF_OK) return st;
+    }
+    if (dVp) {
+        WgradArgs wa{(const uint16_t *)Tt, (const uint16_t *)dY, part_dVp, g.r, g.Cout, g.H, g.W, g.N, p.wg_ipg};
+        st = launch_conv_wgrad(s, "conv_dVp_small", wa, 1, p.wg_groups);
+        if (st != PF_OK) return st;
+    }
+    WgradReduceArgs r0{part_dUk, dUk, p.wg_groups, T, g.r, g.C, (i64)g.C * T, T, 1, accumulate};
+    WgradReduceArgs r1{part_dVp, dVp, p.wg_groups, 1, g.r, g.Cout, 1, g.r, 0, accumulate};
+    return launch_wgrad_reduce(s, r0, r1);
 }
 
 // ------------------------------------------------------------------ dense

@@ -1,0 +1,28 @@
+// Filter-gradient kernel for small images (see pf_conv_wgrad.hip).
+#pragma once
+
+#include "pf_common.h"
+
+namespace pf {
+
+struct WgradArgs {
+    const uint16_t *A; // [N][M][H*W] bf16
+    const uint16_t *B; // [N][Nc][H*W] bf16
+    float *partial;    // [groups][taps][M][Nc]
+    int M, Nc, H, W, N_img, imgs_per_group;
+};
+
+struct WgradReduceArgs {
+    const float *partial; // [groups][taps][M][Nc]
+    float *out;           // out[m * s_m + n * s_n + tap * s_tap]; NULL = nothing to do
+    int groups, taps, M, Nc;
+    i64 s_m, s_n, s_tap;
+    int accumulate;
+};
+
+bool wgrad_supported(int M, int Nc, int H, int W, int k, int stride, int pad);
+int wgrad_nchunk(int M, int k); // B channels per workgroup
+int launch_conv_wgrad(hipStream_t s, const char *name, const WgradArgs &a, int k, int groups);
+int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1);
+
+} // namespace pf

@@ -1,0 +1,240 @@
+// Filter-gradient kernel for small images (bf16 in, fp32 accumulate), stride 1, "same" geometry:
+//     Out[m][n][tap] = sum_{img, y, x}  A[img][m][y][x] * Bpad[img][n][y + ty - 1][x + tx - 1]
+// with tap = 3 ty + tx for a 3x3 stage, or a single tap (no shift) for a 1x1 stage.
+//     dUk (Section 2.2 backward, thin k x k stage):  A = dT  (m = rank index), B = X  (n = input channel)
+//     dVp (1x1 stage), computed transposed:          A = T   (m = rank index), B = dY (n = output channel)
+//
+// The contraction runs over pixels.  An image row of up to 8 pixels is one 8-element MFMA
+// k-fragment (x >= W reads as zero), two rows make one 32x32x16 k-step.  Each workgroup owns a
+// slab of B channels (all taps) and a group of images; it writes one partial sum per group,
+// laid out [tap][m][n] so that stores are coalesced; pf_wgrad_reduce sums the groups and puts
+// the result where the caller's layout wants it.
+//
+// For a 3x3 stage the B rows are staged in LDS three times, shifted by tx - 1 with the zero
+// border baked in, so every fragment read is an aligned 16-byte LDS load; A fragments and 1x1
+// B fragments come straight from global memory.
+#include "pf_conv_wgrad.h"
+
+namespace pf {
+
+constexpr int WG_ROWS = 11; // LDS rows per channel: 1 zero row above, up to 8 rows, zero rows below (pitch 176 B)
+
+typedef uint4 __attribute__((may_alias)) uint4_alias;
+
+__device__ __forceinline__ bf16x8_t wg_as_bf16x8(uint4 v)
+{
+    union {
+        uint4 u;
+        bf16x8_t b;
+    } c;
+    c.u = v;
+    return c.b;
+}
+
+// Row y of one channel plane (W <= 8 pixels) as 8 bf16, zero beyond W.  `plane` points at the channel's
+// first pixel.  W == 8 rows are 16-byte aligned; other widths are read element by element.
+__device__ __forceinline__ uint4 load_row(const uint16_t *plane, int y, int W)
+{
+    if (W == 8) return *(const uint4 *)(plane + 8 * y);
+    const uint16_t *p = plane + W * y;
+    uint32_t e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = i < W ? (uint32_t)p[i] : 0u;
+    return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+}
+
+// TAPS: 9 (3x3, pad 1) or 1.  MB: 32-row blocks of m (M = 32 MB).  NBLK: 32-channel blocks of n per workgroup.
+// Pairs (n-block, tap) are dealt to the four wavefronts round-robin; PW = pairs per wavefront (max).
+template <int TAPS, int MB, int NBLK>
+__global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
+{
+    constexpr int NPAIR = NBLK * TAPS;
+    constexpr int PW = (NPAIR + 3) / 4;
+    constexpr int NCH = 32 * NBLK;
+    constexpr int LDS_ELEMS = TAPS == 9 ? 2 * 3 * NCH * WG_ROWS * 8 : 8;
+    __shared__ __attribute__((aligned(16))) uint16_t Xsh[LDS_ELEMS]; // [buf][tx][channel][row][8]
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int H = a.H, W = a.W, HW = H * W, M = 32 * MB;
+    const int n0 = blockIdx.x * NCH; // first B channel of this workgroup
+    const int g = blockIdx.y;
+    const int img0 = g * a.imgs_per_group;
+    const int img1 = min(a.N_img, img0 + a.imgs_per_group);
+    const int ksteps = (H + 1) / 2;
+
+    if (TAPS == 9) { // zero both buffers once: border rows and unused rows stay zero
+        uint4_alias *z = (uint4_alias *)Xsh;
+        for (int i = tid; i < LDS_ELEMS / 8; i += 256) z[i] = make_uint4(0, 0, 0, 0);
+    }
+
+    f32x16_t acc[MB][PW];
+#pragma unroll
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int p = 0; p < PW; ++p)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[b][p][v] = 0.f;
+
+    // B rows this thread stages per image (3x3 only): NCH channels x H rows over 256 threads
+    constexpr int ROWS_PT = TAPS == 9 ? (NCH * 8 + 255) / 256 : 1;
+    uint4 brow[ROWS_PT];
+    uint4 afr[MB][4];
+
+    auto load_image = [&](int img) {
+        if (TAPS == 9) {
+#pragma unroll
+            for (int i = 0; i < ROWS_PT; ++i) {
+                const int item = tid + 256 * i, c = item >> 3, y = item & 7;
+                brow[i] = make_uint4(0, 0, 0, 0);
+                if (c < NCH && y < H) brow[i] = load_row(a.B + ((i64)img * a.Nc + n0 + c) * HW, y, W);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int y = 2 * j + half;
+                afr[b][j] = make_uint4(0, 0, 0, 0);
+                if (y < H) afr[b][j] = load_row(a.A + ((i64)img * M + 32 * b + col) * HW, y, W);
+            }
+    };
+
+    if (img0 < img1) load_image(img0);
+    __syncthreads();
+
+    int buf = 0;
+    for (int img = img0; img < img1; ++img, buf ^= 1) {
+        uint4 acur[MB][4];
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acur[b][j] = afr[b][j];
+        if (TAPS == 9) {
+            // write the three shifted copies of this thread's rows into buffer `buf`
+#pragma unroll
+            for (int i = 0; i < ROWS_PT; ++i) {
+                const int item = tid + 256 * i, c = item >> 3, y = item & 7;
+                if (c < NCH && y < H) {
+                    const uint4 r = brow[i];
+                    // tx = 0 reads x - 1: shift towards higher x, zero enters at x = 0
+                    const uint4 s0 = make_uint4(r.x << 16, (r.y << 16) | (r.x >> 16), (r.z << 16) | (r.y >> 16),
+                                                (r.w << 16) | (r.z >> 16));
+                    // tx = 2 reads x + 1: shift towards lower x, zero enters at x = 7
+                    const uint4 s2 = make_uint4((r.x >> 16) | (r.y << 16), (r.y >> 16) | (r.z << 16),
+                                                (r.z >> 16) | (r.w << 16), r.w >> 16);
+                    uint16_t *base = &Xsh[((buf * 3) * NCH + c) * WG_ROWS * 8 + (y + 1) * 8];
+                    *(uint4_alias *)(base) = s0;
+                    *(uint4_alias *)(base + NCH * WG_ROWS * 8) = r;
+                    *(uint4_alias *)(base + 2 * NCH * WG_ROWS * 8) = s2;
+                }
+            }
+        }
+        if (img + 1 < img1) load_image(img + 1); // prefetch the next image while this one is multiplied
+        if (TAPS == 9) __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j >= ksteps) break;
+#pragma unroll
+            for (int p = 0; p < PW; ++p) {
+                const int pair = w + 4 * p;
+                if (pair < NPAIR) {
+                    const int nb = pair / TAPS, tap = pair % TAPS;
+                    uint4 bfr;
+                    if (TAPS == 9) {
+                        const int ty = tap / 3, tx = tap % 3;
+                        bfr = *(const uint4_alias *)&Xsh[((buf * 3 + tx) * NCH + 32 * nb + col) * WG_ROWS * 8 +
+                                                         (2 * j + half + ty) * 8];
+                    } else {
+                        const int y = 2 * j + half;
+                        bfr = make_uint4(0, 0, 0, 0);
+                        if (y < H) bfr = load_row(a.B + ((i64)img * a.Nc + n0 + 32 * nb + col) * HW, y, W);
+                    }
+#pragma unroll
+                    for (int b = 0; b < MB; ++b)
+                        acc[b][p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg_as_bf16x8(acur[b][j]), wg_as_bf16x8(bfr),
+                                                                            acc[b][p], 0, 0, 0);
+                }
+            }
+        }
+        // the buffer written two images from now is this one: the barrier of the next iteration orders it
+    }
+
+    // partial[g][tap][m][n]
+    float *part = a.partial + (i64)g * TAPS * M * a.Nc;
+#pragma unroll
+    for (int p = 0; p < PW; ++p) {
+        const int pair = w + 4 * p;
+        if (pair < NPAIR) {
+            const int nb = pair / TAPS, tap = pair % TAPS;
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+                    part[((i64)tap * M + m) * a.Nc + n0 + 32 * nb + col] = acc[b][p][v];
+                }
+        }
+    }
+}
+
+// out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, WgradReduceArgs r1, int blocks0)
+{
+    const bool second = (int)blockIdx.x >= blocks0;
+    const WgradReduceArgs r = second ? r1 : r0;
+    const i64 i = (i64)(blockIdx.x - (second ? blocks0 : 0)) * 256 + threadIdx.x;
+    const i64 count = (i64)r.taps * r.M * r.Nc;
+    if (i >= count) return;
+    float s = 0.f;
+    for (int g = 0; g < r.groups; ++g) s += r.partial[(i64)g * count + i];
+    const int n = (int)(i % r.Nc);
+    const i64 t = i / r.Nc;
+    const int m = (int)(t % r.M), tap = (int)(t / r.M);
+    float *dst = r.out + m * r.s_m + n * r.s_n + tap * r.s_tap;
+    *dst = r.accumulate ? (*dst + s) : s;
+}
+
+bool wgrad_supported(int M, int Nc, int H, int W, int k, int stride, int pad)
+{
+    if (stride != 1) return false;
+    if (!((k == 3 && pad == 1) || (k == 1 && pad == 0))) return false;
+    if (H > 8 || W > 8) return false;
+    if (M != 64 && M != 128) return false;
+    if (k == 3) return Nc % (M == 64 ? 64 : 32) == 0;
+    return Nc % 256 == 0;
+}
+
+int wgrad_nchunk(int M, int k) { return k == 3 ? (M == 64 ? 64 : 32) : 256; }
+
+int launch_conv_wgrad(hipStream_t s, const char *name, const WgradArgs &a, int k, int groups)
+{
+    int st = PF_OK;
+    if (a.N_img <= 0 || groups <= 0) return st;
+    const int M = a.M;
+    const dim3 grid(a.Nc / wgrad_nchunk(M, k), groups), block(256);
+    if (k == 3 && M == 64) {
+        PF_LAUNCH(st, name, (conv_wgrad_kernel<9, 2, 2>), grid, block, s, a);
+    } else if (k == 3 && M == 128) {
+        PF_LAUNCH(st, name, (conv_wgrad_kernel<9, 4, 1>), grid, block, s, a);
+    } else if (k == 1 && M == 64) {
+        PF_LAUNCH(st, name, (conv_wgrad_kernel<1, 2, 8>), grid, block, s, a);
+    } else if (k == 1 && M == 128) {
+        PF_LAUNCH(st, name, (conv_wgrad_kernel<1, 4, 8>), grid, block, s, a);
+    } else {
+        st = PF_ERR_UNSUPPORTED;
+    }
+    return st;
+}
+
+int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1)
+{
+    int st = PF_OK;
+    const i64 c0 = r0.out ? (i64)r0.taps * r0.M * r0.Nc : 0, c1 = r1.out ? (i64)r1.taps * r1.M * r1.Nc : 0;
+    const int b0 = (int)((c0 + 255) / 256), b1 = (int)((c1 + 255) / 256);
+    if (b0 + b1 == 0) return st;
+    PF_LAUNCH(st, "wgrad_reduce", wgrad_reduce_kernel, dim3(b0 + b1), dim3(256), s, r0, r1, b0);
+    return st;
+}
+
+} // namespace pf
