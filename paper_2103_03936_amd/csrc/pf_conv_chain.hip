@@ -27,13 +27,16 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v)
 template <int KS1, int KS2, int R>
 __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 {
-    constexpr int RB = R / 32, T1 = KS1 * KS1, T2 = KS2 * KS2;
+    constexpr int RB = R / 32, R16 = R / 16, T1 = KS1 * KS1, T2 = KS2 * KS2;
     constexpr int TLD = R + 8; // row stride (elements) of the intermediate tile
-    constexpr int S2 = T2 * (R / 16);
+    constexpr int S2 = T2 * R16;
+    // Stage-1 weight fragments are fetched one group of GS1 k-steps ahead of the MFMAs that use them.
+    constexpr int GS1 = KS1 == 3 ? (R == 64 ? 9 : 3) : 4; // k-steps per group
+    constexpr int GPS = 4 * T1 / GS1;                     // groups per 64-channel staging round
+    constexpr int NXV = CH_SUB * CH_PIX / 8 / 64;         // 16-byte input vectors per lane per staging round
     __shared__ __attribute__((aligned(16))) uint16_t Xs[4][CH_PP * CH_XLD];
     __shared__ __attribute__((aligned(16))) float P[4][64 * CH_PLD];
     __shared__ __attribute__((aligned(16))) uint16_t Ts[CH_PP * TLD];
-    __shared__ uint16_t pp1[CH_PIX], pp2[CH_PIX];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -42,15 +45,68 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const int Wp1 = KS1 == 3 ? W + 2 : W, Wp2 = KS2 == 3 ? W + 2 : W;
     const int Z1 = KS1 == 3 ? (H + 2) * (W + 2) : HW; // index of the all-zero row
     const int Z2 = KS2 == 3 ? (H + 2) * (W + 2) : HW;
+    const int cw = C1 / 4;        // stage-1 channels of this wavefront
+    const int nsub = cw / CH_SUB; // staging rounds
+    const int ngroups = nsub * GPS;
+    uint16_t *xs = &Xs[w][0];
 
-    // ---- set-up: pixel -> padded-position tables, zero the tiles (borders stay zero) ----
-    if (tid < CH_PIX) {
-        const int y = tid / W, x = tid - y * W;
-        pp1[tid] = (uint16_t)(tid < HW ? (KS1 == 3 ? (y + 1) * Wp1 + x + 1 : tid) : Z1);
-        pp2[tid] = (uint16_t)(tid < HW ? (KS2 == 3 ? (y + 1) * Wp2 + x + 1 : tid) : Z2);
-    }
+    // ---- issue the first global loads before anything else: input vectors and weight group 0 ----
+    // One staging item = one pixel x 8 consecutive channels (one 16-byte LDS row segment); a lane owns
+    // items lane, lane + 64, ...; neighbouring lanes read neighbouring pixels, so the 2-byte loads coalesce.
+    uint4 xv[NXV];
+    const int nitem = 8 * HW;
+    auto load_x = [&](int sub) __attribute__((always_inline)) {
+        const uint16_t *src = a.in + ((i64)n * C1 + w * cw + sub * CH_SUB) * HW;
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+            const int it = lane + 64 * i;
+            uint32_t e[8];
+            if (it < nitem) {
+                const int o = it / HW, p = it - o * HW;
+                const uint16_t *q = src + (i64)(8 * o) * HW + p;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) e[k] = q[(i64)k * HW];
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) e[k] = 0;
+            }
+            xv[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+        }
+    };
+    auto store_x = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+            const int it = lane + 64 * i;
+            if (it < nitem) {
+                const int o = it / HW, p = it - o * HW;
+                const int y = p / W, x = p - y * W;
+                const int pos = KS1 == 3 ? (y + 1) * Wp1 + x + 1 : p;
+                *(uint4_alias *)&xs[pos * CH_XLD + 8 * o] = xv[i];
+            }
+        }
+    };
+    const uint4 *w1s = a.W1p + ((i64)(w * cw / 16) * T1 * RB) * 64 + lane; // this wavefront's fragment stream
+    // Workgroups that share an L2 (every 8th one) start at different groups, so that between them they pull
+    // the whole weight stream into that L2 early instead of all missing on the same lines at the same time.
+    const int rot1 = nsub > 1 ? (int)((n >> 3) % nsub) * GPS : (int)((n >> 3) % GPS);
+    auto grp = [&](int g) __attribute__((always_inline)) { // g-th group in this workgroup's order
+        const int r = g + rot1;
+        return r >= ngroups ? r - ngroups : r;
+    };
+    uint4 afA[GS1][RB], afB[GS1][RB];
+    auto load_w1 = [&](uint4(&af)[GS1][RB], int g) __attribute__((always_inline)) {
+        const uint4 *src = w1s + (i64)g * GS1 * RB * 64;
+#pragma unroll
+        for (int t = 0; t < GS1; ++t)
+#pragma unroll
+            for (int b = 0; b < RB; ++b) af[t][b] = src[(t * RB + b) * 64];
+    };
+    load_x(grp(0) / GPS);
+    load_w1(afA, grp(0));
+
+    // ---- zero the tiles (borders and the spare row stay zero for the whole kernel) ----
     {
-        uint4 z = make_uint4(0, 0, 0, 0);
+        const uint4 z = make_uint4(0, 0, 0, 0);
         uint4_alias *x4 = (uint4_alias *)&Xs[0][0];
         for (int i = tid; i < 4 * CH_PP * CH_XLD / 8; i += 256) x4[i] = z;
         uint4_alias *t4 = (uint4_alias *)&Ts[0];
@@ -58,15 +114,16 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     }
     __syncthreads();
 
-    // top-left padded position of this lane's two pixels (pixel blocks 0 and 1)
+    // top-left padded position of this lane's two pixels (pixel blocks 0 and 1), both stages
     int pos1[2], pos2[2];
     bool valid[2];
 #pragma unroll
     for (int pb = 0; pb < 2; ++pb) {
         const int p = 32 * pb + col;
+        const int y = p / W, x = p - y * W;
         valid[pb] = p < HW;
-        pos1[pb] = valid[pb] ? pp1[p] - (KS1 == 3 ? Wp1 + 1 : 0) : Z1;
-        pos2[pb] = valid[pb] ? pp2[p] - (KS2 == 3 ? Wp2 + 1 : 0) : Z2;
+        pos1[pb] = valid[pb] ? (KS1 == 3 ? y * Wp1 + x : p) : Z1;
+        pos2[pb] = valid[pb] ? (KS2 == 3 ? y * Wp2 + x : p) : Z2;
     }
 
     // ------------------------------- stage 1 -------------------------------
@@ -78,52 +135,82 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[b][pb][v] = 0.f;
 
-    uint16_t *xs = &Xs[w][0];
-    const int cw = C1 / 4;        // channels of this wavefront
-    const int nsub = cw / CH_SUB; // staging rounds
-    const int nvec = CH_SUB * HW / 8;
-    for (int sub = 0; sub < nsub; ++sub) {
-        const int cb = w * cw + sub * CH_SUB;
-        // stage channels [cb, cb + 64) of image n, transposed to [padded position][channel]
-        if (sub > 0) __syncthreads(); // the previous round's fragment reads are done
-        const uint4 *src = (const uint4 *)(a.in + ((i64)n * C1 + cb) * HW);
-        for (int vi = lane; vi < nvec; vi += 64) {
-            const uint4 d = src[vi];
-            int c = (8 * vi) / HW, p = 8 * vi - c * HW;
-            const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
+    auto compute_group = [&](const uint4(&af)[GS1][RB], int g) __attribute__((always_inline)) {
+        const int gi = g % GPS; // group within the staging round
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                xs[pp1[p] * CH_XLD + c] = (uint16_t)(dw[e >> 1] >> (16 * (e & 1)));
-                if (++p == HW) {
-                    p = 0;
-                    ++c;
-                }
+        for (int t = 0; t < GS1; ++t) {
+            int c16, toff;
+            if (KS1 == 3 && GS1 == 9) {
+                c16 = gi;
+                toff = (t / 3) * Wp1 + (t % 3);
+            } else if (KS1 == 3) {
+                c16 = gi / 3;
+                toff = (gi % 3) * Wp1 + t;
+            } else {
+                c16 = t;
+                toff = 0;
             }
-        }
-        __syncthreads();
-#pragma unroll 1
-        for (int c16 = 0; c16 < CH_SUB / 16; ++c16) {
-            const i64 s0 = (i64)((cb >> 4) + c16) * T1;
-            uint4 af[T1][RB];
+            bf16x8_t bfr[2];
 #pragma unroll
-            for (int t = 0; t < T1; ++t)
+            for (int pb = 0; pb < 2; ++pb)
+                bfr[pb] = as_bf16x8(lds_read16(&xs[(pos1[pb] + (valid[pb] ? toff : 0)) * CH_XLD + 16 * c16 + 8 * half]));
 #pragma unroll
-                for (int b = 0; b < RB; ++b) af[t][b] = a.W1p[((s0 + t) * RB + b) * 64 + lane];
-#pragma unroll
-            for (int t = 0; t < T1; ++t) {
-                const int toff = KS1 == 3 ? (t / 3) * Wp1 + (t % 3) : 0;
-                bf16x8_t bfr[2];
+            for (int b = 0; b < RB; ++b)
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb)
-                    bfr[pb] = as_bf16x8(lds_read16(&xs[(pos1[pb] + (valid[pb] ? toff : 0)) * CH_XLD + 16 * c16 + 8 * half]));
-#pragma unroll
-                for (int b = 0; b < RB; ++b)
-#pragma unroll
-                    for (int pb = 0; pb < 2; ++pb)
-                        acc[b][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[t][b]), bfr[pb], acc[b][pb], 0, 0, 0);
-            }
+                    acc[b][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[t][b]), bfr[pb], acc[b][pb], 0, 0, 0);
+        }
+    };
+    // after group g: if it closed a staging round, bring in the next 64 channels
+    // after the g-th group: if it closed a staging round, bring in the next 64 channels (rounds are
+    // entered at their first group because the rotation is a whole number of rounds when nsub > 1)
+    auto next_round = [&](int g) __attribute__((always_inline)) {
+        if ((g + 1) % GPS == 0 && g + 1 < ngroups) {
+            __syncthreads();
+            store_x();
+            if (g + 1 + GPS < ngroups) load_x(grp(g + 1 + GPS) / GPS);
+            __syncthreads();
+        }
+    };
+
+    store_x();
+    if (nsub > 1) load_x(grp(GPS) / GPS);
+    __syncthreads();
+    for (int g = 0; g < ngroups; g += 2) {
+        if (g + 1 < ngroups) load_w1(afB, grp(g + 1));
+        __builtin_amdgcn_sched_barrier(0);
+        compute_group(afA, grp(g));
+        __builtin_amdgcn_sched_barrier(0);
+        next_round(g);
+        if (g + 1 < ngroups) {
+            if (g + 2 < ngroups) load_w1(afA, grp(g + 2));
+            __builtin_amdgcn_sched_barrier(0);
+            compute_group(afB, grp(g + 1));
+            __builtin_amdgcn_sched_barrier(0);
+            next_round(g + 1);
         }
     }
+
+    // stage-2 weight fragments, one tap (R16 k-steps, two 32-channel output blocks) per group;
+    // the first group is requested now so that it arrives during the partial-sum exchange
+    const int nb2 = C2 / 32;
+    const int npair = (nb2 / 2 + 3 - w) / 4; // output-block pairs of this wavefront: 2 w, 2 w + 8, ...
+    const int ngroups2 = npair * T2;
+    uint4 bwA[2][R16], bwB[2][R16];
+    const int rot2 = (int)((n >> 3) % T2);
+    auto tap_of = [&](int q) __attribute__((always_inline)) { // taps of a pair are visited in a rotated order
+        const int t = q % T2 + rot2;
+        return t >= T2 ? t - T2 : t;
+    };
+    auto load_w2 = [&](uint4(&bw)[2][R16], int q) __attribute__((always_inline)) {
+        const int ob = 2 * w + 8 * (q / T2), tap = tap_of(q);
+        const uint4 *src = a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+            for (int k = 0; k < R16; ++k) bw[bb][k] = src[((i64)bb * S2 + k) * 64];
+    };
+    if (ngroups2 > 0) load_w2(bwA, 0);
 
     // ---------------- sum the four partial tiles, 64 rows of rho at a time ----------------
 #pragma unroll
@@ -139,6 +226,8 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                     pw[(32 * bb + 8 * (v >> 2) + 4 * half + (v & 3)) * CH_PLD + 32 * pb + col] = acc[2 * rh + bb][pb][v];
         __syncthreads();
         const int pix = tid & 63;
+        const int py = pix / W, px = pix - py * W;
+        const int ppos = KS2 == 3 ? (py + 1) * Wp2 + px + 1 : pix;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int r0 = 8 * ((tid >> 6) + 4 * it);
@@ -154,7 +243,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                 pk.y = o[2] | ((uint32_t)o[3] << 16);
                 pk.z = o[4] | ((uint32_t)o[5] << 16);
                 pk.w = o[6] | ((uint32_t)o[7] << 16);
-                *(uint4_alias *)&Ts[pp2[pix] * TLD + 64 * rh + r0] = pk;
+                *(uint4_alias *)&Ts[ppos * TLD + 64 * rh + r0] = pk;
                 if (a.mid_save) {
                     uint16_t *ms = a.mid_save + ((i64)n * R + 64 * rh + r0) * HW + pix;
 #pragma unroll
@@ -166,48 +255,67 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     __syncthreads();
 
     // ------------------------------- stage 2 -------------------------------
-    const int nb2 = C2 / 32;
-    for (int ob = 2 * w; ob < nb2; ob += 8) {
-        f32x16_t acc2[2][2];
+    f32x16_t acc2[2][2];
 #pragma unroll
-        for (int bb = 0; bb < 2; ++bb)
+    for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
+
+    auto compute_group2 = [&](const uint4(&bw)[2][R16], int q) __attribute__((always_inline)) {
+        const int tap = tap_of(q);
+        const int toff = KS2 == 3 ? (tap / 3) * Wp2 + (tap % 3) : 0;
+#pragma unroll
+        for (int k = 0; k < R16; ++k) {
+            bf16x8_t bfr[2];
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
-        const uint4 *w2a = a.W2p + ((i64)ob * S2) * 64 + lane;
-        const uint4 *w2b = w2a + (i64)S2 * 64;
-#pragma unroll
-        for (int t = 0; t < T2; ++t) {
-            const int toff = KS2 == 3 ? (t / 3) * Wp2 + (t % 3) : 0;
-#pragma unroll
-            for (int r16 = 0; r16 < R / 16; ++r16) {
-                const int s2 = t * (R / 16) + r16;
-                const uint4 a0 = w2a[s2 * 64], a1 = w2b[s2 * 64];
-                bf16x8_t bfr[2];
-#pragma unroll
-                for (int pb = 0; pb < 2; ++pb)
-                    bfr[pb] = as_bf16x8(lds_read16(&Ts[(pos2[pb] + (valid[pb] ? toff : 0)) * TLD + 16 * r16 + 8 * half]));
-#pragma unroll
-                for (int pb = 0; pb < 2; ++pb) {
-                    acc2[0][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a0), bfr[pb], acc2[0][pb], 0, 0, 0);
-                    acc2[1][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a1), bfr[pb], acc2[1][pb], 0, 0, 0);
-                }
-            }
-        }
-#pragma unroll
-        for (int bb = 0; bb < 2; ++bb)
+                bfr[pb] = as_bf16x8(lds_read16(&Ts[(pos2[pb] + (valid[pb] ? toff : 0)) * TLD + 16 * k + 8 * half]));
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb) {
-                const int pix = 32 * pb + col;
-                if (pix < HW) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int o = 32 * (ob + bb) + 8 * (v >> 2) + 4 * half + (v & 3);
-                        a.out[((i64)n * C2 + o) * HW + pix] = float_to_bf16_bits(acc2[bb][pb][v]);
-                    }
-                }
+                acc2[0][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(bw[0][k]), bfr[pb], acc2[0][pb], 0, 0, 0);
+                acc2[1][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(bw[1][k]), bfr[pb], acc2[1][pb], 0, 0, 0);
             }
+        }
+        if (q % T2 == T2 - 1) { // this output-block pair is complete: store it and start the next
+            // The 64 output channels x HW pixels of the pair are one contiguous block of `out`.  Round to
+            // bf16 into this wavefront's (now idle) input tile laid out exactly like that block, then
+            // copy it out with 16-byte stores.
+            const int ob = 2 * w + 8 * (q / T2);
+#pragma unroll
+            for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                for (int pb = 0; pb < 2; ++pb) {
+                    const int pix = 32 * pb + col;
+                    if (pix < HW) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            xs[(32 * bb + 8 * (v >> 2) + 4 * half + (v & 3)) * HW + pix] = float_to_bf16_bits(acc2[bb][pb][v]);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
+                }
+            uint4 *dst = (uint4 *)(a.out + ((i64)n * C2 + 32 * ob) * HW);
+            const int nv = 64 * HW / 8;
+#pragma unroll
+            for (int i = 0; i < CH_PIX * CH_PIX / 8 / 64; ++i) {
+                const int vi = lane + 64 * i;
+                if (vi < nv) dst[vi] = *(const uint4_alias *)&xs[8 * vi];
+            }
+        }
+    };
+    for (int q = 0; q < ngroups2; q += 2) {
+        if (q + 1 < ngroups2) load_w2(bwB, q + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_group2(bwA, q);
+        __builtin_amdgcn_sched_barrier(0);
+        if (q + 1 < ngroups2) {
+            if (q + 2 < ngroups2) load_w2(bwA, q + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_group2(bwB, q + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 }
 
