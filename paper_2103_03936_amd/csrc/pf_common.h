@@ -21,14 +21,22 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+typedef __bf16 bf16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw_t __attribute__((ext_vector_type(2)));
+
+// Two floats -> two bf16 (round to nearest even, NaN stays NaN) packed lo | hi << 16: one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    f32x2_hw_t v = {lo, hi};
+    union {
+        bf16x2_hw_t b;
+        uint32_t u;
+    } c;
+    c.b = __builtin_convertvector(v, bf16x2_hw_t);
+    return c.u;
 }
+
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) { return (uint16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return bf16_bits_to_float(x.v); }

@@ -24,16 +24,18 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v)
     return c.b;
 }
 
-template <int KS1, int KS2, int R>
+// HC, WC: image height / width known at compile time (0 = read them from the arguments).
+template <int KS1, int KS2, int R, int HC, int WC>
 __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 {
     constexpr int RB = R / 32, R16 = R / 16, T1 = KS1 * KS1, T2 = KS2 * KS2;
     constexpr int TLD = R + 8; // row stride (elements) of the intermediate tile
     constexpr int S2 = T2 * R16;
-    // Stage-1 weight fragments are fetched one group of GS1 k-steps ahead of the MFMAs that use them.
+    // Stage-1 weight fragments are fetched one group of GS1 k-steps ahead of the MFMAs that use them,
+    // two fragments per k-step, so the vector-memory pipe sees a steady stream instead of bursts.
     constexpr int GS1 = KS1 == 3 ? (R == 64 ? 9 : 3) : 4; // k-steps per group
     constexpr int GPS = 4 * T1 / GS1;                     // groups per 64-channel staging round
-    constexpr int NXV = CH_SUB * CH_PIX / 8 / 64;         // 16-byte input vectors per lane per staging round
+    constexpr int NXV = CH_SUB * CH_PIX / 8 / 64;         // staging items per lane per round (upper bound)
     __shared__ __attribute__((aligned(16))) uint16_t Xs[4][CH_PP * CH_XLD];
     __shared__ __attribute__((aligned(16))) float P[4][64 * CH_PLD];
     __shared__ __attribute__((aligned(16))) uint16_t Ts[CH_PP * TLD];
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const int n = blockIdx.x;
-    const int H = a.H, W = a.W, HW = H * W, C1 = a.C1, C2 = a.C2;
+    const int H = HC ? HC : a.H, W = WC ? WC : a.W, HW = H * W, C1 = a.C1, C2 = a.C2;
     const int Wp1 = KS1 == 3 ? W + 2 : W, Wp2 = KS2 == 3 ? W + 2 : W;
     const int Z1 = KS1 == 3 ? (H + 2) * (W + 2) : HW; // index of the all-zero row
     const int Z2 = KS2 == 3 ? (H + 2) * (W + 2) : HW;
@@ -50,7 +52,6 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const int ngroups = nsub * GPS;
     uint16_t *xs = &Xs[w][0];
 
-    // ---- issue the first global loads before anything else: input vectors and weight group 0 ----
     // One staging item = one pixel x 8 consecutive channels (one 16-byte LDS row segment); a lane owns
     // items lane, lane + 64, ...; neighbouring lanes read neighbouring pixels, so the 2-byte loads coalesce.
     uint4 xv[NXV];
@@ -63,9 +64,9 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             uint32_t e[8];
             if (it < nitem) {
                 const int o = it / HW, p = it - o * HW;
-                const uint16_t *q = src + (i64)(8 * o) * HW + p;
+                const uint16_t *q = src + (8 * o) * HW + p;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) e[k] = q[(i64)k * HW];
+                for (int k = 0; k < 8; ++k) e[k] = q[k * HW];
             } else {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) e[k] = 0;
@@ -89,20 +90,19 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     // Workgroups that share an L2 (every 8th one) start at different groups, so that between them they pull
     // the whole weight stream into that L2 early instead of all missing on the same lines at the same time.
     const int rot1 = nsub > 1 ? (int)((n >> 3) % nsub) * GPS : (int)((n >> 3) % GPS);
-    auto grp = [&](int g) __attribute__((always_inline)) { // g-th group in this workgroup's order
-        const int r = g + rot1;
+    auto grp = [&](int g) __attribute__((always_inline)) { // g-th group in this workgroup's order (clamped)
+        const int r = (g < ngroups ? g : ngroups - 1) + rot1;
         return r >= ngroups ? r - ngroups : r;
     };
     uint4 afA[GS1][RB], afB[GS1][RB];
-    auto load_w1 = [&](uint4(&af)[GS1][RB], int g) __attribute__((always_inline)) {
-        const uint4 *src = w1s + (i64)g * GS1 * RB * 64;
+    load_x(grp(0) / GPS);
+    {
+        const uint4 *src = w1s + (i64)grp(0) * GS1 * RB * 64;
 #pragma unroll
         for (int t = 0; t < GS1; ++t)
 #pragma unroll
-            for (int b = 0; b < RB; ++b) af[t][b] = src[(t * RB + b) * 64];
-    };
-    load_x(grp(0) / GPS);
-    load_w1(afA, grp(0));
+            for (int b = 0; b < RB; ++b) afA[t][b] = src[(t * RB + b) * 64];
+    }
 
     // ---- zero the tiles (borders and the spare row stay zero for the whole kernel) ----
     {
@@ -114,16 +114,17 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     }
     __syncthreads();
 
-    // top-left padded position of this lane's two pixels (pixel blocks 0 and 1), both stages
-    int pos1[2], pos2[2];
+    // top-left padded position of this lane's two pixels (pixel blocks 0 and 1), both stages,
+    // as element offsets into the tiles; lanes without a pixel read the all-zero row
+    int base1[2], base2[2];
     bool valid[2];
 #pragma unroll
     for (int pb = 0; pb < 2; ++pb) {
         const int p = 32 * pb + col;
         const int y = p / W, x = p - y * W;
         valid[pb] = p < HW;
-        pos1[pb] = valid[pb] ? (KS1 == 3 ? y * Wp1 + x : p) : Z1;
-        pos2[pb] = valid[pb] ? (KS2 == 3 ? y * Wp2 + x : p) : Z2;
+        base1[pb] = (valid[pb] ? (KS1 == 3 ? y * Wp1 + x : p) : Z1) * CH_XLD + 8 * half;
+        base2[pb] = (valid[pb] ? (KS2 == 3 ? y * Wp2 + x : p) : Z2) * TLD + 8 * half;
     }
 
     // ------------------------------- stage 1 -------------------------------
@@ -135,33 +136,37 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[b][pb][v] = 0.f;
 
-    auto compute_group = [&](const uint4(&af)[GS1][RB], int g) __attribute__((always_inline)) {
-        const int gi = g % GPS; // group within the staging round
+    // input fragment offset (elements) of k-step t of group g, before the lane's base
+    auto xoff = [&](int gi, int t) __attribute__((always_inline)) {
+        if (KS1 == 3 && GS1 == 9) return ((t / 3) * Wp1 + (t % 3)) * CH_XLD + 16 * gi;
+        if (KS1 == 3) return ((gi % 3) * Wp1 + t) * CH_XLD + 16 * (gi / 3);
+        return 16 * t;
+    };
+    // multiply group g (fragments in cur) while fetching the fragments of group gn into nxt
+    auto run_group = [&](const uint4(&cur)[GS1][RB], uint4(&nxt)[GS1][RB], int g, int gn) __attribute__((always_inline)) {
+        const int gi = g % GPS;
+        const uint4 *src = w1s + (i64)gn * GS1 * RB * 64;
+        uint4 bc[2], bn[2];
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb) bc[pb] = lds_read16(&xs[base1[pb] + (valid[pb] ? xoff(gi, 0) : 0)]);
 #pragma unroll
         for (int t = 0; t < GS1; ++t) {
-            int c16, toff;
-            if (KS1 == 3 && GS1 == 9) {
-                c16 = gi;
-                toff = (t / 3) * Wp1 + (t % 3);
-            } else if (KS1 == 3) {
-                c16 = gi / 3;
-                toff = (gi % 3) * Wp1 + t;
-            } else {
-                c16 = t;
-                toff = 0;
-            }
-            bf16x8_t bfr[2];
 #pragma unroll
-            for (int pb = 0; pb < 2; ++pb)
-                bfr[pb] = as_bf16x8(lds_read16(&xs[(pos1[pb] + (valid[pb] ? toff : 0)) * CH_XLD + 16 * c16 + 8 * half]));
+            for (int b = 0; b < RB; ++b) nxt[t][b] = src[(t * RB + b) * 64];
+            if (t + 1 < GS1) {
+#pragma unroll
+                for (int pb = 0; pb < 2; ++pb) bn[pb] = lds_read16(&xs[base1[pb] + (valid[pb] ? xoff(gi, t + 1) : 0)]);
+            }
 #pragma unroll
             for (int b = 0; b < RB; ++b)
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb)
-                    acc[b][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[t][b]), bfr[pb], acc[b][pb], 0, 0, 0);
+                    acc[b][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[t][b]), as_bf16x8(bc[pb]), acc[b][pb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int pb = 0; pb < 2; ++pb) bc[pb] = bn[pb];
         }
     };
-    // after group g: if it closed a staging round, bring in the next 64 channels
     // after the g-th group: if it closed a staging round, bring in the next 64 channels (rounds are
     // entered at their first group because the rotation is a whole number of rounds when nsub > 1)
     auto next_round = [&](int g) __attribute__((always_inline)) {
@@ -177,16 +182,10 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     if (nsub > 1) load_x(grp(GPS) / GPS);
     __syncthreads();
     for (int g = 0; g < ngroups; g += 2) {
-        if (g + 1 < ngroups) load_w1(afB, grp(g + 1));
-        __builtin_amdgcn_sched_barrier(0);
-        compute_group(afA, grp(g));
-        __builtin_amdgcn_sched_barrier(0);
+        run_group(afA, afB, grp(g), grp(g + 1));
         next_round(g);
         if (g + 1 < ngroups) {
-            if (g + 2 < ngroups) load_w1(afA, grp(g + 2));
-            __builtin_amdgcn_sched_barrier(0);
-            compute_group(afB, grp(g + 1));
-            __builtin_amdgcn_sched_barrier(0);
+            run_group(afB, afA, grp(g + 1), grp(g + 2));
             next_round(g + 1);
         }
     }
@@ -196,34 +195,37 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const int nb2 = C2 / 32;
     const int npair = (nb2 / 2 + 3 - w) / 4; // output-block pairs of this wavefront: 2 w, 2 w + 8, ...
     const int ngroups2 = npair * T2;
-    uint4 bwA[2][R16], bwB[2][R16];
     const int rot2 = (int)((n >> 3) % T2);
     auto tap_of = [&](int q) __attribute__((always_inline)) { // taps of a pair are visited in a rotated order
         const int t = q % T2 + rot2;
         return t >= T2 ? t - T2 : t;
     };
-    auto load_w2 = [&](uint4(&bw)[2][R16], int q) __attribute__((always_inline)) {
-        const int ob = 2 * w + 8 * (q / T2), tap = tap_of(q);
-        const uint4 *src = a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
+    auto w2src = [&](int q) __attribute__((always_inline)) {
+        const int qq = q < ngroups2 ? q : ngroups2 - 1;
+        const int ob = 2 * w + 8 * (qq / T2), tap = tap_of(qq);
+        return a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
+    };
+    uint4 bwA[2][R16], bwB[2][R16];
+    if (ngroups2 > 0) {
+        const uint4 *src = w2src(0);
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
-            for (int k = 0; k < R16; ++k) bw[bb][k] = src[((i64)bb * S2 + k) * 64];
-    };
-    if (ngroups2 > 0) load_w2(bwA, 0);
+            for (int k = 0; k < R16; ++k) bwA[bb][k] = src[(bb * S2 + k) * 64];
+    }
 
     // ---------------- sum the four partial tiles, 64 rows of rho at a time ----------------
 #pragma unroll
     for (int rh = 0; rh < R / 64; ++rh) {
         if (rh > 0) __syncthreads();
-        float *pw = &P[w][0];
+        float *pw = &P[w][(4 * half) * CH_PLD + col];
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    pw[(32 * bb + 8 * (v >> 2) + 4 * half + (v & 3)) * CH_PLD + 32 * pb + col] = acc[2 * rh + bb][pb][v];
+                    pw[(32 * bb + 8 * (v >> 2) + (v & 3)) * CH_PLD + 32 * pb] = acc[2 * rh + bb][pb][v];
         __syncthreads();
         const int pix = tid & 63;
         const int py = pix / W, px = pix - py * W;
@@ -231,23 +233,21 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int r0 = 8 * ((tid >> 6) + 4 * it);
-            uint16_t o[8];
+            float f[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int idx = (r0 + e) * CH_PLD + pix;
-                o[e] = float_to_bf16_bits((P[0][idx] + P[1][idx]) + (P[2][idx] + P[3][idx]));
+                f[e] = (P[0][idx] + P[1][idx]) + (P[2][idx] + P[3][idx]);
             }
             if (pix < HW) {
-                uint4 pk;
-                pk.x = o[0] | ((uint32_t)o[1] << 16);
-                pk.y = o[2] | ((uint32_t)o[3] << 16);
-                pk.z = o[4] | ((uint32_t)o[5] << 16);
-                pk.w = o[6] | ((uint32_t)o[7] << 16);
+                const uint4 pk = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                                            pack_bf16x2(f[6], f[7]));
                 *(uint4_alias *)&Ts[ppos * TLD + 64 * rh + r0] = pk;
                 if (a.mid_save) {
                     uint16_t *ms = a.mid_save + ((i64)n * R + 64 * rh + r0) * HW + pix;
+                    const uint32_t d[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) ms[(i64)e * HW] = o[e];
+                    for (int e = 0; e < 8; ++e) ms[e * HW] = (uint16_t)(d[e >> 1] >> (16 * (e & 1)));
                 }
             }
         }
@@ -263,35 +263,47 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
 
-    auto compute_group2 = [&](const uint4(&bw)[2][R16], int q) __attribute__((always_inline)) {
+    auto run_group2 = [&](const uint4(&cur)[2][R16], uint4(&nxt)[2][R16], int q) __attribute__((always_inline)) {
         const int tap = tap_of(q);
-        const int toff = KS2 == 3 ? (tap / 3) * Wp2 + (tap % 3) : 0;
+        const int toff = (KS2 == 3 ? (tap / 3) * Wp2 + (tap % 3) : 0) * TLD;
+        const uint4 *src = w2src(q + 1);
+        uint4 bc[2], bn[2];
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb) bc[pb] = lds_read16(&Ts[base2[pb] + (valid[pb] ? toff : 0)]);
 #pragma unroll
         for (int k = 0; k < R16; ++k) {
-            bf16x8_t bfr[2];
 #pragma unroll
-            for (int pb = 0; pb < 2; ++pb)
-                bfr[pb] = as_bf16x8(lds_read16(&Ts[(pos2[pb] + (valid[pb] ? toff : 0)) * TLD + 16 * k + 8 * half]));
+            for (int bb = 0; bb < 2; ++bb) nxt[bb][k] = src[(bb * S2 + k) * 64];
+            if (k + 1 < R16) {
+#pragma unroll
+                for (int pb = 0; pb < 2; ++pb) bn[pb] = lds_read16(&Ts[base2[pb] + (valid[pb] ? toff : 0) + 16 * (k + 1)]);
+            }
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb) {
-                acc2[0][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(bw[0][k]), bfr[pb], acc2[0][pb], 0, 0, 0);
-                acc2[1][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(bw[1][k]), bfr[pb], acc2[1][pb], 0, 0, 0);
+                acc2[0][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[0][k]), as_bf16x8(bc[pb]), acc2[0][pb], 0, 0, 0);
+                acc2[1][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[1][k]), as_bf16x8(bc[pb]), acc2[1][pb], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int pb = 0; pb < 2; ++pb) bc[pb] = bn[pb];
         }
         if (q % T2 == T2 - 1) { // this output-block pair is complete: store it and start the next
             // The 64 output channels x HW pixels of the pair are one contiguous block of `out`.  Round to
             // bf16 into this wavefront's (now idle) input tile laid out exactly like that block, then
             // copy it out with 16-byte stores.
             const int ob = 2 * w + 8 * (q / T2);
+            uint16_t *ys = xs + (4 * half) * HW + col;
 #pragma unroll
             for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb) {
-                    const int pix = 32 * pb + col;
-                    if (pix < HW) {
+                    if (32 * pb + col < HW) {
 #pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            xs[(32 * bb + 8 * (v >> 2) + 4 * half + (v & 3)) * HW + pix] = float_to_bf16_bits(acc2[bb][pb][v]);
+                        for (int v = 0; v < 16; v += 2) {
+                            const uint32_t pk = pack_bf16x2(acc2[bb][pb][v], acc2[bb][pb][v + 1]);
+                            ys[(32 * bb + 8 * (v >> 2) + (v & 3)) * HW + 32 * pb] = (uint16_t)pk;
+                            ys[(32 * bb + 8 * (v >> 2) + (v & 3) + 1) * HW + 32 * pb] = (uint16_t)(pk >> 16);
+                        }
                     }
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
@@ -306,16 +318,8 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         }
     };
     for (int q = 0; q < ngroups2; q += 2) {
-        if (q + 1 < ngroups2) load_w2(bwB, q + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_group2(bwA, q);
-        __builtin_amdgcn_sched_barrier(0);
-        if (q + 1 < ngroups2) {
-            if (q + 2 < ngroups2) load_w2(bwA, q + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_group2(bwB, q + 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        run_group2(bwA, bwB, q);
+        if (q + 1 < ngroups2) run_group2(bwB, bwA, q + 1);
     }
 }
 
@@ -396,10 +400,17 @@ int launch_conv_chain(hipStream_t s, const char *name, const ChainArgs &a, int N
     int st = PF_OK;
     if (N <= 0) return st;
     const dim3 grid(N), block(256);
-#define PF_CHAIN_CASE(K1, K2, RR)                                                                   \
-    if (k1 == K1 && k2 == K2 && R == RR) {                                                          \
-        PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR>), grid, block, s, a);                    \
-        return st;                                                                                  \
+    const int hw = (a.H == 8 && a.W == 8) ? 8 : (a.H == 7 && a.W == 7) ? 7 : 0;
+#define PF_CHAIN_CASE(K1, K2, RR)                                                                    \
+    if (k1 == K1 && k2 == K2 && R == RR) {                                                           \
+        if (hw == 8) {                                                                               \
+            PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 8, 8>), grid, block, s, a);           \
+        } else if (hw == 7) {                                                                        \
+            PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 7, 7>), grid, block, s, a);           \
+        } else {                                                                                     \
+            PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 0, 0>), grid, block, s, a);           \
+        }                                                                                            \
+        return st;                                                                                   \
     }
     PF_CHAIN_CASE(3, 1, 64)
     PF_CHAIN_CASE(1, 3, 64)
