@@ -196,6 +196,20 @@ def time_steps(torch, fn, sets, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def capture_graphs(torch, fn, sets):
+    """One HIP graph per buffer set, each holding one whole step (all launches of fwd + bwd)."""
+    graphs = []
+    for s in sets:
+        fn(s)  # eager once: sizes the workspace before capture
+    torch.cuda.synchronize()
+    for s in sets:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn(s)
+        graphs.append(g)
+    return graphs
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -205,6 +219,7 @@ def main():
     ap.add_argument("--buffer-sets", type=int, default=0, help="distinct input/output sets to rotate over (0 = enough to exceed 256 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -224,8 +239,15 @@ def main():
     nsets = min(nsets, 64)
     sets = [one] + [wl.make_set(i, torch, workloads) for i in range(1, nsets)]
 
-    ms = time_steps(torch, lambda s: wl.step(pf, s), sets, args.steps, args.warmup)
-    ms_resident = time_steps(torch, lambda s: wl.step(pf, s), sets[:1], args.steps, args.warmup)
+    ms_eager = time_steps(torch, lambda s: wl.step(pf, s), sets, args.steps, args.warmup)
+    if args.no_graph:
+        ms = ms_eager
+        ms_resident = time_steps(torch, lambda s: wl.step(pf, s), sets[:1], args.steps, args.warmup)
+    else:
+        # the step is launch-bound (a handful of microsecond kernels), so it is replayed as a HIP graph
+        graphs = capture_graphs(torch, lambda s: wl.step(pf, s), sets)
+        ms = time_steps(torch, lambda g: g.replay(), graphs, args.steps, args.warmup)
+        ms_resident = time_steps(torch, lambda g: g.replay(), graphs[:1], args.steps, args.warmup)
     flops = wl.flops()
     value = flops / (ms * 1e-3) / 1e12
 
@@ -258,7 +280,11 @@ def main():
     if not args.no_dense:
         for s in sets:
             wl.dense_prepare(s, torch)
-        dms = time_steps(torch, lambda s: wl.dense_step(pf, s), sets, max(10, args.steps // 4), max(2, args.warmup // 4))
+        if args.no_graph:
+            dms = time_steps(torch, lambda s: wl.dense_step(pf, s), sets, max(10, args.steps // 4), max(2, args.warmup // 4))
+        else:
+            dgraphs = capture_graphs(torch, lambda s: wl.dense_step(pf, s), sets[:4])
+            dms = time_steps(torch, lambda g: g.replay(), dgraphs, max(10, args.steps // 4), max(2, args.warmup // 4))
         dense = {"ms_per_step": dms, "value": wl.dense_flops() / (dms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
                  "speedup_of_factorized": dms / ms}
 
@@ -274,6 +300,7 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
         "data": "synthetic", "config": dict(wl.describe(), buffer_sets=nsets),
         "frac_of_mfma_peak": value / PEAK_TFLOPS[wl.dtype],
+        "launch": "eager" if args.no_graph else "hip_graph", "eager_ms_per_step": ms_eager,
         "cache_resident": {"ms_per_step": ms_resident, "value": flops / (ms_resident * 1e-3) / 1e12},
         "roofline": roofline, "cpu_baseline": cpu, "dense_layer": dense, "kernels": kernels,
     }

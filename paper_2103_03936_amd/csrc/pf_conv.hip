@@ -139,7 +139,8 @@ struct ConvPlan {
     size_t n_T, n_part, fwd_bytes, bwd_bytes;
     bool chain;              // the fused small-image kernel applies (bf16 only)
     bool wgrad;              // the small-image filter-gradient kernel applies (bf16 only)
-    int wg_groups, wg_ipg;   // image groups and images per group of that kernel
+    int wg_groups, wg_ipg;   // image groups and images per group of that kernel, k x k stage
+    int wg_groups2, wg_ipg2; // the same for the 1x1 stage
     size_t n_w1, n_w2;       // packed weight elements, forward direction
     size_t n_w1b, n_w2b;     // packed weight elements, backward direction
 };
@@ -154,16 +155,19 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
     p.n_w2b = chain_w2_elems(g.C, g.r, g.k);
     p.wgrad = p.chain && wgrad_supported(g.r, g.C, g.H, g.W, g.k, g.s, g.p) &&
               wgrad_supported(g.r, g.Cout, g.H, g.W, 1, 1, 0);
-    p.wg_groups = p.wg_ipg = 1;
-    if (p.wgrad) {
-        const int chunks = g.C / wgrad_nchunk(g.r, g.k);
-        int want = 256 / (chunks > 0 ? chunks : 1);
-        if (want < 1) want = 1;
-        if (want > g.N) want = g.N > 0 ? g.N : 1;
-        p.wg_ipg = (g.N + want - 1) / want;
-        if (p.wg_ipg < 1) p.wg_ipg = 1;
-        p.wg_groups = (g.N + p.wg_ipg - 1) / p.wg_ipg;
-        if (p.wg_groups < 1) p.wg_groups = 1;
+    p.wg_groups = p.wg_ipg = p.wg_groups2 = p.wg_ipg2 = 1;
+    if (p.wgrad && g.N > 0) {
+        // image groups: enough workgroups to cover the chip, but few partial sums to add up (the k x k
+        // partials are large, so at most 16 of them; the 1x1 partials are small, so up to 64)
+        auto split = [&](int chunks, int target, int cap, int &groups, int &ipg) {
+            int want = target / (chunks > 0 ? chunks : 1);
+            want = want < 1 ? 1 : want > cap ? cap : want;
+            if (want > g.N) want = g.N;
+            ipg = (g.N + want - 1) / want;
+            groups = (g.N + ipg - 1) / ipg;
+        };
+        split(g.C / wgrad_nchunk(g.r, g.k, 1), 128, 16, p.wg_groups, p.wg_ipg);
+        split(g.Cout / wgrad_nchunk(g.r, 1, 2), 128, 64, p.wg_groups2, p.wg_ipg2);
     }
     const i64 npix = (i64)g.N * g.Ho * g.Wo;
     p.ks_dVp = choose_ksplit(g.Cout, g.r, npix);
@@ -172,7 +176,7 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
     size_t a = (size_t)p.ks_dVp * g.Cout * g.r, b = (size_t)p.ks_dUk * g.r * g.C * g.k * g.k;
     p.n_part = a > b ? a : b;
     if (p.wgrad) { // both partial sets live side by side
-        const size_t both = (size_t)p.wg_groups * ((size_t)g.Cout * g.r + (size_t)g.r * g.C * g.k * g.k);
+        const size_t both = (size_t)p.wg_groups2 * g.Cout * g.r + (size_t)p.wg_groups * g.r * g.C * g.k * g.k;
         if (both > p.n_part) p.n_part = both;
     }
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
@@ -270,11 +274,13 @@ static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
     const int T = g.k * g.k;
     uint16_t *w1 = ws.take<uint16_t>(p.n_w1);
     uint16_t *w2 = ws.take<uint16_t>(p.n_w2);
-    int st = launch_pack_chain_w1(s, (const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1);
-    if (st == PF_OK) st = launch_pack_chain_w2(s, (const uint16_t *)Vp, (uint4 *)w2, g.Cout, g.r, 1, 0, g.r, 1, 0);
+    // only the thin k x k filters need re-ordering; the 1x1 filters Vp[Cout][r] are read in place
+    int st = launch_pack_chain(s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1),
+                               make_pack_w2(nullptr, nullptr, g.Cout, g.r, 1, 0, 0, 0, 0));
     if (st != PF_OK) return st;
-    ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, (const uint4 *)w2, (uint16_t *)Y, (uint16_t *)T_save,
-                g.C,                 g.Cout,            g.H,               g.W};
+    (void)w2;
+    ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, nullptr, (const uint16_t *)Vp, (uint16_t *)Y,
+                (uint16_t *)T_save,  g.C,               g.Cout,  g.H,                  g.W};
     return launch_conv_chain(s, "conv_fwd_fused", a, g.N, g.k, 1, g.r);
 }
 
@@ -296,29 +302,24 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
         if (st != PF_OK) return st;
     }
     // stage 1: dT = Vp^T dY (1x1); stage 2: dX = flipped-Uk * dT (k x k)
-    st = launch_pack_chain_w1(s, (const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0);
-    if (st == PF_OK)
-        st = launch_pack_chain_w2(s, (const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1);
+    st = launch_pack_chain(s, make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0),
+                           make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
     if (st != PF_OK) return st;
-    ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, (uint16_t *)dX, (uint16_t *)dT16,
-                g.Cout,               g.C,               g.H,               g.W};
+    ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)dX,
+                (uint16_t *)dT16,     g.Cout,            g.C,               g.H,     g.W};
     st = launch_conv_chain(s, "conv_bwd_data_fused", a, g.N, 1, g.k, g.r);
     if (st != PF_OK) return st;
     const bf16_t *Tt = T_saved ? T_saved : T16;
     if (!p.wgrad) return conv_wgrads<bf16_t, bf16_t, bf16_t>(g, p, X, dY, Tt, dT16, dUk, dVp, accumulate, part, s);
     float *part_dUk = part, *part_dVp = part + (size_t)p.wg_groups * g.r * g.C * T;
-    if (dUk) {
-        WgradArgs wa{(const uint16_t *)dT16, (const uint16_t *)X, part_dUk, g.r, g.C, g.H, g.W, g.N, p.wg_ipg};
-        st = launch_conv_wgrad(s, "conv_dUk_small", wa, g.k, p.wg_groups);
-        if (st != PF_OK) return st;
-    }
-    if (dVp) {
-        WgradArgs wa{(const uint16_t *)Tt, (const uint16_t *)dY, part_dVp, g.r, g.Cout, g.H, g.W, g.N, p.wg_ipg};
-        st = launch_conv_wgrad(s, "conv_dVp_small", wa, 1, p.wg_groups);
-        if (st != PF_OK) return st;
-    }
+    WgradArgs wa1{(const uint16_t *)dT16, (const uint16_t *)X, dUk ? part_dUk : nullptr, g.r, g.C, g.H, g.W, g.N,
+                  p.wg_ipg,               p.wg_groups};
+    WgradArgs wa2{(const uint16_t *)Tt, (const uint16_t *)dY, dVp ? part_dVp : nullptr, g.r, g.Cout, g.H, g.W, g.N,
+                  p.wg_ipg2,            p.wg_groups2};
+    st = launch_conv_wgrad_pair(s, wa1, g.k, wa2);
+    if (st != PF_OK) return st;
     WgradReduceArgs r0{part_dUk, dUk, p.wg_groups, T, g.r, g.C, (i64)g.C * T, T, 1, accumulate};
-    WgradReduceArgs r1{part_dVp, dVp, p.wg_groups, 1, g.r, g.Cout, 1, g.r, 0, accumulate};
+    WgradReduceArgs r1{part_dVp, dVp, p.wg_groups2, 1, g.r, g.Cout, 1, g.r, 0, accumulate};
     return launch_wgrad_reduce(s, r0, r1);
 }
 

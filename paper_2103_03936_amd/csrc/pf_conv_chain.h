@@ -23,8 +23,9 @@ namespace pf {
 
 struct ChainArgs {
     const uint16_t *in;  // [N][C1][HW] bf16
-    const uint4 *W1p;    // packed stage-1 weights, see pack_chain_w1_kernel
-    const uint4 *W2p;    // packed stage-2 weights, see pack_chain_w2_kernel
+    const uint4 *W1p;    // packed stage-1 weights, see make_pack_w1
+    const uint4 *W2p;    // packed stage-2 weights, see make_pack_w2 (unused when W2nat is set)
+    const uint16_t *W2nat; // 1x1 stage 2 only, nullable: weights in their natural [C2][R] layout
     uint16_t *out;       // [N][C2][HW] bf16
     uint16_t *mid_save;  // [N][R][HW] bf16, nullable
     int C1, C2, H, W;
@@ -36,13 +37,24 @@ size_t chain_w1_elems(int C1, int R, int k); // elements of the packed stage-1 w
 size_t chain_w2_elems(int C2, int R, int k); // elements of the packed stage-2 weights
 
 // W1p[s][b][lane][e] = W1(rho = 32 b + lane % 32, c = 16 (s / T) + 8 (lane / 32) + e, tap = s % T)
-// with W1(rho, c, tap) = src[rho * s_rho + c * s_c + tap * s_tap]; T = k * k.
-int launch_pack_chain_w1(hipStream_t s, const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c,
-                         i64 s_tap);
+// with W1(rho, c, tap) = src[rho * s_rho + c * s_c + tap * s_tap]; T = k * k.  src == NULL: nothing to pack.
+struct PackW1 {
+    const uint16_t *src;
+    uint4 *dst;
+    int n, RB, T; // n = number of 16-byte fragment slots
+    i64 s_rho, s_c, s_tap;
+};
 // W2p[ob][s2][lane][e] = W2(o = 32 ob + lane % 32, tap = s2 / (R / 16), rho = 16 (s2 % (R / 16)) + 8 (lane / 32) + e)
 // with W2(o, tap, rho) = src[base + o * s_o + rho * s_rho + tap * s_tap].
-int launch_pack_chain_w2(hipStream_t s, const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o,
-                         i64 s_rho, i64 s_tap);
+struct PackW2 {
+    const uint16_t *src;
+    uint4 *dst;
+    int n, S2, R16;
+    i64 base, s_o, s_rho, s_tap;
+};
+PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap);
+PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o, i64 s_rho, i64 s_tap);
+int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2);
 // k1 / k2: kernel sizes of the two stages (1 or 3); R: 64 or 128.
 int launch_conv_chain(hipStream_t s, const char *name, const ChainArgs &a, int N, int k1, int k2, int R);
 

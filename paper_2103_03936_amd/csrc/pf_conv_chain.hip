@@ -200,9 +200,14 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         const int t = q % T2 + rot2;
         return t >= T2 ? t - T2 : t;
     };
+    // A 1x1 second stage can read its weights where they are ([C2][R], rows are k-contiguous already):
+    // fragment (block, k) of a lane is the 16 bytes at row 32 block + lane % 32, column 16 k + 8 (lane / 32).
+    const bool w2nat = KS2 == 1 && a.W2nat != nullptr;
+    const i64 w2bb = w2nat ? 4 * R : (i64)S2 * 64, w2k = w2nat ? 2 : 64; // strides in 16-byte units
     auto w2src = [&](int q) __attribute__((always_inline)) {
         const int qq = q < ngroups2 ? q : ngroups2 - 1;
         const int ob = 2 * w + 8 * (qq / T2), tap = tap_of(qq);
+        if (w2nat) return (const uint4 *)(a.W2nat + ((i64)(32 * ob + col) * R + 8 * half));
         return a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
     };
     uint4 bwA[2][R16], bwB[2][R16];
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
-            for (int k = 0; k < R16; ++k) bwA[bb][k] = src[(bb * S2 + k) * 64];
+            for (int k = 0; k < R16; ++k) bwA[bb][k] = src[bb * w2bb + k * w2k];
     }
 
     // ---------------- sum the four partial tiles, 64 rows of rho at a time ----------------
@@ -273,7 +278,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
         for (int k = 0; k < R16; ++k) {
 #pragma unroll
-            for (int bb = 0; bb < 2; ++bb) nxt[bb][k] = src[(bb * S2 + k) * 64];
+            for (int bb = 0; bb < 2; ++bb) nxt[bb][k] = src[bb * w2bb + k * w2k];
             if (k + 1 < R16) {
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb) bn[pb] = lds_read16(&Ts[base2[pb] + (valid[pb] ? toff : 0) + 16 * (k + 1)]);
@@ -324,40 +329,36 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 }
 
 // ------------------------------------------------------------------ packers
-__global__ __launch_bounds__(256) void pack_chain_w1_kernel(const uint16_t *src, uint4 *dst, int nfrag_lanes, int RB,
-                                                             int T, i64 s_rho, i64 s_c, i64 s_tap)
+__device__ __forceinline__ void pack_w1_item(const PackW1 &p, int g)
 {
-    const int g = blockIdx.x * 256 + threadIdx.x; // one 16-byte fragment slot: ((s * RB + b) * 64 + lane)
-    if (g >= nfrag_lanes) return;
-    const int lane = g & 63, fb = g >> 6, b = fb % RB, s = fb / RB;
-    const int rho = 32 * b + (lane & 31), c0 = 16 * (s / T) + 8 * (lane >> 5), tap = s % T;
-    uint16_t e[8];
+    // one 16-byte fragment slot: ((s * RB + b) * 64 + lane)
+    const int lane = g & 63, fb = g >> 6, b = fb % p.RB, s = fb / p.RB;
+    const int rho = 32 * b + (lane & 31), c0 = 16 * (s / p.T) + 8 * (lane >> 5), tap = s % p.T;
+    uint32_t e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = src[rho * s_rho + (c0 + i) * s_c + tap * s_tap];
-    uint4 pk;
-    pk.x = e[0] | ((uint32_t)e[1] << 16);
-    pk.y = e[2] | ((uint32_t)e[3] << 16);
-    pk.z = e[4] | ((uint32_t)e[5] << 16);
-    pk.w = e[6] | ((uint32_t)e[7] << 16);
-    dst[g] = pk;
+    for (int i = 0; i < 8; ++i) e[i] = p.src[rho * p.s_rho + (c0 + i) * p.s_c + tap * p.s_tap];
+    p.dst[g] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
 }
 
-__global__ __launch_bounds__(256) void pack_chain_w2_kernel(const uint16_t *src, uint4 *dst, int nfrag_lanes, int S2,
-                                                             int R16, i64 base, i64 s_o, i64 s_rho, i64 s_tap)
+__device__ __forceinline__ void pack_w2_item(const PackW2 &p, int g)
 {
-    const int g = blockIdx.x * 256 + threadIdx.x; // ((ob * S2 + s2) * 64 + lane)
-    if (g >= nfrag_lanes) return;
-    const int lane = g & 63, fb = g >> 6, s2 = fb % S2, ob = fb / S2;
-    const int o = 32 * ob + (lane & 31), tap = s2 / R16, rho0 = 16 * (s2 % R16) + 8 * (lane >> 5);
-    uint16_t e[8];
+    // ((ob * S2 + s2) * 64 + lane)
+    const int lane = g & 63, fb = g >> 6, s2 = fb % p.S2, ob = fb / p.S2;
+    const int o = 32 * ob + (lane & 31), tap = s2 / p.R16, rho0 = 16 * (s2 % p.R16) + 8 * (lane >> 5);
+    uint32_t e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = src[base + o * s_o + (rho0 + i) * s_rho + tap * s_tap];
-    uint4 pk;
-    pk.x = e[0] | ((uint32_t)e[1] << 16);
-    pk.y = e[2] | ((uint32_t)e[3] << 16);
-    pk.z = e[4] | ((uint32_t)e[5] << 16);
-    pk.w = e[6] | ((uint32_t)e[7] << 16);
-    dst[g] = pk;
+    for (int i = 0; i < 8; ++i) e[i] = p.src[p.base + o * p.s_o + (rho0 + i) * p.s_rho + tap * p.s_tap];
+    p.dst[g] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+}
+
+// Both weight sets of one chain call in a single launch (either count may be zero).
+__global__ __launch_bounds__(256) void pack_chain_kernel(PackW1 p1, PackW2 p2)
+{
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g < p1.n)
+        pack_w1_item(p1, g);
+    else if (g - p1.n < p2.n)
+        pack_w2_item(p2, g - p1.n);
 }
 
 bool chain_supported(int C1, int C2, int R, int H, int W, int k, int stride, int pad)
@@ -373,25 +374,41 @@ bool chain_supported(int C1, int C2, int R, int H, int W, int k, int stride, int
 size_t chain_w1_elems(int C1, int R, int k) { return (size_t)k * k * C1 * R; }
 size_t chain_w2_elems(int C2, int R, int k) { return (size_t)k * k * C2 * R; }
 
-int launch_pack_chain_w1(hipStream_t s, const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c,
-                         i64 s_tap)
+PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap)
 {
-    int st = PF_OK;
-    const int T = k * k, RB = R / 32;
-    const int n = T * (C1 / 16) * RB * 64;
-    PF_LAUNCH(st, "pack_chain_w1", pack_chain_w1_kernel, dim3((n + 255) / 256), dim3(256), s, src, dst, n, RB, T, s_rho,
-              s_c, s_tap);
-    return st;
+    PackW1 p;
+    p.src = src;
+    p.dst = dst;
+    p.T = k * k;
+    p.RB = R / 32;
+    p.n = src ? p.T * (C1 / 16) * p.RB * 64 : 0;
+    p.s_rho = s_rho;
+    p.s_c = s_c;
+    p.s_tap = s_tap;
+    return p;
 }
 
-int launch_pack_chain_w2(hipStream_t s, const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o,
-                         i64 s_rho, i64 s_tap)
+PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o, i64 s_rho, i64 s_tap)
+{
+    PackW2 p;
+    p.src = src;
+    p.dst = dst;
+    p.R16 = R / 16;
+    p.S2 = k * k * p.R16;
+    p.n = src ? (C2 / 32) * p.S2 * 64 : 0;
+    p.base = base;
+    p.s_o = s_o;
+    p.s_rho = s_rho;
+    p.s_tap = s_tap;
+    return p;
+}
+
+int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2)
 {
     int st = PF_OK;
-    const int S2 = k * k * (R / 16);
-    const int n = (C2 / 32) * S2 * 64;
-    PF_LAUNCH(st, "pack_chain_w2", pack_chain_w2_kernel, dim3((n + 255) / 256), dim3(256), s, src, dst, n, S2, R / 16,
-              base, s_o, s_rho, s_tap);
+    const int n = p1.n + p2.n;
+    if (n <= 0) return st;
+    PF_LAUNCH(st, "pack_chain", pack_chain_kernel, dim3((n + 255) / 256), dim3(256), s, p1, p2);
     return st;
 }
 

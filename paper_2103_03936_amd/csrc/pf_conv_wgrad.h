@@ -9,7 +9,7 @@ struct WgradArgs {
     const uint16_t *A; // [N][M][H*W] bf16
     const uint16_t *B; // [N][Nc][H*W] bf16
     float *partial;    // [groups][taps][M][Nc]
-    int M, Nc, H, W, N_img, imgs_per_group;
+    int M, Nc, H, W, N_img, imgs_per_group, groups;
 };
 
 struct WgradReduceArgs {
@@ -21,8 +21,9 @@ struct WgradReduceArgs {
 };
 
 bool wgrad_supported(int M, int Nc, int H, int W, int k, int stride, int pad);
-int wgrad_nchunk(int M, int k); // B channels per workgroup
-int launch_conv_wgrad(hipStream_t s, const char *name, const WgradArgs &a, int k, int groups);
+int wgrad_nchunk(int M, int k, int which); // B channels per workgroup; which = 1 / 2: first / second problem of a pair
+// Both filter gradients in one launch: a1 = the k1 x k1 stage, a2 = the 1x1 stage (partial == NULL skips one).
+int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const WgradArgs &a2);
 int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1);
 
 } // namespace pf

@@ -46,7 +46,7 @@ __device__ __forceinline__ uint4 load_row(const uint16_t *plane, int y, int W)
 // TAPS: 9 (3x3, pad 1) or 1.  MB: 32-row blocks of m (M = 32 MB).  NBLK: 32-channel blocks of n per workgroup.
 // Pairs (n-block, tap) are dealt to the four wavefronts round-robin; PW = pairs per wavefront (max).
 template <int TAPS, int MB, int NBLK>
-__global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
+__device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx, const int g)
 {
     constexpr int NPAIR = NBLK * TAPS;
     constexpr int PW = (NPAIR + 3) / 4;
@@ -57,8 +57,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const int H = a.H, W = a.W, HW = H * W, M = 32 * MB;
-    const int n0 = blockIdx.x * NCH; // first B channel of this workgroup
-    const int g = blockIdx.y;
+    const int n0 = bx * NCH; // first B channel of this workgroup
     const int img0 = g * a.imgs_per_group;
     const int img1 = min(a.N_img, img0 + a.imgs_per_group);
     const int ksteps = (H + 1) / 2;
@@ -76,47 +75,61 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[b][p][v] = 0.f;
 
-    // B rows this thread stages per image (3x3 only): NCH channels x H rows over 256 threads
+    // Everything one image needs from global memory, fetched two images ahead of its use:
+    // the rows of B this thread stages (3x3) or this lane's B fragments (1x1), and this lane's A fragments.
     constexpr int ROWS_PT = TAPS == 9 ? (NCH * 8 + 255) / 256 : 1;
-    uint4 brow[ROWS_PT];
-    uint4 afr[MB][4];
-
-    auto load_image = [&](int img) {
+    constexpr int NBF = TAPS == 9 ? 1 : PW;
+    struct Stage {
+        uint4 brow[ROWS_PT];
+        uint4 bfr[NBF][4];
+        uint4 afr[MB][4];
+    };
+    auto load_image = [&](Stage &st, int img) __attribute__((always_inline)) {
+        if (img >= img1) return;
         if (TAPS == 9) {
 #pragma unroll
             for (int i = 0; i < ROWS_PT; ++i) {
                 const int item = tid + 256 * i, c = item >> 3, y = item & 7;
-                brow[i] = make_uint4(0, 0, 0, 0);
-                if (c < NCH && y < H) brow[i] = load_row(a.B + ((i64)img * a.Nc + n0 + c) * HW, y, W);
+                st.brow[i] = make_uint4(0, 0, 0, 0);
+                if (c < NCH && y < H) st.brow[i] = load_row(a.B + ((i64)img * a.Nc + n0 + c) * HW, y, W);
             }
+        } else {
+#pragma unroll
+            for (int p = 0; p < PW; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int y = 2 * j + half, pair = w + 4 * p;
+                    st.bfr[p][j] = make_uint4(0, 0, 0, 0);
+                    if (y < H && pair < NPAIR) st.bfr[p][j] = load_row(a.B + ((i64)img * a.Nc + n0 + 32 * pair + col) * HW, y, W);
+                }
         }
 #pragma unroll
         for (int b = 0; b < MB; ++b)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int y = 2 * j + half;
-                afr[b][j] = make_uint4(0, 0, 0, 0);
-                if (y < H) afr[b][j] = load_row(a.A + ((i64)img * M + 32 * b + col) * HW, y, W);
+                st.afr[b][j] = make_uint4(0, 0, 0, 0);
+                if (y < H) st.afr[b][j] = load_row(a.A + ((i64)img * M + 32 * b + col) * HW, y, W);
             }
     };
-
-    if (img0 < img1) load_image(img0);
-    __syncthreads();
-
-    int buf = 0;
-    for (int img = img0; img < img1; ++img, buf ^= 1) {
-        uint4 acur[MB][4];
+    // multiply image `img` (its data is in st), then refill st with image img + 2
+    auto process = [&](Stage &st, int img, int buf) __attribute__((always_inline)) {
+        uint4 acur[MB][4], bcur[NBF][4];
 #pragma unroll
         for (int b = 0; b < MB; ++b)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acur[b][j] = afr[b][j];
+            for (int j = 0; j < 4; ++j) acur[b][j] = st.afr[b][j];
+#pragma unroll
+        for (int p = 0; p < NBF; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bcur[p][j] = st.bfr[p][j];
         if (TAPS == 9) {
             // write the three shifted copies of this thread's rows into buffer `buf`
 #pragma unroll
             for (int i = 0; i < ROWS_PT; ++i) {
                 const int item = tid + 256 * i, c = item >> 3, y = item & 7;
                 if (c < NCH && y < H) {
-                    const uint4 r = brow[i];
+                    const uint4 r = st.brow[i];
                     // tx = 0 reads x - 1: shift towards higher x, zero enters at x = 0
                     const uint4 s0 = make_uint4(r.x << 16, (r.y << 16) | (r.x >> 16), (r.z << 16) | (r.y >> 16),
                                                 (r.w << 16) | (r.z >> 16));
@@ -130,7 +143,8 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
                 }
             }
         }
-        if (img + 1 < img1) load_image(img + 1); // prefetch the next image while this one is multiplied
+        load_image(st, img + 2);
+        // one barrier per image: a buffer is rewritten two images later, after the barrier in between
         if (TAPS == 9) __syncthreads();
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -139,16 +153,14 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
             for (int p = 0; p < PW; ++p) {
                 const int pair = w + 4 * p;
                 if (pair < NPAIR) {
-                    const int nb = pair / TAPS, tap = pair % TAPS;
                     uint4 bfr;
                     if (TAPS == 9) {
+                        const int nb = pair / TAPS, tap = pair % TAPS;
                         const int ty = tap / 3, tx = tap % 3;
                         bfr = *(const uint4_alias *)&Xsh[((buf * 3 + tx) * NCH + 32 * nb + col) * WG_ROWS * 8 +
                                                          (2 * j + half + ty) * 8];
                     } else {
-                        const int y = 2 * j + half;
-                        bfr = make_uint4(0, 0, 0, 0);
-                        if (y < H) bfr = load_row(a.B + ((i64)img * a.Nc + n0 + 32 * nb + col) * HW, y, W);
+                        bfr = bcur[p < NBF ? p : 0][j];
                     }
 #pragma unroll
                     for (int b = 0; b < MB; ++b)
@@ -157,7 +169,15 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
                 }
             }
         }
-        // the buffer written two images from now is this one: the barrier of the next iteration orders it
+    };
+
+    Stage sA, sB;
+    load_image(sA, img0);
+    load_image(sB, img0 + 1);
+    __syncthreads();
+    for (int img = img0; img < img1; img += 2) {
+        process(sA, img, 0);
+        if (img + 1 < img1) process(sB, img + 1, 1);
     }
 
     // partial[g][tap][m][n]
@@ -178,21 +198,53 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_kernel(WgradArgs a)
     }
 }
 
-// out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]
+// One launch computes both filter gradients: the first nwg1 workgroups work on problem 1 (taps T1: the
+// k x k stage), the others on problem 2 (always a 1x1 stage).  Each problem has its own image grouping.
+template <int T1, int MB>
+__global__ __launch_bounds__(256, 1) void conv_wgrad_pair_kernel(WgradArgs a1, WgradArgs a2, int nx1, int nx2, int nwg1)
+{
+    const int b = blockIdx.x;
+    if (b < nwg1)
+        conv_wgrad_body<T1, MB, (T1 == 9 ? 1 : 8)>(a1, b % nx1, b / nx1);
+    else
+        conv_wgrad_body<1, MB, 4>(a2, (b - nwg1) % nx2, (b - nwg1) / nx2);
+}
+
+// out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]; four consecutive n per thread
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, WgradReduceArgs r1, int blocks0)
 {
     const bool second = (int)blockIdx.x >= blocks0;
     const WgradReduceArgs r = second ? r1 : r0;
-    const i64 i = (i64)(blockIdx.x - (second ? blocks0 : 0)) * 256 + threadIdx.x;
-    const i64 count = (i64)r.taps * r.M * r.Nc;
-    if (i >= count) return;
-    float s = 0.f;
-    for (int g = 0; g < r.groups; ++g) s += r.partial[(i64)g * count + i];
+    const i64 i4 = (i64)(blockIdx.x - (second ? blocks0 : 0)) * 256 + threadIdx.x;
+    const i64 count = (i64)r.taps * r.M * r.Nc; // multiple of 4: Nc is a multiple of 32
+    if (4 * i4 >= count) return;
+    const float4 *p = (const float4 *)r.partial + i4;
+    const i64 stride4 = count / 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int g = 0;
+    for (; g + 4 <= r.groups; g += 4) { // four independent loads in flight, summed in group order
+        const float4 v0 = p[(i64)g * stride4], v1 = p[(i64)(g + 1) * stride4], v2 = p[(i64)(g + 2) * stride4],
+                     v3 = p[(i64)(g + 3) * stride4];
+        s.x = (((s.x + v0.x) + v1.x) + v2.x) + v3.x;
+        s.y = (((s.y + v0.y) + v1.y) + v2.y) + v3.y;
+        s.z = (((s.z + v0.z) + v1.z) + v2.z) + v3.z;
+        s.w = (((s.w + v0.w) + v1.w) + v2.w) + v3.w;
+    }
+    for (; g < r.groups; ++g) {
+        const float4 v = p[(i64)g * stride4];
+        s.x += v.x;
+        s.y += v.y;
+        s.z += v.z;
+        s.w += v.w;
+    }
+    const i64 i = 4 * i4;
     const int n = (int)(i % r.Nc);
     const i64 t = i / r.Nc;
     const int m = (int)(t % r.M), tap = (int)(t / r.M);
     float *dst = r.out + m * r.s_m + n * r.s_n + tap * r.s_tap;
-    *dst = r.accumulate ? (*dst + s) : s;
+    const float v[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dst[e * r.s_n] = r.accumulate ? (dst[e * r.s_n] + v[e]) : v[e];
 }
 
 bool wgrad_supported(int M, int Nc, int H, int W, int k, int stride, int pad)
@@ -201,26 +253,35 @@ bool wgrad_supported(int M, int Nc, int H, int W, int k, int stride, int pad)
     if (!((k == 3 && pad == 1) || (k == 1 && pad == 0))) return false;
     if (H > 8 || W > 8) return false;
     if (M != 64 && M != 128) return false;
-    if (k == 3) return Nc % (M == 64 ? 64 : 32) == 0;
     return Nc % 256 == 0;
 }
 
-int wgrad_nchunk(int M, int k) { return k == 3 ? (M == 64 ? 64 : 32) : 256; }
+int wgrad_nchunk(int M, int k, int which)
+{
+    (void)M;
+    if (which == 2) return 128; // the 1x1 stage as second problem of a pair
+    return k == 3 ? 32 : 256;
+}
 
-int launch_conv_wgrad(hipStream_t s, const char *name, const WgradArgs &a, int k, int groups)
+// a1: the k x k stage (k = 3 or 1); a2: the 1x1 stage; either may be skipped by passing partial == NULL.
+int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const WgradArgs &a2)
 {
     int st = PF_OK;
-    if (a.N_img <= 0 || groups <= 0) return st;
-    const int M = a.M;
-    const dim3 grid(a.Nc / wgrad_nchunk(M, k), groups), block(256);
-    if (k == 3 && M == 64) {
-        PF_LAUNCH(st, name, (conv_wgrad_kernel<9, 2, 2>), grid, block, s, a);
-    } else if (k == 3 && M == 128) {
-        PF_LAUNCH(st, name, (conv_wgrad_kernel<9, 4, 1>), grid, block, s, a);
-    } else if (k == 1 && M == 64) {
-        PF_LAUNCH(st, name, (conv_wgrad_kernel<1, 2, 8>), grid, block, s, a);
-    } else if (k == 1 && M == 128) {
-        PF_LAUNCH(st, name, (conv_wgrad_kernel<1, 4, 8>), grid, block, s, a);
+    if (a1.N_img <= 0) return st;
+    const int nx1 = a1.partial ? a1.Nc / wgrad_nchunk(a1.M, k1, 1) : 0;
+    const int nx2 = a2.partial ? a2.Nc / wgrad_nchunk(a2.M, 1, 2) : 0;
+    const int nwg1 = nx1 * a1.groups, nwg2 = nx2 * a2.groups;
+    if (nwg1 + nwg2 == 0) return st;
+    const dim3 grid(nwg1 + nwg2), block(256);
+    const int M = a1.M, x1 = nx1 > 0 ? nx1 : 1, x2 = nx2 > 0 ? nx2 : 1;
+    if (k1 == 3 && M == 64) {
+        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<9, 2>), grid, block, s, a1, a2, x1, x2, nwg1);
+    } else if (k1 == 3 && M == 128) {
+        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<9, 4>), grid, block, s, a1, a2, x1, x2, nwg1);
+    } else if (k1 == 1 && M == 64) {
+        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<1, 2>), grid, block, s, a1, a2, x1, x2, nwg1);
+    } else if (k1 == 1 && M == 128) {
+        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<1, 4>), grid, block, s, a1, a2, x1, x2, nwg1);
     } else {
         st = PF_ERR_UNSUPPORTED;
     }
@@ -231,7 +292,7 @@ int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradRed
 {
     int st = PF_OK;
     const i64 c0 = r0.out ? (i64)r0.taps * r0.M * r0.Nc : 0, c1 = r1.out ? (i64)r1.taps * r1.M * r1.Nc : 0;
-    const int b0 = (int)((c0 + 255) / 256), b1 = (int)((c1 + 255) / 256);
+    const int b0 = (int)((c0 / 4 + 255) / 256), b1 = (int)((c1 / 4 + 255) / 256);
     if (b0 + b1 == 0) return st;
     PF_LAUNCH(st, "wgrad_reduce", wgrad_reduce_kernel, dim3(b0 + b1), dim3(256), s, r0, r1, b0);
     return st;
