@@ -31,21 +31,34 @@ __device__ __forceinline__ bf16x8_t wg_as_bf16x8(uint4 v)
     return c.b;
 }
 
-// Row y of one channel plane (W <= 8 pixels) as 8 bf16, zero beyond W.  `plane` points at the channel's
-// first pixel.  W == 8 rows are 16-byte aligned; other widths are read element by element.
-__device__ __forceinline__ uint4 load_row(const uint16_t *plane, int y, int W)
+// Row y of one channel plane (W <= 8 pixels) as 8 bf16, zero beyond W and for y >= H; branch-free so that
+// many row loads can be in flight at once.  `plane` points at the channel's first pixel.  Rows of 8-pixel
+// images are 16-byte aligned; other widths are read element by element (indices clamped into the row).
+template <int WC>
+__device__ __forceinline__ uint4 load_row(const uint16_t *plane, int y, int H, int W)
 {
-    if (W == 8) return *(const uint4 *)(plane + 8 * y);
-    const uint16_t *p = plane + W * y;
-    uint32_t e[8];
+    const int yy = y < H ? y : H - 1;
+    uint4 v;
+    if (WC == 8) {
+        v = *(const uint4 *)(plane + 8 * yy);
+    } else {
+        const uint16_t *p = plane + W * yy;
+        uint32_t e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = i < W ? (uint32_t)p[i] : 0u;
-    return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t x = p[i < W ? i : W - 1];
+            e[i] = i < W ? x : 0u;
+        }
+        v = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+    const bool ok = y < H;
+    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
 }
 
 // TAPS: 9 (3x3, pad 1) or 1.  MB: 32-row blocks of m (M = 32 MB).  NBLK: 32-channel blocks of n per workgroup.
 // Pairs (n-block, tap) are dealt to the four wavefronts round-robin; PW = pairs per wavefront (max).
-template <int TAPS, int MB, int NBLK>
+// HC, WC: image height / width known at compile time (0 = read them from the arguments).
+template <int TAPS, int MB, int NBLK, int HC, int WC>
 __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx, const int g)
 {
     constexpr int NPAIR = NBLK * TAPS;
@@ -56,7 +69,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
-    const int H = a.H, W = a.W, HW = H * W, M = 32 * MB;
+    const int H = HC ? HC : a.H, W = WC ? WC : a.W, HW = H * W, M = 32 * MB;
     const int n0 = bx * NCH; // first B channel of this workgroup
     const int img0 = g * a.imgs_per_group;
     const int img1 = min(a.N_img, img0 + a.imgs_per_group);
@@ -90,8 +103,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
             for (int i = 0; i < ROWS_PT; ++i) {
                 const int item = tid + 256 * i, c = item >> 3, y = item & 7;
-                st.brow[i] = make_uint4(0, 0, 0, 0);
-                if (c < NCH && y < H) st.brow[i] = load_row(a.B + ((i64)img * a.Nc + n0 + c) * HW, y, W);
+                st.brow[i] = load_row<WC>(a.B + ((i64)img * a.Nc + n0 + c) * HW, y, H, W);
             }
         } else {
 #pragma unroll
@@ -99,8 +111,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int y = 2 * j + half, pair = w + 4 * p;
-                    st.bfr[p][j] = make_uint4(0, 0, 0, 0);
-                    if (y < H && pair < NPAIR) st.bfr[p][j] = load_row(a.B + ((i64)img * a.Nc + n0 + 32 * pair + col) * HW, y, W);
+                    st.bfr[p][j] = load_row<WC>(a.B + ((i64)img * a.Nc + n0 + 32 * (pair < NPAIR ? pair : 0) + col) * HW, y, H, W);
                 }
         }
 #pragma unroll
@@ -108,8 +119,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int y = 2 * j + half;
-                st.afr[b][j] = make_uint4(0, 0, 0, 0);
-                if (y < H) st.afr[b][j] = load_row(a.A + ((i64)img * M + 32 * b + col) * HW, y, W);
+                st.afr[b][j] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, y, H, W);
             }
     };
     // multiply image `img` (its data is in st), then refill st with image img + 2
@@ -128,7 +138,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
             for (int i = 0; i < ROWS_PT; ++i) {
                 const int item = tid + 256 * i, c = item >> 3, y = item & 7;
-                if (c < NCH && y < H) {
+                if (y < H) {
                     const uint4 r = st.brow[i];
                     // tx = 0 reads x - 1: shift towards higher x, zero enters at x = 0
                     const uint4 s0 = make_uint4(r.x << 16, (r.y << 16) | (r.x >> 16), (r.z << 16) | (r.y >> 16),
@@ -200,14 +210,14 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 
 // One launch computes both filter gradients: the first nwg1 workgroups work on problem 1 (taps T1: the
 // k x k stage), the others on problem 2 (always a 1x1 stage).  Each problem has its own image grouping.
-template <int T1, int MB>
+template <int T1, int MB, int HC, int WC>
 __global__ __launch_bounds__(256, 1) void conv_wgrad_pair_kernel(WgradArgs a1, WgradArgs a2, int nx1, int nx2, int nwg1)
 {
     const int b = blockIdx.x;
     if (b < nwg1)
-        conv_wgrad_body<T1, MB, (T1 == 9 ? 1 : 8)>(a1, b % nx1, b / nx1);
+        conv_wgrad_body<T1, MB, (T1 == 9 ? 1 : 8), HC, WC>(a1, b % nx1, b / nx1);
     else
-        conv_wgrad_body<1, MB, 4>(a2, (b - nwg1) % nx2, (b - nwg1) / nx2);
+        conv_wgrad_body<1, MB, 4, HC, WC>(a2, (b - nwg1) % nx2, (b - nwg1) / nx2);
 }
 
 // out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]; four consecutive n per thread
@@ -222,13 +232,17 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, W
     const i64 stride4 = count / 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     int g = 0;
-    for (; g + 4 <= r.groups; g += 4) { // four independent loads in flight, summed in group order
-        const float4 v0 = p[(i64)g * stride4], v1 = p[(i64)(g + 1) * stride4], v2 = p[(i64)(g + 2) * stride4],
-                     v3 = p[(i64)(g + 3) * stride4];
-        s.x = (((s.x + v0.x) + v1.x) + v2.x) + v3.x;
-        s.y = (((s.y + v0.y) + v1.y) + v2.y) + v3.y;
-        s.z = (((s.z + v0.z) + v1.z) + v2.z) + v3.z;
-        s.w = (((s.w + v0.w) + v1.w) + v2.w) + v3.w;
+    for (; g + 8 <= r.groups; g += 8) { // eight independent loads in flight, summed in group order
+        float4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = p[(i64)(g + k) * stride4];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            s.x += v[k].x;
+            s.y += v[k].y;
+            s.z += v[k].z;
+            s.w += v[k].w;
+        }
     }
     for (; g < r.groups; ++g) {
         const float4 v = p[(i64)g * stride4];
@@ -274,18 +288,24 @@ int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const Wgr
     if (nwg1 + nwg2 == 0) return st;
     const dim3 grid(nwg1 + nwg2), block(256);
     const int M = a1.M, x1 = nx1 > 0 ? nx1 : 1, x2 = nx2 > 0 ? nx2 : 1;
-    if (k1 == 3 && M == 64) {
-        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<9, 2>), grid, block, s, a1, a2, x1, x2, nwg1);
-    } else if (k1 == 3 && M == 128) {
-        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<9, 4>), grid, block, s, a1, a2, x1, x2, nwg1);
-    } else if (k1 == 1 && M == 64) {
-        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<1, 2>), grid, block, s, a1, a2, x1, x2, nwg1);
-    } else if (k1 == 1 && M == 128) {
-        PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<1, 4>), grid, block, s, a1, a2, x1, x2, nwg1);
-    } else {
-        st = PF_ERR_UNSUPPORTED;
+    const bool sq8 = a1.H == 8 && a1.W == 8;
+#define PF_WGRAD_CASE(T1, MBV)                                                                                     \
+    if (k1 * k1 == T1 && M == 32 * MBV) {                                                                          \
+        if (sq8) {                                                                                                 \
+            PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<T1, MBV, 8, 8>), grid, block, s, a1, a2, x1,  \
+                      x2, nwg1);                                                                                   \
+        } else {                                                                                                   \
+            PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<T1, MBV, 0, 0>), grid, block, s, a1, a2, x1,  \
+                      x2, nwg1);                                                                                   \
+        }                                                                                                          \
+        return st;                                                                                                 \
     }
-    return st;
+    PF_WGRAD_CASE(9, 2)
+    PF_WGRAD_CASE(9, 4)
+    PF_WGRAD_CASE(1, 2)
+    PF_WGRAD_CASE(1, 4)
+#undef PF_WGRAD_CASE
+    return PF_ERR_UNSUPPORTED;
 }
 
 int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1)
