@@ -75,6 +75,20 @@ class ConvWorkload:
             pf.pf_dense_conv_fwd(g["X"], g["Wd"], 1, g["pad"])
             pf.pf_dense_conv_bwd(g["X"], g["Wd"], g["dY"], 1, g["pad"])
 
+    def library_dense_prepare(self, s, torch):
+        out = []
+        for g in s.values():
+            X = g["X"].detach().clone().requires_grad_(True)
+            Wd = g["Wd"].detach().clone().requires_grad_(True)
+            out.append((X, Wd, g["dY"], g["pad"]))
+        return out
+
+    def library_dense_step(self, prep, torch):
+        for X, Wd, dY, pad in prep:
+            X.grad = None
+            Wd.grad = None
+            torch.nn.functional.conv2d(X, Wd, padding=pad).backward(dY)
+
     def kernel_work(self):
         """{kernel name: (algorithmic flops per launch, algorithmic bytes per launch)} for single-layer workloads."""
         if len(self.layers) != 1:
@@ -82,14 +96,19 @@ class ConvWorkload:
         (C, Co, r, k, p), = self.layers.values()
         s = 2 if self.dtype == "bf16" else 4
         npix, K = self.N * self.H * self.W, C * k * k
+        f1, f2 = 2.0 * npix * r * K, 2.0 * npix * r * Co  # one pass over the k x k stage / the 1x1 stage
         return {
-            "conv_T=Uk*X": (2.0 * npix * r * K, s * (npix * C + r * K + npix * r)),
-            "conv_Y=Vp*T": (2.0 * npix * r * Co, s * (npix * r + Co * r + npix * Co)),
-            "conv_dT=Vpt*dY": (2.0 * npix * r * Co, s * (npix * Co + Co * r) + 4 * npix * r),
-            "conv_dVp=dY*Tt": (2.0 * npix * r * Co, s * (npix * Co + npix * r) + 4 * Co * r),
-            "conv_dX=Ukt*dT": (2.0 * npix * r * K, s * (r * K + npix * C) + 4 * npix * r),
-            "conv_dUk=dT*Xcolt": (2.0 * npix * r * K, s * npix * C + 4 * (npix * r + r * K)),
-            "conv_fwd_fused": (2.0 * npix * r * (K + Co), s * (npix * C + r * K + Co * r + npix * Co + npix * r)),
+            # any-shape path, one launch per contraction
+            "conv_T=Uk*X": (f1, s * (npix * C + r * K + npix * r)),
+            "conv_Y=Vp*T": (f2, s * (npix * r + Co * r + npix * Co)),
+            "conv_dT=Vpt*dY": (f2, s * (npix * Co + Co * r) + 4 * npix * r),
+            "conv_dVp=dY*Tt": (f2, s * (npix * Co + npix * r) + 4 * Co * r),
+            "conv_dX=Ukt*dT": (f1, s * (r * K + npix * C) + 4 * npix * r),
+            "conv_dUk=dT*Xcolt": (f1, s * npix * C + 4 * (npix * r + r * K)),
+            # fused small-image path
+            "conv_fwd_fused": (f1 + f2, s * (npix * C + r * K + Co * r + npix * Co + npix * r)),
+            "conv_bwd_data_fused": (f1 + f2, s * (npix * Co + r * K + Co * r + npix * C + npix * r)),
+            "conv_wgrad_pair": (f1 + f2, s * (npix * C + npix * Co + 2 * npix * r) + 4 * (r * K + Co * r)),
         }
 
     def cpu_baseline(self, oracle, workloads, reps=3):
@@ -145,6 +164,22 @@ class LinearWorkload:
             pf.pf_dense_linear_fwd(g["X"], g["W"], g["bias"])
             pf.pf_dense_linear_bwd(g["X"], g["W"], g["dY"], has_bias=True)
 
+    def library_dense_prepare(self, s, torch):
+        out = []
+        for g in s.values():
+            X = g["X"].detach().clone().requires_grad_(True)
+            W = g["W"].detach().clone().requires_grad_(True)
+            b = g["bias"].detach().clone().requires_grad_(True)
+            out.append((X, W, b, g["dY"]))
+        return out
+
+    def library_dense_step(self, prep, torch):
+        for X, W, b, dY in prep:
+            X.grad = None
+            W.grad = None
+            b.grad = None
+            torch.nn.functional.linear(X, W, b).backward(dY)
+
     def kernel_work(self):
         if len(self.layers) != 1:
             return {}
@@ -173,6 +208,21 @@ class LinearWorkload:
         return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there is no
+    figure or the kernel's source file has changed since the counters were taken."""
+    import glob
+    import hashlib
+    for path in glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic.md")):
+        for line in open(path):
+            f = line.split()
+            if len(f) == 6 and f[0] == "traffic" and f[1] == workload and f[2] == kernel:
+                src = os.path.join(ROOT, f[4])
+                if os.path.exists(src) and hashlib.sha256(open(src, "rb").read()).hexdigest() == f[5]:
+                    return float(f[3])
+    return None
+
+
 def make_workload(name):
     import workloads
     cfg = workloads.CONFIGS[name]
@@ -196,18 +246,35 @@ def time_steps(torch, fn, sets, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def capture_graphs(torch, fn, sets):
-    """One HIP graph per buffer set, each holding one whole step (all launches of fwd + bwd)."""
-    graphs = []
+def capture_graph(torch, fn, sets, count):
+    """One HIP graph holding `count` whole steps (all launches of fwd + bwd), walking the buffer sets in turn."""
     for s in sets:
         fn(s)  # eager once: sizes the workspace before capture
     torch.cuda.synchronize()
-    for s in sets:
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            fn(s)
-        graphs.append(g)
-    return graphs
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(count):
+            fn(sets[i % len(sets)])
+    return g
+
+
+def time_graph_steps(torch, fn, sets, steps, warmup):
+    """Exactly `steps` steps as replays of one graph of len(sets) steps plus one graph for the remainder."""
+    per = len(sets)
+    full = capture_graph(torch, fn, sets, per)
+    rem = capture_graph(torch, fn, sets, steps % per) if steps % per else None
+    for i in range(max(1, warmup // per)):
+        full.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps // per):
+        full.replay()
+    if rem is not None:
+        rem.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
 
 
 def main():
@@ -219,6 +286,8 @@ def main():
     ap.add_argument("--buffer-sets", type=int, default=0, help="distinct input/output sets to rotate over (0 = enough to exceed 256 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device copy, so that byte counters of a profiler run can be scaled")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -245,9 +314,8 @@ def main():
         ms_resident = time_steps(torch, lambda s: wl.step(pf, s), sets[:1], args.steps, args.warmup)
     else:
         # the step is launch-bound (a handful of microsecond kernels), so it is replayed as a HIP graph
-        graphs = capture_graphs(torch, lambda s: wl.step(pf, s), sets)
-        ms = time_steps(torch, lambda g: g.replay(), graphs, args.steps, args.warmup)
-        ms_resident = time_steps(torch, lambda g: g.replay(), graphs[:1], args.steps, args.warmup)
+        ms = time_graph_steps(torch, lambda s: wl.step(pf, s), sets, args.steps, args.warmup)
+        ms_resident = time_graph_steps(torch, lambda s: wl.step(pf, s), sets[:1] * 8, args.steps, args.warmup)
     flops = wl.flops()
     value = flops / (ms * 1e-3) / 1e12
 
@@ -269,7 +337,8 @@ def main():
             kflops, kbytes = work[dom]
             peak = PEAK_TFLOPS[wl.dtype]
             roofline = {"kernel": dom, "bound": "mfma", "achieved": kflops / avg_s / 1e12, "peak": peak,
-                        "unit": "TFLOP/s", "frac": kflops / avg_s / 1e12 / peak, "traffic": None,
+                        "unit": "TFLOP/s", "frac": kflops / avg_s / 1e12 / peak,
+                        "traffic": measured_traffic(wl.name, dom), "algorithmic_bytes": kbytes,
                         "avg_us": kernels[dom]["avg_us"], "algorithmic_GBps": kbytes / avg_s / 1e9,
                         "frac_of_hbm_peak": kbytes / avg_s / 1e9 / HBM_GBS}
         else:
@@ -283,10 +352,21 @@ def main():
         if args.no_graph:
             dms = time_steps(torch, lambda s: wl.dense_step(pf, s), sets, max(10, args.steps // 4), max(2, args.warmup // 4))
         else:
-            dgraphs = capture_graphs(torch, lambda s: wl.dense_step(pf, s), sets[:4])
-            dms = time_steps(torch, lambda g: g.replay(), dgraphs, max(10, args.steps // 4), max(2, args.warmup // 4))
+            dms = time_graph_steps(torch, lambda s: wl.dense_step(pf, s), sets[:4], max(10, args.steps // 4), 4)
         dense = {"ms_per_step": dms, "value": wl.dense_flops() / (dms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
                  "speedup_of_factorized": dms / ms}
+
+    library = None
+    if not args.no_dense and hasattr(wl, "library_dense_step"):
+        # the same dense layer through the vendor library (torch -> MIOpen / hipBLASLt), as an outside reference
+        try:
+            prep = [wl.library_dense_prepare(s, torch) for s in sets[:4]]
+            lms = time_steps(torch, lambda p: wl.library_dense_step(p, torch), prep, max(10, args.steps // 4), 5)
+            library = {"ms_per_step": lms, "value": wl.dense_flops() / (lms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
+                       "what": "torch.nn.functional dense layer fwd+bwd, bf16, vendor library kernels",
+                       "speedup_of_factorized": lms / ms}
+        except Exception as e:  # the reference is optional
+            library = {"error": repr(e)[:200]}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -295,6 +375,12 @@ def main():
         cpu = {"value": cflops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": sample, "seconds": secs}
 
+    if args.copy_calibration:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
@@ -302,7 +388,8 @@ def main():
         "frac_of_mfma_peak": value / PEAK_TFLOPS[wl.dtype],
         "launch": "eager" if args.no_graph else "hip_graph", "eager_ms_per_step": ms_eager,
         "cache_resident": {"ms_per_step": ms_resident, "value": flops / (ms_resident * 1e-3) / 1e12},
-        "roofline": roofline, "cpu_baseline": cpu, "dense_layer": dense, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "dense_layer": dense, "dense_layer_vendor_library": library,
+        "kernels": kernels,
     }
     print(json.dumps(out))
 
