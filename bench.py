@@ -90,26 +90,32 @@ class ConvWorkload:
             torch.nn.functional.conv2d(X, Wd, padding=pad).backward(dY)
 
     def kernel_work(self):
-        """{kernel name: (algorithmic flops per launch, algorithmic bytes per launch)} for single-layer workloads."""
-        if len(self.layers) != 1:
-            return {}
-        (C, Co, r, k, p), = self.layers.values()
+        """{kernel name: [algorithmic flops per step, algorithmic bytes per step, launches per step]}, summed over
+        the workload's layers (each layer launches each of its kernels once per step)."""
         s = 2 if self.dtype == "bf16" else 4
-        npix, K = self.N * self.H * self.W, C * k * k
-        f1, f2 = 2.0 * npix * r * K, 2.0 * npix * r * Co  # one pass over the k x k stage / the 1x1 stage
-        return {
+        out = {}
+
+        def add(name, flops, nbytes):
+            e = out.setdefault(name, [0.0, 0.0, 0])
+            e[0] += flops
+            e[1] += nbytes
+            e[2] += 1
+
+        for C, Co, r, k, p in self.layers.values():
+            npix, K = self.N * self.H * self.W, C * k * k
+            f1, f2 = 2.0 * npix * r * K, 2.0 * npix * r * Co  # one pass over the k x k stage / the 1x1 stage
             # any-shape path, one launch per contraction
-            "conv_T=Uk*X": (f1, s * (npix * C + r * K + npix * r)),
-            "conv_Y=Vp*T": (f2, s * (npix * r + Co * r + npix * Co)),
-            "conv_dT=Vpt*dY": (f2, s * (npix * Co + Co * r) + 4 * npix * r),
-            "conv_dVp=dY*Tt": (f2, s * (npix * Co + npix * r) + 4 * Co * r),
-            "conv_dX=Ukt*dT": (f1, s * (r * K + npix * C) + 4 * npix * r),
-            "conv_dUk=dT*Xcolt": (f1, s * npix * C + 4 * (npix * r + r * K)),
+            add("conv_T=Uk*X", f1, s * (npix * C + r * K + npix * r))
+            add("conv_Y=Vp*T", f2, s * (npix * r + Co * r + npix * Co))
+            add("conv_dT=Vpt*dY", f2, s * (npix * Co + Co * r) + 4 * npix * r)
+            add("conv_dVp=dY*Tt", f2, s * (npix * Co + npix * r) + 4 * Co * r)
+            add("conv_dX=Ukt*dT", f1, s * (r * K + npix * C) + 4 * npix * r)
+            add("conv_dUk=dT*Xcolt", f1, s * npix * C + 4 * (npix * r + r * K))
             # fused small-image path
-            "conv_fwd_fused": (f1 + f2, s * (npix * C + r * K + Co * r + npix * Co + npix * r)),
-            "conv_bwd_data_fused": (f1 + f2, s * (npix * Co + r * K + Co * r + npix * C + npix * r)),
-            "conv_wgrad_pair": (f1 + f2, s * (npix * C + npix * Co + 2 * npix * r) + 4 * (r * K + Co * r)),
-        }
+            add("conv_fwd_fused", f1 + f2, s * (npix * C + r * K + Co * r + npix * Co + npix * r))
+            add("conv_bwd_data_fused", f1 + f2, s * (npix * Co + r * K + Co * r + npix * C + npix * r))
+            add("conv_wgrad_pair", f1 + f2, s * (npix * C + npix * Co + 2 * npix * r) + 4 * (r * K + Co * r))
+        return out
 
     def cpu_baseline(self, oracle, workloads, reps=3):
         inputs = [(workloads.conv_inputs(self.N, C, self.H, self.W, Co, r, k, 1, p, dtype=self.dtype, seed=self.seed), p)
@@ -181,19 +187,28 @@ class LinearWorkload:
             torch.nn.functional.linear(X, W, b).backward(dY)
 
     def kernel_work(self):
-        if len(self.layers) != 1:
-            return {}
-        (i, o, r), = self.layers.values()
         s = 2 if self.dtype == "bf16" else 4
         M = self.M
-        return {
-            "linear_T=X*V": (2.0 * M * r * i, s * (M * i + i * r + M * r)),
-            "linear_Y=T*Ut": (2.0 * M * r * o, s * (M * r + o * r + M * o)),
-            "linear_dT=dY*U": (2.0 * M * r * o, s * (M * o + o * r) + 4 * M * r),
-            "linear_dX=dT*Vt": (2.0 * M * r * i, s * (i * r + M * i) + 4 * M * r),
-            "linear_dU=dYt*T": (2.0 * M * r * o, s * (M * o + M * r) + 4 * o * r),
-            "linear_dV=Xt*dT": (2.0 * M * r * i, s * M * i + 4 * (M * r + i * r)),
-        }
+        out = {}
+
+        def add(name, flops, nbytes):
+            e = out.setdefault(name, [0.0, 0.0, 0])
+            e[0] += flops
+            e[1] += nbytes
+            e[2] += 1
+
+        for i, o, r in self.layers.values():
+            add("linear_T=X*V", 2.0 * M * r * i, s * (M * i + i * r + M * r))
+            add("linear_Y=T*Ut", 2.0 * M * r * o, s * (M * r + o * r + M * o))
+            add("linear_dT=dY*U", 2.0 * M * r * o, s * (M * o + o * r) + 4 * M * r)
+            add("linear_dX=dT*Vt", 2.0 * M * r * i, s * (i * r + M * i) + 4 * M * r)
+            add("linear_dU=dYt*T", 2.0 * M * r * o, s * (M * o + M * r) + 4 * o * r)
+            add("linear_dV=Xt*dT", 2.0 * M * r * i, s * M * i + 4 * (M * r + i * r))
+            # fused path
+            add("linear_fwd_fused", 2.0 * M * r * (i + o), s * (M * i + M * o + M * r + r * (i + o)))
+            add("linear_bwd_data_fused", 2.0 * M * r * (i + o), s * (M * o + M * i + M * r + r * (i + o)))
+            add("linear_wgrad_pair", 2.0 * M * r * (i + o), s * (M * i + M * o + 2 * M * r) + 4 * r * (i + o))
+        return out
 
     def cpu_baseline(self, oracle, workloads, reps=3):
         inputs = [workloads.linear_inputs(self.M, i, o, r, dtype=self.dtype, seed=self.seed, bias=True)
@@ -332,18 +347,24 @@ def main():
     roofline = None
     if kernels:
         dom = next(iter(kernels))
-        avg_s = kernels[dom]["avg_us"] * 1e-6
+        peak = PEAK_TFLOPS[wl.dtype]
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": None, "peak": peak, "unit": "TFLOP/s", "frac": None,
+                    "traffic": None, "avg_us": kernels[dom]["avg_us"]}
         if dom in work:
-            kflops, kbytes = work[dom]
-            peak = PEAK_TFLOPS[wl.dtype]
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": kflops / avg_s / 1e12, "peak": peak,
-                        "unit": "TFLOP/s", "frac": kflops / avg_s / 1e12 / peak,
-                        "traffic": measured_traffic(wl.name, dom), "algorithmic_bytes": kbytes,
-                        "avg_us": kernels[dom]["avg_us"], "algorithmic_GBps": kbytes / avg_s / 1e9,
-                        "frac_of_hbm_peak": kbytes / avg_s / 1e9 / HBM_GBS}
-        else:
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": None, "peak": PEAK_TFLOPS[wl.dtype],
-                        "unit": "TFLOP/s", "frac": None, "traffic": None, "avg_us": kernels[dom]["avg_us"]}
+            kflops, kbytes, per_step = work[dom]
+            step_s = kernels[dom]["avg_us"] * 1e-6 * per_step  # time this kernel takes per step, all layers
+            ai = kflops / kbytes
+            bound = "mfma" if ai >= peak * 1e12 / (HBM_GBS * 1e9) else "hbm"
+            roofline.update({"bound": bound, "launches_per_step": per_step, "algorithmic_flops_per_step": kflops,
+                             "algorithmic_bytes_per_step": kbytes, "traffic": measured_traffic(wl.name, dom)})
+            if bound == "mfma":
+                roofline.update({"achieved": kflops / step_s / 1e12, "peak": peak, "unit": "TFLOP/s",
+                                 "frac": kflops / step_s / 1e12 / peak})
+            else:
+                roofline.update({"achieved": kbytes / step_s / 1e9, "peak": HBM_GBS, "unit": "GB/s",
+                                 "frac": kbytes / step_s / 1e9 / HBM_GBS})
+            roofline["tflops"] = kflops / step_s / 1e12
+            roofline["algorithmic_GBps"] = kbytes / step_s / 1e9
 
     dense = None
     if not args.no_dense:

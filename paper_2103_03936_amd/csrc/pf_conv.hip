@@ -280,7 +280,8 @@ static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
     if (st != PF_OK) return st;
     (void)w2;
     ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, nullptr, (const uint16_t *)Vp, (uint16_t *)Y,
-                (uint16_t *)T_save,  g.C,               g.Cout,  g.H,                  g.W};
+                (uint16_t *)T_save,  g.C,               g.Cout,  g.H,                  g.W,
+                0,                   nullptr};
     return launch_conv_chain(s, "conv_fwd_fused", a, g.N, g.k, 1, g.r);
 }
 
@@ -306,16 +307,17 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
                            make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
     if (st != PF_OK) return st;
     ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)dX,
-                (uint16_t *)dT16,     g.Cout,            g.C,               g.H,     g.W};
+                (uint16_t *)dT16,     g.Cout,            g.C,               g.H,     g.W,
+                0,                    nullptr};
     st = launch_conv_chain(s, "conv_bwd_data_fused", a, g.N, 1, g.k, g.r);
     if (st != PF_OK) return st;
     const bf16_t *Tt = T_saved ? T_saved : T16;
     if (!p.wgrad) return conv_wgrads<bf16_t, bf16_t, bf16_t>(g, p, X, dY, Tt, dT16, dUk, dVp, accumulate, part, s);
     float *part_dUk = part, *part_dVp = part + (size_t)p.wg_groups * g.r * g.C * T;
     WgradArgs wa1{(const uint16_t *)dT16, (const uint16_t *)X, dUk ? part_dUk : nullptr, g.r, g.C, g.H, g.W, g.N,
-                  p.wg_ipg,               p.wg_groups};
+                  p.wg_ipg,               p.wg_groups, 0};
     WgradArgs wa2{(const uint16_t *)Tt, (const uint16_t *)dY, dVp ? part_dVp : nullptr, g.r, g.Cout, g.H, g.W, g.N,
-                  p.wg_ipg2,            p.wg_groups2};
+                  p.wg_ipg2,            p.wg_groups2, 0};
     st = launch_conv_wgrad_pair(s, wa1, g.k, wa2);
     if (st != PF_OK) return st;
     WgradReduceArgs r0{part_dUk, dUk, p.wg_groups, T, g.r, g.C, (i64)g.C * T, T, 1, accumulate};

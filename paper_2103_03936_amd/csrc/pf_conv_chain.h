@@ -29,6 +29,9 @@ struct ChainArgs {
     uint16_t *out;       // [N][C2][HW] bf16
     uint16_t *mid_save;  // [N][R][HW] bf16, nullable
     int C1, C2, H, W;
+    // fully connected ("channels last") mode only: in = X[rows][C1], out = Y[rows][C2], mid_save = T[rows][R]
+    i64 rows;
+    const void *bias; // bf16 [C2], nullable
 };
 
 // Can the chain kernel take this problem?  (C1, C2: channels in / out of the chain.)
@@ -55,6 +58,9 @@ struct PackW2 {
 PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap);
 PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o, i64 s_rho, i64 s_tap);
 int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2);
+// The fully connected layer on the same kernel: Y[rows][C2] = (X[rows][C1] W1^T) W2^T + bias, W2 = a.W2nat.
+bool linear_chain_supported(i64 n_in, i64 n_out, i64 r);
+int launch_linear_chain(hipStream_t s, const char *name, const ChainArgs &a, int R);
 // k1 / k2: kernel sizes of the two stages (1 or 3); R: 64 or 128.
 int launch_conv_chain(hipStream_t s, const char *name, const ChainArgs &a, int N, int k1, int k2, int R);
 

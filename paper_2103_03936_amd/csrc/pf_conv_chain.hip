@@ -25,7 +25,10 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v)
 }
 
 // HC, WC: image height / width known at compile time (0 = read them from the arguments).
-template <int KS1, int KS2, int R, int HC, int WC>
+// CL ("channels last", the fully connected layer): the input is a row-major matrix X[rows][C1], one tile =
+// 64 consecutive rows standing where the 64 pixels of an image stand; the intermediate and the output are
+// row-major too (T[rows][R], Y[rows][C2]), a bias may be added, and both stages are 1x1.
+template <int KS1, int KS2, int R, int HC, int WC, bool CL = false>
 __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 {
     constexpr int RB = R / 32, R16 = R / 16, T1 = KS1 * KS1, T2 = KS2 * KS2;
@@ -57,6 +60,16 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     uint4 xv[NXV];
     const int nitem = 8 * HW;
     auto load_x = [&](int sub) __attribute__((always_inline)) {
+        if (CL) { // item = (row m, channel octet o): 16 contiguous bytes of X; rows past the end re-read the last row
+#pragma unroll
+            for (int i = 0; i < NXV; ++i) {
+                const int it = lane + 64 * i, m = it >> 3, o = it & 7;
+                i64 row = (i64)n * CH_PIX + m;
+                row = row < a.rows ? row : a.rows - 1;
+                xv[i] = *(const uint4 *)(a.in + row * C1 + w * cw + sub * CH_SUB + 8 * o);
+            }
+            return;
+        }
         const uint16_t *src = a.in + ((i64)n * C1 + w * cw + sub * CH_SUB) * HW;
 #pragma unroll
         for (int i = 0; i < NXV; ++i) {
@@ -75,6 +88,14 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         }
     };
     auto store_x = [&]() __attribute__((always_inline)) {
+        if (CL) {
+#pragma unroll
+            for (int i = 0; i < NXV; ++i) {
+                const int it = lane + 64 * i, m = it >> 3, o = it & 7;
+                *(uint4_alias *)&xs[m * CH_XLD + 8 * o] = xv[i];
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NXV; ++i) {
             const int it = lane + 64 * i;
@@ -248,7 +269,10 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                 const uint4 pk = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
                                             pack_bf16x2(f[6], f[7]));
                 *(uint4_alias *)&Ts[ppos * TLD + 64 * rh + r0] = pk;
-                if (a.mid_save) {
+                if (a.mid_save && CL) {
+                    const i64 row = (i64)n * CH_PIX + pix;
+                    if (row < a.rows) *(uint4 *)(a.mid_save + row * R + 64 * rh + r0) = pk;
+                } else if (a.mid_save) {
                     uint16_t *ms = a.mid_save + ((i64)n * R + 64 * rh + r0) * HW + pix;
                     const uint32_t d[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
@@ -297,6 +321,45 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             // bf16 into this wavefront's (now idle) input tile laid out exactly like that block, then
             // copy it out with 16-byte stores.
             const int ob = 2 * w + 8 * (q / T2);
+            if (CL) {
+                // Row-major output: a lane holds 4 consecutive output channels of one row per accumulator
+                // quad.  Stage the 64 rows x 64 channels of the pair in the idle input tile ([row][channel],
+                // rows 144 bytes apart), then write 16 bytes per lane: 8 lanes cover one row's 128 bytes.
+                const uint16_t *bias = (const uint16_t *)a.bias;
+#pragma unroll
+                for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                    for (int pb = 0; pb < 2; ++pb) {
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4) {
+                            const int oc = 32 * bb + 8 * v4 + 4 * half; // channel within the pair's 64
+                            float f[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) f[e] = acc2[bb][pb][4 * v4 + e];
+                            if (bias) {
+                                const uint2 bv = *(const uint2 *)(bias + 32 * ob + oc);
+                                f[0] += bf16_bits_to_float((uint16_t)bv.x);
+                                f[1] += bf16_bits_to_float((uint16_t)(bv.x >> 16));
+                                f[2] += bf16_bits_to_float((uint16_t)bv.y);
+                                f[3] += bf16_bits_to_float((uint16_t)(bv.y >> 16));
+                            }
+                            uint2 pk2;
+                            pk2.x = pack_bf16x2(f[0], f[1]);
+                            pk2.y = pack_bf16x2(f[2], f[3]);
+                            *(uint2 __attribute__((may_alias)) *)&xs[(32 * pb + col) * CH_XLD + oc] = pk2;
+                        }
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
+                    }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int it = lane + 64 * i, m = it >> 3, o8 = it & 7;
+                    const i64 row = (i64)n * CH_PIX + m;
+                    if (row < a.rows)
+                        *(uint4 *)(a.out + row * C2 + 32 * ob + 8 * o8) = *(const uint4_alias *)&xs[m * CH_XLD + 8 * o8];
+                }
+                return;
+            }
             uint16_t *ys = xs + (4 * half) * HW + col;
 #pragma unroll
             for (int bb = 0; bb < 2; ++bb)
@@ -410,6 +473,26 @@ int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2)
     if (n <= 0) return st;
     PF_LAUNCH(st, "pack_chain", pack_chain_kernel, dim3((n + 255) / 256), dim3(256), s, p1, p2);
     return st;
+}
+
+int launch_linear_chain(hipStream_t s, const char *name, const ChainArgs &a, int R)
+{
+    int st = PF_OK;
+    if (a.rows <= 0) return st;
+    const dim3 grid((unsigned)((a.rows + CH_PIX - 1) / CH_PIX)), block(256);
+    if (R == 64) {
+        PF_LAUNCH(st, name, (conv_chain_kernel<1, 1, 64, 8, 8, true>), grid, block, s, a);
+    } else if (R == 128) {
+        PF_LAUNCH(st, name, (conv_chain_kernel<1, 1, 128, 8, 8, true>), grid, block, s, a);
+    } else {
+        st = PF_ERR_UNSUPPORTED;
+    }
+    return st;
+}
+
+bool linear_chain_supported(i64 n_in, i64 n_out, i64 r)
+{
+    return (r == 64 || r == 128) && n_in % 256 == 0 && n_out % 256 == 0;
 }
 
 int launch_conv_chain(hipStream_t s, const char *name, const ChainArgs &a, int N, int k1, int k2, int R)

@@ -111,7 +111,8 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int y = 2 * j + half, pair = w + 4 * p;
-                    st.bfr[p][j] = load_row<WC>(a.B + ((i64)img * a.Nc + n0 + 32 * (pair < NPAIR ? pair : 0) + col) * HW, y, H, W);
+                    const int ch = n0 + 32 * (pair < NPAIR ? pair : 0) + col;
+                    st.bfr[p][j] = load_row<WC>(a.B + ((i64)img * a.Nc + ch) * HW, y, H, W);
                 }
         }
 #pragma unroll

@@ -1,6 +1,8 @@
 // Factorized fully connected layer (paper Section 2.1): Y = (X V) U^T + bias and its
 // gradients, plus the dense comparator.  Host-side validation, workspace planning and
 // dispatch; the any-shape path composes the guarded tile GEMM.
+#include "pf_conv_chain.h"
+#include "pf_conv_wgrad.h"
 #include "pf_gemm.h"
 
 namespace pf {
@@ -25,6 +27,39 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *src, float
                                               red[3][threadIdx.x];
 }
 
+// bf16, cols a multiple of 8: a thread owns 8 neighbouring columns (one 16-byte load per row) and every 32nd
+// row of the chunk; the 32 row-lanes of a column group are added through LDS in a fixed order.
+__global__ __launch_bounds__(256) void colsum_partial_bf16x8_kernel(const uint16_t *src, float *partial, int rows, int cols,
+                                                                     i64 ld, int rows_per_chunk)
+{
+    __shared__ float red[32][64 + 1];
+    const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3; // column group within the block's 64 columns, row lane
+    const int c0 = blockIdx.x * 64 + 8 * cg;
+    const int rbeg = blockIdx.y * rows_per_chunk, rend = min(rows, rbeg + rows_per_chunk);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (c0 < cols) {
+#pragma unroll 4
+        for (int r = rbeg + rl; r < rend; r += 32) {
+            const uint4 v = *(const uint4 *)(src + (i64)r * ld + c0);
+            const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += __uint_as_float(d[e] << 16);
+                acc[2 * e + 1] += __uint_as_float(d[e] & 0xffff0000u);
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[rl][8 * cg + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < 64 && blockIdx.x * 64 + threadIdx.x < cols) {
+        float sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) sum += red[q][threadIdx.x];
+        partial[(i64)blockIdx.y * cols + blockIdx.x * 64 + threadIdx.x] = sum;
+    }
+}
+
 int colsum_chunks(i64 rows)
 {
     i64 c = (rows + 511) / 512;
@@ -40,8 +75,13 @@ int launch_colsum(hipStream_t stream, const T *src, float *partial, float *out, 
     const int chunks = colsum_chunks(rows);
     const int per = (int)((rows + chunks - 1) / chunks);
     dim3 grid((unsigned)((cols + 63) / 64), chunks);
-    PF_LAUNCH(status, "colsum_partial", (colsum_partial_kernel<T>), grid, dim3(256), stream, src, partial, (int)rows,
-              (int)cols, ld, per);
+    if (sizeof(T) == 2 && cols % 8 == 0 && ld % 8 == 0) {
+        PF_LAUNCH(status, "colsum_partial", colsum_partial_bf16x8_kernel, grid, dim3(256), stream,
+                  (const uint16_t *)src, partial, (int)rows, (int)cols, ld, per);
+    } else {
+        PF_LAUNCH(status, "colsum_partial", (colsum_partial_kernel<T>), grid, dim3(256), stream, src, partial,
+                  (int)rows, (int)cols, ld, per);
+    }
     if (status != PF_OK) return status;
     return launch_splitk_reduce(stream, partial, out, cols, chunks, accumulate);
 }
@@ -66,6 +106,8 @@ struct LinearPlan {
     int ks_dU, ks_dV;
     size_t fwd_bytes, bwd_bytes;
     size_t n_T, n_dT, n_part;
+    bool fused;         // bf16 and shapes the fused chain / factor-gradient kernels take
+    int wg_groups, wg_ipg; // row-tile groups of the factor-gradient kernel and tiles per group
 };
 
 static LinearPlan plan_linear(const pf_linear_desc *d)
@@ -81,6 +123,26 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     if (part_db > p.n_part) p.n_part = part_db;
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
     p.bwd_bytes = align_up(p.n_T * sizeof(float)) + align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
+    p.fused = d->dtype == PF_BF16 && linear_chain_supported(d->in, d->out, d->r);
+    p.wg_groups = p.wg_ipg = 1;
+    if (p.fused) {
+        const i64 tiles = (d->M + 63) / 64;
+        const i64 chunks = d->in / 256 + d->out / 256;
+        i64 want = 192 / chunks; // workgroups over the chip; each keeps two 64-row tiles in flight
+        want = want < 1 ? 1 : want > 32 ? 32 : want;
+        if (want > tiles) want = tiles > 0 ? tiles : 1;
+        p.wg_ipg = (int)((tiles + want - 1) / want);
+        if (p.wg_ipg < 1) p.wg_ipg = 1;
+        p.wg_groups = (int)((tiles + p.wg_ipg - 1) / p.wg_ipg);
+        if (p.wg_groups < 1) p.wg_groups = 1;
+        const size_t wmax = (size_t)(d->in > d->out ? d->in : d->out) * d->r;
+        const size_t fwd = align_up(wmax * 2);
+        const size_t grads = (size_t)p.wg_groups * d->r * (d->in + d->out);
+        const size_t part = grads > p.n_part ? grads : p.n_part;
+        const size_t bwd = align_up(wmax * 2) + 2 * align_up(p.n_T * 2) + align_up(part * sizeof(float));
+        if (fwd > p.fwd_bytes) p.fwd_bytes = fwd;
+        if (bwd > p.bwd_bytes) p.bwd_bytes = bwd;
+    }
     return p;
 }
 
@@ -157,6 +219,67 @@ static int linear_bwd_generic(const pf_linear_desc *d, const T *X, const T *V, c
         if (st != PF_OK) return st;
     }
     if (d->has_bias && dbias) st = launch_colsum<T>(s, dY, part, dbias, M, out, out, accumulate);
+    return st;
+}
+
+// ------------------------------------------------------------- fused (bf16)
+// Y = (X V) U^T + bias on the two-stage chain kernel: stage 1 weights = V^T re-ordered into MFMA fragments,
+// stage 2 weights = U[out][r] read in place.
+static int linear_fwd_fused(const pf_linear_desc *d, const bf16_t *X, const bf16_t *V, const bf16_t *U,
+                            const bf16_t *bias, bf16_t *Y, bf16_t *T_save, Workspace &ws, hipStream_t s)
+{
+    const int in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    uint16_t *w1 = ws.take<uint16_t>((size_t)(in > out ? in : out) * r);
+    int st = launch_pack_chain(s, make_pack_w1((const uint16_t *)V, (uint4 *)w1, in, r, 1, 1, r, 0),
+                               make_pack_w2(nullptr, nullptr, out, r, 1, 0, 0, 0, 0));
+    if (st != PF_OK) return st;
+    ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, nullptr, (const uint16_t *)U, (uint16_t *)Y,
+                (uint16_t *)T_save,  in,                out,     8,                   8,
+                d->M,                d->has_bias ? bias : nullptr};
+    return launch_linear_chain(s, "linear_fwd_fused", a, r);
+}
+
+// dT = dY U, dX = dT V^T on the same kernel (stage 1 weights = U^T re-ordered, stage 2 weights = V[in][r] in
+// place); then both factor gradients in one launch, their group sums, and the bias gradient.
+static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const bf16_t *X, const bf16_t *V,
+                            const bf16_t *U, const bf16_t *dY, const bf16_t *T_saved, bf16_t *dX, float *dU, float *dV,
+                            float *dbias, int accumulate, Workspace &ws, hipStream_t s)
+{
+    const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    uint16_t *w1 = ws.take<uint16_t>((size_t)(in > out ? in : out) * r);
+    bf16_t *dT16 = ws.take<bf16_t>(p.n_T);
+    bf16_t *T16 = ws.take<bf16_t>(p.n_T);
+    const size_t grads = (size_t)p.wg_groups * r * (in + out);
+    float *part = ws.take<float>(grads > p.n_part ? grads : p.n_part);
+    int st = PF_OK;
+    if (dU && !T_saved) { // T was not saved: recompute it
+        st = launch_gemm_generic<bf16_t, true, false>(
+            "linear_T=X*V", s, GemmShape{M, r, in, 1, 1}, OpA_RowMajor<bf16_t>{X, in, 0}, OpB_KN<bf16_t>{V, r, 0, 0},
+            EpiRowMajor<bf16_t, bf16_t>{T16, nullptr, r, nullptr, 0});
+        if (st != PF_OK) return st;
+    }
+    st = launch_pack_chain(s, make_pack_w1((const uint16_t *)U, (uint4 *)w1, out, r, 1, 1, r, 0),
+                           make_pack_w2(nullptr, nullptr, in, r, 1, 0, 0, 0, 0));
+    if (st != PF_OK) return st;
+    ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, nullptr, (const uint16_t *)V, (uint16_t *)dX,
+                (uint16_t *)dT16,     out,               in,      8,                   8,
+                d->M,                 nullptr};
+    st = launch_linear_chain(s, "linear_bwd_data_fused", a, r);
+    if (st != PF_OK) return st;
+    const int tiles = (M + 63) / 64;
+    float *part_dU = part, *part_dV = part + (size_t)p.wg_groups * r * out;
+    const bf16_t *Tt = T_saved ? T_saved : T16;
+    WgradArgs a1{(const uint16_t *)Tt, (const uint16_t *)dY, dU ? part_dU : nullptr, r, out, 8, 8, tiles, p.wg_ipg,
+                 p.wg_groups,          d->M};
+    WgradArgs a2{(const uint16_t *)dT16, (const uint16_t *)X, dV ? part_dV : nullptr, r, in, 8, 8, tiles, p.wg_ipg,
+                 p.wg_groups,            d->M};
+    st = launch_linear_wgrad_pair(s, a1, a2);
+    if (st != PF_OK) return st;
+    WgradReduceArgs r0{part_dU, dU, p.wg_groups, 1, r, out, 1, r, 0, accumulate};
+    WgradReduceArgs r1{part_dV, dV, p.wg_groups, 1, r, in, 1, r, 0, accumulate};
+    st = launch_wgrad_reduce(s, r0, r1);
+    if (st != PF_OK) return st;
+    if (d->has_bias && dbias) st = launch_colsum<bf16_t>(s, dY, part, dbias, M, out, out, accumulate);
     return st;
 }
 
@@ -249,6 +372,9 @@ int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V,
     if (d->dtype == PF_F32)
         return linear_fwd_generic<float>(d, (const float *)X, (const float *)V, (const float *)U, (const float *)bias,
                                          (float *)Y, (float *)T_save, ws, s);
+    if (plan_linear(d).fused)
+        return linear_fwd_fused(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U, (const bf16_t *)bias,
+                                (bf16_t *)Y, (bf16_t *)T_save, ws, s);
     return linear_fwd_generic<bf16_t>(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U,
                                       (const bf16_t *)bias, (bf16_t *)Y, (bf16_t *)T_save, ws, s);
 }
@@ -269,6 +395,11 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
         return linear_bwd_generic<float>(d, (const float *)X, (const float *)V, (const float *)U, (const float *)dY,
                                          (const float *)T_saved, (float *)dX, (float *)dU, (float *)dV,
                                          (float *)dbias, accumulate, ws, s);
+    const LinearPlan p = plan_linear(d);
+    if (p.fused && dX && d->M > 0)
+        return linear_bwd_fused(d, p, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U, (const bf16_t *)dY,
+                                (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dU, (float *)dV, (float *)dbias,
+                                accumulate, ws, s);
     return linear_bwd_generic<bf16_t>(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U,
                                       (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dU,
                                       (float *)dV, (float *)dbias, accumulate, ws, s);
