@@ -223,6 +223,81 @@ class LinearWorkload:
         return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
 
 
+class LstmWorkload:
+    """The 2-layer factorized LSTM language model (Section 2.3, Appendix D): one step = forward through T time
+    steps and back-propagation through time, one cell call per (time step, layer)."""
+
+    def __init__(self, name, cfg, groups=1):
+        self.name, self.dtype, self.cfg, self.groups = name, "f32", cfg, groups
+
+    def describe(self):
+        c = self.cfg
+        return {"workload": self.name, "seq_len": c["T"], "batch": c["B"], "layers": c["layers"], "d": c["d"],
+                "h": c["h"], "r": c["r"], "groups": self.groups}
+
+    def flops(self):
+        c = self.cfg
+        per_cell = 6.0 * c["B"] * self.groups * c["r"] * (c["d"] + c["h"]) + 6.0 * c["B"] * c["r"] * 8 * c["h"]
+        return per_cell * c["T"] * c["layers"]
+
+    def dense_flops(self):
+        c = self.cfg
+        return 6.0 * c["B"] * 4 * c["h"] * (c["d"] + c["h"]) * c["T"] * c["layers"]
+
+    def make_set(self, i, torch, workloads):
+        c = self.cfg
+        inp = workloads.lstm_lm_inputs(c["vocab"], c["d"], c["h"], c["r"], c["layers"], c["T"], c["B"],
+                                       groups=self.groups, seed=c["seed"] * 1000 + i)
+        g = {"x": torch.from_numpy(inp["E"][inp["tokens"]]).cuda().contiguous(),  # [T, B, d] embedded inputs
+             "dH": torch.from_numpy(inp["dH_top"]).cuda().contiguous(),
+             "P": [{k: torch.from_numpy(v).cuda().contiguous() for k, v in p.items()} for p in inp["layers"]],
+             "zero": torch.zeros((c["B"], c["h"]), device="cuda")}
+        return {"lm": g}
+
+    def step(self, pf, s):
+        g = s["lm"]
+        T, L, groups = g["x"].shape[0], len(g["P"]), self.groups
+        hs, cs = [g["zero"]] * L, [g["zero"]] * L
+        saved = [[None] * T for _ in range(L)]
+        for t in range(T):
+            x = g["x"][t]
+            for l, p in enumerate(g["P"]):
+                ho, co, gates, Tx, Th = pf.pf_lowrank_lstm_cell_fwd(x, hs[l], cs[l], p["Vx"], p["Ux"], p["Vh"], p["Uh"],
+                                                                    p["bias"], groups)
+                saved[l][t] = (x, hs[l], cs[l], co, gates, Tx, Th)
+                hs[l], cs[l] = ho, co
+                x = ho
+        grads = [None] * L
+        dh_next, dc_next = [g["zero"]] * L, [g["zero"]] * L
+        for t in reversed(range(T)):
+            above = g["dH"][t]
+            for l in reversed(range(L)):
+                p = g["P"][l]
+                x, hp, cp, co, gates, Tx, Th = saved[l][t]
+                dx, dhp, dcp, grads[l] = pf.pf_lowrank_lstm_cell_bwd(x, hp, cp, co, gates, Tx, Th, p["Vx"], p["Ux"],
+                                                                     p["Vh"], p["Uh"], above + dh_next[l], dc_next[l],
+                                                                     groups, grads=grads[l])
+                dh_next[l], dc_next[l] = dhp, dcp
+                above = dx
+
+    def kernel_work(self):
+        return {}
+
+    def cpu_baseline(self, oracle, workloads, reps=1):
+        import numpy as np
+        c = self.cfg
+        a = workloads.lstm_cell_inputs(c["B"], c["d"], c["h"], c["r"], groups=self.groups, seed=c["seed"])
+        t0 = time.perf_counter()
+        n = 8
+        for _ in range(n):
+            ho, co, gates, Tx, Th = oracle.lowrank_lstm_cell_fwd(a["x"], a["h_prev"], a["c_prev"], a["Vx"], a["Ux"],
+                                                                 a["Vh"], a["Uh"], a["bias"], self.groups)
+            oracle.lowrank_lstm_cell_bwd(a["x"], a["h_prev"], a["c_prev"], co, gates, Tx, Th, a["Vx"], a["Ux"], a["Vh"],
+                                         a["Uh"], a["dh"], a["dc"], self.groups)
+        secs = time.perf_counter() - t0
+        return secs, self.flops() / (c["T"] * c["layers"]) * n, f"{n} cell steps (fwd+bwd) of one layer; the full workload is {c['T'] * c['layers']} of them"
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there is no
     figure or the kernel's source file has changed since the counters were taken."""
@@ -245,7 +320,9 @@ def make_workload(name):
         return ConvWorkload(name, cfg)
     if cfg["kind"] in ("linear", "linear_set"):
         return LinearWorkload(name, cfg)
-    raise SystemExit(f"workload {name} is not a bench workload (the LSTM stack is measured by its parity test)")
+    if cfg["kind"] == "lstm":
+        return LstmWorkload(name, cfg)
+    raise SystemExit(f"unknown workload {name}")
 
 
 def time_steps(torch, fn, sets, steps, warmup):

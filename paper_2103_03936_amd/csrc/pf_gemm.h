@@ -244,13 +244,14 @@ struct EpiGrad {
     }
 };
 
-// Epilogue for k-split partial sums: P[ks][m * ld + n] = acc  (count = M * ld per split)
+// Epilogue for k-split partial sums: P[ks][m * ld + zb * zoff + n] = acc  (count = M * ld per split)
 struct EpiPartial {
     float *p;
     i64 ld, count;
-    __device__ __forceinline__ void operator()(int m, int n, float acc, int, int ks) const
+    i64 zoff = 0;
+    __device__ __forceinline__ void operator()(int m, int n, float acc, int zb, int ks) const
     {
-        p[(i64)ks * count + (i64)m * ld + n] = acc;
+        p[(i64)ks * count + (i64)m * ld + zb * zoff + n] = acc;
     }
 };
 

@@ -8,15 +8,17 @@ namespace pf {
 __device__ __forceinline__ float sigmoidf_acc(float z) { return 1.0f / (1.0f + expf(-z)); }
 
 // z[B x 4h] pre-activations (i|f|g|o) -> gates, c, h
-__global__ __launch_bounds__(256) void lstm_pointwise_fwd_kernel(const float *z, const float *c_prev, float *h_out,
-                                                                  float *c_out, float *gates, int B, int h)
+__global__ __launch_bounds__(256) void lstm_pointwise_fwd_kernel(const float *z, const float *bias, const float *c_prev,
+                                                                  float *h_out, float *c_out, float *gates, int B, int h)
 {
     const i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (i64)B * h) return;
     const int b = (int)(idx / h), j = (int)(idx % h);
     const i64 base = (i64)b * 4 * h + j;
-    const float ig = sigmoidf_acc(z[base]), fg = sigmoidf_acc(z[base + h]);
-    const float gg = tanhf(z[base + 2 * (i64)h]), og = sigmoidf_acc(z[base + 3 * (i64)h]);
+    const float b0 = bias ? bias[j] : 0.f, b1 = bias ? bias[j + h] : 0.f, b2 = bias ? bias[j + 2 * (i64)h] : 0.f,
+                b3 = bias ? bias[j + 3 * (i64)h] : 0.f;
+    const float ig = sigmoidf_acc(z[base] + b0), fg = sigmoidf_acc(z[base + h] + b1);
+    const float gg = tanhf(z[base + 2 * (i64)h] + b2), og = sigmoidf_acc(z[base + 3 * (i64)h] + b3);
     const float c = fg * c_prev[idx] + ig * gg;
     gates[base] = ig;
     gates[base + h] = fg;
@@ -82,14 +84,33 @@ static int check_lstm_desc(const pf_lstm_desc *d)
 
 struct LstmPlan {
     size_t n_z, n_dT, fwd_bytes, bwd_bytes, n_part;
+    // k-splits of the skinny products (the batch is a handful of rows, so the contraction is spread over the chip)
+    int ks_Tx, ks_Th, ks_z, ks_dT, ks_dx, ks_dh;
 };
 static LstmPlan plan_lstm(const pf_lstm_desc *d)
 {
     LstmPlan p;
     p.n_z = (size_t)(d->B * 4 * d->h);
     p.n_dT = (size_t)(d->B * d->groups * d->r);
-    p.n_part = (size_t)colsum_chunks(d->B) * 4 * d->h;
-    p.fwd_bytes = align_up(p.n_z * sizeof(float));
+    const i64 gr = (i64)d->groups * d->r, Kz = d->groups == 4 ? d->h : 4 * d->h, nb = d->groups == 4 ? 4 : 1;
+    p.ks_Tx = choose_ksplit(d->B, gr, d->d_in);
+    p.ks_Th = choose_ksplit(d->B, gr, d->h);
+    p.ks_z = choose_ksplit(d->B, d->h, 2 * d->r, 4);
+    p.ks_dT = choose_ksplit(d->B, d->r, Kz, (int)nb);
+    p.ks_dx = choose_ksplit(d->B, d->d_in, gr);
+    p.ks_dh = choose_ksplit(d->B, d->h, gr);
+    size_t part = (size_t)colsum_chunks(d->B) * 4 * d->h;
+    auto upd = [&](size_t n) {
+        if (n > part) part = n;
+    };
+    upd((size_t)p.ks_Tx * d->B * gr);
+    upd((size_t)p.ks_Th * d->B * gr);
+    upd((size_t)p.ks_z * d->B * 4 * d->h);
+    upd((size_t)p.ks_dT * d->B * gr);
+    upd((size_t)p.ks_dx * d->B * d->d_in);
+    upd((size_t)p.ks_dh * d->B * d->h);
+    p.n_part = part;
+    p.fwd_bytes = align_up(p.n_z * sizeof(float)) + align_up(p.n_part * sizeof(float));
     p.bwd_bytes = align_up(p.n_z * sizeof(float)) + 2 * align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
     return p;
 }
@@ -100,23 +121,28 @@ static int lstm_fwd_generic(const pf_lstm_desc *d, const float *x, const float *
                             hipStream_t s)
 {
     const int B = (int)d->B, din = (int)d->d_in, h = (int)d->h, r = (int)d->r, gr = d->groups * r;
-    float *z = ws.take<float>((size_t)B * 4 * h);
-    int st = launch_gemm_generic<float, true, false>("lstm_Tx=x*Vx", s, GemmShape{B, gr, din, 1, 1},
+    const LstmPlan p = plan_lstm(d);
+    float *z = ws.take<float>(p.n_z);
+    float *part = ws.take<float>(p.n_part);
+    int st = launch_gemm_generic<float, true, false>("lstm_Tx=x*Vx", s, GemmShape{B, gr, din, 1, p.ks_Tx},
                                                      OpA_RowMajor<float>{x, din, 0}, OpB_KN<float>{Vx, gr, 0, 0},
-                                                     EpiRowMajor<float, float>{Tx, nullptr, gr, nullptr, 0});
+                                                     EpiPartial{part, gr, (i64)B * gr});
+    if (st == PF_OK) st = launch_splitk_reduce(s, part, Tx, (i64)B * gr, p.ks_Tx, 0);
     if (st != PF_OK) return st;
-    st = launch_gemm_generic<float, true, false>("lstm_Th=h*Vh", s, GemmShape{B, gr, h, 1, 1},
+    st = launch_gemm_generic<float, true, false>("lstm_Th=h*Vh", s, GemmShape{B, gr, h, 1, p.ks_Th},
                                                  OpA_RowMajor<float>{h_prev, h, 0}, OpB_KN<float>{Vh, gr, 0, 0},
-                                                 EpiRowMajor<float, float>{Th, nullptr, gr, nullptr, 0});
+                                                 EpiPartial{part, gr, (i64)B * gr});
+    if (st == PF_OK) st = launch_splitk_reduce(s, part, Th, (i64)B * gr, p.ks_Th, 0);
     if (st != PF_OK) return st;
-    st = launch_gemm_generic<float, true, true>(
-        "lstm_z=[Tx|Th]*[Ux|Uh]t", s, GemmShape{B, h, 2 * r, 4, 1},
-        OpA_LstmT{Tx, Th, r, gr, d->groups == 4 ? r : 0}, OpB_LstmU{Ux, Uh, r, h},
-        EpiRowMajor<float, float>{z, nullptr, 4 * (i64)h, d->has_bias ? bias : nullptr, h});
+    st = launch_gemm_generic<float, true, true>("lstm_z=[Tx|Th]*[Ux|Uh]t", s, GemmShape{B, h, 2 * r, 4, p.ks_z},
+                                                OpA_LstmT{Tx, Th, r, gr, d->groups == 4 ? r : 0},
+                                                OpB_LstmU{Ux, Uh, r, h},
+                                                EpiPartial{part, 4 * (i64)h, (i64)B * 4 * h, h});
+    if (st == PF_OK) st = launch_splitk_reduce(s, part, z, (i64)B * 4 * h, p.ks_z, 0);
     if (st != PF_OK) return st;
     dim3 grid((unsigned)(((i64)B * h + 255) / 256));
-    PF_LAUNCH(st, "lstm_pointwise_fwd", lstm_pointwise_fwd_kernel, grid, dim3(256), s, z, c_prev, h_out, c_out, gates,
-              B, h);
+    PF_LAUNCH(st, "lstm_pointwise_fwd", lstm_pointwise_fwd_kernel, grid, dim3(256), s, z, d->has_bias ? bias : nullptr,
+              c_prev, h_out, c_out, gates, B, h);
     return st;
 }
 
@@ -153,20 +179,22 @@ static int lstm_bwd_generic(const pf_lstm_desc *d, const float *x, const float *
         const float *U = path ? Uh : Ux;
         float *dT = path ? dTh : dTx;
         st = launch_gemm_generic<float, true, false>(path ? "lstm_dTh=dz*Uh" : "lstm_dTx=dz*Ux", s,
-                                                     GemmShape{B, r, Kz, nb, 1}, OpA_RowMajor<float>{dz, 4 * (i64)h, h},
-                                                     OpB_KN<float>{U, r, h, 0},
-                                                     EpiRowMajor<float, float>{dT, nullptr, gr, nullptr, r});
+                                                     GemmShape{B, r, Kz, nb, p.ks_dT}, OpA_RowMajor<float>{dz, 4 * (i64)h, h},
+                                                     OpB_KN<float>{U, r, h, 0}, EpiPartial{part, gr, (i64)B * gr, r});
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dT, (i64)B * gr, p.ks_dT, 0);
         if (st != PF_OK) return st;
     }
     if (dx) {
-        st = launch_gemm_generic<float, true, true>("lstm_dx=dTx*Vxt", s, GemmShape{B, din, gr, 1, 1},
+        st = launch_gemm_generic<float, true, true>("lstm_dx=dTx*Vxt", s, GemmShape{B, din, gr, 1, p.ks_dx},
                                                     OpA_RowMajor<float>{dTx, gr, 0}, OpB_NK<float>{Vx, gr, 0},
-                                                    EpiRowMajor<float, float>{dx, nullptr, din, nullptr, 0});
+                                                    EpiPartial{part, din, (i64)B * din});
+        if (st == PF_OK) st = launch_splitk_reduce(s, part, dx, (i64)B * din, p.ks_dx, 0);
         if (st != PF_OK) return st;
     }
-    st = launch_gemm_generic<float, true, true>("lstm_dh=dTh*Vht", s, GemmShape{B, h, gr, 1, 1},
+    st = launch_gemm_generic<float, true, true>("lstm_dh=dTh*Vht", s, GemmShape{B, h, gr, 1, p.ks_dh},
                                                 OpA_RowMajor<float>{dTh, gr, 0}, OpB_NK<float>{Vh, gr, 0},
-                                                EpiRowMajor<float, float>{dh_prev, nullptr, h, nullptr, 0});
+                                                EpiPartial{part, h, (i64)B * h});
+    if (st == PF_OK) st = launch_splitk_reduce(s, part, dh_prev, (i64)B * h, p.ks_dh, 0);
     if (st != PF_OK) return st;
     // dU[gate rows, :] (+)= dz[:, gate rows]^T T[:, gate's group]
     for (int path = 0; path < 2; ++path) {
