@@ -2,6 +2,7 @@
 // back-propagation through time.  Host-side validation, workspace planning and dispatch;
 // the any-shape path composes the guarded tile GEMM with two pointwise kernels.
 #include "pf_gemm.h"
+#include "pf_skinny.h"
 
 namespace pf {
 
@@ -223,6 +224,273 @@ static int lstm_bwd_generic(const pf_lstm_desc *d, const float *x, const float *
     return st;
 }
 
+
+// ------------------------------------------------------------------ small-batch path (B <= 32)
+// Seven launches per cell instead of two dozen: every product streams its factor once from all compute
+// units (pf_skinny.h); slice sums ride along with the gate arithmetic and with the gradient updates.
+
+// z = bias + sum of the pre-activation slices, then the gate arithmetic of eq. (2)
+__global__ __launch_bounds__(256) void lstm_slices_pointwise_fwd_kernel(const float *P, int nslices, i64 pcount,
+                                                                         const float *bias, const float *c_prev,
+                                                                         float *h_out, float *c_out, float *gates, int B,
+                                                                         int h)
+{
+    const i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (i64)B * h) return;
+    const int b = (int)(idx / h), j = (int)(idx % h);
+    const i64 base = (i64)b * 4 * h + j;
+    float z[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) z[g] = 0.f;
+    for (int sl = 0; sl < nslices; ++sl) {
+        const float *p = P + (i64)sl * pcount + base;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) z[g] += p[(i64)g * h];
+    }
+    if (bias) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) z[g] += bias[j + (i64)g * h];
+    }
+    const float ig = sigmoidf_acc(z[0]), fg = sigmoidf_acc(z[1]);
+    const float gg = tanhf(z[2]), og = sigmoidf_acc(z[3]);
+    const float c = fg * c_prev[idx] + ig * gg;
+    gates[base] = ig;
+    gates[base + h] = fg;
+    gates[base + 2 * (i64)h] = gg;
+    gates[base + 3 * (i64)h] = og;
+    c_out[idx] = c;
+    h_out[idx] = og * tanhf(c);
+}
+
+// (every extent of the sliced products must hold one 16-byte load: see launch_skinny_gemm)
+static bool lstm_skinny_ok(const pf_lstm_desc *d)
+{
+    return d->B > 0 && d->B <= SK_MAX_ROWS && d->d_in >= 4 && d->h >= 4 && d->r >= 4;
+}
+
+static SkinnyProb skinny_prob(const float *A, i64 lda, const float *W, i64 ldw, int K, int N, int ldp, i64 pcount)
+{
+    SkinnyProb p = {};
+    p.A = A;
+    p.W = W;
+    p.lda = lda;
+    p.ldw = ldw;
+    p.K = K;
+    p.N = N;
+    p.ldp = ldp;
+    p.pcount = pcount;
+    return p;
+}
+
+// The four launches with sliced contractions.  Each builder fills the problem list, places the slice sums
+// from `part` on (NULL when only the size is wanted) and returns the number of floats they take.
+static size_t build_T(const pf_lstm_desc *d, const float *x, const float *hp, const float *Vx, const float *Vh,
+                      float *part, SkinnyArgs &a)
+{
+    const int B = (int)d->B, gr = (int)(d->groups * d->r);
+    a = SkinnyArgs{};
+    a.M = B;
+    a.nprob = 2;
+    const i64 pc = (i64)B * gr;
+    a.p[0] = skinny_prob(x, d->d_in, Vx, gr, (int)d->d_in, gr, gr, pc);
+    a.p[1] = skinny_prob(hp, d->h, Vh, gr, (int)d->h, gr, gr, pc);
+    skinny_plan(a);
+    a.p[0].P = part;
+    a.p[1].P = part ? part + a.p[0].ksplit * pc : nullptr;
+    return (size_t)((a.p[0].ksplit + a.p[1].ksplit) * pc);
+}
+
+// z slices: the x-path problems write slices [0, ks_x), the h-path problems [ks_x, ks_x + ks_h)
+static size_t build_z(const pf_lstm_desc *d, const float *Tx, const float *Th, const float *Ux, const float *Uh,
+                      float *part, SkinnyArgs &a, int *nslices)
+{
+    const int B = (int)d->B, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
+    a = SkinnyArgs{};
+    a.M = B;
+    const i64 pc = (i64)B * 4 * h;
+    for (int path = 0; path < 2; ++path) {
+        const float *T = path ? Th : Tx, *U = path ? Uh : Ux;
+        if (G == 1) {
+            a.p[a.nprob++] = skinny_prob(T, gr, U, r, r, 4 * h, 4 * h, pc);
+        } else {
+            for (int g = 0; g < 4; ++g)
+                a.p[a.nprob++] = skinny_prob(T ? T + (i64)g * r : nullptr, gr, U ? U + (i64)g * h * r : nullptr, r, r, h,
+                                             4 * h, pc);
+        }
+    }
+    skinny_plan(a);
+    const int per = a.nprob / 2, ksx = a.p[0].ksplit, ksh = a.p[per].ksplit;
+    for (int q = 0; q < a.nprob; ++q) {
+        const int path = q / per, g = q % per;
+        a.p[q].P = part ? part + (i64)(path ? ksx : 0) * pc + (G == 4 ? (i64)g * h : 0) : nullptr;
+    }
+    *nslices = ksx + ksh;
+    return (size_t)((ksx + ksh) * pc);
+}
+
+// dT = dz U per path (per gate block when groups == 4)
+static size_t build_dT(const pf_lstm_desc *d, const float *dz, const float *Ux, const float *Uh, float *part,
+                       SkinnyArgs &a)
+{
+    const int B = (int)d->B, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
+    a = SkinnyArgs{};
+    a.M = B;
+    const i64 pc = (i64)B * gr;
+    for (int path = 0; path < 2; ++path) {
+        const float *U = path ? Uh : Ux;
+        if (G == 1) {
+            a.p[a.nprob++] = skinny_prob(dz, 4 * (i64)h, U, r, 4 * h, r, gr, pc);
+        } else {
+            for (int g = 0; g < 4; ++g)
+                a.p[a.nprob++] = skinny_prob(dz ? dz + (i64)g * h : nullptr, 4 * (i64)h, U ? U + (i64)g * h * r : nullptr,
+                                             r, h, r, gr, pc);
+        }
+    }
+    skinny_plan(a);
+    const int per = a.nprob / 2, ks = a.p[0].ksplit;
+    for (int q = 0; q < a.nprob; ++q) {
+        const int path = q / per, g = q % per;
+        a.p[q].P = part ? part + (i64)(path ? ks : 0) * pc + (G == 4 ? (i64)g * r : 0) : nullptr;
+    }
+    return (size_t)(2 * ks * pc);
+}
+
+// dx = dTx Vx^T (skipped when dx == NULL and want_dx is false), dh_prev = dTh Vh^T
+static size_t build_dxh(const pf_lstm_desc *d, bool want_dx, const float *dTx, const float *dTh, const float *Vx,
+                        const float *Vh, float *part, SkinnyArgs &a)
+{
+    const int B = (int)d->B, h = (int)d->h, gr = (int)(d->groups * d->r), din = (int)d->d_in;
+    a = SkinnyArgs{};
+    a.M = B;
+    if (want_dx) a.p[a.nprob++] = skinny_prob(dTx, gr, Vx, gr, gr, din, din, (i64)B * din);
+    a.p[a.nprob++] = skinny_prob(dTh, gr, Vh, gr, gr, h, h, (i64)B * h);
+    skinny_plan(a);
+    size_t used = 0;
+    for (int q = 0; q < a.nprob; ++q) {
+        a.p[q].P = part ? part + used : nullptr;
+        used += (size_t)(a.p[q].ksplit * a.p[q].pcount);
+    }
+    return used;
+}
+
+static SliceSumSeg slice_seg(const SkinnyProb &p, float *out, i64 ldo, int N)
+{
+    SliceSumSeg s;
+    s.P = p.P;
+    s.out = out;
+    s.pcount = p.pcount;
+    s.ldo = ldo;
+    s.ldp = p.ldp;
+    s.ksplit = p.ksplit;
+    s.N = N;
+    return s;
+}
+
+struct SkinnyLstmPlan {
+    size_t n_part_fwd, n_part_bwd, fwd_bytes, bwd_bytes;
+};
+static SkinnyLstmPlan plan_lstm_skinny(const pf_lstm_desc *d)
+{
+    SkinnyLstmPlan p;
+    SkinnyArgs a;
+    int ns;
+    const size_t f1 = build_T(d, nullptr, nullptr, nullptr, nullptr, nullptr, a);
+    const size_t f2 = build_z(d, nullptr, nullptr, nullptr, nullptr, nullptr, a, &ns);
+    p.n_part_fwd = f1 > f2 ? f1 : f2;
+    const size_t b1 = build_dT(d, nullptr, nullptr, nullptr, nullptr, a);
+    const size_t b2 = build_dxh(d, true, nullptr, nullptr, nullptr, nullptr, nullptr, a);
+    p.n_part_bwd = b1 > b2 ? b1 : b2;
+    p.fwd_bytes = align_up(p.n_part_fwd * sizeof(float));
+    p.bwd_bytes = align_up((size_t)(d->B * 4 * d->h) * sizeof(float)) +
+                  2 * align_up((size_t)(d->B * d->groups * d->r) * sizeof(float)) +
+                  align_up(p.n_part_bwd * sizeof(float));
+    return p;
+}
+
+static int lstm_fwd_skinny(const pf_lstm_desc *d, const float *x, const float *h_prev, const float *c_prev,
+                           const float *Vx, const float *Ux, const float *Vh, const float *Uh, const float *bias,
+                           float *h_out, float *c_out, float *gates, float *Tx, float *Th, Workspace &ws, hipStream_t s)
+{
+    const int B = (int)d->B, h = (int)d->h, gr = (int)(d->groups * d->r);
+    const SkinnyLstmPlan p = plan_lstm_skinny(d);
+    float *part = ws.take<float>(p.n_part_fwd);
+    SkinnyArgs a;
+    build_T(d, x, h_prev, Vx, Vh, part, a);
+    int st = launch_skinny_gemm(s, "lstm_T=[x*Vx|h*Vh]", a, false);
+    if (st != PF_OK) return st;
+    SliceSumArgs ss = {};
+    ss.M = B;
+    ss.nseg = 2;
+    ss.s[0] = slice_seg(a.p[0], Tx, gr, gr);
+    ss.s[1] = slice_seg(a.p[1], Th, gr, gr);
+    st = launch_slice_sum(s, ss);
+    if (st != PF_OK) return st;
+    int nslices = 0;
+    build_z(d, Tx, Th, Ux, Uh, part, a, &nslices);
+    st = launch_skinny_gemm(s, "lstm_z=[Tx|Th]*[Ux|Uh]t", a, true);
+    if (st != PF_OK) return st;
+    dim3 grid((unsigned)(((i64)B * h + 255) / 256));
+    PF_LAUNCH(st, "lstm_pointwise_fwd", lstm_slices_pointwise_fwd_kernel, grid, dim3(256), s, part, nslices,
+              (i64)B * 4 * h, d->has_bias ? bias : nullptr, c_prev, h_out, c_out, gates, B, h);
+    return st;
+}
+
+static int lstm_bwd_skinny(const pf_lstm_desc *d, const float *x, const float *h_prev, const float *c_prev,
+                           const float *c_out, const float *gates, const float *Tx, const float *Th, const float *Vx,
+                           const float *Ux, const float *Vh, const float *Uh, const float *dh, const float *dc_next,
+                           float *dx, float *dh_prev, float *dc_prev, float *dVx, float *dUx, float *dVh, float *dUh,
+                           float *dbias, int accumulate, Workspace &ws, hipStream_t s)
+{
+    const int B = (int)d->B, din = (int)d->d_in, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
+    const SkinnyLstmPlan p = plan_lstm_skinny(d);
+    float *dz = ws.take<float>((size_t)B * 4 * h);
+    float *dTx = ws.take<float>((size_t)B * gr);
+    float *dTh = ws.take<float>((size_t)B * gr);
+    float *part = ws.take<float>(p.n_part_bwd);
+    int st = PF_OK;
+    dim3 grid((unsigned)(((i64)B * h + 255) / 256));
+    PF_LAUNCH(st, "lstm_pointwise_bwd", lstm_pointwise_bwd_kernel, grid, dim3(256), s, gates, c_prev, c_out, dh,
+              dc_next, dz, dc_prev, B, h);
+    if (st != PF_OK) return st;
+    SkinnyArgs a;
+    build_dT(d, dz, Ux, Uh, part, a);
+    st = launch_skinny_gemm(s, "lstm_dT=dz*[Ux|Uh]", a, false);
+    if (st != PF_OK) return st;
+    SliceSumArgs ss = {};
+    ss.M = B;
+    ss.nseg = 2;
+    ss.s[0] = slice_seg(a.p[0], dTx, gr, gr);
+    ss.s[1] = slice_seg(a.p[a.nprob / 2], dTh, gr, gr);
+    st = launch_slice_sum(s, ss);
+    if (st != PF_OK) return st;
+    build_dxh(d, dx != nullptr, dTx, dTh, Vx, Vh, part, a);
+    st = launch_skinny_gemm(s, "lstm_dxh=[dTx*Vxt|dTh*Vht]", a, true);
+    if (st != PF_OK) return st;
+    ss = SliceSumArgs{};
+    ss.M = B;
+    int q = 0;
+    if (dx) ss.s[ss.nseg++] = slice_seg(a.p[q++], dx, din, din);
+    ss.s[ss.nseg++] = slice_seg(a.p[q], dh_prev, h, h);
+    // weight gradients: rank-B updates, with the slice sums of dx and dh_prev in the same launch
+    RankArgs ra = {};
+    ra.M = B;
+    ra.accumulate = accumulate;
+    for (int path = 0; path < 2; ++path) {
+        const float *T = path ? Th : Tx;
+        float *dU = path ? dUh : dUx;
+        if (G == 1) {
+            rank_add(ra, dz, 4 * (i64)h, T, gr, dU, r, 4 * h, r);
+        } else {
+            for (int g = 0; g < 4; ++g)
+                rank_add(ra, dz + (i64)g * h, 4 * (i64)h, T + (i64)g * r, gr, dU + (i64)g * h * r, r, h, r);
+        }
+    }
+    rank_add(ra, x, din, dTx, gr, dVx, gr, din, gr);
+    rank_add(ra, h_prev, h, dTh, gr, dVh, gr, h, gr);
+    if (dbias) rank_add(ra, dz, 4 * (i64)h, nullptr, 0, dbias, 1, 4 * h, 1);
+    return launch_rank_update(s, ra, ss);
+}
+
 } // namespace pf
 
 using namespace pf;
@@ -232,13 +500,13 @@ extern "C" {
 size_t pf_lowrank_lstm_cell_fwd_workspace_bytes(const pf_lstm_desc *d)
 {
     if (check_lstm_desc(d) != PF_OK) return 0;
-    return plan_lstm(d).fwd_bytes;
+    return lstm_skinny_ok(d) ? plan_lstm_skinny(d).fwd_bytes : plan_lstm(d).fwd_bytes;
 }
 
 size_t pf_lowrank_lstm_cell_bwd_workspace_bytes(const pf_lstm_desc *d)
 {
     if (check_lstm_desc(d) != PF_OK) return 0;
-    return plan_lstm(d).bwd_bytes;
+    return lstm_skinny_ok(d) ? plan_lstm_skinny(d).bwd_bytes : plan_lstm(d).bwd_bytes;
 }
 
 int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x, const void *h_prev, const void *c_prev,
@@ -251,10 +519,15 @@ int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x, const void *h
     if (!Vx || !Ux || !Vh || !Uh || (d->has_bias && !bias)) return PF_ERR_NULL;
     if (d->B > 0 && (!x || !h_prev || !c_prev || !h_out || !c_out || !gates_save || !Tx_save || !Th_save))
         return PF_ERR_NULL;
-    const size_t need = plan_lstm(d).fwd_bytes;
+    const size_t need = pf_lowrank_lstm_cell_fwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     if (d->B == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
+    if (lstm_skinny_ok(d))
+        return lstm_fwd_skinny(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)Vx,
+                               (const float *)Ux, (const float *)Vh, (const float *)Uh, (const float *)bias,
+                               (float *)h_out, (float *)c_out, (float *)gates_save, (float *)Tx_save, (float *)Th_save,
+                               ws, (hipStream_t)stream);
     return lstm_fwd_generic(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)Vx,
                             (const float *)Ux, (const float *)Vh, (const float *)Uh, (const float *)bias,
                             (float *)h_out, (float *)c_out, (float *)gates_save, (float *)Tx_save, (float *)Th_save, ws,
@@ -274,9 +547,16 @@ int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x, const void *h
     if (d->B > 0 && (!x || !h_prev || !c_prev || !c_out || !gates_saved || !Tx_saved || !Th_saved || !dh || !dh_prev ||
                      !dc_prev))
         return PF_ERR_NULL;
-    const size_t need = plan_lstm(d).bwd_bytes;
+    const size_t need = pf_lowrank_lstm_cell_bwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);
+    if (lstm_skinny_ok(d))
+        return lstm_bwd_skinny(d, (const float *)x, (const float *)h_prev, (const float *)c_prev,
+                               (const float *)c_out, (const float *)gates_saved, (const float *)Tx_saved,
+                               (const float *)Th_saved, (const float *)Vx, (const float *)Ux, (const float *)Vh,
+                               (const float *)Uh, (const float *)dh, (const float *)dc_next, (float *)dx,
+                               (float *)dh_prev, (float *)dc_prev, (float *)dVx, (float *)dUx, (float *)dVh,
+                               (float *)dUh, (float *)dbias, accumulate, ws, (hipStream_t)stream);
     return lstm_bwd_generic(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)c_out,
                             (const float *)gates_saved, (const float *)Tx_saved, (const float *)Th_saved,
                             (const float *)Vx, (const float *)Ux, (const float *)Vh, (const float *)Uh,
