@@ -54,7 +54,15 @@ __global__ void splitk_reduce_kernel(const float *partial, float *out, i64 count
     const i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
     float acc = 0.f;
-    for (int s = 0; s < ksplit; ++s) acc += partial[(i64)s * count + i];
+    int s = 0;
+    for (; s + 8 <= ksplit; s += 8) { // eight loads in flight, added in split order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(i64)(s + u) * count + i];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; s < ksplit; ++s) acc += partial[(i64)s * count + i];
     out[i] = accumulate ? (out[i] + acc) : acc;
 }
 

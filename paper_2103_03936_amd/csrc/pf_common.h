@@ -53,6 +53,28 @@ __device__ __forceinline__ bf16_t from_float<bf16_t>(float f)
     return r;
 }
 
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+
+// Transposing LDS read (ds_read_b64_tr_b16): within each group of 16 lanes, lane 4 q + c receives element c of
+// the 8-byte chunks addressed by lanes q, q + 4, q + 8, q + 12.  Pointing lane q + 4 e at &tile[m0 + e][c0 + 4 q]
+// hands lane i the four rows m0 .. m0 + 3 of column c0 + i; two such reads make one MFMA fragment:
+// the 8 consecutive rows r0 + 8 (lane / 32) + 0..7 of column c0 + lane % 32 of a row-major bf16 LDS tile.
+__device__ __forceinline__ bf16x8_t lds_frag_tr(const uint16_t *tile, int pitch, int r0, int c0, int lane)
+{
+    const int g = lane >> 4, i = lane & 15;
+    const uint16_t *p = tile + (r0 + 8 * (g >> 1) + (i >> 2)) * pitch + c0 + 16 * (g & 1) + 4 * (i & 3);
+    typedef __attribute__((address_space(3))) bf16x4_t *lds_ptr;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)p);
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(p + 4 * pitch));
+    bf16x8_t r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        r[e] = lo[e];
+        r[4 + e] = hi[e];
+    }
+    return r;
+}
+
 // ------------------------------------------------------------ host helpers
 int set_hip_error(hipError_t e); // records e for pf_last_hip_error(), returns PF_ERR_LAUNCH
 

@@ -21,12 +21,21 @@ struct WgradReduceArgs {
     int accumulate;
 };
 
+// out[c] (+)= sum over tiles of partial[tile][c]; cols a multiple of 32
+struct ColsumTilesArgs {
+    const float *partial;
+    float *out;
+    int tiles, cols, accumulate;
+};
+
 bool wgrad_supported(int M, int Nc, int H, int W, int k, int stride, int pad);
 int wgrad_nchunk(int M, int k, int which); // B channels per workgroup; which = 1 / 2: first / second problem of a pair
 // Both filter gradients in one launch: a1 = the k1 x k1 stage, a2 = the 1x1 stage (partial == NULL skips one).
 int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const WgradArgs &a2);
 // The fully connected layer: A[rows][M], B[rows][Nc] row-major; Out[m][n] = sum_rows A[row][m] B[row][n].
 int launch_linear_wgrad_pair(hipStream_t s, const WgradArgs &a1, const WgradArgs &a2);
-int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1);
+// cs (nullable): a column-sum problem for extra blocks of the same launch
+int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1,
+                        const ColsumTilesArgs *cs = nullptr);
 
 } // namespace pf

@@ -222,8 +222,36 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pair_kernel(WgradArgs a1, W
 }
 
 // out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]; four consecutive n per thread
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, WgradReduceArgs r1, int blocks0)
+// The blocks past blocks01 add up per-tile column sums instead (a bias gradient): 32 columns per block,
+// eight threads per column take every eighth tile, and their sums are added in a fixed order.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, WgradReduceArgs r1, int blocks0,
+                                                            ColsumTilesArgs cs, int blocks01)
 {
+    if ((int)blockIdx.x >= blocks01) {
+        __shared__ float part[8][32];
+        const int tc = threadIdx.x & 31, tg = threadIdx.x >> 5;
+        const int colm = (blockIdx.x - blocks01) * 32 + tc;
+        const float *p = cs.partial + colm;
+        float acc = 0.f;
+        int t = tg;
+        for (; t + 56 < cs.tiles; t += 64) { // eight loads in flight
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[(i64)(t + 8 * u) * cs.cols];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; t < cs.tiles; t += 8) acc += p[(i64)t * cs.cols];
+        part[tg][tc] = acc;
+        __syncthreads();
+        if (tg == 0) {
+            float sum = 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += part[u][tc];
+            cs.out[colm] = cs.accumulate ? cs.out[colm] + sum : sum;
+        }
+        return;
+    }
     const bool second = (int)blockIdx.x >= blocks0;
     const WgradReduceArgs r = second ? r1 : r0;
     const i64 i4 = (i64)(blockIdx.x - (second ? blocks0 : 0)) * 256 + threadIdx.x;
@@ -309,13 +337,17 @@ int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const Wgr
     return PF_ERR_UNSUPPORTED;
 }
 
-int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1)
+int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1, const ColsumTilesArgs *cs)
 {
     int st = PF_OK;
     const i64 c0 = r0.out ? (i64)r0.taps * r0.M * r0.Nc : 0, c1 = r1.out ? (i64)r1.taps * r1.M * r1.Nc : 0;
     const int b0 = (int)((c0 / 4 + 255) / 256), b1 = (int)((c1 / 4 + 255) / 256);
-    if (b0 + b1 == 0) return st;
-    PF_LAUNCH(st, "wgrad_reduce", wgrad_reduce_kernel, dim3(b0 + b1), dim3(256), s, r0, r1, b0);
+    ColsumTilesArgs c = {};
+    if (cs && cs->out && cs->tiles > 0) c = *cs;
+    if (c.cols % 32 != 0) return PF_ERR_UNSUPPORTED;
+    const int b2 = c.cols / 32;
+    if (b0 + b1 + b2 == 0) return st;
+    PF_LAUNCH(st, "wgrad_reduce", wgrad_reduce_kernel, dim3(b0 + b1 + b2), dim3(256), s, r0, r1, b0, c, b0 + b1);
     return st;
 }
 

@@ -2,6 +2,7 @@
 // gradients, plus the dense comparator.  Host-side validation, workspace planning and
 // dispatch; the any-shape path composes the guarded tile GEMM.
 #include "pf_conv_chain.h"
+#include "pf_linear_chain.h"
 #include "pf_conv_wgrad.h"
 #include "pf_gemm.h"
 
@@ -107,6 +108,8 @@ struct LinearPlan {
     size_t fwd_bytes, bwd_bytes;
     size_t n_T, n_dT, n_part;
     bool fused;         // bf16 and shapes the fused chain / factor-gradient kernels take
+    bool chain2;        // ... and the rank the 32-row chain kernel is built for: no weight re-ordering pass
+    size_t n_colsum;    // per-tile column sums of dY (bias gradient), floats
     int wg_groups, wg_ipg; // row-tile groups of the factor-gradient kernel and tiles per group
 };
 
@@ -124,6 +127,8 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
     p.bwd_bytes = align_up(p.n_T * sizeof(float)) + align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
     p.fused = d->dtype == PF_BF16 && linear_chain_supported(d->in, d->out, d->r);
+    p.chain2 = p.fused && linear_chain2_supported(d->in, d->out, d->r);
+    p.n_colsum = p.chain2 ? (size_t)((d->M + LC_ROWS - 1) / LC_ROWS) * d->out : 0;
     p.wg_groups = p.wg_ipg = 1;
     if (p.fused) {
         const i64 tiles = (d->M + 63) / 64;
@@ -139,7 +144,8 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
         const size_t fwd = align_up(wmax * 2);
         const size_t grads = (size_t)p.wg_groups * d->r * (d->in + d->out);
         const size_t part = grads > p.n_part ? grads : p.n_part;
-        const size_t bwd = align_up(wmax * 2) + 2 * align_up(p.n_T * 2) + align_up(part * sizeof(float));
+        const size_t bwd = align_up(wmax * 2) + 2 * align_up(p.n_T * 2) + align_up(part * sizeof(float)) +
+                           align_up(p.n_colsum * sizeof(float));
         if (fwd > p.fwd_bytes) p.fwd_bytes = fwd;
         if (bwd > p.bwd_bytes) p.bwd_bytes = bwd;
     }
@@ -229,6 +235,12 @@ static int linear_fwd_fused(const pf_linear_desc *d, const bf16_t *X, const bf16
                             const bf16_t *bias, bf16_t *Y, bf16_t *T_save, Workspace &ws, hipStream_t s)
 {
     const int in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    if (linear_chain2_supported(in, out, r)) {
+        LinChainArgs c{(const uint16_t *)X, (const uint16_t *)V, (const uint16_t *)U,
+                       d->has_bias ? (const uint16_t *)bias : nullptr, (uint16_t *)Y, (uint16_t *)T_save, nullptr,
+                       d->M, in, out};
+        return launch_linear_chain2(s, "linear_fwd_fused", c);
+    }
     uint16_t *w1 = ws.take<uint16_t>((size_t)(in > out ? in : out) * r);
     int st = launch_pack_chain(s, make_pack_w1((const uint16_t *)V, (uint4 *)w1, in, r, 1, 1, r, 0),
                                make_pack_w2(nullptr, nullptr, out, r, 1, 0, 0, 0, 0));
@@ -251,6 +263,8 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
     bf16_t *T16 = ws.take<bf16_t>(p.n_T);
     const size_t grads = (size_t)p.wg_groups * r * (in + out);
     float *part = ws.take<float>(grads > p.n_part ? grads : p.n_part);
+    float *colsum = p.chain2 ? ws.take<float>(p.n_colsum) : nullptr;
+    const bool want_db = d->has_bias && dbias;
     int st = PF_OK;
     if (dU && !T_saved) { // T was not saved: recompute it
         st = launch_gemm_generic<bf16_t, true, false>(
@@ -258,13 +272,19 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
             EpiRowMajor<bf16_t, bf16_t>{T16, nullptr, r, nullptr, 0});
         if (st != PF_OK) return st;
     }
-    st = launch_pack_chain(s, make_pack_w1((const uint16_t *)U, (uint4 *)w1, out, r, 1, 1, r, 0),
-                           make_pack_w2(nullptr, nullptr, in, r, 1, 0, 0, 0, 0));
-    if (st != PF_OK) return st;
-    ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, nullptr, (const uint16_t *)V, (uint16_t *)dX,
-                (uint16_t *)dT16,     out,               in,      8,                   8,
-                d->M,                 nullptr};
-    st = launch_linear_chain(s, "linear_bwd_data_fused", a, r);
+    if (p.chain2) {
+        LinChainArgs c{(const uint16_t *)dY, (const uint16_t *)U, (const uint16_t *)V, nullptr, (uint16_t *)dX,
+                       (uint16_t *)dT16, want_db ? colsum : nullptr, d->M, out, in};
+        st = launch_linear_chain2(s, "linear_bwd_data_fused", c);
+    } else {
+        st = launch_pack_chain(s, make_pack_w1((const uint16_t *)U, (uint4 *)w1, out, r, 1, 1, r, 0),
+                               make_pack_w2(nullptr, nullptr, in, r, 1, 0, 0, 0, 0));
+        if (st != PF_OK) return st;
+        ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, nullptr, (const uint16_t *)V, (uint16_t *)dX,
+                    (uint16_t *)dT16,     out,               in,      8,                   8,
+                    d->M,                 nullptr};
+        st = launch_linear_chain(s, "linear_bwd_data_fused", a, r);
+    }
     if (st != PF_OK) return st;
     const int tiles = (M + 63) / 64;
     float *part_dU = part, *part_dV = part + (size_t)p.wg_groups * r * out;
@@ -277,9 +297,11 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
     if (st != PF_OK) return st;
     WgradReduceArgs r0{part_dU, dU, p.wg_groups, 1, r, out, 1, r, 0, accumulate};
     WgradReduceArgs r1{part_dV, dV, p.wg_groups, 1, r, in, 1, r, 0, accumulate};
-    st = launch_wgrad_reduce(s, r0, r1);
+    // (the chain kernel left one row of column sums of dY per 32-row tile: the bias gradient rides along)
+    const ColsumTilesArgs cs{colsum, dbias, (M + LC_ROWS - 1) / LC_ROWS, out, accumulate};
+    st = launch_wgrad_reduce(s, r0, r1, want_db && p.chain2 ? &cs : nullptr);
     if (st != PF_OK) return st;
-    if (d->has_bias && dbias) st = launch_colsum<bf16_t>(s, dY, part, dbias, M, out, out, accumulate);
+    if (want_db && !p.chain2) st = launch_colsum<bf16_t>(s, dY, part, dbias, M, out, out, accumulate);
     return st;
 }
 

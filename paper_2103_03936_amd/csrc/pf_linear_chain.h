@@ -1,0 +1,32 @@
+// Fully connected low-rank layer as one kernel (bf16 in, fp32 accumulate), both factors read in place:
+//     mid[rows][R] = in[rows][C1] * W1[C1][R],   out[rows][C2] = mid * W2[C2][R]^T (+ bias)
+//   forward  (Section 2.1): in = X,  W1 = V,  W2 = U, mid = T  (kept on chip, copied out once for backward)
+//   backward data:          in = dY, W1 = U,  W2 = V, mid = dT
+// A workgroup owns 32 rows.  The contraction of stage 1 runs over the rows of W1, the slow index of a
+// row-major factor, so W1 passes through LDS as it is and the MFMA fragments come out of it with the
+// transposing LDS read; W2 is already contraction-fast and goes from global memory straight to registers.
+#pragma once
+
+#include "pf_common.h"
+
+namespace pf {
+
+struct LinChainArgs {
+    const uint16_t *in;   // [rows][C1] bf16
+    const uint16_t *W1;   // [C1][R] bf16
+    const uint16_t *W2;   // [C2][R] bf16
+    const uint16_t *bias; // [C2] bf16, nullable
+    uint16_t *out;        // [rows][C2] bf16
+    uint16_t *mid_save;   // [rows][R] bf16, nullable
+    float *colsum;        // [row tiles][C1] column sums of `in` per row tile, nullable
+    i64 rows;
+    int C1, C2;
+};
+
+constexpr int LC_ROWS = 32; // rows per workgroup
+
+// R == 128, C1 and C2 multiples of 256
+bool linear_chain2_supported(i64 n_in, i64 n_out, i64 r);
+int launch_linear_chain2(hipStream_t s, const char *name, const LinChainArgs &a);
+
+} // namespace pf

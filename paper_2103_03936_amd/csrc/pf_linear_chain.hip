@@ -1,0 +1,228 @@
+// Fused fully connected low-rank layer: see pf_linear_chain.h.
+//
+// Workgroup = 4 wavefronts, 32 rows.
+//   stage 1: wavefront w owns rho block w (32 of the 128 rank channels) over the whole contraction, which is
+//            cut into chunks of 128.  A chunk of the input rows [32][128] and of W1 [128][128] is copied to
+//            LDS (16-byte loads, register rings 4 and 2 chunks deep so that HBM and L2 latency are covered,
+//            two LDS buffers, one barrier per chunk).  Per 16-deep k-step: one 16-byte LDS read for the row
+//            fragment, two transposing reads for the W1 fragment, one MFMA.
+//   stage 2: the 32 x 128 intermediate goes to LDS in bf16 and every wavefront keeps its 8 fragments in
+//            registers; wavefront w owns a quarter of the output blocks, two at a time, W2 fragments are
+//            16-byte global loads prefetched one pair ahead.  The output pair is turned row-major through a
+//            per-wavefront LDS patch and leaves as 16-byte stores.
+#include "pf_linear_chain.h"
+
+namespace pf {
+
+// native vectors (plain SSA values for the compiler, unlike the uint4 struct)
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef u32x4_t __attribute__((may_alias)) uint4_alias;
+typedef u32x2_t __attribute__((may_alias)) uint2_alias;
+
+constexpr int LC_R = 128;          // rank
+constexpr int LC_KC = 128;         // contraction chunk of stage 1
+constexpr int LC_XP = LC_KC + 8;   // LDS pitch (elements) of the row chunk: 272 bytes
+constexpr int LC_VP = LC_R + 16;   // of the W1 chunk: 288 bytes (32 mod 128, what the transposing read likes)
+constexpr int LC_TP = LC_R + 8;    // of the intermediate
+constexpr int LC_YP = 64 + 8;      // of the output patch (two 32-wide blocks)
+
+__device__ __forceinline__ bf16x8_t lc_as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
+
+__global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][LC_ROWS * LC_XP];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[2][LC_KC * LC_VP];
+    __shared__ __attribute__((aligned(16))) uint16_t Ts[LC_ROWS * LC_TP];
+    __shared__ __attribute__((aligned(16))) uint16_t Ys[4][LC_ROWS * LC_YP];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, col = lane & 31;
+    const i64 row0 = (i64)blockIdx.x * LC_ROWS;
+    const int C1 = a.C1, C2 = a.C2;
+    const int nch = C1 / LC_KC;
+
+    struct XR { // a chunk of the input rows in flight (per thread)
+        u32x4_t r[2];
+    };
+    struct VR { // a chunk of W1 in flight
+        u32x4_t r[8];
+    };
+    struct UR { // W2 fragments of a pair of output blocks, and their bias values
+        u32x2_t b[2][4];
+        u32x4_t r[2][8];
+    };
+
+    // ---- copy roles: thread -> (row or k, 16-byte column) of a chunk
+    const int cr = tid >> 4, co = tid & 15; // 16 threads per 128-element row; 16 rows per pass
+    const uint16_t *xsrc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        i64 row = row0 + cr + 16 * i;
+        if (row > a.rows - 1) row = a.rows - 1; // rows past the end re-read the last one; never stored
+        xsrc[i] = a.in + row * C1 + 8 * co;
+    }
+    const uint16_t *vsrc = a.W1 + (i64)cr * LC_R + 8 * co;
+
+    // Loads are unconditional, so that the compiler can count them exactly when it places the waits:
+    // a chunk index past the end re-reads the last chunk, and what it brings is never multiplied.
+    auto load_x = [&](XR &x, int c) __attribute__((always_inline)) {
+        c = min(c, nch - 1);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) x.r[i] = *(const uint4_alias *)(xsrc[i] + c * LC_KC);
+    };
+    auto load_v = [&](VR &v, int c) __attribute__((always_inline)) {
+        c = min(c, nch - 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v.r[i] = *(const uint4_alias *)(vsrc + ((i64)c * LC_KC + 16 * i) * LC_R);
+    };
+
+    // ---- stage 2 operands: W2 fragments of a pair of output blocks, straight from global memory
+    const int obw = C2 / 128; // output blocks per wavefront
+    auto load_u = [&](UR &u, int g) __attribute__((always_inline)) {
+        g = min(g, obw / 2 - 1);
+        // bias first: it is needed first, and loads return in order (no bias: any 8 readable bytes, masked below)
+        const uint16_t *bsrc = a.bias ? a.bias + 32 * (w * obw + 2 * g) + 4 * half : a.W2;
+        const unsigned bmask = a.bias ? 0xffffffffu : 0u;
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u32x2_t t = *(const uint2_alias *)(a.bias ? bsrc + 32 * bi + 8 * q : bsrc);
+                u.b[bi][q] = u32x2_t{t.x & bmask, t.y & bmask};
+            }
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi) {
+            const uint16_t *p = a.W2 + (i64)(32 * (w * obw + 2 * g + bi) + col) * LC_R + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) u.r[bi][ks] = *(const uint4_alias *)(p + 16 * ks);
+        }
+    };
+
+    XR x0, x1, x2, x3;
+    VR v0, v1;
+    UR ua, ub;
+    load_x(x0, 0);
+    load_v(v0, 0);
+    load_x(x1, 1);
+    load_v(v1, 1);
+    load_x(x2, 2);
+    load_x(x3, 3);
+    load_u(ua, 0);
+
+    f32x16_t acc0, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+
+    auto step = [&](XR &xr, VR &vr, int c, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *(uint4_alias *)&Xs[buf][(cr + 16 * i) * LC_XP + 8 * co] = xr.r[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(uint4_alias *)&Vs[buf][(cr + 16 * i) * LC_VP + 8 * co] = vr.r[i];
+        load_x(xr, c + 4);
+        load_v(vr, c + 2);
+        __syncthreads(); // one barrier per chunk: the buffer rewritten next was last read two chunks ago
+        if (c >= nch) return; // uniform; past the end only the copies above ran
+        if (a.colsum && tid < LC_KC) { // column sums of the valid rows of this chunk (bias gradient)
+            const i64 left = a.rows - row0;
+            const int nr = left < LC_ROWS ? (int)left : LC_ROWS;
+            float s = 0.f;
+            for (int r = 0; r < nr; ++r) s += bf16_bits_to_float(Xs[buf][r * LC_XP + tid]);
+            a.colsum[(i64)blockIdx.x * C1 + c * LC_KC + tid] = s;
+        }
+#pragma unroll
+        for (int ks = 0; ks < LC_KC / 16; ++ks) {
+            const bf16x8_t xf = lc_as_bf16x8(*(const uint4_alias *)&Xs[buf][col * LC_XP + 16 * ks + 8 * half]);
+            const bf16x8_t vf = lds_frag_tr(&Vs[buf][0], LC_VP, 16 * ks, 32 * w, lane);
+            if (ks & 1)
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, xf, acc1, 0, 0, 0);
+            else
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, xf, acc0, 0, 0, 0);
+        }
+    };
+    for (int c = 0; c < nch; c += 4) {
+        step(x0, v0, c, 0);
+        step(x1, v1, c + 1, 1);
+        step(x2, v0, c + 2, 0);
+        step(x3, v1, c + 3, 1);
+    }
+
+    // ---- intermediate -> LDS (bf16, row-major): lane holds row `col`, rho = 32 w + 8 q + 4 half + 0..3
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        u32x2_t pk;
+        pk.x = pack_bf16x2(acc0[4 * q] + acc1[4 * q], acc0[4 * q + 1] + acc1[4 * q + 1]);
+        pk.y = pack_bf16x2(acc0[4 * q + 2] + acc1[4 * q + 2], acc0[4 * q + 3] + acc1[4 * q + 3]);
+        *(uint2_alias *)&Ts[col * LC_TP + 32 * w + 8 * q + 4 * half] = pk;
+    }
+    __syncthreads();
+    if (a.mid_save) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = cr + 16 * i;
+            if (row0 + r < a.rows)
+                *(uint4_alias *)(a.mid_save + (row0 + r) * LC_R + 8 * co) = *(const uint4_alias *)&Ts[r * LC_TP + 8 * co];
+        }
+    }
+    bf16x8_t tf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) tf[ks] = lc_as_bf16x8(*(const uint4_alias *)&Ts[col * LC_TP + 16 * ks + 8 * half]);
+
+    // ---- stage 2: pairs of output blocks
+    auto pair = [&](const UR &ur, int g) __attribute__((always_inline)) {
+        if (2 * g >= obw) return;
+        const int ob0 = w * obw + 2 * g;
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi) {
+            f32x16_t y;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) y[v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lc_as_bf16x8(ur.r[bi][ks]), tf[ks], y, 0, 0, 0);
+            // lane holds row `col`, outputs o = 32 (ob0 + bi) + 8 q + 4 half + 0..3
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u32x2_t bb = ur.b[bi][q];
+                const float b[4] = {__uint_as_float(bb.x << 16), __uint_as_float(bb.x & 0xffff0000u),
+                                    __uint_as_float(bb.y << 16), __uint_as_float(bb.y & 0xffff0000u)};
+                u32x2_t pk;
+                pk.x = pack_bf16x2(y[4 * q] + b[0], y[4 * q + 1] + b[1]);
+                pk.y = pack_bf16x2(y[4 * q + 2] + b[2], y[4 * q + 3] + b[3]);
+                *(uint2_alias *)&Ys[w][col * LC_YP + 32 * bi + 8 * q + 4 * half] = pk;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // the patch [32 rows][64 outputs] leaves as 16-byte stores: 8 lanes per row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
+            const u32x4_t v = *(const uint4_alias *)&Ys[w][r * LC_YP + 8 * ch];
+            if (row0 + r < a.rows) *(uint4_alias *)(a.out + (row0 + r) * C2 + 32 * ob0 + 8 * ch) = v;
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    for (int g = 0; 2 * g < obw; g += 2) {
+        load_u(ub, g + 1);
+        pair(ua, g);
+        load_u(ua, g + 2);
+        pair(ub, g + 1);
+    }
+}
+
+bool linear_chain2_supported(i64 n_in, i64 n_out, i64 r)
+{
+    return r == LC_R && n_in > 0 && n_out > 0 && n_in % 256 == 0 && n_out % 256 == 0 && n_in <= (1 << 20) &&
+           n_out <= (1 << 20);
+}
+
+int launch_linear_chain2(hipStream_t s, const char *name, const LinChainArgs &a)
+{
+    int st = PF_OK;
+    if (a.rows <= 0) return st;
+    if (!linear_chain2_supported(a.C1, a.C2, LC_R)) return PF_ERR_UNSUPPORTED;
+    const i64 tiles = (a.rows + LC_ROWS - 1) / LC_ROWS;
+    if (tiles > 0x7fffffffLL) return PF_ERR_SHAPE;
+    PF_LAUNCH(st, name, linear_chain2_kernel, dim3((unsigned)tiles), dim3(256), s, a);
+    return st;
+}
+
+} // namespace pf

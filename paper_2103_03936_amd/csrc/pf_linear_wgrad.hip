@@ -15,28 +15,9 @@
 namespace pf {
 
 typedef uint4 __attribute__((may_alias)) uint4_alias;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-
 constexpr int LW_ROWS = 64;  // rows per tile
 constexpr int LW_COLS = 256; // B columns per workgroup
 constexpr int LW_BP = LW_COLS + 16; // LDS row pitch (elements) of the B tile: 544 bytes, 32 mod 128
-
-// 8 consecutive rows (r0 + 8 half + 0..7) of column c0 + lane % 32 of a row-major LDS tile as one MFMA fragment
-__device__ __forceinline__ bf16x8_t lds_frag_tr(const uint16_t *tile, int pitch, int r0, int c0, int lane)
-{
-    const int g = lane >> 4, i = lane & 15;
-    const uint16_t *p = tile + (r0 + 8 * (g >> 1) + (i >> 2)) * pitch + c0 + 16 * (g & 1) + 4 * (i & 3);
-    typedef __attribute__((address_space(3))) bf16x4_t *lds_ptr;
-    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)p);
-    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(p + 4 * pitch));
-    bf16x8_t r;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        r[e] = lo[e];
-        r[4 + e] = hi[e];
-    }
-    return r;
-}
 
 // MB: 32-row blocks of rho (M = 32 MB = the rank, 64 or 128).
 template <int MB>

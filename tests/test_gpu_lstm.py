@@ -14,6 +14,8 @@ CELLS = [
     (1, 1, 1, 1),
     (3, 5, 4, 2),
     (20, 70, 50, 13),
+    (32, 37, 29, 7),    # small-batch path: every extent ragged
+    (7, 130, 260, 129),  # several column tiles and contraction slices, all with tails
     (33, 96, 128, 32),
     (20, 1500, 1500, 375),  # the language model's layer shape (Appendix D)
 ]
