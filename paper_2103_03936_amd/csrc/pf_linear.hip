@@ -128,7 +128,7 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     p.bwd_bytes = align_up(p.n_T * sizeof(float)) + align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
     p.fused = d->dtype == PF_BF16 && linear_chain_supported(d->in, d->out, d->r);
     p.chain2 = p.fused && linear_chain2_supported(d->in, d->out, d->r);
-    p.n_colsum = p.chain2 ? (size_t)((d->M + LC_ROWS - 1) / LC_ROWS) * d->out : 0;
+    p.n_colsum = p.chain2 ? (size_t)(2 * ((d->M + LC_ROWS - 1) / LC_ROWS)) * d->out : 0;
     p.wg_groups = p.wg_ipg = 1;
     if (p.fused) {
         const i64 tiles = (d->M + 63) / 64;
@@ -297,8 +297,8 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
     if (st != PF_OK) return st;
     WgradReduceArgs r0{part_dU, dU, p.wg_groups, 1, r, out, 1, r, 0, accumulate};
     WgradReduceArgs r1{part_dV, dV, p.wg_groups, 1, r, in, 1, r, 0, accumulate};
-    // (the chain kernel left one row of column sums of dY per 32-row tile: the bias gradient rides along)
-    const ColsumTilesArgs cs{colsum, dbias, (M + LC_ROWS - 1) / LC_ROWS, out, accumulate};
+    // (the chain kernel left two rows of column sums of dY per 32-row tile: the bias gradient rides along)
+    const ColsumTilesArgs cs{colsum, dbias, 2 * ((M + LC_ROWS - 1) / LC_ROWS), out, accumulate};
     st = launch_wgrad_reduce(s, r0, r1, want_db && p.chain2 ? &cs : nullptr);
     if (st != PF_OK) return st;
     if (want_db && !p.chain2) st = launch_colsum<bf16_t>(s, dY, part, dbias, M, out, out, accumulate);

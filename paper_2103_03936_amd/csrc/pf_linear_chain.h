@@ -18,7 +18,7 @@ struct LinChainArgs {
     const uint16_t *bias; // [C2] bf16, nullable
     uint16_t *out;        // [rows][C2] bf16
     uint16_t *mid_save;   // [rows][R] bf16, nullable
-    float *colsum;        // [row tiles][C1] column sums of `in` per row tile, nullable
+    float *colsum;        // [2 * row tiles][C1] column sums of `in` per 16 rows, nullable
     i64 rows;
     int C1, C2;
 };

@@ -29,6 +29,9 @@ constexpr int LC_YP = 64 + 8;      // of the output patch (two 32-wide blocks)
 
 __device__ __forceinline__ bf16x8_t lc_as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
 
+// NP: pairs of output blocks per wavefront (C2 / 256) when it is one of 1, 2, 4, 8 -- then stage 2 is fully
+// unrolled and its W2 fragments are fetched two pairs ahead, the first two during stage 1; NP == 0: any C2.
+template <int NP>
 __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][LC_ROWS * LC_XP];
@@ -65,21 +68,34 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
 
     // Loads are unconditional, so that the compiler can count them exactly when it places the waits:
     // a chunk index past the end re-reads the last chunk, and what it brings is never multiplied.
+    // Workgroups walk the chunks (and, in stage 2, the output-block pairs) from different starting points, so
+    // that they do not all ask the same L2 channel for the same factor rows at the same moment.  Workgroups
+    // are dealt round-robin to the 8 XCDs, each with its own L2: neighbours within an XCD are 8 apart.
+    const int rot1 = (blockIdx.x >> 3) % nch;
+    auto chunk_of = [&](int c) __attribute__((always_inline)) {
+        c = min(c, nch - 1) + rot1;
+        return c >= nch ? c - nch : c;
+    };
     auto load_x = [&](XR &x, int c) __attribute__((always_inline)) {
-        c = min(c, nch - 1);
+        c = chunk_of(c);
 #pragma unroll
         for (int i = 0; i < 2; ++i) x.r[i] = *(const uint4_alias *)(xsrc[i] + c * LC_KC);
     };
     auto load_v = [&](VR &v, int c) __attribute__((always_inline)) {
-        c = min(c, nch - 1);
+        c = chunk_of(c);
 #pragma unroll
         for (int i = 0; i < 8; ++i) v.r[i] = *(const uint4_alias *)(vsrc + ((i64)c * LC_KC + 16 * i) * LC_R);
     };
 
     // ---- stage 2 operands: W2 fragments of a pair of output blocks, straight from global memory
     const int obw = C2 / 128; // output blocks per wavefront
+    const int rot2 = (blockIdx.x >> 3) % (obw / 2);
+    auto pair_of = [&](int g) __attribute__((always_inline)) {
+        g = min(g, obw / 2 - 1) + rot2;
+        return g >= obw / 2 ? g - obw / 2 : g;
+    };
     auto load_u = [&](UR &u, int g) __attribute__((always_inline)) {
-        g = min(g, obw / 2 - 1);
+        g = pair_of(g);
         // bias first: it is needed first, and loads return in order (no bias: any 8 readable bytes, masked below)
         const uint16_t *bsrc = a.bias ? a.bias + 32 * (w * obw + 2 * g) + 4 * half : a.W2;
         const unsigned bmask = a.bias ? 0xffffffffu : 0u;
@@ -90,44 +106,52 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
                 const u32x2_t t = *(const uint2_alias *)(a.bias ? bsrc + 32 * bi + 8 * q : bsrc);
                 u.b[bi][q] = u32x2_t{t.x & bmask, t.y & bmask};
             }
+        // W2 rows as they lie in memory: 16 lanes fetch one 256-byte row, an instruction four rows (a lane per
+        // row, which is what the MFMA wants, would touch 64 cache lines per instruction instead of 8)
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi) {
-            const uint16_t *p = a.W2 + (i64)(32 * (w * obw + 2 * g + bi) + col) * LC_R + 8 * half;
+            const uint16_t *p = a.W2 + (i64)(32 * (w * obw + 2 * g + bi) + (lane >> 4)) * LC_R + 8 * (lane & 15);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) u.r[bi][ks] = *(const uint4_alias *)(p + 16 * ks);
+            for (int j = 0; j < 8; ++j) u.r[bi][j] = *(const uint4_alias *)(p + (i64)4 * j * LC_R);
         }
     };
 
     XR x0, x1, x2, x3;
     VR v0, v1;
-    UR ua, ub;
+    UR ur[3];
+    // Only what the first two chunks need is requested up front; the rest follows once chunk 0 is in LDS,
+    // so that the first MFMA does not wait behind a long queue of requests.
     load_x(x0, 0);
     load_v(v0, 0);
     load_x(x1, 1);
     load_v(v1, 1);
-    load_x(x2, 2);
-    load_x(x3, 3);
-    load_u(ua, 0);
 
     f32x16_t acc0, acc1;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
 
-    auto step = [&](XR &xr, VR &vr, int c, int buf) __attribute__((always_inline)) {
+    auto step = [&](XR &xr, VR &vr, int c, int buf, auto extra) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) *(uint4_alias *)&Xs[buf][(cr + 16 * i) * LC_XP + 8 * co] = xr.r[i];
 #pragma unroll
         for (int i = 0; i < 8; ++i) *(uint4_alias *)&Vs[buf][(cr + 16 * i) * LC_VP + 8 * co] = vr.r[i];
+        extra(0);
         load_x(xr, c + 4);
         load_v(vr, c + 2);
+        extra(1);
         __syncthreads(); // one barrier per chunk: the buffer rewritten next was last read two chunks ago
         if (c >= nch) return; // uniform; past the end only the copies above ran
-        if (a.colsum && tid < LC_KC) { // column sums of the valid rows of this chunk (bias gradient)
+        if (a.colsum) { // column sums of the valid rows of this chunk (bias gradient): 16 rows per thread
             const i64 left = a.rows - row0;
             const int nr = left < LC_ROWS ? (int)left : LC_ROWS;
+            const int cc = tid & (LC_KC - 1), hr = tid >> 7;
             float s = 0.f;
-            for (int r = 0; r < nr; ++r) s += bf16_bits_to_float(Xs[buf][r * LC_XP + tid]);
-            a.colsum[(i64)blockIdx.x * C1 + c * LC_KC + tid] = s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v = bf16_bits_to_float(Xs[buf][(16 * hr + r) * LC_XP + cc]);
+                s += 16 * hr + r < nr ? v : 0.f;
+            }
+            a.colsum[((i64)2 * blockIdx.x + hr) * C1 + chunk_of(c) * LC_KC + cc] = s;
         }
 #pragma unroll
         for (int ks = 0; ks < LC_KC / 16; ++ks) {
@@ -139,11 +163,26 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, xf, acc0, 0, 0, 0);
         }
     };
-    for (int c = 0; c < nch; c += 4) {
-        step(x0, v0, c, 0);
-        step(x1, v1, c + 1, 1);
-        step(x2, v0, c + 2, 0);
-        step(x3, v1, c + 3, 1);
+    auto none = [](int) __attribute__((always_inline)) {};
+    // first round: the remaining start-up requests are slipped in (stage-2 operands last: they are needed last)
+    step(x0, v0, 0, 0, [&](int when) __attribute__((always_inline)) {
+        if (when == 0) {
+            load_x(x2, 2);
+            load_x(x3, 3);
+        } else {
+            load_u(ur[0], 0);
+        }
+    });
+    step(x1, v1, 1, 1, [&](int when) __attribute__((always_inline)) {
+        if (when == 1 && NP != 1) load_u(ur[1], 1);
+    });
+    step(x2, v0, 2, 0, none);
+    step(x3, v1, 3, 1, none);
+    for (int c = 4; c < nch; c += 4) {
+        step(x0, v0, c, 0, none);
+        step(x1, v1, c + 1, 1, none);
+        step(x2, v0, c + 2, 0, none);
+        step(x3, v1, c + 3, 1, none);
     }
 
     // ---- intermediate -> LDS (bf16, row-major): lane holds row `col`, rho = 32 w + 8 q + 4 half + 0..3
@@ -168,25 +207,42 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
     for (int ks = 0; ks < 8; ++ks) tf[ks] = lc_as_bf16x8(*(const uint4_alias *)&Ts[col * LC_TP + 16 * ks + 8 * half]);
 
     // ---- stage 2: pairs of output blocks
-    auto pair = [&](const UR &ur, int g) __attribute__((always_inline)) {
+    uint16_t *Us = &Vs[0][0] + w * (64 * LC_TP); // 64 rows of W2 per wavefront
+    static_assert(4 * 64 * LC_TP <= 2 * LC_KC * LC_VP, "the W2 patches must fit in the W1 buffers");
+    auto pair = [&](const UR &u, int g) __attribute__((always_inline)) {
         if (2 * g >= obw) return;
-        const int ob0 = w * obw + 2 * g;
+        const int ob0 = w * obw + 2 * pair_of(g);
+        f32x16_t y[2];
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) y[bi][v] = 0.f;
+        // rows -> MFMA fragments through this wavefront's patch of LDS (the W1 buffers are free by now)
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                *(uint4_alias *)&Us[(32 * bi + 4 * j + (lane >> 4)) * LC_TP + 8 * (lane & 15)] = u.r[bi][j];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi) { // two independent accumulators, alternating
+                const bf16x8_t uf = lc_as_bf16x8(*(const uint4_alias *)&Us[(32 * bi + col) * LC_TP + 16 * ks + 8 * half]);
+                y[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(uf, tf[ks], y[bi], 0, 0, 0);
+            }
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi) {
-            f32x16_t y;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) y[v] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lc_as_bf16x8(ur.r[bi][ks]), tf[ks], y, 0, 0, 0);
             // lane holds row `col`, outputs o = 32 (ob0 + bi) + 8 q + 4 half + 0..3
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const u32x2_t bb = ur.b[bi][q];
+                const u32x2_t bb = u.b[bi][q];
                 const float b[4] = {__uint_as_float(bb.x << 16), __uint_as_float(bb.x & 0xffff0000u),
                                     __uint_as_float(bb.y << 16), __uint_as_float(bb.y & 0xffff0000u)};
                 u32x2_t pk;
-                pk.x = pack_bf16x2(y[4 * q] + b[0], y[4 * q + 1] + b[1]);
-                pk.y = pack_bf16x2(y[4 * q + 2] + b[2], y[4 * q + 3] + b[3]);
+                pk.x = pack_bf16x2(y[bi][4 * q] + b[0], y[bi][4 * q + 1] + b[1]);
+                pk.y = pack_bf16x2(y[bi][4 * q + 2] + b[2], y[bi][4 * q + 3] + b[3]);
                 *(uint2_alias *)&Ys[w][col * LC_YP + 32 * bi + 8 * q + 4 * half] = pk;
             }
         }
@@ -200,11 +256,19 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
         }
         __builtin_amdgcn_wave_barrier();
     };
-    for (int g = 0; 2 * g < obw; g += 2) {
-        load_u(ub, g + 1);
-        pair(ua, g);
-        load_u(ua, g + 2);
-        pair(ub, g + 1);
+    if (NP > 0) {
+#pragma unroll
+        for (int g = 0; g < NP; ++g) {
+            if (g + 2 < NP) load_u(ur[(g + 2) % 3], g + 2);
+            pair(ur[g % 3], g);
+        }
+    } else { // any number of pairs: one pair ahead, requests past the end repeat the last pair
+        for (int g = 0; 2 * g < obw; g += 2) {
+            pair(ur[0], g);
+            load_u(ur[0], g + 2);
+            pair(ur[1], g + 1);
+            load_u(ur[1], g + 3);
+        }
     }
 }
 
@@ -221,7 +285,14 @@ int launch_linear_chain2(hipStream_t s, const char *name, const LinChainArgs &a)
     if (!linear_chain2_supported(a.C1, a.C2, LC_R)) return PF_ERR_UNSUPPORTED;
     const i64 tiles = (a.rows + LC_ROWS - 1) / LC_ROWS;
     if (tiles > 0x7fffffffLL) return PF_ERR_SHAPE;
-    PF_LAUNCH(st, name, linear_chain2_kernel, dim3((unsigned)tiles), dim3(256), s, a);
+    const dim3 grid((unsigned)tiles), block(256);
+    switch (a.C2 / 256) {
+    case 1: PF_LAUNCH(st, name, linear_chain2_kernel<1>, grid, block, s, a); break;
+    case 2: PF_LAUNCH(st, name, linear_chain2_kernel<2>, grid, block, s, a); break;
+    case 4: PF_LAUNCH(st, name, linear_chain2_kernel<4>, grid, block, s, a); break;
+    case 8: PF_LAUNCH(st, name, linear_chain2_kernel<8>, grid, block, s, a); break;
+    default: PF_LAUNCH(st, name, linear_chain2_kernel<0>, grid, block, s, a); break;
+    }
     return st;
 }
 

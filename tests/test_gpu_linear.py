@@ -21,6 +21,7 @@ SHAPES = [
     (150, 256, 512, 64),   # fused-kernel shapes with a ragged last row tile
     (257, 512, 256, 128),
     (1000, 256, 256, 128),
+    (100, 768, 1024, 128),  # fused kernel: four output-block pairs per wavefront forward, three backward
 ]
 
 
