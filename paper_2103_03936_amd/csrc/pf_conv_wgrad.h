@@ -33,7 +33,7 @@ int wgrad_nchunk(int M, int k, int which); // B channels per workgroup; which = 
 // Both filter gradients in one launch: a1 = the k1 x k1 stage, a2 = the 1x1 stage (partial == NULL skips one).
 int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const WgradArgs &a2);
 // The fully connected layer: A[rows][M], B[rows][Nc] row-major; Out[m][n] = sum_rows A[row][m] B[row][n].
-int launch_linear_wgrad_pair(hipStream_t s, const WgradArgs &a1, const WgradArgs &a2);
+int launch_linear_wgrad_pair(hipStream_t s, const WgradArgs &a1, const WgradArgs &a2, int cols = 256);
 // cs (nullable): a column-sum problem for extra blocks of the same launch
 int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradReduceArgs &r1,
                         const ColsumTilesArgs *cs = nullptr);

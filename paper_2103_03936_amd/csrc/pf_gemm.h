@@ -161,6 +161,7 @@ inline int launch_gemm_generic(const char *name, hipStream_t stream, GemmShape s
 inline int choose_ksplit(i64 M, i64 N, i64 K, int batch = 1)
 {
     i64 tiles = ((M + GEMM_BM - 1) / GEMM_BM) * ((N + GEMM_BN - 1) / GEMM_BN) * batch;
+    if (tiles <= 0) return 1; // empty product
     i64 want = (512 + tiles - 1) / tiles;
     i64 kmax = (K + 4 * GEMM_BK - 1) / (4 * GEMM_BK); // at least 4 k-steps per split
     if (want > kmax) want = kmax;

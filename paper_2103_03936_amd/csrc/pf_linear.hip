@@ -111,6 +111,7 @@ struct LinearPlan {
     bool chain2;        // ... and the rank the 32-row chain kernel is built for: no weight re-ordering pass
     size_t n_colsum;    // per-tile column sums of dY (bias gradient), floats
     int wg_groups, wg_ipg; // row-tile groups of the factor-gradient kernel and tiles per group
+    int wg_cols;           // columns per workgroup of that kernel
 };
 
 static LinearPlan plan_linear(const pf_linear_desc *d)
@@ -130,12 +131,18 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     p.chain2 = p.fused && linear_chain2_supported(d->in, d->out, d->r);
     p.n_colsum = p.chain2 ? (size_t)(2 * ((d->M + LC_ROWS - 1) / LC_ROWS)) * d->out : 0;
     p.wg_groups = p.wg_ipg = 1;
+    p.wg_cols = 256;
     if (p.fused) {
         const i64 tiles = (d->M + 63) / 64;
-        const i64 chunks = d->in / 256 + d->out / 256;
-        i64 want = 192 / chunks; // workgroups over the chip; each keeps two 64-row tiles in flight
-        want = want < 1 ? 1 : want > 32 ? 32 : want;
+        i64 chunks = d->in / 256 + d->out / 256;
+        i64 want = 256 / chunks; // workgroups over the chip; each keeps two 64-row tiles in flight
+        want = want < 1 ? 1 : want > 32 ? 32 : want; // (the cap bounds the partial sums the groups write)
         if (want > tiles) want = tiles > 0 ? tiles : 1;
+        p.wg_cols = 256;
+        if (chunks * want < 200) { // too few workgroups for the chip: narrower column tiles
+            p.wg_cols = 128;
+            chunks *= 2;
+        }
         p.wg_ipg = (int)((tiles + want - 1) / want);
         if (p.wg_ipg < 1) p.wg_ipg = 1;
         p.wg_groups = (int)((tiles + p.wg_ipg - 1) / p.wg_ipg);
@@ -293,7 +300,7 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
                  p.wg_groups,          d->M};
     WgradArgs a2{(const uint16_t *)dT16, (const uint16_t *)X, dV ? part_dV : nullptr, r, in, 8, 8, tiles, p.wg_ipg,
                  p.wg_groups,            d->M};
-    st = launch_linear_wgrad_pair(s, a1, a2);
+    st = launch_linear_wgrad_pair(s, a1, a2, p.wg_cols);
     if (st != PF_OK) return st;
     WgradReduceArgs r0{part_dU, dU, p.wg_groups, 1, r, out, 1, r, 0, accumulate};
     WgradReduceArgs r1{part_dV, dV, p.wg_groups, 1, r, in, 1, r, 0, accumulate};

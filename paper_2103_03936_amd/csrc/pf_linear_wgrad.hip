@@ -16,11 +16,10 @@ namespace pf {
 
 typedef uint4 __attribute__((may_alias)) uint4_alias;
 constexpr int LW_ROWS = 64;  // rows per tile
-constexpr int LW_COLS = 256; // B columns per workgroup
-constexpr int LW_BP = LW_COLS + 16; // LDS row pitch (elements) of the B tile: 544 bytes, 32 mod 128
 
-// MB: 32-row blocks of rho (M = 32 MB = the rank, 64 or 128).
-template <int MB>
+// MB: 32-row blocks of rho (M = 32 MB = the rank, 64 or 128).  LW_COLS: B columns per workgroup, 256 or 128
+// (the narrower tile doubles the number of workgroups when the layer is small).
+template <int MB, int LW_COLS>
 __global__ __launch_bounds__(256, 1) void linear_wgrad_pair_kernel(WgradArgs a1, WgradArgs a2, int nx1, int nx2, int nwg1)
 {
     // Both factor gradients in one launch: problem 1 in the first nwg1 workgroups, problem 2 in the rest.
@@ -30,8 +29,9 @@ __global__ __launch_bounds__(256, 1) void linear_wgrad_pair_kernel(WgradArgs a1,
     const int bx = bidx % nx, g = bidx / nx;
     constexpr int M = 32 * MB;
     constexpr int AP = M + 16;          // LDS row pitch of the A tile (288 or 160 bytes: 32 mod 128)
+    constexpr int LW_BP = LW_COLS + 16; // LDS row pitch (elements) of the B tile: 32 bytes mod 128
     constexpr int RW = 2;               // rho blocks per wavefront
-    constexpr int CW = MB;              // column blocks per wavefront (8 MB blocks over 4 wavefronts, RW each)
+    constexpr int CW = (LW_COLS / 32) * MB / 8; // column blocks per wavefront (MB x LW_COLS / 32 blocks over 4 wavefronts)
     constexpr int AV = LW_ROWS * M / 8 / 256;       // 16-byte vectors of the A tile per thread (4 or 2)
     constexpr int BV = LW_ROWS * LW_COLS / 8 / 256; // of the B tile (8)
     __shared__ __attribute__((aligned(16))) uint16_t As[2][LW_ROWS * AP];
@@ -125,20 +125,25 @@ __global__ __launch_bounds__(256, 1) void linear_wgrad_pair_kernel(WgradArgs a1,
 }
 
 // a1, a2: A[rows][M], B[rows][Nc] row-major bf16, N_img = number of 64-row tiles, Nc a multiple of 256,
-// M = 64 or 128; partial == NULL skips a problem.
-int launch_linear_wgrad_pair(hipStream_t s, const WgradArgs &a1, const WgradArgs &a2)
+// M = 64 or 128; partial == NULL skips a problem.  cols: B columns per workgroup, 256 or 128.
+int launch_linear_wgrad_pair(hipStream_t s, const WgradArgs &a1, const WgradArgs &a2, int cols)
 {
     int st = PF_OK;
     if (a1.N_img <= 0) return st;
-    const int nx1 = a1.partial ? a1.Nc / LW_COLS : 0, nx2 = a2.partial ? a2.Nc / LW_COLS : 0;
+    if (cols != 256 && cols != 128) return PF_ERR_UNSUPPORTED;
+    const int nx1 = a1.partial ? a1.Nc / cols : 0, nx2 = a2.partial ? a2.Nc / cols : 0;
     const int nwg1 = nx1 * a1.groups, nwg2 = nx2 * a2.groups;
     if (nwg1 + nwg2 == 0) return st;
     const dim3 grid(nwg1 + nwg2), block(256);
     const int x1 = nx1 > 0 ? nx1 : 1, x2 = nx2 > 0 ? nx2 : 1;
-    if (a1.M == 64) {
-        PF_LAUNCH(st, "linear_wgrad_pair", (linear_wgrad_pair_kernel<2>), grid, block, s, a1, a2, x1, x2, nwg1);
+    if (a1.M == 64 && cols == 256) {
+        PF_LAUNCH(st, "linear_wgrad_pair", (linear_wgrad_pair_kernel<2, 256>), grid, block, s, a1, a2, x1, x2, nwg1);
+    } else if (a1.M == 64) {
+        PF_LAUNCH(st, "linear_wgrad_pair", (linear_wgrad_pair_kernel<2, 128>), grid, block, s, a1, a2, x1, x2, nwg1);
+    } else if (a1.M == 128 && cols == 256) {
+        PF_LAUNCH(st, "linear_wgrad_pair", (linear_wgrad_pair_kernel<4, 256>), grid, block, s, a1, a2, x1, x2, nwg1);
     } else if (a1.M == 128) {
-        PF_LAUNCH(st, "linear_wgrad_pair", (linear_wgrad_pair_kernel<4>), grid, block, s, a1, a2, x1, x2, nwg1);
+        PF_LAUNCH(st, "linear_wgrad_pair", (linear_wgrad_pair_kernel<4, 128>), grid, block, s, a1, a2, x1, x2, nwg1);
     } else {
         st = PF_ERR_UNSUPPORTED;
     }

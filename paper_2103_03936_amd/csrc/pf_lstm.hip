@@ -519,9 +519,9 @@ int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x, const void *h
     if (!Vx || !Ux || !Vh || !Uh || (d->has_bias && !bias)) return PF_ERR_NULL;
     if (d->B > 0 && (!x || !h_prev || !c_prev || !h_out || !c_out || !gates_save || !Tx_save || !Th_save))
         return PF_ERR_NULL;
+    if (d->B == 0) return PF_OK; // nothing to compute, nothing to check
     const size_t need = pf_lowrank_lstm_cell_fwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
-    if (d->B == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
     if (lstm_skinny_ok(d))
         return lstm_fwd_skinny(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)Vx,

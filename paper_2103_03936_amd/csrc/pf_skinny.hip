@@ -278,13 +278,30 @@ __global__ __launch_bounds__(256) void rank_update_kernel(RankArgs a, SliceSumAr
     for (int b0 = 0; b0 < a.M; b0 += SK_MAX_ROWS) {
         const int nb = min(SK_MAX_ROWS, a.M - b0);
         if (b0) __syncthreads();
-        for (int e = tid; e < nb * RK_TI; e += 256) {
-            const int b = e / RK_TI, ii = e % RK_TI;
-            As[b][ii] = i0 + ii < I ? pb.A[(i64)(b0 + b) * pb.lda + i0 + ii] : 0.f;
+        // 16-byte pieces, all of a thread's requests in flight together (rows are only 4-byte aligned)
+        if (tid < nb * (RK_TI / 4)) {
+            const int b = tid / (RK_TI / 4), i4 = 4 * (tid % (RK_TI / 4));
+            const int left = I - (i0 + i4);
+            *(f32x4_t *)&As[b][i4] = ld4n(pb.A + (i64)(b0 + b) * pb.lda + (left > 0 ? i0 + i4 : 0), left);
         }
-        for (int e = tid; e < nb * RK_TJ; e += 256) {
-            const int b = e / RK_TJ, jj = e % RK_TJ;
-            Bs[b][jj] = j0 + jj < J ? (pb.Bm ? pb.Bm[(i64)(b0 + b) * pb.ldb + j0 + jj] : 1.f) : 0.f;
+        f32x4_t bv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + 256 * q, b = e / (RK_TJ / 4), j4 = 4 * (e % (RK_TJ / 4));
+            const int left = J - (j0 + j4);
+            bv[q] = f32x4_t{1.f, 1.f, 1.f, 1.f};
+            if (e < nb * (RK_TJ / 4) && pb.Bm) bv[q] = ld4n(pb.Bm + (i64)(b0 + b) * pb.ldb + (left > 0 ? j0 + j4 : 0), left);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + 256 * q, b = e / (RK_TJ / 4), j4 = 4 * (e % (RK_TJ / 4));
+            const int left = J - (j0 + j4);
+            if (e < nb * (RK_TJ / 4)) {
+                f32x4_t v = bv[q];
+#pragma unroll
+                for (int f = 0; f < 4; ++f) v[f] = f < left ? v[f] : 0.f; // past J: zero (also for the ones column)
+                *(f32x4_t *)&Bs[b][j4] = v;
+            }
         }
         __syncthreads();
         for (int b = 0; b < nb; ++b) {

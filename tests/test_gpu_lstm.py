@@ -178,3 +178,19 @@ def test_language_model_full_size():
     for l in range(2):
         for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
             assert_close(grads[l][k], grads_o[l][k], "f32", f"layer {l} {k}")
+
+
+def test_empty_batch():
+    """B = 0: nothing to compute forward; backward zeroes the parameter gradients it owns."""
+    import paper_2103_03936_amd as pf
+    a = workloads.lstm_cell_inputs(0, 6, 5, 3, groups=1, seed=2)
+    g = {k: to_gpu(v) for k, v in a.items()}
+    h_out, c_out, gates, Tx, Th = pf.pf_lowrank_lstm_cell_fwd(g["x"], g["h_prev"], g["c_prev"], g["Vx"], g["Ux"],
+                                                              g["Vh"], g["Uh"], g["bias"], 1)
+    assert h_out.shape == (0, 5) and gates.shape == (0, 20)
+    dx, dhp, dcp, gr = pf.pf_lowrank_lstm_cell_bwd(g["x"], g["h_prev"], g["c_prev"], c_out, gates, Tx, Th, g["Vx"],
+                                                   g["Ux"], g["Vh"], g["Uh"], g["dh"], g["dc"], 1)
+    torch.cuda.synchronize()
+    assert dx.shape == (0, 6)
+    for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+        assert float(gr[k].abs().max()) == 0.0
