@@ -167,7 +167,7 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
             groups = (g.N + ipg - 1) / ipg;
         };
         split(g.C / wgrad_nchunk(g.r, g.k, 1), 128, 16, p.wg_groups, p.wg_ipg);
-        split(g.Cout / wgrad_nchunk(g.r, 1, 2), 128, 64, p.wg_groups2, p.wg_ipg2);
+        split(g.Cout / wgrad_nchunk(g.r, 1, 2), 128, 16, p.wg_groups2, p.wg_ipg2);
     }
     const i64 npix = (i64)g.N * g.Ho * g.Wo;
     p.ks_dVp = choose_ksplit(g.Cout, g.r, npix);
