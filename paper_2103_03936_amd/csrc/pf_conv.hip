@@ -157,8 +157,9 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
               wgrad_supported(g.r, g.Cout, g.H, g.W, 1, 1, 0);
     p.wg_groups = p.wg_ipg = p.wg_groups2 = p.wg_ipg2 = 1;
     if (p.wgrad && g.N > 0) {
-        // image groups: enough workgroups to cover the chip, but few partial sums to add up (the k x k
-        // partials are large, so at most 16 of them; the 1x1 partials are small, so up to 64)
+        // image groups: enough workgroups to cover the chip, but few partial sums to add up (at most 16
+        // per stage: the k x k stage then fills half the chip, the 1x1 stage an eighth, with equally long
+        // workgroups, and the group sums stay a small part of the step)
         auto split = [&](int chunks, int target, int cap, int &groups, int &ipg) {
             int want = target / (chunks > 0 ? chunks : 1);
             want = want < 1 ? 1 : want > cap ? cap : want;
