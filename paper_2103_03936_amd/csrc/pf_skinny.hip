@@ -195,30 +195,42 @@ int launch_skinny_gemm(hipStream_t s, const char *name, const SkinnyArgs &a, boo
 }
 
 // ------------------------------------------------------------------ slice sums
-__device__ __forceinline__ void slice_sum_block(const SliceSumArgs &a, int block, int nblocks)
+// A block takes 64 outputs at a time; four threads share an output, each adds every fourth slice (eight loads in
+// flight), and the four sums are added in a fixed order.  `sh` is 256 floats of LDS.
+__device__ __forceinline__ void slice_sum_block(const SliceSumArgs &a, int block, int nblocks, float *sh)
 {
+    const int e = threadIdx.x & 63, sg = threadIdx.x >> 6;
     for (int q = 0; q < a.nseg; ++q) {
-        const SliceSumSeg &sg = a.s[q];
-        const i64 count = (i64)a.M * sg.N;
-        for (i64 e = (i64)block * 256 + threadIdx.x; e < count; e += (i64)nblocks * 256) {
-            const int m = (int)(e / sg.N), n = (int)(e % sg.N);
-            const float *p = sg.P + (i64)m * sg.ldp + n;
+        const SliceSumSeg &sg_ = a.s[q];
+        const i64 count = (i64)a.M * sg_.N;
+        for (i64 base = (i64)block * 64; base < count; base += (i64)nblocks * 64) { // uniform trip count
+            const i64 idx = base + e;
+            const bool ok = idx < count;
+            const int m = (int)((ok ? idx : 0) / sg_.N), n = (int)((ok ? idx : 0) % sg_.N);
+            const float *p = sg_.P + (i64)m * sg_.ldp + n;
             float acc = 0.f;
-            int ks = 0;
-            for (; ks + 8 <= sg.ksplit; ks += 8) { // eight loads in flight, added in slice order
+            int ks = sg;
+            for (; ks + 28 < sg_.ksplit; ks += 32) {
                 float v[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = p[(i64)(ks + u) * sg.pcount];
+                for (int u = 0; u < 8; ++u) v[u] = p[(i64)(ks + 4 * u) * sg_.pcount];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) acc += v[u];
             }
-            for (; ks < sg.ksplit; ++ks) acc += p[(i64)ks * sg.pcount];
-            sg.out[(i64)m * sg.ldo + n] = acc;
+            for (; ks < sg_.ksplit; ks += 4) acc += p[(i64)ks * sg_.pcount];
+            __syncthreads();
+            sh[threadIdx.x] = acc;
+            __syncthreads();
+            if (sg == 0 && ok) sg_.out[(i64)m * sg_.ldo + n] = (sh[e] + sh[64 + e]) + (sh[128 + e] + sh[192 + e]);
         }
     }
 }
 
-__global__ __launch_bounds__(256) void slice_sum_kernel(SliceSumArgs a) { slice_sum_block(a, blockIdx.x, gridDim.x); }
+__global__ __launch_bounds__(256) void slice_sum_kernel(SliceSumArgs a)
+{
+    __shared__ float sh[256];
+    slice_sum_block(a, blockIdx.x, gridDim.x, sh);
+}
 
 static int slice_sum_blocks(const SliceSumArgs &a)
 {
@@ -227,8 +239,8 @@ static int slice_sum_blocks(const SliceSumArgs &a)
         const i64 c = (i64)a.M * a.s[q].N;
         if (c > most) most = c;
     }
-    i64 nb = (most + 255) / 256;
-    if (nb > 1024) nb = 1024;
+    i64 nb = (most + 63) / 64;
+    if (nb > 2048) nb = 2048;
     return (int)nb;
 }
 
@@ -246,12 +258,12 @@ constexpr int RK_TI = 32, RK_TJ = 128;
 
 __global__ __launch_bounds__(256) void rank_update_kernel(RankArgs a, SliceSumArgs seg, int nseg_blocks)
 {
-    if ((int)blockIdx.x >= a.nwg) { // the extra workgroups do the slice sums
-        slice_sum_block(seg, blockIdx.x - a.nwg, nseg_blocks);
-        return;
-    }
     __shared__ __attribute__((aligned(16))) float As[SK_MAX_ROWS][RK_TI];
     __shared__ __attribute__((aligned(16))) float Bs[SK_MAX_ROWS][RK_TJ];
+    if ((int)blockIdx.x >= a.nwg) { // the extra workgroups do the slice sums
+        slice_sum_block(seg, blockIdx.x - a.nwg, nseg_blocks, &Bs[0][0]);
+        return;
+    }
     int pi = 0;
 #pragma unroll
     for (int q = 1; q < RK_MAX_PROB; ++q)
