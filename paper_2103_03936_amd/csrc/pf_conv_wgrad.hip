@@ -34,6 +34,10 @@ __device__ __forceinline__ bf16x8_t wg_as_bf16x8(uint4 v)
 // Row y of one channel plane (W <= 8 pixels) as 8 bf16, zero beyond W and for y >= H; branch-free so that
 // many row loads can be in flight at once.  `plane` points at the channel's first pixel.  Rows of 8-pixel
 // images are 16-byte aligned; other widths are read element by element (indices clamped into the row).
+struct __attribute__((packed, aligned(2))) U16x8 {
+    uint16_t v[8];
+};
+
 template <int WC>
 __device__ __forceinline__ uint4 load_row(const uint16_t *plane, int y, int H, int W)
 {
@@ -41,6 +45,16 @@ __device__ __forceinline__ uint4 load_row(const uint16_t *plane, int y, int H, i
     uint4 v;
     if (WC == 8) {
         v = *(const uint4 *)(plane + 8 * yy);
+    } else if (WC == 7) {
+        // A row is 14 bytes at a 2-byte aligned address: one unaligned 16-byte load.  It reaches one element
+        // past the row, so the last row (H >= 2) is read one element early and shifted down, which keeps the
+        // load inside the plane.
+        const bool last = yy == H - 1;
+        const U16x8 t = *(const U16x8 *)(plane + 7 * yy - (last ? 1 : 0));
+        const uint32_t w0 = t.v[0] | ((uint32_t)t.v[1] << 16), w1 = t.v[2] | ((uint32_t)t.v[3] << 16),
+                       w2 = t.v[4] | ((uint32_t)t.v[5] << 16), w3 = t.v[6] | ((uint32_t)t.v[7] << 16);
+        v = last ? make_uint4((w0 >> 16) | (w1 << 16), (w1 >> 16) | (w2 << 16), (w2 >> 16) | (w3 << 16), w3 >> 16)
+                 : make_uint4(w0, w1, w2, w3 & 0xffffu);
     } else {
         const uint16_t *p = plane + W * yy;
         uint32_t e[8];
@@ -317,11 +331,14 @@ int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const Wgr
     if (nwg1 + nwg2 == 0) return st;
     const dim3 grid(nwg1 + nwg2), block(256);
     const int M = a1.M, x1 = nx1 > 0 ? nx1 : 1, x2 = nx2 > 0 ? nx2 : 1;
-    const bool sq8 = a1.H == 8 && a1.W == 8;
+    const bool sq8 = a1.H == 8 && a1.W == 8, sq7 = a1.H == 7 && a1.W == 7;
 #define PF_WGRAD_CASE(T1, MBV)                                                                                     \
     if (k1 * k1 == T1 && M == 32 * MBV) {                                                                          \
         if (sq8) {                                                                                                 \
             PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<T1, MBV, 8, 8>), grid, block, s, a1, a2, x1,  \
+                      x2, nwg1);                                                                                   \
+        } else if (sq7) {                                                                                          \
+            PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<T1, MBV, 7, 7>), grid, block, s, a1, a2, x1,  \
                       x2, nwg1);                                                                                   \
         } else {                                                                                                   \
             PF_LAUNCH(st, "conv_wgrad_pair", (conv_wgrad_pair_kernel<T1, MBV, 0, 0>), grid, block, s, a1, a2, x1,  \
