@@ -474,7 +474,7 @@ def main():
             prep = [wl.library_dense_prepare(s, torch) for s in sets[:4]]
             lms = time_steps(torch, lambda p: wl.library_dense_step(p, torch), prep, max(10, args.steps // 4), 5)
             library = {"ms_per_step": lms, "value": wl.dense_flops() / (lms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
-                       "what": "torch.nn.functional dense layer fwd+bwd, bf16, vendor library kernels",
+                       "what": f"torch.nn.functional dense layer fwd+bwd, {wl.dtype}, vendor library kernels",
                        "speedup_of_factorized": lms / ms}
         except Exception as e:  # the reference is optional
             library = {"error": repr(e)[:200]}

@@ -3,6 +3,7 @@
 // dispatch; the any-shape path composes the guarded tile GEMM.
 #include "pf_conv_chain.h"
 #include "pf_linear_chain.h"
+#include "pf_skinny.h"
 #include "pf_conv_wgrad.h"
 #include "pf_gemm.h"
 
@@ -112,7 +113,32 @@ struct LinearPlan {
     size_t n_colsum;    // per-tile column sums of dY (bias gradient), floats
     int wg_groups, wg_ipg; // row-tile groups of the factor-gradient kernel and tiles per group
     int wg_cols;           // columns per workgroup of that kernel
+    bool skinny;           // fp32 with at most 128 rows: the weight-streaming kernels of the LSTM cell
+    size_t n_part_sk;      // their slice sums, floats
 };
+
+// fp32, few rows: row blocks of up to 32 rows become the problems of one sliced streaming product
+// C[M x N] = A[M x K] W (pf_skinny.h).  Returns the floats the slice sums take; part == NULL: size only.
+static size_t build_rows(int M, const float *A, i64 lda, const float *W, i64 ldw, int K, int N, float *part,
+                         SkinnyArgs &a)
+{
+    a = SkinnyArgs{};
+    const i64 pc = (i64)M * N;
+    for (int m0 = 0; m0 < M; m0 += SK_MAX_ROWS)
+        a.p[a.nprob++] = skinny_prob(M - m0 < SK_MAX_ROWS ? M - m0 : SK_MAX_ROWS, A ? A + (i64)m0 * lda : nullptr, lda,
+                                     W, ldw, K, N, N, pc);
+    skinny_plan(a);
+    for (int q = 0; q < a.nprob; ++q) a.p[q].P = part ? part + (i64)SK_MAX_ROWS * q * N : nullptr;
+    return (size_t)(a.p[0].ksplit * pc); // every block has the same K and N, hence the same slicing
+}
+// all row blocks of a product summed in one segment
+static SliceSumSeg rows_seg(const SkinnyArgs &a, int M, float *out, const float *bias)
+{
+    SliceSumSeg sg = slice_seg(a.p[0], out, a.p[0].N, a.p[0].N);
+    sg.M = M;
+    sg.bias = bias;
+    return sg;
+}
 
 static LinearPlan plan_linear(const pf_linear_desc *d)
 {
@@ -128,6 +154,23 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
     p.bwd_bytes = align_up(p.n_T * sizeof(float)) + align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
     p.fused = d->dtype == PF_BF16 && linear_chain_supported(d->in, d->out, d->r);
+    p.skinny = d->dtype == PF_F32 && d->M > 0 && d->M <= SK_MAX_ROWS * SK_MAX_PROB / 2 && d->in >= 4 && d->out >= 4 &&
+               d->r >= 4;
+    p.n_part_sk = 0;
+    if (p.skinny) {
+        SkinnyArgs a;
+        const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
+        const size_t n1 = build_rows(M, nullptr, in, nullptr, r, in, r, nullptr, a);   // T = X V
+        const size_t n2 = build_rows(M, nullptr, r, nullptr, r, r, out, nullptr, a);   // Y = T U^T
+        const size_t n3 = build_rows(M, nullptr, out, nullptr, r, out, r, nullptr, a); // dT = dY U
+        const size_t n4 = build_rows(M, nullptr, r, nullptr, r, r, in, nullptr, a);    // dX = dT V^T
+        const size_t f = n1 > n2 ? n1 : n2, b = n3 > n4 ? n3 : n4;
+        p.n_part_sk = f > b ? f : b;
+        const size_t fwd = align_up(p.n_T * sizeof(float)) + align_up(p.n_part_sk * sizeof(float));
+        const size_t bwd = 2 * align_up(p.n_T * sizeof(float)) + align_up(p.n_part_sk * sizeof(float));
+        if (fwd > p.fwd_bytes) p.fwd_bytes = fwd;
+        if (bwd > p.bwd_bytes) p.bwd_bytes = bwd;
+    }
     p.chain2 = p.fused && linear_chain2_supported(d->in, d->out, d->r);
     p.n_colsum = p.chain2 ? (size_t)(2 * ((d->M + LC_ROWS - 1) / LC_ROWS)) * d->out : 0;
     p.wg_groups = p.wg_ipg = 1;
@@ -312,6 +355,77 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
     return st;
 }
 
+
+// ------------------------------------------------------------- fp32, few rows
+static int linear_T_skinny(const pf_linear_desc *d, const float *X, const float *V, float *T, float *part, hipStream_t s)
+{
+    const int M = (int)d->M, in = (int)d->in, r = (int)d->r;
+    SkinnyArgs a;
+    build_rows(M, X, in, V, r, in, r, part, a);
+    int st = launch_skinny_gemm(s, "linear_T=X*V", a, false);
+    if (st != PF_OK) return st;
+    SliceSumArgs ss = {};
+    ss.s[ss.nseg++] = rows_seg(a, M, T, nullptr);
+    return launch_slice_sum(s, ss);
+}
+
+static int linear_fwd_skinny(const pf_linear_desc *d, const LinearPlan &p, const float *X, const float *V, const float *U,
+                             const float *bias, float *Y, float *T_save, Workspace &ws, hipStream_t s)
+{
+    const int M = (int)d->M, out = (int)d->out, r = (int)d->r;
+    float *Tws = ws.take<float>(p.n_T);
+    float *part = ws.take<float>(p.n_part_sk);
+    float *T = T_save ? T_save : Tws;
+    int st = linear_T_skinny(d, X, V, T, part, s);
+    if (st != PF_OK) return st;
+    SkinnyArgs a;
+    build_rows(M, T, r, U, r, r, out, part, a);
+    st = launch_skinny_gemm(s, "linear_Y=T*Ut", a, true);
+    if (st != PF_OK) return st;
+    SliceSumArgs ss = {};
+    ss.s[ss.nseg++] = rows_seg(a, M, Y, d->has_bias ? bias : nullptr);
+    return launch_slice_sum(s, ss);
+}
+
+static int linear_bwd_skinny(const pf_linear_desc *d, const LinearPlan &p, const float *X, const float *V, const float *U,
+                             const float *dY, const float *T_saved, float *dX, float *dU, float *dV, float *dbias,
+                             int accumulate, Workspace &ws, hipStream_t s)
+{
+    const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    float *Tws = ws.take<float>(p.n_T);
+    float *dT = ws.take<float>(p.n_T);
+    float *part = ws.take<float>(p.n_part_sk);
+    int st = PF_OK;
+    if (dU && !T_saved) { // T was not saved: recompute it
+        st = linear_T_skinny(d, X, V, Tws, part, s);
+        if (st != PF_OK) return st;
+    }
+    const float *T = T_saved ? T_saved : Tws;
+    SkinnyArgs a;
+    build_rows(M, dY, out, U, r, out, r, part, a);
+    st = launch_skinny_gemm(s, "linear_dT=dY*U", a, false);
+    if (st != PF_OK) return st;
+    SliceSumArgs ss = {};
+    ss.s[ss.nseg++] = rows_seg(a, M, dT, nullptr);
+    st = launch_slice_sum(s, ss);
+    if (st != PF_OK) return st;
+    ss = SliceSumArgs{};
+    if (dX) {
+        build_rows(M, dT, r, V, r, r, in, part, a);
+        st = launch_skinny_gemm(s, "linear_dX=dT*Vt", a, true);
+        if (st != PF_OK) return st;
+        ss.s[ss.nseg++] = rows_seg(a, M, dX, nullptr);
+    }
+    // factor gradients are rank-M updates; the slice sums of dX ride along
+    RankArgs ra = {};
+    ra.M = M;
+    ra.accumulate = accumulate;
+    rank_add(ra, dY, out, T, r, dU, r, out, r);
+    rank_add(ra, X, in, dT, r, dV, r, in, r);
+    if (d->has_bias && dbias) rank_add(ra, dY, out, nullptr, 0, dbias, 1, out, 1);
+    return launch_rank_update(s, "linear_grads", ra, ss);
+}
+
 // ------------------------------------------------------------------ dense
 struct DensePlan {
     int ks;
@@ -398,6 +512,9 @@ int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V,
     if (d->M == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32 && plan_linear(d).skinny)
+        return linear_fwd_skinny(d, plan_linear(d), (const float *)X, (const float *)V, (const float *)U,
+                                 (const float *)bias, (float *)Y, (float *)T_save, ws, s);
     if (d->dtype == PF_F32)
         return linear_fwd_generic<float>(d, (const float *)X, (const float *)V, (const float *)U, (const float *)bias,
                                          (float *)Y, (float *)T_save, ws, s);
@@ -420,6 +537,10 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32 && plan_linear(d).skinny)
+        return linear_bwd_skinny(d, plan_linear(d), (const float *)X, (const float *)V, (const float *)U,
+                                 (const float *)dY, (const float *)T_saved, (float *)dX, (float *)dU, (float *)dV,
+                                 (float *)dbias, accumulate, ws, s);
     if (d->dtype == PF_F32)
         return linear_bwd_generic<float>(d, (const float *)X, (const float *)V, (const float *)U, (const float *)dY,
                                          (const float *)T_saved, (float *)dX, (float *)dU, (float *)dV,

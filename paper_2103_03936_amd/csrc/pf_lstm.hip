@@ -268,20 +268,6 @@ static bool lstm_skinny_ok(const pf_lstm_desc *d)
     return d->B > 0 && d->B <= SK_MAX_ROWS && d->d_in >= 4 && d->h >= 4 && d->r >= 4;
 }
 
-static SkinnyProb skinny_prob(const float *A, i64 lda, const float *W, i64 ldw, int K, int N, int ldp, i64 pcount)
-{
-    SkinnyProb p = {};
-    p.A = A;
-    p.W = W;
-    p.lda = lda;
-    p.ldw = ldw;
-    p.K = K;
-    p.N = N;
-    p.ldp = ldp;
-    p.pcount = pcount;
-    return p;
-}
-
 // The four launches with sliced contractions.  Each builder fills the problem list, places the slice sums
 // from `part` on (NULL when only the size is wanted) and returns the number of floats they take.
 static size_t build_T(const pf_lstm_desc *d, const float *x, const float *hp, const float *Vx, const float *Vh,
@@ -289,11 +275,10 @@ static size_t build_T(const pf_lstm_desc *d, const float *x, const float *hp, co
 {
     const int B = (int)d->B, gr = (int)(d->groups * d->r);
     a = SkinnyArgs{};
-    a.M = B;
     a.nprob = 2;
     const i64 pc = (i64)B * gr;
-    a.p[0] = skinny_prob(x, d->d_in, Vx, gr, (int)d->d_in, gr, gr, pc);
-    a.p[1] = skinny_prob(hp, d->h, Vh, gr, (int)d->h, gr, gr, pc);
+    a.p[0] = skinny_prob(B, x, d->d_in, Vx, gr, (int)d->d_in, gr, gr, pc);
+    a.p[1] = skinny_prob(B, hp, d->h, Vh, gr, (int)d->h, gr, gr, pc);
     skinny_plan(a);
     a.p[0].P = part;
     a.p[1].P = part ? part + a.p[0].ksplit * pc : nullptr;
@@ -306,15 +291,14 @@ static size_t build_z(const pf_lstm_desc *d, const float *Tx, const float *Th, c
 {
     const int B = (int)d->B, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
     a = SkinnyArgs{};
-    a.M = B;
     const i64 pc = (i64)B * 4 * h;
     for (int path = 0; path < 2; ++path) {
         const float *T = path ? Th : Tx, *U = path ? Uh : Ux;
         if (G == 1) {
-            a.p[a.nprob++] = skinny_prob(T, gr, U, r, r, 4 * h, 4 * h, pc);
+            a.p[a.nprob++] = skinny_prob(B, T, gr, U, r, r, 4 * h, 4 * h, pc);
         } else {
             for (int g = 0; g < 4; ++g)
-                a.p[a.nprob++] = skinny_prob(T ? T + (i64)g * r : nullptr, gr, U ? U + (i64)g * h * r : nullptr, r, r, h,
+                a.p[a.nprob++] = skinny_prob(B, T ? T + (i64)g * r : nullptr, gr, U ? U + (i64)g * h * r : nullptr, r, r, h,
                                              4 * h, pc);
         }
     }
@@ -334,15 +318,14 @@ static size_t build_dT(const pf_lstm_desc *d, const float *dz, const float *Ux, 
 {
     const int B = (int)d->B, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
     a = SkinnyArgs{};
-    a.M = B;
     const i64 pc = (i64)B * gr;
     for (int path = 0; path < 2; ++path) {
         const float *U = path ? Uh : Ux;
         if (G == 1) {
-            a.p[a.nprob++] = skinny_prob(dz, 4 * (i64)h, U, r, 4 * h, r, gr, pc);
+            a.p[a.nprob++] = skinny_prob(B, dz, 4 * (i64)h, U, r, 4 * h, r, gr, pc);
         } else {
             for (int g = 0; g < 4; ++g)
-                a.p[a.nprob++] = skinny_prob(dz ? dz + (i64)g * h : nullptr, 4 * (i64)h, U ? U + (i64)g * h * r : nullptr,
+                a.p[a.nprob++] = skinny_prob(B, dz ? dz + (i64)g * h : nullptr, 4 * (i64)h, U ? U + (i64)g * h * r : nullptr,
                                              r, h, r, gr, pc);
         }
     }
@@ -361,9 +344,8 @@ static size_t build_dxh(const pf_lstm_desc *d, bool want_dx, const float *dTx, c
 {
     const int B = (int)d->B, h = (int)d->h, gr = (int)(d->groups * d->r), din = (int)d->d_in;
     a = SkinnyArgs{};
-    a.M = B;
-    if (want_dx) a.p[a.nprob++] = skinny_prob(dTx, gr, Vx, gr, gr, din, din, (i64)B * din);
-    a.p[a.nprob++] = skinny_prob(dTh, gr, Vh, gr, gr, h, h, (i64)B * h);
+    if (want_dx) a.p[a.nprob++] = skinny_prob(B, dTx, gr, Vx, gr, gr, din, din, (i64)B * din);
+    a.p[a.nprob++] = skinny_prob(B, dTh, gr, Vh, gr, gr, h, h, (i64)B * h);
     skinny_plan(a);
     size_t used = 0;
     for (int q = 0; q < a.nprob; ++q) {
@@ -371,19 +353,6 @@ static size_t build_dxh(const pf_lstm_desc *d, bool want_dx, const float *dTx, c
         used += (size_t)(a.p[q].ksplit * a.p[q].pcount);
     }
     return used;
-}
-
-static SliceSumSeg slice_seg(const SkinnyProb &p, float *out, i64 ldo, int N)
-{
-    SliceSumSeg s;
-    s.P = p.P;
-    s.out = out;
-    s.pcount = p.pcount;
-    s.ldo = ldo;
-    s.ldp = p.ldp;
-    s.ksplit = p.ksplit;
-    s.N = N;
-    return s;
 }
 
 struct SkinnyLstmPlan {
@@ -419,7 +388,6 @@ static int lstm_fwd_skinny(const pf_lstm_desc *d, const float *x, const float *h
     int st = launch_skinny_gemm(s, "lstm_T=[x*Vx|h*Vh]", a, false);
     if (st != PF_OK) return st;
     SliceSumArgs ss = {};
-    ss.M = B;
     ss.nseg = 2;
     ss.s[0] = slice_seg(a.p[0], Tx, gr, gr);
     ss.s[1] = slice_seg(a.p[1], Th, gr, gr);
@@ -457,7 +425,6 @@ static int lstm_bwd_skinny(const pf_lstm_desc *d, const float *x, const float *h
     st = launch_skinny_gemm(s, "lstm_dT=dz*[Ux|Uh]", a, false);
     if (st != PF_OK) return st;
     SliceSumArgs ss = {};
-    ss.M = B;
     ss.nseg = 2;
     ss.s[0] = slice_seg(a.p[0], dTx, gr, gr);
     ss.s[1] = slice_seg(a.p[a.nprob / 2], dTh, gr, gr);
@@ -467,7 +434,6 @@ static int lstm_bwd_skinny(const pf_lstm_desc *d, const float *x, const float *h
     st = launch_skinny_gemm(s, "lstm_dxh=[dTx*Vxt|dTh*Vht]", a, true);
     if (st != PF_OK) return st;
     ss = SliceSumArgs{};
-    ss.M = B;
     int q = 0;
     if (dx) ss.s[ss.nseg++] = slice_seg(a.p[q++], dx, din, din);
     ss.s[ss.nseg++] = slice_seg(a.p[q], dh_prev, h, h);
@@ -488,7 +454,7 @@ static int lstm_bwd_skinny(const pf_lstm_desc *d, const float *x, const float *h
     rank_add(ra, x, din, dTx, gr, dVx, gr, din, gr);
     rank_add(ra, h_prev, h, dTh, gr, dVh, gr, h, gr);
     if (dbias) rank_add(ra, dz, 4 * (i64)h, nullptr, 0, dbias, 1, 4 * h, 1);
-    return launch_rank_update(s, ra, ss);
+    return launch_rank_update(s, "lstm_grads", ra, ss);
 }
 
 } // namespace pf

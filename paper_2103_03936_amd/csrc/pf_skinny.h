@@ -18,12 +18,12 @@ struct SkinnyProb {
     const float *W; // weights, KN: W[k * ldw + n], NK: W[n * ldw + k]
     float *P;       // slice sums, P[ks * pcount + m * ldp + n]; only n < N is written
     i64 lda, ldw, pcount;
-    int K, N, ldp;
+    int M, K, N, ldp;              // M <= 32 rows of A (and of P) belong to this problem
     int ntiles, ksplit, kper, wg0; // filled by skinny_plan
 };
 struct SkinnyArgs {
     SkinnyProb p[SK_MAX_PROB];
-    int nprob, M, nwg;
+    int nprob, nwg;
 };
 // Chooses the slicing of every problem (about `target` workgroups in all) and numbers the workgroups.
 void skinny_plan(SkinnyArgs &a, int target = 256);
@@ -32,18 +32,52 @@ int skinny_ksplit(i64 K, i64 total_tiles, int target = 256);
 inline i64 skinny_tiles(i64 N) { return (N + SK_TILE_N - 1) / SK_TILE_N; }
 int launch_skinny_gemm(hipStream_t s, const char *name, const SkinnyArgs &a, bool nk);
 
-// out[m * ldo + n] = sum over ks < ksplit of P[ks * pcount + m * ldp + n], several segments in one launch
+// out[m * ldo + n] = bias[n] + sum over ks < ksplit of P[ks * pcount + m * ldp + n], m < M; several segments in
+// one launch (bias nullable)
 struct SliceSumSeg {
-    const float *P;
+    const float *P, *bias;
     float *out;
     i64 pcount, ldo;
-    int ldp, ksplit, N;
+    int M, ldp, ksplit, N;
 };
 struct SliceSumArgs {
     SliceSumSeg s[4];
-    int nseg, M;
+    int nseg;
 };
 int launch_slice_sum(hipStream_t s, const SliceSumArgs &a);
+
+inline SkinnyProb skinny_prob(int M, const float *A, i64 lda, const float *W, i64 ldw, int K, int N, int ldp,
+                              i64 pcount)
+{
+    SkinnyProb p = {};
+    p.M = M;
+    p.A = A;
+    p.W = W;
+    p.lda = lda;
+    p.ldw = ldw;
+    p.K = K;
+    p.N = N;
+    p.ldp = ldp;
+    p.pcount = pcount;
+    return p;
+}
+
+// the slice sums of problem p into out[m * ldo + n], n < N
+inline SliceSumSeg slice_seg(const SkinnyProb &p, float *out, i64 ldo, int N)
+{
+    SliceSumSeg s;
+    s.P = p.P;
+    s.bias = nullptr;
+    s.M = p.M;
+    s.out = out;
+    s.pcount = p.pcount;
+    s.ldo = ldo;
+    s.ldp = p.ldp;
+    s.ksplit = p.ksplit;
+    s.N = N;
+    return s;
+}
+
 
 // out[i * ldo + j] (+)= sum_b A[b * lda + i] * Bm[b * ldb + j], b < M: the weight gradients of a cell are
 // rank-M updates.  Bm == NULL stands for a column of ones (a bias gradient, J = 1).
@@ -60,6 +94,6 @@ struct RankArgs {
 };
 void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, float *out, i64 ldo, int I, int J);
 // seg: optional slice sums done by extra workgroups of the same launch (nseg == 0: none)
-int launch_rank_update(hipStream_t s, const RankArgs &a, const SliceSumArgs &seg);
+int launch_rank_update(hipStream_t s, const char *name, const RankArgs &a, const SliceSumArgs &seg);
 
 } // namespace pf

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256, 1) void skinny_gemm_kernel(SkinnyArgs a)
     const float *__restrict__ A = pb.A;
     const float *__restrict__ W = pb.W;
     const i64 lda = pb.lda, ldw = pb.ldw;
-    const int K = pb.K, N = pb.N, M = a.M;
+    const int K = pb.K, N = pb.N, M = pb.M;
     const int local = blockIdx.x - pb.wg0, tile = local % pb.ntiles, ks = local / pb.ntiles;
     const int n0 = tile * SK_TILE_N;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, i = lane & 31;
@@ -180,11 +180,12 @@ void skinny_plan(SkinnyArgs &a, int target)
 int launch_skinny_gemm(hipStream_t s, const char *name, const SkinnyArgs &a, bool nk)
 {
     int st = PF_OK;
-    if (a.nwg <= 0 || a.M <= 0) return st;
-    if (a.M > SK_MAX_ROWS || a.nprob > SK_MAX_PROB) return PF_ERR_UNSUPPORTED;
+    if (a.nwg <= 0 || a.nprob <= 0) return st;
+    if (a.nprob > SK_MAX_PROB) return PF_ERR_UNSUPPORTED;
     // the kernel pulls 16-byte loads back inside the matrix by up to three elements: both extents must hold four
     for (int q = 0; q < a.nprob; ++q)
-        if (a.p[q].K < 4 || a.p[q].N < 4 || a.p[q].lda < a.p[q].K || a.p[q].ldw < (nk ? a.p[q].K : a.p[q].N))
+        if (a.p[q].M < 1 || a.p[q].M > SK_MAX_ROWS || a.p[q].K < 4 || a.p[q].N < 4 || a.p[q].lda < a.p[q].K ||
+            a.p[q].ldw < (nk ? a.p[q].K : a.p[q].N))
             return PF_ERR_UNSUPPORTED;
     if (nk) {
         PF_LAUNCH(st, name, skinny_gemm_kernel<true>, dim3(a.nwg), dim3(256), s, a);
@@ -202,7 +203,7 @@ __device__ __forceinline__ void slice_sum_block(const SliceSumArgs &a, int block
     const int e = threadIdx.x & 63, sg = threadIdx.x >> 6;
     for (int q = 0; q < a.nseg; ++q) {
         const SliceSumSeg &sg_ = a.s[q];
-        const i64 count = (i64)a.M * sg_.N;
+        const i64 count = (i64)sg_.M * sg_.N;
         for (i64 base = (i64)block * 64; base < count; base += (i64)nblocks * 64) { // uniform trip count
             const i64 idx = base + e;
             const bool ok = idx < count;
@@ -221,7 +222,9 @@ __device__ __forceinline__ void slice_sum_block(const SliceSumArgs &a, int block
             __syncthreads();
             sh[threadIdx.x] = acc;
             __syncthreads();
-            if (sg == 0 && ok) sg_.out[(i64)m * sg_.ldo + n] = (sh[e] + sh[64 + e]) + (sh[128 + e] + sh[192 + e]);
+            if (sg == 0 && ok)
+                sg_.out[(i64)m * sg_.ldo + n] =
+                    ((sh[e] + sh[64 + e]) + (sh[128 + e] + sh[192 + e])) + (sg_.bias ? sg_.bias[n] : 0.f);
         }
     }
 }
@@ -236,7 +239,7 @@ static int slice_sum_blocks(const SliceSumArgs &a)
 {
     i64 most = 0;
     for (int q = 0; q < a.nseg; ++q) {
-        const i64 c = (i64)a.M * a.s[q].N;
+        const i64 c = (i64)a.s[q].M * a.s[q].N;
         if (c > most) most = c;
     }
     i64 nb = (most + 63) / 64;
@@ -361,12 +364,12 @@ void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, fl
     ++a.nprob;
 }
 
-int launch_rank_update(hipStream_t s, const RankArgs &a, const SliceSumArgs &seg)
+int launch_rank_update(hipStream_t s, const char *name, const RankArgs &a, const SliceSumArgs &seg)
 {
     int st = PF_OK;
     const int nsb = seg.nseg > 0 ? slice_sum_blocks(seg) : 0;
     if (a.nwg + nsb <= 0) return st;
-    PF_LAUNCH(st, "lstm_grads", rank_update_kernel, dim3(a.nwg + nsb), dim3(256), s, a, seg, nsb);
+    PF_LAUNCH(st, name, rank_update_kernel, dim3(a.nwg + nsb), dim3(256), s, a, seg, nsb);
     return st;
 }
 

@@ -18,6 +18,7 @@ SHAPES = [
     (257, 96, 192, 64),
     (64, 512, 512, 128),   # VGG-19 fc17/fc18
     (70, 33, 31, 33),      # rank above min(in, out)
+    (100, 130, 260, 129),  # fp32: four row blocks on the streaming kernels, every extent ragged
     (150, 256, 512, 64),   # fused-kernel shapes with a ragged last row tile
     (257, 512, 256, 128),
     (1000, 256, 256, 128),
