@@ -248,6 +248,46 @@ def lowrank_lstm_cell_bwd(x, hprev, cprev, c_out, gates, Tx, Th, Vx, Ux, Vh, Uh,
     return dx, dhp, dcp, grads
 
 
+def lowrank_lstm_seq_fwd(x, h0, c0, Vx, Ux, Vh, Uh, bias=None, groups=1):
+    """One factorized LSTM layer over T time steps: eq. (2) applied step by step, h_t and c_t fed to step
+    t + 1.  x is [T, B, d].  Returns (h_all [T,B,h], c_all [T,B,h], gates_all [T,B,4h], Tx_all, Th_all)."""
+    T, B, d = x.shape
+    h = h0.shape[1]
+    gr = groups * Ux.shape[1]
+    h_all, c_all = np.zeros((T, B, h)), np.zeros((T, B, h))
+    gates_all, Tx_all, Th_all = np.zeros((T, B, 4 * h)), np.zeros((T, B, gr)), np.zeros((T, B, gr))
+    hp, cp = np.asarray(h0, dtype=np.float64), np.asarray(c0, dtype=np.float64)
+    for t in range(T):
+        h_all[t], c_all[t], gates_all[t], Tx_all[t], Th_all[t] = lowrank_lstm_cell_fwd(
+            x[t], hp, cp, Vx, Ux, Vh, Uh, bias, groups)
+        hp, cp = h_all[t], c_all[t]
+    return h_all, c_all, gates_all, Tx_all, Th_all
+
+
+def lowrank_lstm_seq_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux, Vh, Uh, dh_all,
+                         dhT=None, dcT=None, groups=1, grads=None):
+    """Back-propagation through time of lowrank_lstm_seq_fwd: dh_all[t] is the gradient arriving at h_t from
+    above, dhT / dcT the gradients arriving at the final state.  Steps are taken in reverse with the cell's
+    backward; parameter gradients add up over time (and onto ``grads`` if given).
+    Returns (dx_all [T,B,d], dh0, dc0, grads)."""
+    T, B, d = x.shape
+    h = h0.shape[1]
+    dx_all = np.zeros((T, B, d))
+    dh = np.array(dh_all[T - 1], dtype=np.float64) + (0.0 if dhT is None else np.asarray(dhT, dtype=np.float64))
+    dc = np.zeros((B, h)) if dcT is None else np.asarray(dcT, dtype=np.float64)
+    for t in range(T - 1, -1, -1):
+        hp = h_all[t - 1] if t > 0 else np.asarray(h0, dtype=np.float64)
+        cp = c_all[t - 1] if t > 0 else np.asarray(c0, dtype=np.float64)
+        if grads is None:  # first call creates the gradient buffers, later calls accumulate
+            dx_all[t], dhp, dc, grads = lowrank_lstm_cell_bwd(x[t], hp, cp, c_all[t], gates_all[t], Tx_all[t], Th_all[t],
+                                                            Vx, Ux, Vh, Uh, dh, dc, groups)
+        else:
+            dx_all[t], dhp, dc, grads = lowrank_lstm_cell_bwd(x[t], hp, cp, c_all[t], gates_all[t], Tx_all[t], Th_all[t],
+                                                            Vx, Ux, Vh, Uh, dh, dc, groups, grads)
+        dh = dhp + (dh_all[t - 1] if t > 0 else 0.0)
+    return dx_all, dh, dc, grads
+
+
 # ------------------------------------------------------------------- SVD
 
 def svd_split(W, r):

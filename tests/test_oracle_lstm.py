@@ -194,3 +194,46 @@ def test_printed_totals_fix_the_per_gate_reading():
     assert 4 * (d * r + r * h) + 4 * (h * r + r * h) == 4 * d * r + 12 * h * r
     # MACs per token per layer: 18 M dense, 9 M factorized per gate
     assert 4 * (d * h + h * h) == 18_000_000 and 8 * (d * r + r * h) == 9_000_000
+
+
+@pytest.mark.parametrize("groups", [1, 4])
+def test_sequence_matches_torch_lstm_and_autograd(groups):
+    """The sequence oracle (cells chained over time, BPTT with accumulated parameter gradients) against
+    torch.nn.LSTM with W = U V^T and torch autograd through the factors (library routines)."""
+    T, B, d, h, r = 5, 3, 4, 6, 2
+    rng = np.random.default_rng(77 + groups)
+    gr = groups * r
+    x = rng.standard_normal((T, B, d))
+    h0, c0 = rng.standard_normal((B, h)) * 0.5, rng.standard_normal((B, h)) * 0.5
+    Vx, Ux = rng.standard_normal((d, gr)) * 0.4, rng.standard_normal((4 * h, r)) * 0.4
+    Vh, Uh = rng.standard_normal((h, gr)) * 0.4, rng.standard_normal((4 * h, r)) * 0.4
+    bias = rng.standard_normal((4 * h,)) * 0.3
+    G, GhT, GcT = rng.standard_normal((T, B, h)), rng.standard_normal((B, h)), rng.standard_normal((B, h))
+
+    h_all, c_all, gates_all, Tx_all, Th_all = oracle.lowrank_lstm_seq_fwd(x, h0, c0, Vx, Ux, Vh, Uh, bias, groups)
+    dx_all, dh0, dc0, grads = oracle.lowrank_lstm_seq_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all,
+                                                         Vx, Ux, Vh, Uh, G, GhT, GcT, groups)
+
+    tt = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    tx, th0, tc0, tVx, tUx, tVh, tUh, tb = map(tt, (x, h0, c0, Vx, Ux, Vh, Uh, bias))
+
+    def dense(U, V):  # gate block g of W is U_g V_g^T (per-gate V when groups == 4, shared otherwise)
+        blocks = []
+        for g in range(4):
+            Vg = V[:, g * r:(g + 1) * r] if groups == 4 else V
+            blocks.append(U[g * h:(g + 1) * h] @ Vg.T)
+        return torch.cat(blocks, 0)
+
+    lstm = torch.nn.LSTM(d, h, num_layers=1, bias=True, dtype=torch.float64)
+    params = {"weight_ih_l0": dense(tUx, tVx), "weight_hh_l0": dense(tUh, tVh), "bias_ih_l0": tb,
+              "bias_hh_l0": torch.zeros(4 * h, dtype=torch.float64)}
+    out, (hT, cT) = torch.func.functional_call(lstm, params, (tx, (th0[None], tc0[None])))
+    np.testing.assert_allclose(h_all, out.detach().numpy(), rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(c_all[-1], cT[0].detach().numpy(), rtol=1e-10, atol=1e-10)
+    loss = (out * torch.tensor(G)).sum() + (hT[0] * torch.tensor(GhT)).sum() + (cT[0] * torch.tensor(GcT)).sum()
+    loss.backward()
+    np.testing.assert_allclose(dx_all, tx.grad.numpy(), rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(dh0, th0.grad.numpy(), rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(dc0, tc0.grad.numpy(), rtol=1e-9, atol=1e-9)
+    for name, tv in (("dVx", tVx), ("dUx", tUx), ("dVh", tVh), ("dUh", tUh), ("dbias", tb)):
+        np.testing.assert_allclose(grads[name], tv.grad.numpy(), rtol=1e-9, atol=1e-9, err_msg=name)
