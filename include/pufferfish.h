@@ -172,6 +172,54 @@ int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x,
                              size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ */
+/* Factorized LSTM layer over a whole sequence (Section 2.3, eq. (2)     */
+/* applied for t = 0 .. T-1 with h_t, c_t fed to step t+1), fp32.       */
+/* Same arithmetic as T calls of the cell; the input path x_t Vx Ux^T   */
+/* does not depend on the recurrence and is computed for all time steps */
+/* at once, and the parameter gradients are formed once over all steps. */
+/*   x[T,B,d_in]; h0, c0 [B,h]; factors and bias as for the cell.       */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t T, B, d_in, h, r;
+    int groups;   /* 1 or 4 */
+    int dtype;    /* PF_F32 */
+    int has_bias;
+} pf_lstm_seq_desc;
+
+size_t pf_lowrank_lstm_seq_fwd_workspace_bytes(const pf_lstm_seq_desc *d);
+size_t pf_lowrank_lstm_seq_bwd_workspace_bytes(const pf_lstm_seq_desc *d);
+
+/* Outputs h_all, c_all [T,B,h] (h_all[t] = h_t); saved for backward:
+ * gates_all[T,B,4h] (activated i|f|g|o), Tx_all, Th_all [T,B,groups r].  All
+ * device pointers, all required (bias nullable); T == 0 or B == 0: nothing is
+ * done.  Errors as for the cell. */
+int pf_lowrank_lstm_seq_fwd(const pf_lstm_seq_desc *d, const void *x,
+                            const void *h0, const void *c0, const void *Vx,
+                            const void *Ux, const void *Vh, const void *Uh,
+                            const void *bias /* nullable */, void *h_all,
+                            void *c_all, void *gates_all, void *Tx_all,
+                            void *Th_all, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/* Back-propagation through time.  dh_all[T,B,h] = dL/dh_t arriving from
+ * above at every step; dhT, dcT [B,h] = gradients arriving at the final state
+ * (NULL = 0).  Outputs dx_all[T,B,d_in] (nullable), dh0, dc0 [B,h] and the
+ * float parameter gradients (dbias nullable), overwritten or accumulated. */
+int pf_lowrank_lstm_seq_bwd(const pf_lstm_seq_desc *d, const void *x,
+                            const void *h0, const void *c0, const void *h_all,
+                            const void *c_all, const void *gates_all,
+                            const void *Tx_all, const void *Th_all,
+                            const void *Vx, const void *Ux, const void *Vh,
+                            const void *Uh, const void *dh_all,
+                            const void *dhT /* nullable */,
+                            const void *dcT /* nullable */,
+                            void *dx_all /* nullable */, void *dh0, void *dc0,
+                            void *dVx, void *dUx, void *dVh, void *dUh,
+                            void *dbias /* nullable */, int accumulate,
+                            void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/* ------------------------------------------------------------------ */
 /* Dense (un-factorized) comparators, for benchmarks only: the layers   */
 /* of Section 2.1 / 2.2 before factorization, on the same tiling code.  */
 /*   linear: W[out x in];  conv: Wd[Cout,Cin,k,k].                      */

@@ -38,6 +38,11 @@ class pf_lstm_desc(ctypes.Structure):
                 ("groups", ctypes.c_int), ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
 
 
+class pf_lstm_seq_desc(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("B", ctypes.c_int64), ("d_in", ctypes.c_int64), ("h", ctypes.c_int64),
+                ("r", ctypes.c_int64), ("groups", ctypes.c_int), ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
+
+
 EXPORTS = [
     "pf_status_string", "pf_last_hip_error", "pf_version",
     "pf_lowrank_linear_fwd_workspace_bytes", "pf_lowrank_linear_bwd_workspace_bytes",
@@ -46,6 +51,8 @@ EXPORTS = [
     "pf_lowrank_conv_fwd", "pf_lowrank_conv_bwd",
     "pf_lowrank_lstm_cell_fwd_workspace_bytes", "pf_lowrank_lstm_cell_bwd_workspace_bytes",
     "pf_lowrank_lstm_cell_fwd", "pf_lowrank_lstm_cell_bwd",
+    "pf_lowrank_lstm_seq_fwd_workspace_bytes", "pf_lowrank_lstm_seq_bwd_workspace_bytes",
+    "pf_lowrank_lstm_seq_fwd", "pf_lowrank_lstm_seq_bwd",
     "pf_dense_linear_workspace_bytes", "pf_dense_linear_fwd", "pf_dense_linear_bwd",
     "pf_dense_conv_workspace_bytes", "pf_dense_conv_fwd", "pf_dense_conv_bwd",
     "pf_timing_enable", "pf_timing_collect", "pf_timing_entry", "pf_timing_reset",
@@ -294,6 +301,54 @@ def pf_lowrank_lstm_cell_bwd(x, h_prev, c_prev, c_out, gates, Tx, Th, Vx, Ux, Vh
         ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
         "pf_lowrank_lstm_cell_bwd")
     return dx, dh_prev, dc_prev, grads
+
+
+def _lstm_seq_desc(x, h0, Ux, groups, has_bias):
+    T, B, d_in = x.shape
+    return pf_lstm_seq_desc(T, B, d_in, h0.shape[1], Ux.shape[1], groups, _dtype_code(x), 1 if has_bias else 0)
+
+
+def pf_lowrank_lstm_seq_fwd(x, h0, c0, Vx, Ux, Vh, Uh, bias=None, groups=1):
+    """One factorized LSTM layer over a sequence x[T,B,d].  Returns (h_all, c_all, gates_all, Tx_all, Th_all)."""
+    d = _lstm_seq_desc(x, h0, Ux, groups, bias is not None)
+    f32 = torch.float32
+    dev = x.device
+    h_all = torch.empty((d.T, d.B, d.h), dtype=f32, device=dev)
+    c_all = torch.empty((d.T, d.B, d.h), dtype=f32, device=dev)
+    gates_all = torch.empty((d.T, d.B, 4 * d.h), dtype=f32, device=dev)
+    Tx_all = torch.empty((d.T, d.B, groups * d.r), dtype=f32, device=dev)
+    Th_all = torch.empty((d.T, d.B, groups * d.r), dtype=f32, device=dev)
+    ws = _workspace(lib.pf_lowrank_lstm_seq_fwd_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_lowrank_lstm_seq_fwd(ctypes.byref(d), _ptr(x, f32), _ptr(h0, f32), _ptr(c0, f32), _ptr(Vx, f32),
+                                       _ptr(Ux, f32), _ptr(Vh, f32), _ptr(Uh, f32), _ptr(bias, f32), _ptr(h_all),
+                                       _ptr(c_all), _ptr(gates_all), _ptr(Tx_all), _ptr(Th_all), _ptr(ws),
+                                       ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_lstm_seq_fwd")
+    return h_all, c_all, gates_all, Tx_all, Th_all
+
+
+def pf_lowrank_lstm_seq_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux, Vh, Uh, dh_all, dhT=None,
+                            dcT=None, groups=1, need_dx=True, grads=None):
+    """Back-propagation through time.  Returns (dx_all, dh0, dc0, grads); if `grads` is given the parameter
+    gradients are accumulated into it."""
+    d = _lstm_seq_desc(x, h0, Ux, groups, True)
+    f32 = torch.float32
+    dev = x.device
+    dx_all = torch.empty_like(x) if need_dx else None
+    dh0 = torch.empty_like(h0)
+    dc0 = torch.empty_like(c0)
+    accumulate = grads is not None
+    if grads is None:
+        grads = dict(dVx=torch.empty_like(Vx), dUx=torch.empty_like(Ux), dVh=torch.empty_like(Vh),
+                     dUh=torch.empty_like(Uh), dbias=torch.empty((4 * d.h,), dtype=f32, device=dev))
+    ws = _workspace(lib.pf_lowrank_lstm_seq_bwd_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_lowrank_lstm_seq_bwd(
+        ctypes.byref(d), _ptr(x, f32), _ptr(h0, f32), _ptr(c0, f32), _ptr(h_all, f32), _ptr(c_all, f32),
+        _ptr(gates_all, f32), _ptr(Tx_all, f32), _ptr(Th_all, f32), _ptr(Vx, f32), _ptr(Ux, f32), _ptr(Vh, f32),
+        _ptr(Uh, f32), _ptr(dh_all, f32), _ptr(dhT, f32), _ptr(dcT, f32), _ptr(dx_all), _ptr(dh0), _ptr(dc0),
+        _ptr(grads["dVx"], f32), _ptr(grads["dUx"], f32), _ptr(grads["dVh"], f32), _ptr(grads["dUh"], f32),
+        _ptr(grads["dbias"], f32), ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()),
+        _stream()), "pf_lowrank_lstm_seq_bwd")
+    return dx_all, dh0, dc0, grads
 
 
 # ------------------------------------------------------------------ timing

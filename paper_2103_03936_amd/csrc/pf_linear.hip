@@ -117,29 +117,6 @@ struct LinearPlan {
     size_t n_part_sk;      // their slice sums, floats
 };
 
-// fp32, few rows: row blocks of up to 32 rows become the problems of one sliced streaming product
-// C[M x N] = A[M x K] W (pf_skinny.h).  Returns the floats the slice sums take; part == NULL: size only.
-static size_t build_rows(int M, const float *A, i64 lda, const float *W, i64 ldw, int K, int N, float *part,
-                         SkinnyArgs &a)
-{
-    a = SkinnyArgs{};
-    const i64 pc = (i64)M * N;
-    for (int m0 = 0; m0 < M; m0 += SK_MAX_ROWS)
-        a.p[a.nprob++] = skinny_prob(M - m0 < SK_MAX_ROWS ? M - m0 : SK_MAX_ROWS, A ? A + (i64)m0 * lda : nullptr, lda,
-                                     W, ldw, K, N, N, pc);
-    skinny_plan(a);
-    for (int q = 0; q < a.nprob; ++q) a.p[q].P = part ? part + (i64)SK_MAX_ROWS * q * N : nullptr;
-    return (size_t)(a.p[0].ksplit * pc); // every block has the same K and N, hence the same slicing
-}
-// all row blocks of a product summed in one segment
-static SliceSumSeg rows_seg(const SkinnyArgs &a, int M, float *out, const float *bias)
-{
-    SliceSumSeg sg = slice_seg(a.p[0], out, a.p[0].N, a.p[0].N);
-    sg.M = M;
-    sg.bias = bias;
-    return sg;
-}
-
 static LinearPlan plan_linear(const pf_linear_desc *d)
 {
     LinearPlan p;
@@ -160,10 +137,10 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     if (p.skinny) {
         SkinnyArgs a;
         const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
-        const size_t n1 = build_rows(M, nullptr, in, nullptr, r, in, r, nullptr, a);   // T = X V
-        const size_t n2 = build_rows(M, nullptr, r, nullptr, r, r, out, nullptr, a);   // Y = T U^T
-        const size_t n3 = build_rows(M, nullptr, out, nullptr, r, out, r, nullptr, a); // dT = dY U
-        const size_t n4 = build_rows(M, nullptr, r, nullptr, r, r, in, nullptr, a);    // dX = dT V^T
+        const size_t n1 = skinny_rows(M, nullptr, in, nullptr, r, in, r, nullptr, a);   // T = X V
+        const size_t n2 = skinny_rows(M, nullptr, r, nullptr, r, r, out, nullptr, a);   // Y = T U^T
+        const size_t n3 = skinny_rows(M, nullptr, out, nullptr, r, out, r, nullptr, a); // dT = dY U
+        const size_t n4 = skinny_rows(M, nullptr, r, nullptr, r, r, in, nullptr, a);    // dX = dT V^T
         const size_t f = n1 > n2 ? n1 : n2, b = n3 > n4 ? n3 : n4;
         p.n_part_sk = f > b ? f : b;
         const size_t fwd = align_up(p.n_T * sizeof(float)) + align_up(p.n_part_sk * sizeof(float));
@@ -361,11 +338,11 @@ static int linear_T_skinny(const pf_linear_desc *d, const float *X, const float 
 {
     const int M = (int)d->M, in = (int)d->in, r = (int)d->r;
     SkinnyArgs a;
-    build_rows(M, X, in, V, r, in, r, part, a);
+    skinny_rows(M, X, in, V, r, in, r, part, a);
     int st = launch_skinny_gemm(s, "linear_T=X*V", a, false);
     if (st != PF_OK) return st;
     SliceSumArgs ss = {};
-    ss.s[ss.nseg++] = rows_seg(a, M, T, nullptr);
+    ss.s[ss.nseg++] = skinny_rows_seg(a, M, T, a.p[0].N, nullptr);
     return launch_slice_sum(s, ss);
 }
 
@@ -379,11 +356,11 @@ static int linear_fwd_skinny(const pf_linear_desc *d, const LinearPlan &p, const
     int st = linear_T_skinny(d, X, V, T, part, s);
     if (st != PF_OK) return st;
     SkinnyArgs a;
-    build_rows(M, T, r, U, r, r, out, part, a);
+    skinny_rows(M, T, r, U, r, r, out, part, a);
     st = launch_skinny_gemm(s, "linear_Y=T*Ut", a, true);
     if (st != PF_OK) return st;
     SliceSumArgs ss = {};
-    ss.s[ss.nseg++] = rows_seg(a, M, Y, d->has_bias ? bias : nullptr);
+    ss.s[ss.nseg++] = skinny_rows_seg(a, M, Y, a.p[0].N, d->has_bias ? bias : nullptr);
     return launch_slice_sum(s, ss);
 }
 
@@ -402,19 +379,19 @@ static int linear_bwd_skinny(const pf_linear_desc *d, const LinearPlan &p, const
     }
     const float *T = T_saved ? T_saved : Tws;
     SkinnyArgs a;
-    build_rows(M, dY, out, U, r, out, r, part, a);
+    skinny_rows(M, dY, out, U, r, out, r, part, a);
     st = launch_skinny_gemm(s, "linear_dT=dY*U", a, false);
     if (st != PF_OK) return st;
     SliceSumArgs ss = {};
-    ss.s[ss.nseg++] = rows_seg(a, M, dT, nullptr);
+    ss.s[ss.nseg++] = skinny_rows_seg(a, M, dT, a.p[0].N, nullptr);
     st = launch_slice_sum(s, ss);
     if (st != PF_OK) return st;
     ss = SliceSumArgs{};
     if (dX) {
-        build_rows(M, dT, r, V, r, r, in, part, a);
+        skinny_rows(M, dT, r, V, r, r, in, part, a);
         st = launch_skinny_gemm(s, "linear_dX=dT*Vt", a, true);
         if (st != PF_OK) return st;
-        ss.s[ss.nseg++] = rows_seg(a, M, dX, nullptr);
+        ss.s[ss.nseg++] = skinny_rows_seg(a, M, dX, a.p[0].N, nullptr);
     }
     // factor gradients are rank-M updates; the slice sums of dX ride along
     RankArgs ra = {};

@@ -78,6 +78,28 @@ inline SliceSumSeg slice_seg(const SkinnyProb &p, float *out, i64 ldo, int N)
     return s;
 }
 
+// Row blocks of up to 32 rows of one product C[M x N] = A[M x K] W become the problems of one launch
+// (M <= 32 * SK_MAX_PROB).  Places the slice sums from `part` on (NULL: size only) and returns the floats they take.
+inline size_t skinny_rows(int M, const float *A, i64 lda, const float *W, i64 ldw, int K, int N, float *part,
+                          SkinnyArgs &a)
+{
+    a = SkinnyArgs{};
+    const i64 pc = (i64)M * N;
+    for (int m0 = 0; m0 < M; m0 += SK_MAX_ROWS)
+        a.p[a.nprob++] = skinny_prob(M - m0 < SK_MAX_ROWS ? M - m0 : SK_MAX_ROWS, A ? A + (i64)m0 * lda : nullptr, lda,
+                                     W, ldw, K, N, N, pc);
+    skinny_plan(a);
+    for (int q = 0; q < a.nprob; ++q) a.p[q].P = part ? part + (i64)SK_MAX_ROWS * q * N : nullptr;
+    return (size_t)(a.p[0].ksplit * pc); // every block has the same K and N, hence the same slicing
+}
+// all row blocks of such a product summed in one segment: out[m * ldo + n] (+ bias[n])
+inline SliceSumSeg skinny_rows_seg(const SkinnyArgs &a, int M, float *out, i64 ldo, const float *bias)
+{
+    SliceSumSeg sg = slice_seg(a.p[0], out, ldo, a.p[0].N);
+    sg.M = M;
+    sg.bias = bias;
+    return sg;
+}
 
 // out[i * ldo + j] (+)= sum_b A[b * lda + i] * Bm[b * ldb + j], b < M: the weight gradients of a cell are
 // rank-M updates.  Bm == NULL stands for a column of ones (a bias gradient, J = 1).
@@ -85,14 +107,15 @@ struct RankProb {
     const float *A, *Bm;
     float *out;
     i64 lda, ldb, ldo;
-    int I, J, wg0, jt; // jt = column tiles
+    int M, I, J, wg0, jt; // M = rows summed over; jt = column tiles
 };
 constexpr int RK_MAX_PROB = 12;
 struct RankArgs {
     RankProb p[RK_MAX_PROB];
-    int nprob, M, accumulate, nwg;
+    int nprob, M, accumulate, nwg; // M: rows of a problem added without a count of its own
 };
-void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, float *out, i64 ldo, int I, int J);
+void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, float *out, i64 ldo, int I, int J,
+              int M = -1);
 // seg: optional slice sums done by extra workgroups of the same launch (nseg == 0: none)
 int launch_rank_update(hipStream_t s, const char *name, const RankArgs &a, const SliceSumArgs &seg);
 

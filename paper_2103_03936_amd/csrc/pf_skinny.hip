@@ -290,8 +290,8 @@ __global__ __launch_bounds__(256) void rank_update_kernel(RankArgs a, SliceSumAr
         for (int f = 0; f < 4; ++f) acc[e][f] = old[f];
     }
 
-    for (int b0 = 0; b0 < a.M; b0 += SK_MAX_ROWS) {
-        const int nb = min(SK_MAX_ROWS, a.M - b0);
+    for (int b0 = 0; b0 < pb.M; b0 += SK_MAX_ROWS) {
+        const int nb = min(SK_MAX_ROWS, pb.M - b0);
         if (b0) __syncthreads();
         // 16-byte pieces, all of a thread's requests in flight together (rows are only 4-byte aligned)
         if (tid < nb * (RK_TI / 4)) {
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(256) void rank_update_kernel(RankArgs a, SliceSumAr
     }
 }
 
-void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, float *out, i64 ldo, int I, int J)
+void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, float *out, i64 ldo, int I, int J, int M)
 {
     if (!out || a.nprob >= RK_MAX_PROB) return;
     RankProb &p = a.p[a.nprob];
@@ -356,6 +356,7 @@ void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, fl
     p.lda = lda;
     p.ldb = ldb;
     p.ldo = ldo;
+    p.M = M >= 0 ? M : a.M;
     p.I = I;
     p.J = J;
     p.jt = (J + RK_TJ - 1) / RK_TJ;

@@ -101,3 +101,18 @@ def test_lstm_validation():
     assert f(ctypes.byref(_lstm()), *bad, None, z, None) == 1
     assert f(ctypes.byref(_lstm()), *args, None, z, None) == 4
     assert f(ctypes.byref(_lstm(B=0)), *args, None, z, None) == 0
+
+
+def test_lstm_seq_validation():
+    f = pf.lib.pf_lowrank_lstm_seq_fwd
+    z = ctypes.c_size_t(0)
+    args = [FAKE] * 13
+    mk = lambda T=3, B=2, d=8, h=8, r=4, groups=1, dtype=0, bias=1: pf.pf_lstm_seq_desc(T, B, d, h, r, groups, dtype, bias)
+    assert f(None, *args, None, z, None) == 1
+    assert f(ctypes.byref(mk(groups=3)), *args, None, z, None) == 3
+    assert f(ctypes.byref(mk(T=-1)), *args, None, z, None) == 2
+    assert f(ctypes.byref(mk(B=40)), *args, None, z, None) == 3  # built for small batches
+    assert f(ctypes.byref(mk()), *args, None, z, None) == 4      # workspace missing
+    assert f(ctypes.byref(mk(T=0)), *args, None, z, None) == 0
+    ws = pf.lib.pf_lowrank_lstm_seq_bwd_workspace_bytes(ctypes.byref(mk()))
+    assert ws > 0

@@ -194,3 +194,90 @@ def test_empty_batch():
     assert dx.shape == (0, 6)
     for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
         assert float(gr[k].abs().max()) == 0.0
+
+
+SEQS = [
+    # T, B, d, h, r
+    (1, 3, 8, 8, 4),
+    (6, 5, 40, 36, 10),
+    (4, 20, 70, 50, 13),
+    (3, 32, 37, 29, 7),
+]
+
+
+def _seq_inputs(T, B, d, h, r, groups, seed):
+    rng_cell = workloads.lstm_cell_inputs(B, d, h, r, groups=groups, seed=seed)  # factors, bias, h0 / c0
+    s = workloads.Stream(workloads.SEED_BASE + 500 + seed, "f32")
+    return dict(x=s.normal((T, B, d)), h0=rng_cell["h_prev"], c0=rng_cell["c_prev"], Vx=rng_cell["Vx"],
+                Ux=rng_cell["Ux"], Vh=rng_cell["Vh"], Uh=rng_cell["Uh"], bias=rng_cell["bias"],
+                dh_all=s.normal((T, B, h)), dhT=s.normal((B, h)), dcT=s.normal((B, h)))
+
+
+@pytest.mark.parametrize("groups", [1, 4])
+@pytest.mark.parametrize("shape", SEQS)
+def test_sequence_layer(shape, groups):
+    """pf_lowrank_lstm_seq_fwd/bwd against the sequence oracle (cells chained over time, BPTT)."""
+    import paper_2103_03936_amd as pf
+    T, B, d, h, r = shape
+    a = _seq_inputs(T, B, d, h, r, groups, seed=7)
+    ho, co, go, Txo, Tho = oracle.lowrank_lstm_seq_fwd(a["x"], a["h0"], a["c0"], a["Vx"], a["Ux"], a["Vh"], a["Uh"],
+                                                       a["bias"], groups)
+    dxo, dh0o, dc0o, gro = oracle.lowrank_lstm_seq_bwd(a["x"], a["h0"], a["c0"], ho, co, go, Txo, Tho, a["Vx"], a["Ux"],
+                                                      a["Vh"], a["Uh"], a["dh_all"], a["dhT"], a["dcT"], groups)
+    g = {k: to_gpu(v) for k, v in a.items()}
+    h_all, c_all, gates_all, Tx_all, Th_all = pf.pf_lowrank_lstm_seq_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"],
+                                                                         g["Vh"], g["Uh"], g["bias"], groups)
+    tag = f"seq {shape} groups={groups}"
+    for name, got, want in (("h", h_all, ho), ("c", c_all, co), ("gates", gates_all, go), ("Tx", Tx_all, Txo),
+                            ("Th", Th_all, Tho)):
+        assert_close(got, want, "f32", f"{tag} {name}")
+    dx, dh0, dc0, gr = pf.pf_lowrank_lstm_seq_bwd(g["x"], g["h0"], g["c0"], h_all, c_all, gates_all, Tx_all, Th_all,
+                                                  g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["dh_all"], g["dhT"], g["dcT"],
+                                                  groups)
+    assert_close(dx, dxo, "f32", tag + " dx")
+    assert_close(dh0, dh0o, "f32", tag + " dh0")
+    assert_close(dc0, dc0o, "f32", tag + " dc0")
+    for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+        assert_close(gr[k], gro[k], "f32", f"{tag} {k}")
+    # a second call accumulates onto the first; without dx, final-state gradients or bias
+    dx2, _, _, gr2 = pf.pf_lowrank_lstm_seq_bwd(g["x"], g["h0"], g["c0"], h_all, c_all, gates_all, Tx_all, Th_all,
+                                                g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["dh_all"], g["dhT"], g["dcT"],
+                                                groups, need_dx=False, grads=gr)
+    assert dx2 is None
+    for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+        assert_close(gr2[k], 2 * gro[k], "f32", f"{tag} accumulated {k}")
+
+
+def test_sequence_layer_matches_cells_full_size():
+    """Language-model layer shape (Appendix D), 35 steps: the sequence entry points against the cell entry
+    points chained by hand (both on the GPU; the cells are checked against the oracle above)."""
+    import paper_2103_03936_amd as pf
+    T, B, d, h, r = 35, 20, 1500, 1500, 375
+    a = _seq_inputs(T, B, d, h, r, 1, seed=9)
+    g = {k: to_gpu(v) for k, v in a.items()}
+    h_all, c_all, gates_all, Tx_all, Th_all = pf.pf_lowrank_lstm_seq_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"],
+                                                                         g["Vh"], g["Uh"], g["bias"], 1)
+    hp, cp = g["h0"], g["c0"]
+    saved = []
+    for t in range(T):
+        ht, ct, gt, Txt, Tht = pf.pf_lowrank_lstm_cell_fwd(g["x"][t], hp, cp, g["Vx"], g["Ux"], g["Vh"], g["Uh"],
+                                                          g["bias"], 1)
+        saved.append((hp, cp, ct, gt, Txt, Tht))
+        hp, cp = ht, ct
+        if t in (0, 17, 34):
+            assert_close(h_all[t], ht.double().cpu().numpy(), "f32", f"h_{t}")
+            assert_close(c_all[t], ct.double().cpu().numpy(), "f32", f"c_{t}")
+    dx, dh0, dc0, gr = pf.pf_lowrank_lstm_seq_bwd(g["x"], g["h0"], g["c0"], h_all, c_all, gates_all, Tx_all, Th_all,
+                                                  g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["dh_all"], g["dhT"], g["dcT"], 1)
+    dh, dc, grc = g["dh_all"][T - 1] + g["dhT"], g["dcT"], None
+    for t in range(T - 1, -1, -1):
+        hp, cp, ct, gt, Txt, Tht = saved[t]
+        dxt, dhp, dc, grc = pf.pf_lowrank_lstm_cell_bwd(g["x"][t], hp, cp, ct, gt, Txt, Tht, g["Vx"], g["Ux"], g["Vh"],
+                                                        g["Uh"], dh, dc, 1, grads=grc)
+        if t in (0, 17, 34):
+            assert_close(dx[t], dxt.double().cpu().numpy(), "f32", f"dx_{t}")
+        dh = dhp + (g["dh_all"][t - 1] if t > 0 else 0)
+    assert_close(dh0, dh.double().cpu().numpy(), "f32", "dh0")
+    assert_close(dc0, dc.double().cpu().numpy(), "f32", "dc0")
+    for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+        assert_close(gr[k], grc[k].double().cpu().numpy(), "f32", "full size " + k)
