@@ -229,11 +229,14 @@ class LstmWorkload:
 
     def __init__(self, name, cfg, groups=1):
         self.name, self.dtype, self.cfg, self.groups = name, "f32", cfg, groups
+        self.seq = bool(cfg.get("seq"))  # sequence-level entry points instead of one call per cell
 
     def describe(self):
         c = self.cfg
         return {"workload": self.name, "seq_len": c["T"], "batch": c["B"], "layers": c["layers"], "d": c["d"],
-                "h": c["h"], "r": c["r"], "groups": self.groups}
+                "h": c["h"], "r": c["r"], "groups": self.groups,
+                "calls": "pf_lowrank_lstm_seq_*, one per layer and direction" if self.seq else
+                         "pf_lowrank_lstm_cell_*, one per time step, layer and direction"}
 
     def flops(self):
         c = self.cfg
@@ -254,7 +257,24 @@ class LstmWorkload:
              "zero": torch.zeros((c["B"], c["h"]), device="cuda")}
         return {"lm": g}
 
+    def step_seq(self, pf, s):
+        g = s["lm"]
+        L, groups = len(g["P"]), self.groups
+        x, saved = g["x"], []
+        for p in g["P"]:
+            out = pf.pf_lowrank_lstm_seq_fwd(x, g["zero"], g["zero"], p["Vx"], p["Ux"], p["Vh"], p["Uh"], p["bias"], groups)
+            saved.append((x,) + out)
+            x = out[0]
+        above = g["dH"]
+        for l in reversed(range(L)):
+            p = g["P"][l]
+            xin, h_all, c_all, gates_all, Tx_all, Th_all = saved[l]
+            above, _, _, _ = pf.pf_lowrank_lstm_seq_bwd(xin, g["zero"], g["zero"], h_all, c_all, gates_all, Tx_all, Th_all,
+                                                        p["Vx"], p["Ux"], p["Vh"], p["Uh"], above, None, None, groups)
+
     def step(self, pf, s):
+        if self.seq:
+            return self.step_seq(pf, s)
         g = s["lm"]
         T, L, groups = g["x"].shape[0], len(g["P"]), self.groups
         hs, cs = [g["zero"]] * L, [g["zero"]] * L
@@ -286,6 +306,17 @@ class LstmWorkload:
         c = self.cfg
         B, d, h, r, g = c["B"], c["d"], c["h"], c["r"], self.groups
         gr, cells = g * r, c["T"] * c["layers"]
+        if self.seq:  # per-step hidden-path launches, and the batched gradient launch (one per layer)
+            Mt, L = c["T"] * B, c["layers"]
+            ws = {
+                "lstm_seq_Th=h*Vh": (2.0 * B * gr * h, 4 * (gr * h + B * h + B * gr), cells),
+                "lstm_seq_zh=Th*Uht": (2.0 * B * 4 * h * r, 4 * (4 * h * r + B * gr + 2 * B * 4 * h), cells),
+                "lstm_seq_dTh=dz*Uh": (2.0 * B * 4 * h * r, 4 * (4 * h * r + B * 4 * h + B * gr), cells),
+                "lstm_seq_dh=dTh*Vht": (2.0 * B * gr * h, 4 * (gr * h + B * gr + B * h), cells),
+                "lstm_seq_grads": (2.0 * Mt * (8 * h * r + gr * (d + h)),
+                                   4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)), 2 * L),
+            }
+            return {k: [f * n, b * n, n] for k, (f, b, n) in ws.items()}
         w = {
             "lstm_T=[x*Vx|h*Vh]": (2.0 * B * gr * (d + h), 4 * (gr * (d + h) + B * (d + h) + 2 * B * gr)),
             "lstm_z=[Tx|Th]*[Ux|Uh]t": (2.0 * B * 4 * h * 2 * r, 4 * (8 * h * r + 2 * B * gr + B * 4 * h)),

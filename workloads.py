@@ -140,6 +140,9 @@ CONFIGS = {
                                 k=3, stride=1, pad=1, seed=1),
     "lstm_lm_f32": dict(kind="lstm", dtype="f32", vocab=33278, d=1500, h=1500, r=375, layers=2,
                         T=35, B=20, seed=2),
+    # the same model through the sequence-level entry points (one call per layer and direction)
+    "lstm_lm_seq_f32": dict(kind="lstm", dtype="f32", vocab=33278, d=1500, h=1500, r=375, layers=2,
+                            T=35, B=20, seed=2, seq=True),
     "transformer_block_bf16": dict(kind="linear_set", dtype="bf16", M=64 * 128, seed=3, layers=dict(
         wq=(512, 512, 128), wk=(512, 512, 128), wv=(512, 512, 128), wo=(512, 512, 128),
         ffn1=(512, 2048, 128), ffn2=(2048, 512, 128))),
