@@ -80,6 +80,11 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
     constexpr int NCH = 32 * NBLK;
     constexpr int LDS_ELEMS = TAPS == 9 ? 2 * 3 * NCH * WG_ROWS * 8 : 8;
     __shared__ __attribute__((aligned(16))) uint16_t Xsh[LDS_ELEMS]; // [buf][tx][channel][row][8]
+    // 1x1 stage: the A fragments of an image are the same for all four wavefronts.  Each fetches a quarter
+    // (k-step j = its own index, all m blocks) and they trade through LDS: a lane-per-row fragment load costs the
+    // L1 one cache line per lane, an LDS read of the finished fragment 16 bytes.
+    constexpr bool SHARE_A = TAPS == 1;
+    __shared__ __attribute__((aligned(16))) uint4 Ash[SHARE_A ? 2 * MB * 4 * 64 : 1]; // [buf][m block][k-step][lane]
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -130,20 +135,30 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
                 }
         }
 #pragma unroll
-        for (int b = 0; b < MB; ++b)
+        for (int b = 0; b < MB; ++b) {
+            if (SHARE_A) { // this wavefront's share: k-step w of every m block (kept in slot 0)
+                st.afr[b][0] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, 2 * w + half, H, W);
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int y = 2 * j + half;
-                st.afr[b][j] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, y, H, W);
+                for (int j = 0; j < 4; ++j) {
+                    const int y = 2 * j + half;
+                    st.afr[b][j] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, y, H, W);
+                }
             }
+        }
     };
     // multiply image `img` (its data is in st), then refill st with image img + 2
     auto process = [&](Stage &st, int img, int buf) __attribute__((always_inline)) {
         uint4 acur[MB][4], bcur[NBF][4];
+        if (SHARE_A) {
 #pragma unroll
-        for (int b = 0; b < MB; ++b)
+            for (int b = 0; b < MB; ++b) *(uint4_alias *)&Ash[((buf * MB + b) * 4 + w) * 64 + lane] = st.afr[b][0];
+        } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acur[b][j] = st.afr[b][j];
+            for (int b = 0; b < MB; ++b)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acur[b][j] = st.afr[b][j];
+        }
 #pragma unroll
         for (int p = 0; p < NBF; ++p)
 #pragma unroll
@@ -170,7 +185,13 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
         }
         load_image(st, img + 2);
         // one barrier per image: a buffer is rewritten two images later, after the barrier in between
-        if (TAPS == 9) __syncthreads();
+        if (TAPS == 9 || SHARE_A) __syncthreads();
+        if (SHARE_A) {
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acur[b][j] = *(const uint4_alias *)&Ash[((buf * MB + b) * 4 + j) * 64 + lane];
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (j >= ksteps) break;
