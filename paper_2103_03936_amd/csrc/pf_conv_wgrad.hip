@@ -80,10 +80,10 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
     constexpr int NCH = 32 * NBLK;
     constexpr int LDS_ELEMS = TAPS == 9 ? 2 * 3 * NCH * WG_ROWS * 8 : 8;
     __shared__ __attribute__((aligned(16))) uint16_t Xsh[LDS_ELEMS]; // [buf][tx][channel][row][8]
-    // 1x1 stage: the A fragments of an image are the same for all four wavefronts.  Each fetches a quarter
-    // (k-step j = its own index, all m blocks) and they trade through LDS: a lane-per-row fragment load costs the
-    // L1 one cache line per lane, an LDS read of the finished fragment 16 bytes.
-    constexpr bool SHARE_A = TAPS == 1;
+    // The A fragments of an image are the same for all four wavefronts.  Each fetches a quarter (k-step j = its
+    // own index, all m blocks) and they trade through LDS: a lane-per-row fragment load costs the L1 one cache
+    // line per lane, an LDS read of the finished fragment 16 bytes.
+    constexpr bool SHARE_A = true;
     __shared__ __attribute__((aligned(16))) uint4 Ash[SHARE_A ? 2 * MB * 4 * 64 : 1]; // [buf][m block][k-step][lane]
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
