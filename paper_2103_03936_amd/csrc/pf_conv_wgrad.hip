@@ -107,14 +107,15 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[b][p][v] = 0.f;
 
-    // Everything one image needs from global memory, fetched two images ahead of its use:
-    // the rows of B this thread stages (3x3) or this lane's B fragments (1x1), and this lane's A fragments.
+    // Everything one image needs from global memory, fetched two images ahead of its staging:
+    // the rows of B this thread stages (3x3) or this lane's B fragments (1x1), and this wavefront's share of
+    // the A fragments (k-step w of every m block).
     constexpr int ROWS_PT = TAPS == 9 ? (NCH * 8 + 255) / 256 : 1;
     constexpr int NBF = TAPS == 9 ? 1 : PW;
     struct Stage {
         uint4 brow[ROWS_PT];
         uint4 bfr[NBF][4];
-        uint4 afr[MB][4];
+        uint4 afr[MB];
     };
     auto load_image = [&](Stage &st, int img) __attribute__((always_inline)) {
         if (img >= img1) return;
@@ -135,36 +136,20 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
                 }
         }
 #pragma unroll
-        for (int b = 0; b < MB; ++b) {
-            if (SHARE_A) { // this wavefront's share: k-step w of every m block (kept in slot 0)
-                st.afr[b][0] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, 2 * w + half, H, W);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int y = 2 * j + half;
-                    st.afr[b][j] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, y, H, W);
-                }
-            }
-        }
+        for (int b = 0; b < MB; ++b)
+            st.afr[b] = load_row<WC>(a.A + ((i64)img * M + 32 * b + col) * HW, 2 * w + half, H, W);
     };
-    // multiply image `img` (its data is in st), then refill st with image img + 2
-    auto process = [&](Stage &st, int img, int buf) __attribute__((always_inline)) {
-        uint4 acur[MB][4], bcur[NBF][4];
-        if (SHARE_A) {
+    // The image held in st goes to LDS buffer `buf` (A fragments; for 3x3 the three shifted copies of this
+    // thread's B rows); 1x1 B fragments stay in registers (bnext) until their image is multiplied.
+    uint4 bnext[NBF][4];
+    auto stage_to_lds = [&](const Stage &st, int buf) __attribute__((always_inline)) {
 #pragma unroll
-            for (int b = 0; b < MB; ++b) *(uint4_alias *)&Ash[((buf * MB + b) * 4 + w) * 64 + lane] = st.afr[b][0];
-        } else {
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acur[b][j] = st.afr[b][j];
-        }
+        for (int b = 0; b < MB; ++b) *(uint4_alias *)&Ash[((buf * MB + b) * 4 + w) * 64 + lane] = st.afr[b];
 #pragma unroll
         for (int p = 0; p < NBF; ++p)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bcur[p][j] = st.bfr[p][j];
+            for (int j = 0; j < 4; ++j) bnext[p][j] = st.bfr[p][j];
         if (TAPS == 9) {
-            // write the three shifted copies of this thread's rows into buffer `buf`
 #pragma unroll
             for (int i = 0; i < ROWS_PT; ++i) {
                 const int item = tid + 256 * i, c = item >> 3, y = item & 7;
@@ -183,47 +168,61 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
                 }
             }
         }
-        load_image(st, img + 2);
-        // one barrier per image: a buffer is rewritten two images later, after the barrier in between
-        if (TAPS == 9 || SHARE_A) __syncthreads();
-        if (SHARE_A) {
+    };
+    // One image: its fragments come out of LDS buffer `buf` into registers; then the next image (in st) is
+    // staged into the other buffer and st refilled two images further on, so that those LDS writes, the global
+    // requests and the barrier's wait overlap this image's MFMAs, which only need registers.
+    auto step = [&](Stage &st, int img, int buf) __attribute__((always_inline)) {
+        uint4 acur[MB][4], bcur[PW][4];
 #pragma unroll
-            for (int b = 0; b < MB; ++b)
+        for (int b = 0; b < MB; ++b)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acur[b][j] = *(const uint4_alias *)&Ash[((buf * MB + b) * 4 + j) * 64 + lane];
+            for (int j = 0; j < 4; ++j) acur[b][j] = *(const uint4_alias *)&Ash[((buf * MB + b) * 4 + j) * 64 + lane];
+#pragma unroll
+        for (int p = 0; p < PW; ++p) {
+            const int pair = w + 4 * p;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (TAPS == 9) {
+                    const int pr = pair < NPAIR ? pair : 0, nb = pr / TAPS, tap = pr % TAPS;
+                    const int ty = tap / 3, tx = tap % 3;
+                    bcur[p][j] = *(const uint4_alias *)&Xsh[((buf * 3 + tx) * NCH + 32 * nb + col) * WG_ROWS * 8 +
+                                                            (2 * j + half + ty) * 8];
+                } else {
+                    bcur[p][j] = bnext[p < NBF ? p : 0][j];
+                }
+            }
         }
+        if (img + 1 < img1) stage_to_lds(st, buf ^ 1); // (uniform)
+        load_image(st, img + 3);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (j >= ksteps) break;
 #pragma unroll
             for (int p = 0; p < PW; ++p) {
-                const int pair = w + 4 * p;
-                if (pair < NPAIR) {
-                    uint4 bfr;
-                    if (TAPS == 9) {
-                        const int nb = pair / TAPS, tap = pair % TAPS;
-                        const int ty = tap / 3, tx = tap % 3;
-                        bfr = *(const uint4_alias *)&Xsh[((buf * 3 + tx) * NCH + 32 * nb + col) * WG_ROWS * 8 +
-                                                         (2 * j + half + ty) * 8];
-                    } else {
-                        bfr = bcur[p < NBF ? p : 0][j];
-                    }
+                if (w + 4 * p < NPAIR) {
 #pragma unroll
                     for (int b = 0; b < MB; ++b)
-                        acc[b][p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg_as_bf16x8(acur[b][j]), wg_as_bf16x8(bfr),
-                                                                            acc[b][p], 0, 0, 0);
+                        acc[b][p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg_as_bf16x8(acur[b][j]),
+                                                                            wg_as_bf16x8(bcur[p][j]), acc[b][p], 0, 0, 0);
                 }
             }
         }
+        __syncthreads(); // the staged image is complete; the buffer just read may be rewritten
     };
 
-    Stage sA, sB;
-    load_image(sA, img0);
-    load_image(sB, img0 + 1);
-    __syncthreads();
-    for (int img = img0; img < img1; img += 2) {
-        process(sA, img, 0);
-        if (img + 1 < img1) process(sB, img + 1, 1);
+    if (img0 < img1) { // (uniform; an empty group writes zeros below)
+        Stage sA, sB;
+        load_image(sA, img0);
+        load_image(sB, img0 + 1);
+        __syncthreads(); // the zero fill above
+        stage_to_lds(sA, 0);
+        load_image(sA, img0 + 2);
+        __syncthreads();
+        for (int img = img0; img < img1; img += 2) {
+            step(sB, img, 0);
+            if (img + 1 < img1) step(sA, img + 1, 1);
+        }
     }
 
     // partial[g][tap][m][n]
