@@ -220,6 +220,26 @@ int pf_lowrank_lstm_seq_bwd(const pf_lstm_seq_desc *d, const void *x,
                             void *stream);
 
 /* ------------------------------------------------------------------ */
+/* Truncated-SVD factor initialisation (Algorithm 1, the step before    */
+/* the factorized layers are trained): W[m x n] (fp32, row-major) ->    */
+/*   U[m x r] = Ut_r S_r^(1/2),  V[n x r] = Vt_r S_r^(1/2)  (fp32),     */
+/* so that U V^T is the best rank-r approximation of W; sigma (nullable)*/
+/* receives all min(m, n) singular values in descending order.          */
+/* One-sided Jacobi in double precision; factors are unique only up to  */
+/* the sign of each column pair.  r <= min(m, n) <= 8192 (else          */
+/* PF_ERR_SHAPE / PF_ERR_UNSUPPORTED).  For a convolution unroll        */
+/* W[c_out, c_in, k, k] to [c_in k^2, c_out] first (Section 2.2).       */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t m, n, r;
+} pf_svd_desc;
+
+size_t pf_svd_split_workspace_bytes(const pf_svd_desc *d);
+int pf_svd_split(const pf_svd_desc *d, const void *W, void *U, void *V,
+                 void *sigma /* nullable */, void *workspace,
+                 size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ */
 /* Dense (un-factorized) comparators, for benchmarks only: the layers   */
 /* of Section 2.1 / 2.2 before factorization, on the same tiling code.  */
 /*   linear: W[out x in];  conv: Wd[Cout,Cin,k,k].                      */

@@ -43,6 +43,10 @@ class pf_lstm_seq_desc(ctypes.Structure):
                 ("r", ctypes.c_int64), ("groups", ctypes.c_int), ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
 
 
+class pf_svd_desc(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int64), ("n", ctypes.c_int64), ("r", ctypes.c_int64)]
+
+
 EXPORTS = [
     "pf_status_string", "pf_last_hip_error", "pf_version",
     "pf_lowrank_linear_fwd_workspace_bytes", "pf_lowrank_linear_bwd_workspace_bytes",
@@ -53,6 +57,7 @@ EXPORTS = [
     "pf_lowrank_lstm_cell_fwd", "pf_lowrank_lstm_cell_bwd",
     "pf_lowrank_lstm_seq_fwd_workspace_bytes", "pf_lowrank_lstm_seq_bwd_workspace_bytes",
     "pf_lowrank_lstm_seq_fwd", "pf_lowrank_lstm_seq_bwd",
+    "pf_svd_split_workspace_bytes", "pf_svd_split",
     "pf_dense_linear_workspace_bytes", "pf_dense_linear_fwd", "pf_dense_linear_bwd",
     "pf_dense_conv_workspace_bytes", "pf_dense_conv_fwd", "pf_dense_conv_bwd",
     "pf_timing_enable", "pf_timing_collect", "pf_timing_entry", "pf_timing_reset",
@@ -349,6 +354,33 @@ def pf_lowrank_lstm_seq_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, 
         _ptr(grads["dbias"], f32), ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()),
         _stream()), "pf_lowrank_lstm_seq_bwd")
     return dx_all, dh0, dc0, grads
+
+
+def pf_svd_split(W, r):
+    """Algorithm 1's factor initialisation: W[m, n] float32 -> (U[m, r], V[n, r], sigma[min(m, n)]) with
+    U V^T the best rank-r approximation of W and the singular values split evenly between the factors."""
+    if W.dtype != torch.float32 or W.dim() != 2:
+        raise PfError("pf_svd_split takes a 2-D float32 matrix")
+    W = W.contiguous()
+    m, n = W.shape
+    d = pf_svd_desc(m, n, r)
+    dev = W.device
+    U = torch.empty((m, r), dtype=torch.float32, device=dev)
+    V = torch.empty((n, r), dtype=torch.float32, device=dev)
+    sigma = torch.empty((min(m, n),), dtype=torch.float32, device=dev)
+    ws = _workspace(lib.pf_svd_split_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_svd_split(ctypes.byref(d), _ptr(W), _ptr(U), _ptr(V), _ptr(sigma), _ptr(ws),
+                            ctypes.c_size_t(ws.numel()), _stream()), "pf_svd_split")
+    return U, V, sigma
+
+
+def pf_svd_split_conv(Wd, r):
+    """A dense filter bank Wd[c_out, c_in, k, k] -> (Uk[r, c_in, k, k], Vp[c_out, r]) (Section 2.2: unroll to
+    [c_in k^2, c_out], factor, fold the left factor back into r thin filters)."""
+    co, ci, k, _ = Wd.shape
+    Wu = Wd.reshape(co, ci * k * k).t().contiguous()  # [c_in k^2, c_out], row index c k^2 + i k + j
+    U, V, sigma = pf_svd_split(Wu, r)
+    return U.t().contiguous().reshape(r, ci, k, k), V.contiguous(), sigma
 
 
 # ------------------------------------------------------------------ timing

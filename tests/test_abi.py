@@ -116,3 +116,16 @@ def test_lstm_seq_validation():
     assert f(ctypes.byref(mk(T=0)), *args, None, z, None) == 0
     ws = pf.lib.pf_lowrank_lstm_seq_bwd_workspace_bytes(ctypes.byref(mk()))
     assert ws > 0
+
+
+def test_svd_validation():
+    f = pf.lib.pf_svd_split
+    z = ctypes.c_size_t(0)
+    mk = lambda m=8, n=6, r=3: pf.pf_svd_desc(m, n, r)
+    assert f(None, FAKE, FAKE, FAKE, None, None, z, None) == 1
+    assert f(ctypes.byref(mk(r=7)), FAKE, FAKE, FAKE, None, None, z, None) == 2   # r > min(m, n)
+    assert f(ctypes.byref(mk(m=0)), FAKE, FAKE, FAKE, None, None, z, None) == 2
+    assert f(ctypes.byref(mk(m=20000, n=20000, r=4)), FAKE, FAKE, FAKE, None, None, z, None) == 3
+    assert f(ctypes.byref(mk()), None, FAKE, FAKE, None, None, z, None) == 1
+    assert f(ctypes.byref(mk()), FAKE, FAKE, FAKE, None, None, z, None) == 4      # workspace missing
+    assert pf.lib.pf_svd_split_workspace_bytes(ctypes.byref(mk())) > 0
