@@ -357,6 +357,39 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def svd_bench(args, torch, pf, workloads):
+    """Truncated-SVD factor initialisation (Algorithm 1), not part of the training step: one line with the time per
+    matrix on the GPU and, for the smallest matrix, the oracle's time on the host."""
+    cfg = workloads.CONFIGS[args.workload]
+    res = {}
+    for name, (m, n, r) in cfg["layers"].items():
+        W = torch.from_numpy(workloads.Stream(workloads.SEED_BASE + cfg["seed"], "f32").normal((m, n)).astype("float32")).cuda()
+        pf.pf_svd_split(W, r)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = max(1, min(args.steps, 3))
+        for _ in range(reps):
+            pf.pf_svd_split(W, r)
+        torch.cuda.synchronize()
+        res[name] = {"m": m, "n": n, "r": r, "ms": (time.perf_counter() - t0) / reps * 1e3}
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        name, (m, n, r) = next(iter(cfg["layers"].items()))
+        W = workloads.Stream(workloads.SEED_BASE + cfg["seed"], "f32").normal((m, n))
+        t0 = time.perf_counter()
+        oracle.svd_split(W, r)
+        cpu = {"value": 1.0 / (time.perf_counter() - t0), "unit": "factorizations/s", "cores": 1, "kind": "oracle",
+               "sample": f"{name} ({m} x {n}, r = {r}) only"}
+    total_ms = sum(v["ms"] for v in res.values())
+    print(json.dumps({
+        "metric": "truncated-SVD factor initialisation (Algorithm 1), layer matrices factorized per second, 1 MI355X",
+        "value": len(res) / (total_ms * 1e-3), "unit": "factorizations/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic", "config": {"workload": args.workload, "layers": res}, "roofline": None,
+        "cpu_baseline": cpu}))
+
+
 def make_workload(name):
     import workloads
     cfg = workloads.CONFIGS[name]
@@ -436,6 +469,8 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU: the HIP library has no CPU path")
     torch.cuda.set_device(0)
+    if workloads.CONFIGS[args.workload]["kind"] == "svd":
+        return svd_bench(args, torch, pf, workloads)
     wl = make_workload(args.workload)
 
     one = wl.make_set(0, torch, workloads)
