@@ -13,6 +13,11 @@
  *     bfloat16, products accumulate in float, activation outputs (Y, dX, T_save)
  *     are rounded to bfloat16.  Parameter gradients (dU, dV, dbias, ...) are
  *     ALWAYS float.
+ *   - Activations, factors, biases and saved tensors must be 16-byte aligned
+ *     (any device allocation is); parameter-gradient outputs need only 4-byte
+ *     alignment, so they may be slices of ONE flat float buffer laid out back
+ *     to back -- the single all-reduce payload of the paper's Section 4
+ *     ("implementation details").  Otherwise PF_ERR_UNSUPPORTED.
  *   - `accumulate` != 0 adds parameter gradients to what the buffers hold
  *     (gradient accumulation, back-propagation through time); 0 overwrites.
  *   - Scratch memory comes from the caller: ask pf_*_workspace_bytes(desc),

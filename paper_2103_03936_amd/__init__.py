@@ -385,6 +385,28 @@ def pf_svd_split_conv(Wd, r):
 
 # ------------------------------------------------------------------ timing
 
+class GradBuffer:
+    """One flat float32 device buffer that holds every parameter gradient of a model back to back, in the order
+    the entries are given (paper Section 4, implementation details: all gradient tensors are packed into one
+    flat buffer so that a single all-reduce sums them).  Nothing is copied: `views[name]` are slices of `flat`
+    to pass as `grads=` to the backward calls, which then write (after `zero()`: accumulate) in place.  Gradient
+    outputs need only 4-byte alignment, so no padding goes between the entries."""
+
+    def __init__(self, entries, device="cuda"):
+        self.offsets = {}
+        n = 0
+        for name, shape in entries:
+            self.offsets[name] = (n, tuple(shape))
+            n += int(torch.Size(shape).numel())
+        self.flat = torch.empty((n,), dtype=torch.float32, device=device)
+        self.views = {name: self.flat[o:o + int(torch.Size(sh).numel())].view(sh)
+                      for name, (o, sh) in self.offsets.items()}
+
+    def zero(self):
+        self.flat.zero_()
+        return self
+
+
 def timing_enable(on=True):
     lib.pf_timing_enable(ctypes.c_int(1 if on else 0))
 

@@ -6,7 +6,18 @@
 
 #include "../../include/pufferfish.h"
 
+#include <initializer_list>
+
 namespace pf {
+
+// true when one of the (non-NULL) pointers is not a multiple of `a` bytes
+inline bool any_misaligned(std::initializer_list<const void *> ps, uintptr_t a)
+{
+    for (const void *q : ps)
+        if (((uintptr_t)q & (a - 1)) != 0) return true;
+    return false;
+}
+
 
 typedef long long i64;
 

@@ -404,6 +404,7 @@ int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, co
     if (st != PF_OK) return st;
     if (!Uk || !Vp) return PF_ERR_NULL;
     if (g.N > 0 && (!X || !Y)) return PF_ERR_NULL;
+    if (any_misaligned({X, Uk, Vp, Y, T_save}, 16)) return PF_ERR_UNSUPPORTED;
     const ConvPlan p = plan_conv(g, d->dtype);
     if (p.fwd_bytes > 0 && (!workspace || workspace_bytes < p.fwd_bytes)) return PF_ERR_WORKSPACE;
     if (g.N == 0) return PF_OK;
@@ -428,6 +429,7 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, co
     if (st != PF_OK) return st;
     if (!Uk || !Vp) return PF_ERR_NULL;
     if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
+    if (any_misaligned({X, Uk, Vp, dY, T_saved, dX}, 16) || any_misaligned({dUk, dVp}, 4)) return PF_ERR_UNSUPPORTED;
     const ConvPlan p = plan_conv(g, d->dtype);
     if (p.bwd_bytes > 0 && (!workspace || workspace_bytes < p.bwd_bytes)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);

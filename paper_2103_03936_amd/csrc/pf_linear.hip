@@ -484,6 +484,7 @@ int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V,
     if (st != PF_OK) return st;
     if (!V || !U || (d->has_bias && !bias)) return PF_ERR_NULL;
     if (d->M > 0 && (!X || !Y)) return PF_ERR_NULL;
+    if (any_misaligned({X, V, U, bias, Y, T_save}, 16)) return PF_ERR_UNSUPPORTED;
     const size_t need = plan_linear(d).fwd_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     if (d->M == 0) return PF_OK;
@@ -510,6 +511,7 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
     if (st != PF_OK) return st;
     if (!V || !U) return PF_ERR_NULL;
     if (d->M > 0 && (!X || !dY)) return PF_ERR_NULL;
+    if (any_misaligned({X, V, U, dY, T_saved, dX}, 16) || any_misaligned({dU, dV, dbias}, 4)) return PF_ERR_UNSUPPORTED;
     const size_t need = plan_linear(d).bwd_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);

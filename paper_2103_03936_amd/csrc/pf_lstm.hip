@@ -768,6 +768,8 @@ int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x, const void *h
     if (!Vx || !Ux || !Vh || !Uh || (d->has_bias && !bias)) return PF_ERR_NULL;
     if (d->B > 0 && (!x || !h_prev || !c_prev || !h_out || !c_out || !gates_save || !Tx_save || !Th_save))
         return PF_ERR_NULL;
+    if (any_misaligned({x, h_prev, c_prev, Vx, Ux, Vh, Uh, bias, h_out, c_out, gates_save, Tx_save, Th_save}, 16))
+        return PF_ERR_UNSUPPORTED;
     if (d->B == 0) return PF_OK; // nothing to compute, nothing to check
     const size_t need = pf_lowrank_lstm_cell_fwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
@@ -796,6 +798,10 @@ int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x, const void *h
     if (d->B > 0 && (!x || !h_prev || !c_prev || !c_out || !gates_saved || !Tx_saved || !Th_saved || !dh || !dh_prev ||
                      !dc_prev))
         return PF_ERR_NULL;
+    if (any_misaligned({x, h_prev, c_prev, c_out, gates_saved, Tx_saved, Th_saved, Vx, Ux, Vh, Uh, dh, dc_next, dx,
+                        dh_prev, dc_prev}, 16) ||
+        any_misaligned({dVx, dUx, dVh, dUh, dbias}, 4))
+        return PF_ERR_UNSUPPORTED;
     const size_t need = pf_lowrank_lstm_cell_bwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);
@@ -837,6 +843,8 @@ int pf_lowrank_lstm_seq_fwd(const pf_lstm_seq_desc *d, const void *x, const void
     int st = check_lstm_seq_desc(d, &c);
     if (st != PF_OK) return st;
     if (!Vx || !Ux || !Vh || !Uh || (d->has_bias && !bias)) return PF_ERR_NULL;
+    if (any_misaligned({x, h0, c0, Vx, Ux, Vh, Uh, bias, h_all, c_all, gates_all, Tx_all, Th_all}, 16))
+        return PF_ERR_UNSUPPORTED;
     if (d->T == 0 || d->B == 0) return PF_OK;
     if (!x || !h0 || !c0 || !h_all || !c_all || !gates_all || !Tx_all || !Th_all) return PF_ERR_NULL;
     const size_t need = plan_lstm_seq(d, &c).fwd_bytes;
@@ -859,6 +867,10 @@ int pf_lowrank_lstm_seq_bwd(const pf_lstm_seq_desc *d, const void *x, const void
     int st = check_lstm_seq_desc(d, &c);
     if (st != PF_OK) return st;
     if (!Vx || !Ux || !Vh || !Uh || !dVx || !dUx || !dVh || !dUh) return PF_ERR_NULL;
+    if (any_misaligned({x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux, Vh, Uh, dh_all, dhT, dcT, dx_all,
+                        dh0, dc0}, 16) ||
+        any_misaligned({dVx, dUx, dVh, dUh, dbias}, 4))
+        return PF_ERR_UNSUPPORTED;
     if (d->T == 0 || d->B == 0) { // no rows: the gradients this call owns are zero
         if (!accumulate) {
             hipStream_t s = (hipStream_t)stream;

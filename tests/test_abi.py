@@ -57,6 +57,12 @@ def test_linear_validation():
     b = pf.lib.pf_lowrank_linear_bwd
     assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 1
     assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 4
+    # activations and factors 16-byte aligned, parameter gradients 4-byte aligned
+    odd, odd2 = P(256 + 4), P(256 + 2)
+    assert f(ctypes.byref(_lin()), odd, FAKE, FAKE, None, FAKE, None, None, z, None) == 3
+    assert b(ctypes.byref(_lin()), FAKE, FAKE, odd, FAKE, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 3
+    assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, odd2, FAKE, None, 0, None, z, None) == 3
+    assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, odd, odd, None, 0, None, z, None) == 4
     # full rank and beyond is legal
     assert pf.lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(_lin(r=64))) >= 0
 
