@@ -157,18 +157,38 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
               wgrad_supported(g.r, g.Cout, g.H, g.W, 1, 1, 0);
     p.wg_groups = p.wg_ipg = p.wg_groups2 = p.wg_ipg2 = 1;
     if (p.wgrad && g.N > 0) {
-        // image groups: enough workgroups to cover the chip, but few partial sums to add up (at most 16
-        // per stage: the k x k stage then fills half the chip, the 1x1 stage an eighth, with equally long
-        // workgroups, and the group sums stay a small part of the step)
-        auto split = [&](int chunks, int target, int cap, int &groups, int &ipg) {
-            int want = target / (chunks > 0 ? chunks : 1);
-            want = want < 1 ? 1 : want > cap ? cap : want;
-            if (want > g.N) want = g.N;
-            ipg = (g.N + want - 1) / want;
-            groups = (g.N + ipg - 1) / ipg;
-        };
-        split(g.C / wgrad_nchunk(g.r, g.k, 1), 128, 16, p.wg_groups, p.wg_ipg);
-        split(g.Cout / wgrad_nchunk(g.r, 1, 2), 128, 16, p.wg_groups2, p.wg_ipg2);
+        // Image groups of the two problems of the launch.  A problem has `units` independent output blocks;
+        // with g groups it runs units * g workgroups of ceil(N / g) images each and writes g partial sums.  Both
+        // problems should fit the chip in one round (one workgroup per compute unit) and finish together, and
+        // every extra group costs a partial sum to write and to add up.  Costs in thousands of cycles, from
+        // traces of the kernel: an image of a 3x3 stage 1.4, of a 1x1 stage 1.0 (rank 64) or 2.0 (rank 128);
+        // a megabyte of partial sums 1.0.  The search is tiny: every g1, and for it the fewest groups g2 that
+        // do not make problem 2 the longer one.
+        const int units1 = (g.C / wgrad_nchunk(g.r, g.k, 1)) * ((g.k == 3 && g.r == 128) ? 2 : 1);
+        const int units2 = g.Cout / wgrad_nchunk(g.r, 1, 2);
+        const double c1 = g.k == 3 ? 1.4 : g.r == 128 ? 2.0 : 1.0, c2 = g.r == 128 ? 2.0 : 1.0;
+        const double mb1 = 1.0e-6 * 4.0 * g.r * g.C * g.k * g.k, mb2 = 1.0e-6 * 4.0 * g.r * g.Cout;
+        const int budget = 256;
+        double best = 1e30;
+        for (int g1 = 1; g1 <= g.N && (g1 == 1 || units1 * g1 + units2 <= budget); ++g1) {
+            const int ipg1 = (g.N + g1 - 1) / g1;
+            int g2max = (budget - units1 * g1) / units2;
+            g2max = g2max < 1 ? 1 : g2max > g.N ? g.N : g2max;
+            int ipg2 = (int)(ipg1 * c1 / c2); // images a workgroup of problem 2 may take
+            ipg2 = ipg2 < 1 ? 1 : ipg2;
+            int g2 = (g.N + ipg2 - 1) / ipg2;
+            g2 = g2 > g2max ? g2max : g2;
+            ipg2 = (g.N + g2 - 1) / g2;
+            const double t1 = ipg1 * c1, t2 = ipg2 * c2;
+            const double t = (t1 > t2 ? t1 : t2) + g1 * mb1 + g2 * mb2;
+            if (t < best) {
+                best = t;
+                p.wg_ipg = ipg1;
+                p.wg_ipg2 = ipg2;
+            }
+        }
+        p.wg_groups = (g.N + p.wg_ipg - 1) / p.wg_ipg;
+        p.wg_groups2 = (g.N + p.wg_ipg2 - 1) / p.wg_ipg2;
     }
     const i64 npix = (i64)g.N * g.Ho * g.Wo;
     p.ks_dVp = choose_ksplit(g.Cout, g.r, npix);
