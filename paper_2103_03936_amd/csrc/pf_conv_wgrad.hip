@@ -360,7 +360,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void conv_wgrad_pair_kernel(WgradArg
     }
 }
 
-// out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]; four consecutive n per thread
+// out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]; four consecutive n per output
 // The blocks past blocks01 add up per-tile column sums instead (a bias gradient): 32 columns per block,
 // eight threads per column take every eighth tile, and their sums are added in a fixed order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, WgradReduceArgs r1, int blocks0,
@@ -391,16 +391,20 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, W
         }
         return;
     }
+    // 64 outputs of four floats per block; the groups are dealt to four threads per output, which add their
+    // share with up to eight loads in flight, and the four sums are added in a fixed order.
     const bool second = (int)blockIdx.x >= blocks0;
     const WgradReduceArgs r = second ? r1 : r0;
-    const i64 i4 = (i64)(blockIdx.x - (second ? blocks0 : 0)) * 256 + threadIdx.x;
+    const int q = threadIdx.x >> 6, o = threadIdx.x & 63;
     const i64 count = (i64)r.taps * r.M * r.Nc; // multiple of 4: Nc is a multiple of 32
-    if (4 * i4 >= count) return;
-    const float4 *p = (const float4 *)r.partial + i4;
     const i64 stride4 = count / 4;
+    const i64 i4 = (i64)(blockIdx.x - (second ? blocks0 : 0)) * 64 + o;
+    const bool live = i4 < stride4;
+    const float4 *p = (const float4 *)r.partial + (live ? i4 : stride4 - 1);
+    const int per = (r.groups + 3) / 4, gend = min(r.groups, (q + 1) * per);
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    int g = 0;
-    for (; g + 8 <= r.groups; g += 8) { // eight independent loads in flight, summed in group order
+    int g = q * per;
+    for (; g + 8 <= gend; g += 8) {
         float4 v[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) v[k] = p[(i64)(g + k) * stride4];
@@ -412,19 +416,31 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, W
             s.w += v[k].w;
         }
     }
-    if (g < r.groups) { // the last groups, again all in flight together
+    if (g < gend) { // the last groups of this share, again all in flight together
         float4 v[7];
 #pragma unroll
-        for (int k = 0; k < 7; ++k) v[k] = p[(i64)(g + k < r.groups ? g + k : r.groups - 1) * stride4];
+        for (int k = 0; k < 7; ++k) v[k] = p[(i64)(g + k < gend ? g + k : gend - 1) * stride4];
 #pragma unroll
         for (int k = 0; k < 7; ++k) {
-            if (g + k < r.groups) {
+            if (g + k < gend) {
                 s.x += v[k].x;
                 s.y += v[k].y;
                 s.z += v[k].z;
                 s.w += v[k].w;
             }
         }
+    }
+    __shared__ float4 shares[4][64];
+    shares[q][o] = s;
+    __syncthreads();
+    if (q != 0 || !live) return;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+        const float4 t = shares[k][o];
+        s.x += t.x;
+        s.y += t.y;
+        s.z += t.z;
+        s.w += t.w;
     }
     const i64 i = 4 * i4;
     const int n = (int)(i % r.Nc);
@@ -493,7 +509,7 @@ int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradRed
 {
     int st = PF_OK;
     const i64 c0 = r0.out ? (i64)r0.taps * r0.M * r0.Nc : 0, c1 = r1.out ? (i64)r1.taps * r1.M * r1.Nc : 0;
-    const int b0 = (int)((c0 / 4 + 255) / 256), b1 = (int)((c1 / 4 + 255) / 256);
+    const int b0 = (int)((c0 / 4 + 63) / 64), b1 = (int)((c1 / 4 + 63) / 64);
     ColsumTilesArgs c = {};
     if (cs && cs->out && cs->tiles > 0) c = *cs;
     if (c.cols % 32 != 0) return PF_ERR_UNSUPPORTED;
