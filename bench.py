@@ -62,8 +62,8 @@ class ConvWorkload:
 
     def step(self, pf, s):
         for g in s.values():
-            Y, T = pf.pf_lowrank_conv_fwd(g["X"], g["Uk"], g["Vp"], 1, g["pad"], save_T=True)
-            pf.pf_lowrank_conv_bwd(g["X"], g["Uk"], g["Vp"], g["dY"], T_saved=T, stride=1, pad=g["pad"])
+            Y, T, Wsv = pf.pf_lowrank_conv_fwd(g["X"], g["Uk"], g["Vp"], 1, g["pad"], save_T=True, save_W=True)
+            pf.pf_lowrank_conv_bwd(g["X"], g["Uk"], g["Vp"], g["dY"], T_saved=T, stride=1, pad=g["pad"], W_saved=Wsv)
 
     def dense_prepare(self, s, torch):
         for g in s.values():

@@ -111,18 +111,29 @@ typedef struct {
 size_t pf_lowrank_conv_fwd_workspace_bytes(const pf_conv_desc *d);
 size_t pf_lowrank_conv_bwd_workspace_bytes(const pf_conv_desc *d);
 
-/* T = Uk * X (k x k, stride, pad), Y = Vp * T (1x1).  T_save nullable. */
+/* Bytes of the optional W_save buffer: both factors re-ordered the way the
+ * backward pass's kernels read them (0 when that pass reads them in place). */
+size_t pf_lowrank_conv_saved_weights_bytes(const pf_conv_desc *d);
+
+/* T = Uk * X (k x k, stride, pad), Y = Vp * T (1x1).  T_save nullable.
+ * W_save (nullable, pf_lowrank_conv_saved_weights_bytes(d) bytes): like T_save a
+ * tensor kept for the backward pass -- the forward call's weight re-ordering
+ * launch fills it, and a backward call that is handed it (with Uk, Vp
+ * unchanged in between) skips its own re-ordering launch. */
 int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk,
                         const void *Vp, void *Y, void *T_save /* nullable */,
+                        void *W_save /* nullable */,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* Given dY[N,Cout,Ho,Wo]:  dT = Vp^T dY (1x1),  dVp[o,q] = sum dY T,
  * dX = transposed k x k convolution of dT with Uk,
  * dUk[q,c,i,j] = sum dT[n,q,y,x] Xpad[n,c,y s+i-p,x s+j-p].
- * T_saved nullable (recomputed).  dX, dUk, dVp each nullable; dUk, dVp float. */
+ * T_saved nullable (recomputed); W_saved nullable (the forward call's W_save).
+ * dX, dUk, dVp each nullable; dUk, dVp float. */
 int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk,
                         const void *Vp, const void *dY,
-                        const void *T_saved /* nullable */, void *dX,
+                        const void *T_saved /* nullable */,
+                        const void *W_saved /* nullable */, void *dX,
                         void *dUk, void *dVp, int accumulate, void *workspace,
                         size_t workspace_bytes, void *stream);
 

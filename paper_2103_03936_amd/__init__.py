@@ -52,7 +52,7 @@ EXPORTS = [
     "pf_lowrank_linear_fwd_workspace_bytes", "pf_lowrank_linear_bwd_workspace_bytes",
     "pf_lowrank_linear_fwd", "pf_lowrank_linear_bwd",
     "pf_lowrank_conv_fwd_workspace_bytes", "pf_lowrank_conv_bwd_workspace_bytes",
-    "pf_lowrank_conv_fwd", "pf_lowrank_conv_bwd",
+    "pf_lowrank_conv_saved_weights_bytes", "pf_lowrank_conv_fwd", "pf_lowrank_conv_bwd",
     "pf_lowrank_lstm_cell_fwd_workspace_bytes", "pf_lowrank_lstm_cell_bwd_workspace_bytes",
     "pf_lowrank_lstm_cell_fwd", "pf_lowrank_lstm_cell_bwd",
     "pf_lowrank_lstm_seq_fwd_workspace_bytes", "pf_lowrank_lstm_seq_bwd_workspace_bytes",
@@ -71,7 +71,7 @@ if not os.path.exists(LIB_PATH):
 lib = ctypes.CDLL(LIB_PATH)
 lib.pf_status_string.restype = ctypes.c_char_p
 for _n in EXPORTS:
-    if _n.endswith("workspace_bytes"):
+    if _n.endswith("_bytes"):
         getattr(lib, _n).restype = ctypes.c_size_t
 
 
@@ -201,20 +201,24 @@ def conv_out_hw(d):
     return (d.H + 2 * d.pad - d.k) // d.stride + 1, (d.W + 2 * d.pad - d.k) // d.stride + 1
 
 
-def pf_lowrank_conv_fwd(X, Uk, Vp, stride=1, pad=0, save_T=True):
-    """Thin k x k conv (Uk[r,C,k,k]) then 1x1 conv (Vp[Cout,r]).  Returns (Y, T)."""
+def pf_lowrank_conv_fwd(X, Uk, Vp, stride=1, pad=0, save_T=True, save_W=False):
+    """Thin k x k conv (Uk[r,C,k,k]) then 1x1 conv (Vp[Cout,r]).  Returns (Y, T), or (Y, T, W) with
+    save_W: W holds the factors as the backward kernels read them (None when they read them in place)."""
     d = _conv_desc(X, Uk, Vp, stride, pad)
     Ho, Wo = conv_out_hw(d)
     dt = X.dtype
     Y = torch.empty((d.N, d.Cout, Ho, Wo), dtype=dt, device=X.device)
     T = torch.empty((d.N, d.r, Ho, Wo), dtype=dt, device=X.device) if save_T else None
+    nW = lib.pf_lowrank_conv_saved_weights_bytes(ctypes.byref(d)) if save_W else 0
+    Wsv = torch.empty((nW,), dtype=torch.uint8, device=X.device) if nW else None
     ws = _workspace(lib.pf_lowrank_conv_fwd_workspace_bytes(ctypes.byref(d)), X.device)
     _check(lib.pf_lowrank_conv_fwd(ctypes.byref(d), _ptr(X), _ptr(Uk, dt), _ptr(Vp, dt), _ptr(Y), _ptr(T),
-                                   _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_conv_fwd")
-    return Y, T
+                                   _ptr(Wsv), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "pf_lowrank_conv_fwd")
+    return (Y, T, Wsv) if save_W else (Y, T)
 
 
-def pf_lowrank_conv_bwd(X, Uk, Vp, dY, T_saved=None, stride=1, pad=0, need_dX=True, grads=None):
+def pf_lowrank_conv_bwd(X, Uk, Vp, dY, T_saved=None, stride=1, pad=0, need_dX=True, grads=None, W_saved=None):
     """Returns (dX, dUk, dVp); dUk, dVp are float32 (accumulated into `grads` = (dUk, dVp) if given)."""
     d = _conv_desc(X, Uk, Vp, stride, pad)
     dt = X.dtype
@@ -227,9 +231,9 @@ def pf_lowrank_conv_bwd(X, Uk, Vp, dY, T_saved=None, stride=1, pad=0, need_dX=Tr
         dUk, dVp = grads
     ws = _workspace(lib.pf_lowrank_conv_bwd_workspace_bytes(ctypes.byref(d)), X.device)
     _check(lib.pf_lowrank_conv_bwd(ctypes.byref(d), _ptr(X), _ptr(Uk, dt), _ptr(Vp, dt), _ptr(dY, dt),
-                                   _ptr(T_saved, dt), _ptr(dX), _ptr(dUk, torch.float32), _ptr(dVp, torch.float32),
-                                   ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()),
-                                   _stream()), "pf_lowrank_conv_bwd")
+                                   _ptr(T_saved, dt), _ptr(W_saved), _ptr(dX), _ptr(dUk, torch.float32),
+                                   _ptr(dVp, torch.float32), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
+                                   ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_conv_bwd")
     return dX, dUk, dVp
 
 

@@ -143,6 +143,7 @@ struct ConvPlan {
     int wg_groups2, wg_ipg2; // the same for the 1x1 stage
     size_t n_w1, n_w2;       // packed weight elements, forward direction
     size_t n_w1b, n_w2b;     // packed weight elements, backward direction
+    size_t saved_bytes;      // the backward direction's packed weights when the forward call saves them
 };
 
 static ConvPlan plan_conv(const ConvGeom &g, int dtype)
@@ -153,6 +154,7 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
     p.n_w2 = chain_w2_elems(g.Cout, g.r, 1);
     p.n_w1b = chain_w1_elems(g.Cout, g.r, 1);
     p.n_w2b = chain_w2_elems(g.C, g.r, g.k);
+    p.saved_bytes = p.chain ? align_up(p.n_w1b * 2) + align_up(p.n_w2b * 2) : 0;
     p.wgrad = p.chain && wgrad_supported(g.r, g.C, g.H, g.W, g.k, g.s, g.p) &&
               wgrad_supported(g.r, g.Cout, g.H, g.W, 1, 1, 0);
     p.wg_groups = p.wg_ipg = p.wg_groups2 = p.wg_ipg2 = 1;
@@ -290,14 +292,19 @@ static int conv_bwd_generic(const ConvGeom &g, const ConvPlan &p, const T *X, co
 
 // ----------------------------------------------------- fused small-image path (bf16)
 static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X, const bf16_t *Uk, const bf16_t *Vp,
-                          bf16_t *Y, bf16_t *T_save, Workspace &ws, hipStream_t s)
+                          bf16_t *Y, bf16_t *T_save, void *W_save, Workspace &ws, hipStream_t s)
 {
     const int T = g.k * g.k;
     uint16_t *w1 = ws.take<uint16_t>(p.n_w1);
     uint16_t *w2 = ws.take<uint16_t>(p.n_w2);
-    // only the thin k x k filters need re-ordering; the 1x1 filters Vp[Cout][r] are read in place
-    int st = launch_pack_chain(s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1),
-                               make_pack_w2(nullptr, nullptr, g.Cout, g.r, 1, 0, 0, 0, 0));
+    // only the thin k x k filters need re-ordering; the 1x1 filters Vp[Cout][r] are read in place.  The same
+    // launch can re-order both factors the way the backward pass wants them (W_save), which saves that pass a
+    // launch of its own.
+    uint16_t *s1 = (uint16_t *)W_save, *s2 = W_save ? (uint16_t *)((char *)W_save + align_up(p.n_w1b * 2)) : nullptr;
+    int st = launch_pack_chain(
+        s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1),
+        make_pack_w2(W_save ? (const uint16_t *)Uk : nullptr, (uint4 *)s2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1),
+        make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0));
     if (st != PF_OK) return st;
     (void)w2;
     ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, nullptr, (const uint16_t *)Vp, (uint16_t *)Y,
@@ -307,12 +314,16 @@ static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
 }
 
 static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X, const bf16_t *Uk, const bf16_t *Vp,
-                          const bf16_t *dY, const bf16_t *T_saved, bf16_t *dX, float *dUk, float *dVp, int accumulate,
-                          Workspace &ws, hipStream_t s)
+                          const bf16_t *dY, const bf16_t *T_saved, const void *W_saved, bf16_t *dX, float *dUk,
+                          float *dVp, int accumulate, Workspace &ws, hipStream_t s)
 {
     const int T = g.k * g.k;
-    uint16_t *w1 = ws.take<uint16_t>(p.n_w1b);
-    uint16_t *w2 = ws.take<uint16_t>(p.n_w2b);
+    const uint16_t *w1 = ws.take<uint16_t>(p.n_w1b);
+    const uint16_t *w2 = ws.take<uint16_t>(p.n_w2b);
+    if (W_saved) { // the forward call packed them already
+        w1 = (const uint16_t *)W_saved;
+        w2 = (const uint16_t *)((const char *)W_saved + align_up(p.n_w1b * 2));
+    }
     bf16_t *dT16 = ws.take<bf16_t>(p.n_T);
     bf16_t *T16 = ws.take<bf16_t>(p.n_T);
     float *part = ws.take<float>(p.n_part);
@@ -324,8 +335,9 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
         if (st != PF_OK) return st;
     }
     // stage 1: dT = Vp^T dY (1x1); stage 2: dX = flipped-Uk * dT (k x k)
-    st = launch_pack_chain(s, make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0),
-                           make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
+    if (!W_saved)
+        st = launch_pack_chain(s, make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0),
+                               make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
     if (st != PF_OK) return st;
     ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)dX,
                 (uint16_t *)dT16,     g.Cout,            g.C,               g.H,     g.W,
@@ -416,15 +428,22 @@ size_t pf_lowrank_conv_bwd_workspace_bytes(const pf_conv_desc *d)
     return plan_conv(g, d->dtype).bwd_bytes;
 }
 
+size_t pf_lowrank_conv_saved_weights_bytes(const pf_conv_desc *d)
+{
+    ConvGeom g;
+    if (check_conv_desc(d, &g) != PF_OK) return 0;
+    return d->dtype == PF_BF16 ? plan_conv(g, d->dtype).saved_bytes : 0;
+}
+
 int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, void *Y, void *T_save,
-                        void *workspace, size_t workspace_bytes, void *stream)
+                        void *W_save, void *workspace, size_t workspace_bytes, void *stream)
 {
     ConvGeom g;
     int st = check_conv_desc(d, &g);
     if (st != PF_OK) return st;
     if (!Uk || !Vp) return PF_ERR_NULL;
     if (g.N > 0 && (!X || !Y)) return PF_ERR_NULL;
-    if (any_misaligned({X, Uk, Vp, Y, T_save}, 16)) return PF_ERR_UNSUPPORTED;
+    if (any_misaligned({X, Uk, Vp, Y, T_save, W_save}, 16)) return PF_ERR_UNSUPPORTED;
     const ConvPlan p = plan_conv(g, d->dtype);
     if (p.fwd_bytes > 0 && (!workspace || workspace_bytes < p.fwd_bytes)) return PF_ERR_WORKSPACE;
     if (g.N == 0) return PF_OK;
@@ -435,21 +454,21 @@ int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, co
                                        (float *)T_save, ws, s);
     if (p.chain)
         return conv_fwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
-                              (bf16_t *)T_save, ws, s);
+                              (bf16_t *)T_save, W_save, ws, s);
     return conv_fwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
                                     (bf16_t *)T_save, ws, s);
 }
 
 int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dY,
-                        const void *T_saved, void *dX, void *dUk, void *dVp, int accumulate, void *workspace,
-                        size_t workspace_bytes, void *stream)
+                        const void *T_saved, const void *W_saved, void *dX, void *dUk, void *dVp, int accumulate,
+                        void *workspace, size_t workspace_bytes, void *stream)
 {
     ConvGeom g;
     int st = check_conv_desc(d, &g);
     if (st != PF_OK) return st;
     if (!Uk || !Vp) return PF_ERR_NULL;
     if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
-    if (any_misaligned({X, Uk, Vp, dY, T_saved, dX}, 16) || any_misaligned({dUk, dVp}, 4)) return PF_ERR_UNSUPPORTED;
+    if (any_misaligned({X, Uk, Vp, dY, T_saved, W_saved, dX}, 16) || any_misaligned({dUk, dVp}, 4)) return PF_ERR_UNSUPPORTED;
     const ConvPlan p = plan_conv(g, d->dtype);
     if (p.bwd_bytes > 0 && (!workspace || workspace_bytes < p.bwd_bytes)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);
@@ -467,7 +486,8 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, co
                                        s);
     if (p.chain && dX)
         return conv_bwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
-                              (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk, (float *)dVp, accumulate, ws, s);
+                              (const bf16_t *)T_saved, p.saved_bytes ? W_saved : nullptr, (bf16_t *)dX, (float *)dUk,
+                              (float *)dVp, accumulate, ws, s);
     return conv_bwd_generic<bf16_t>(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp,
                                     (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk,
                                     (float *)dVp, accumulate, ws, s);

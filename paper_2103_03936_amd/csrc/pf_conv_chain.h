@@ -57,7 +57,7 @@ struct PackW2 {
 };
 PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap);
 PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o, i64 s_rho, i64 s_tap);
-int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2);
+int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3 = PackW1{});
 // The fully connected layer on the same kernel: Y[rows][C2] = (X[rows][C1] W1^T) W2^T + bias, W2 = a.W2nat.
 bool linear_chain_supported(i64 n_in, i64 n_out, i64 r);
 int launch_linear_chain(hipStream_t s, const char *name, const ChainArgs &a, int R);

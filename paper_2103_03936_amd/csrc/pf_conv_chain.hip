@@ -414,14 +414,16 @@ __device__ __forceinline__ void pack_w2_item(const PackW2 &p, int g)
     p.dst[g] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
 }
 
-// Both weight sets of one chain call in a single launch (either count may be zero).
-__global__ __launch_bounds__(256) void pack_chain_kernel(PackW1 p1, PackW2 p2)
+// All weight sets of one call in a single launch (any count may be zero).
+__global__ __launch_bounds__(256) void pack_chain_kernel(PackW1 p1, PackW2 p2, PackW1 p3)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
     if (g < p1.n)
         pack_w1_item(p1, g);
     else if (g - p1.n < p2.n)
         pack_w2_item(p2, g - p1.n);
+    else if (g - p1.n - p2.n < p3.n)
+        pack_w1_item(p3, g - p1.n - p2.n);
 }
 
 bool chain_supported(int C1, int C2, int R, int H, int W, int k, int stride, int pad)
@@ -466,12 +468,12 @@ PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 b
     return p;
 }
 
-int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2)
+int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3)
 {
     int st = PF_OK;
-    const int n = p1.n + p2.n;
+    const int n = p1.n + p2.n + p3.n;
     if (n <= 0) return st;
-    PF_LAUNCH(st, "pack_chain", pack_chain_kernel, dim3((n + 255) / 256), dim3(256), s, p1, p2);
+    PF_LAUNCH(st, "pack_chain", pack_chain_kernel, dim3((n + 255) / 256), dim3(256), s, p1, p2, p3);
     return st;
 }
 

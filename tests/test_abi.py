@@ -74,20 +74,25 @@ def _conv(N=2, C=3, H=5, W=5, Cout=4, r=2, k=3, s=1, p=1, dtype=0):
 def test_conv_validation():
     f = pf.lib.pf_lowrank_conv_fwd
     z = ctypes.c_size_t(0)
-    assert f(None, FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 1
-    assert f(ctypes.byref(_conv(C=0)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 2
-    assert f(ctypes.byref(_conv(s=0)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 2
-    assert f(ctypes.byref(_conv(H=2, W=2, k=5, p=0)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 2
-    assert f(ctypes.byref(_conv(dtype=9)), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 3
-    assert f(ctypes.byref(_conv()), FAKE, None, FAKE, FAKE, None, None, z, None) == 1
+    assert f(None, FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 1
+    assert f(ctypes.byref(_conv(C=0)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 2
+    assert f(ctypes.byref(_conv(s=0)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 2
+    assert f(ctypes.byref(_conv(H=2, W=2, k=5, p=0)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 2
+    assert f(ctypes.byref(_conv(dtype=9)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 3
+    assert f(ctypes.byref(_conv()), FAKE, None, FAKE, FAKE, None, None, None, z, None) == 1
     d = _conv()
     need = pf.lib.pf_lowrank_conv_fwd_workspace_bytes(ctypes.byref(d))
     if need:
-        assert f(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, z, None) == 4
-    assert f(ctypes.byref(_conv(N=0)), None, FAKE, FAKE, None, None, None, z, None) == 0
+        assert f(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 4
+    assert f(ctypes.byref(_conv(N=0)), None, FAKE, FAKE, None, None, None, None, z, None) == 0
     b = pf.lib.pf_lowrank_conv_bwd
-    assert b(ctypes.byref(_conv()), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, 0, None, z, None) == 1
-    assert b(ctypes.byref(_conv()), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 0, None, z, None) == 4
+    assert b(ctypes.byref(_conv()), FAKE, FAKE, FAKE, None, None, None, FAKE, FAKE, FAKE, 0, None, z, None) == 1
+    assert b(ctypes.byref(_conv()), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, 0, None, z, None) == 4
+    # the saved-weights buffer exists for the fused bf16 path only
+    assert pf.lib.pf_lowrank_conv_saved_weights_bytes(ctypes.byref(_conv())) == 0
+    fused = _conv(N=4, C=256, H=8, W=8, Cout=256, r=64, dtype=1)
+    assert pf.lib.pf_lowrank_conv_saved_weights_bytes(ctypes.byref(fused)) == 2 * (256 * 64 + 9 * 256 * 64)
+    assert f(ctypes.byref(fused), FAKE, FAKE, FAKE, FAKE, None, P(256 + 8), None, z, None) == 3
 
 
 def _lstm(B=2, d=3, h=4, r=2, groups=1, dtype=0, bias=1):

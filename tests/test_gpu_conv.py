@@ -23,16 +23,20 @@ SHAPES = [
 ]
 
 
-def _run(shape, dtype, saved_T=True, seed=0):
+def _run(shape, dtype, saved_T=True, seed=0, saved_W=False):
     import paper_2103_03936_amd as pf
     N, C, H, W, Cout, r, k, s, p = shape
     a = workloads.conv_inputs(N, C, H, W, Cout, r, k, s, p, dtype=dtype, seed=seed)
     Yo, To = oracle.lowrank_conv_fwd(a["X"], a["Uk"], a["Vp"], s, p)
     dXo, dUo, dVo = oracle.lowrank_conv_bwd(a["X"], a["Uk"], a["Vp"], a["dY"], s, p)
     g = {k_: to_gpu(v, dtype) for k_, v in a.items()}
-    Y, T = pf.pf_lowrank_conv_fwd(g["X"], g["Uk"], g["Vp"], s, p, save_T=True)
+    Wsv = None
+    if saved_W:
+        Y, T, Wsv = pf.pf_lowrank_conv_fwd(g["X"], g["Uk"], g["Vp"], s, p, save_T=True, save_W=True)
+    else:
+        Y, T = pf.pf_lowrank_conv_fwd(g["X"], g["Uk"], g["Vp"], s, p, save_T=True)
     dX, dUk, dVp = pf.pf_lowrank_conv_bwd(g["X"], g["Uk"], g["Vp"], g["dY"], T_saved=T if saved_T else None,
-                                          stride=s, pad=p)
+                                          stride=s, pad=p, W_saved=Wsv)
     torch.cuda.synchronize()
     tag = f"conv{shape}[{dtype}]"
     assert_close(Y, Yo, dtype, tag + " Y")
@@ -48,6 +52,34 @@ def _run(shape, dtype, saved_T=True, seed=0):
 @pytest.mark.parametrize("shape", SHAPES)
 def test_parity(shape, dtype):
     _run(shape, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_parity_with_weights_saved_by_forward(shape, dtype):
+    """The forward call also re-orders the factors for the backward kernels (W_save); where the backward pass
+    reads them in place the buffer is empty and nothing changes."""
+    _run(shape, dtype, saved_W=True, seed=3)
+
+
+# shapes the fused small-image kernels take in bfloat16 (channels a multiple of 256, rank 64 or 128, images of at
+# most 8 x 8): 8 x 8 and 7 x 7 have their own instantiations, every other height and width shares one
+FUSED_SHAPES = [
+    (9, 256, 8, 8, 256, 64, 3, 1, 1),
+    (5, 512, 7, 7, 256, 128, 3, 1, 1),
+    (6, 256, 7, 7, 512, 128, 1, 1, 0),
+    (3, 256, 5, 6, 256, 64, 3, 1, 1),
+    (4, 256, 3, 8, 256, 128, 3, 1, 1),
+    (2, 256, 4, 4, 512, 128, 1, 1, 0),
+    (7, 512, 2, 3, 256, 64, 1, 1, 0),
+    (1, 256, 1, 1, 256, 64, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("saved_W", [False, True])
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+def test_parity_fused_shapes(shape, saved_W):
+    _run(shape, "bf16", saved_W=saved_W, seed=11)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -109,7 +141,8 @@ def test_resnet18_conv4_full_size():
     # CIFAR ResNet-18 conv4_x, batch 128 (Appendix D): the benchmark workload, in the
     # configuration bench.py times
     c = workloads.CONFIGS["resnet18_conv4_bf16"]
-    _run((c["N"], c["C"], c["H"], c["W"], c["Cout"], c["r"], c["k"], c["stride"], c["pad"]), c["dtype"], seed=c["seed"])
+    _run((c["N"], c["C"], c["H"], c["W"], c["Cout"], c["r"], c["k"], c["stride"], c["pad"]), c["dtype"], seed=c["seed"],
+         saved_W=True)
 
 
 @pytest.mark.parametrize("layer", ["conv1", "conv2", "conv3"])
@@ -119,4 +152,4 @@ def test_resnet50_conv5_full_size(layer):
     # compared for a 16-image batch as well (same kernels and tiling, fewer tiles).
     c = workloads.CONFIGS["resnet50_conv5_bf16"]
     Cin, Cout, r, k, p = c["layers"][layer]
-    _run((16, Cin, c["H"], c["W"], Cout, r, k, 1, p), c["dtype"], seed=c["seed"])
+    _run((16, Cin, c["H"], c["W"], Cout, r, k, 1, p), c["dtype"], seed=c["seed"], saved_W=True)
