@@ -136,10 +136,15 @@ class LinearWorkload:
     def __init__(self, name, cfg):
         self.name, self.dtype, self.M, self.seed = name, cfg["dtype"], cfg["M"], cfg["seed"]
         self.layers = cfg["layers"] if cfg["kind"] == "linear_set" else {"fc": (cfg["n_in"], cfg["n_out"], cfg["r"])}
+        # names of layers of one shape that read the same input and run through the shared-input entry points
+        self.shared = tuple(cfg.get("shared", ()))
 
     def describe(self):
-        return {"workload": self.name, "tokens": self.M,
-                "layers": {k: {"in": v[0], "out": v[1], "r": v[2]} for k, v in self.layers.items()}}
+        d = {"workload": self.name, "tokens": self.M,
+             "layers": {k: {"in": v[0], "out": v[1], "r": v[2]} for k, v in self.layers.items()}}
+        if self.shared:
+            d["shared_input"] = list(self.shared)
+        return d
 
     def flops(self):
         return sum(6.0 * self.M * r * (i + o) for i, o, r in self.layers.values())
@@ -151,32 +156,50 @@ class LinearWorkload:
         td = torch.bfloat16 if self.dtype == "bf16" else torch.float32
         out = {}
         for lname, (i, o, r) in self.layers.items():
+            if lname in self.shared:
+                continue
             a = workloads.linear_inputs(self.M, i, o, r, dtype=self.dtype, seed=self.seed * 1000 + idx, bias=True)
             out[lname] = {n: torch.from_numpy(v).to(td).cuda().contiguous() for n, v in a.items()}
+        if self.shared:
+            i, o, r = self.layers[self.shared[0]]
+            a = workloads.linear_shared_inputs(self.M, i, o, r, len(self.shared), dtype=self.dtype,
+                                               seed=self.seed * 1000 + idx, bias=True)
+            out["+".join(self.shared)] = {n: torch.from_numpy(v).to(td).cuda().contiguous() for n, v in a.items()}
         return out
 
     def step(self, pf, s):
         for g in s.values():
-            Y, T = pf.pf_lowrank_linear_fwd(g["X"], g["V"], g["U"], g["bias"], save_T=True)
-            pf.pf_lowrank_linear_bwd(g["X"], g["V"], g["U"], g["dY"], T_saved=T, has_bias=True)
+            if g["V"].dim() == 3:
+                Y, T = pf.pf_lowrank_linear_shared_fwd(g["X"], g["V"], g["U"], g["bias"], save_T=True)
+                pf.pf_lowrank_linear_shared_bwd(g["X"], g["V"], g["U"], g["dY"], T_saved=T, has_bias=True)
+            else:
+                Y, T = pf.pf_lowrank_linear_fwd(g["X"], g["V"], g["U"], g["bias"], save_T=True)
+                pf.pf_lowrank_linear_bwd(g["X"], g["V"], g["U"], g["dY"], T_saved=T, has_bias=True)
+
+    @staticmethod
+    def _dense_layers(g):
+        """(X, W, bias, dY) of every dense layer a set entry stands for."""
+        if g["V"].dim() == 3:
+            return [(g["X"], g["W"][k], g["bias"][k], g["dY"][k]) for k in range(g["V"].shape[0])]
+        return [(g["X"], g["W"], g["bias"], g["dY"])]
 
     def dense_prepare(self, s, torch):
         for g in s.values():
             if "W" not in g:
-                g["W"] = (g["U"].float() @ g["V"].float().T).to(g["X"].dtype).contiguous()
+                g["W"] = (g["U"].float() @ g["V"].float().transpose(-1, -2)).to(g["X"].dtype).contiguous()
 
     def dense_step(self, pf, s):
         for g in s.values():
-            pf.pf_dense_linear_fwd(g["X"], g["W"], g["bias"])
-            pf.pf_dense_linear_bwd(g["X"], g["W"], g["dY"], has_bias=True)
+            for X, W, b, dY in self._dense_layers(g):
+                pf.pf_dense_linear_fwd(X, W, b)
+                pf.pf_dense_linear_bwd(X, W, dY, has_bias=True)
 
     def library_dense_prepare(self, s, torch):
         out = []
         for g in s.values():
-            X = g["X"].detach().clone().requires_grad_(True)
-            W = g["W"].detach().clone().requires_grad_(True)
-            b = g["bias"].detach().clone().requires_grad_(True)
-            out.append((X, W, b, g["dY"]))
+            for X, W, b, dY in self._dense_layers(g):
+                out.append((X.detach().clone().requires_grad_(True), W.detach().clone().requires_grad_(True),
+                            b.detach().clone().requires_grad_(True), dY))
         return out
 
     def library_dense_step(self, prep, torch):
@@ -208,17 +231,31 @@ class LinearWorkload:
             add("linear_fwd_fused", 2.0 * M * r * (i + o), s * (M * i + M * o + M * r + r * (i + o)))
             add("linear_bwd_data_fused", 2.0 * M * r * (i + o), s * (M * o + M * i + M * r + r * (i + o)))
             add("linear_wgrad_pair", 2.0 * M * r * (i + o), s * (M * i + M * o + 2 * M * r) + 4 * r * (i + o))
+        if self.shared:  # one launch for all the projections of the shared input: X and dX move once
+            i, o, r = self.layers[self.shared[0]]
+            G = len(self.shared)
+            add("linear_shared_fwd_fused", 2.0 * G * M * r * (i + o), s * (M * i + G * (M * o + M * r + r * (i + o))))
+            add("linear_shared_bwd_data_fused", 2.0 * G * M * r * (i + o),
+                s * (M * i + G * (M * o + M * r + r * (i + o))))
         return out
 
     def cpu_baseline(self, oracle, workloads, reps=3):
         inputs = [workloads.linear_inputs(self.M, i, o, r, dtype=self.dtype, seed=self.seed, bias=True)
-                  for i, o, r in self.layers.values()]
+                  for n, (i, o, r) in self.layers.items() if n not in self.shared]
+        shared = None
+        if self.shared:
+            i, o, r = self.layers[self.shared[0]]
+            shared = workloads.linear_shared_inputs(self.M, i, o, r, len(self.shared), dtype=self.dtype, seed=self.seed,
+                                                    bias=True)
         times = []
         for rep in range(reps):
             t0 = time.perf_counter()
             for a in inputs:
                 oracle.lowrank_linear_fwd(a["X"], a["V"], a["U"], a["bias"])
                 oracle.lowrank_linear_bwd(a["X"], a["V"], a["U"], a["dY"])
+            if shared:
+                oracle.lowrank_linear_shared_fwd(shared["X"], shared["V"], shared["U"], shared["bias"])
+                oracle.lowrank_linear_shared_bwd(shared["X"], shared["V"], shared["U"], shared["dY"])
             times.append(time.perf_counter() - t0)
         return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
 

@@ -94,6 +94,43 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
                           size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ */
+/* Several factorized projections of the same shape that read the SAME */
+/* input, e.g. the query, key and value matrices of an attention block  */
+/* (paper Section 2.4; each is the layer of Section 2.1):              */
+/*   Y_g = (X V_g) U_g^T + bias_g,  g = 0 .. groups-1.                  */
+/*   V[groups, in, r], U[groups, out, r], bias[groups, out],            */
+/*   Y[groups, M, out], T_save[groups, M, r] (nullable).                */
+/* Backward: dY[groups, M, out] gives dX = sum_g dY_g U_g V_g^T (ONE    */
+/* tensor [M, in]: the input is shared) and dU, dV, dbias per group in  */
+/* the layouts of U, V, bias (float; each nullable).  Results equal     */
+/* those of `groups` calls of pf_lowrank_linear_fwd/bwd with the input   */
+/* gradients added up; X and the running sum dX are read and written    */
+/* once instead of once per projection.                                 */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t M, n_in, n_out, r;
+    int groups; /* 1 .. 64 */
+    int dtype;  /* pf_dtype */
+    int has_bias;
+} pf_linear_shared_desc;
+
+size_t pf_lowrank_linear_shared_fwd_workspace_bytes(const pf_linear_shared_desc *d);
+size_t pf_lowrank_linear_shared_bwd_workspace_bytes(const pf_linear_shared_desc *d);
+
+int pf_lowrank_linear_shared_fwd(const pf_linear_shared_desc *d, const void *X,
+                                 const void *V, const void *U,
+                                 const void *bias /* nullable */, void *Y,
+                                 void *T_save /* nullable */, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+int pf_lowrank_linear_shared_bwd(const pf_linear_shared_desc *d, const void *X,
+                                 const void *V, const void *U, const void *dY,
+                                 const void *T_saved /* nullable */, void *dX,
+                                 void *dU, void *dV, void *dbias, int accumulate,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/* ------------------------------------------------------------------ */
 /* Convolution layer (paper Section 2.2 "Factorizing a convolution      */
 /* layer"; Appendix B "Convolution layer").                            */
 /*   X[N,Cin,H,W] (NCHW); Uk[r,Cin,k,k] = the r thin k x k basis        */

@@ -118,6 +118,33 @@ def lowrank_linear_bwd(X, V, U, dY):
     return dX, dU, dV, db
 
 
+def lowrank_linear_shared_fwd(X, V, U, bias=None):
+    """Projections that read one input (Section 2.4: the query, key and value matrices, each the layer of
+    Section 2.1): Y_g = (X V_g) U_g^T + b_g.  V[G,in,r], U[G,out,r], bias[G,out]; returns (Y[G,M,out], T[G,M,r])."""
+    G = U.shape[0]
+    Ys, Ts = [], []
+    for g in range(G):
+        Y, T = lowrank_linear_fwd(X, V[g], U[g], None if bias is None else bias[g])
+        Ys.append(Y)
+        Ts.append(T)
+    return np.stack(Ys), np.stack(Ts)
+
+
+def lowrank_linear_shared_bwd(X, V, U, dY):
+    """The input is shared, so its gradient is the sum of the projections' input gradients; the parameter
+    gradients are each projection's own.  Returns (dX[M,in], dU[G,out,r], dV[G,in,r], db[G,out])."""
+    G = U.shape[0]
+    dX = np.zeros(X.shape, dtype=np.float64)
+    dUs, dVs, dbs = [], [], []
+    for g in range(G):
+        dXg, dU, dV, db = lowrank_linear_bwd(X, V[g], U[g], dY[g])
+        dX += dXg
+        dUs.append(dU)
+        dVs.append(dV)
+        dbs.append(db)
+    return dX, np.stack(dUs), np.stack(dVs), np.stack(dbs)
+
+
 # ------------------------------------------------------------------ conv
 
 def dense_conv_fwd(X, Wd, stride=1, pad=0):

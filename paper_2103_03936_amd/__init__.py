@@ -27,6 +27,11 @@ class pf_linear_desc(ctypes.Structure):
                 ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
 
 
+class pf_linear_shared_desc(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("n_in", ctypes.c_int64), ("n_out", ctypes.c_int64), ("r", ctypes.c_int64),
+                ("groups", ctypes.c_int), ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
+
+
 class pf_conv_desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("Cin", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
                 ("Cout", ctypes.c_int64), ("r", ctypes.c_int64), ("k", ctypes.c_int), ("stride", ctypes.c_int),
@@ -51,6 +56,8 @@ EXPORTS = [
     "pf_status_string", "pf_last_hip_error", "pf_version",
     "pf_lowrank_linear_fwd_workspace_bytes", "pf_lowrank_linear_bwd_workspace_bytes",
     "pf_lowrank_linear_fwd", "pf_lowrank_linear_bwd",
+    "pf_lowrank_linear_shared_fwd_workspace_bytes", "pf_lowrank_linear_shared_bwd_workspace_bytes",
+    "pf_lowrank_linear_shared_fwd", "pf_lowrank_linear_shared_bwd",
     "pf_lowrank_conv_fwd_workspace_bytes", "pf_lowrank_conv_bwd_workspace_bytes",
     "pf_lowrank_conv_saved_weights_bytes", "pf_lowrank_conv_fwd", "pf_lowrank_conv_bwd",
     "pf_lowrank_lstm_cell_fwd_workspace_bytes", "pf_lowrank_lstm_cell_bwd_workspace_bytes",
@@ -161,6 +168,48 @@ def pf_lowrank_linear_bwd(X, V, U, dY, T_saved=None, need_dX=True, has_bias=Fals
                                      _ptr(T_saved, dt), _ptr(dX), _ptr(dU, torch.float32), _ptr(dV, torch.float32),
                                      _ptr(db, torch.float32), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
                                      ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_linear_bwd")
+    return dX, dU, dV, db
+
+
+def _shared_desc(X, U, bias_flag):
+    M, n_in = X.shape
+    G, n_out, r = U.shape
+    return pf_linear_shared_desc(M, n_in, n_out, r, G, _dtype_code(X), 1 if bias_flag else 0)
+
+
+def pf_lowrank_linear_shared_fwd(X, V, U, bias=None, save_T=True):
+    """G projections of one input (Q, K, V of attention): X[M,in], V[G,in,r], U[G,out,r], bias[G,out] -> (Y[G,M,out],
+    T[G,M,r])."""
+    d = _shared_desc(X, U, bias is not None)
+    dt = X.dtype
+    Y = torch.empty((d.groups, d.M, d.n_out), dtype=dt, device=X.device)
+    T = torch.empty((d.groups, d.M, d.r), dtype=dt, device=X.device) if save_T else None
+    ws = _workspace(lib.pf_lowrank_linear_shared_fwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_linear_shared_fwd(ctypes.byref(d), _ptr(X), _ptr(V, dt), _ptr(U, dt), _ptr(bias, dt), _ptr(Y),
+                                            _ptr(T), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "pf_lowrank_linear_shared_fwd")
+    return Y, T
+
+
+def pf_lowrank_linear_shared_bwd(X, V, U, dY, T_saved=None, need_dX=True, has_bias=False, grads=None):
+    """dY[G,M,out] -> (dX[M,in] summed over the projections, dU[G,out,r], dV[G,in,r], dbias[G,out]); the parameter
+    gradients are float32 and accumulate into `grads` = (dU, dV, dbias) when given."""
+    d = _shared_desc(X, U, has_bias)
+    dt = X.dtype
+    f32 = torch.float32
+    dX = torch.empty_like(X) if need_dX else None
+    accumulate = grads is not None
+    if grads is None:
+        dU = torch.empty(U.shape, dtype=f32, device=X.device)
+        dV = torch.empty(V.shape, dtype=f32, device=X.device)
+        db = torch.empty((d.groups, d.n_out), dtype=f32, device=X.device) if has_bias else None
+    else:
+        dU, dV, db = grads
+    ws = _workspace(lib.pf_lowrank_linear_shared_bwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_linear_shared_bwd(ctypes.byref(d), _ptr(X, dt), _ptr(V, dt), _ptr(U, dt), _ptr(dY, dt),
+                                            _ptr(T_saved, dt), _ptr(dX), _ptr(dU, f32), _ptr(dV, f32), _ptr(db, f32),
+                                            ctypes.c_int(1 if accumulate else 0), _ptr(ws),
+                                            ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_linear_shared_bwd")
     return dX, dU, dV, db
 
 

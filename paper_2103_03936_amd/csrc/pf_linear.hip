@@ -103,6 +103,12 @@ static int check_linear_desc(const pf_linear_desc *d)
     return PF_OK;
 }
 
+int linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias, void *Y,
+                     void *T_save, void *workspace, size_t workspace_bytes, void *stream, int align);
+int linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
+                     const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate, void *workspace,
+                     size_t workspace_bytes, void *stream, int align);
+
 // ---------------------------------------------------------- workspace plan
 struct LinearPlan {
     int ks_dU, ks_dV;
@@ -278,6 +284,31 @@ static int linear_fwd_fused(const pf_linear_desc *d, const bf16_t *X, const bf16
     return launch_linear_chain(s, "linear_fwd_fused", a, r);
 }
 
+// Both factor gradients in one launch, their group sums, and the bias gradient (from the column sums the chain
+// kernel left, two rows per 32-row tile, or from dY).
+static int linear_wgrads_fused(const pf_linear_desc *d, const LinearPlan &p, const bf16_t *X, const bf16_t *dY,
+                               const bf16_t *Tt, const bf16_t *dT16, float *dU, float *dV, float *dbias,
+                               const float *colsum, int accumulate, float *part, hipStream_t s)
+{
+    const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    const bool want_db = d->has_bias && dbias;
+    const int tiles = (M + 63) / 64;
+    float *part_dU = part, *part_dV = part + (size_t)p.wg_groups * r * out;
+    WgradArgs a1{(const uint16_t *)Tt, (const uint16_t *)dY, dU ? part_dU : nullptr, r, out, 8, 8, tiles, p.wg_ipg,
+                 p.wg_groups,          d->M};
+    WgradArgs a2{(const uint16_t *)dT16, (const uint16_t *)X, dV ? part_dV : nullptr, r, in, 8, 8, tiles, p.wg_ipg,
+                 p.wg_groups,            d->M};
+    int st = launch_linear_wgrad_pair(s, a1, a2, p.wg_cols);
+    if (st != PF_OK) return st;
+    WgradReduceArgs r0{part_dU, dU, p.wg_groups, 1, r, out, 1, r, 0, accumulate};
+    WgradReduceArgs r1{part_dV, dV, p.wg_groups, 1, r, in, 1, r, 0, accumulate};
+    const ColsumTilesArgs cs{colsum, dbias, 2 * ((M + LC_ROWS - 1) / LC_ROWS), out, accumulate};
+    st = launch_wgrad_reduce(s, r0, r1, want_db && colsum ? &cs : nullptr);
+    if (st != PF_OK) return st;
+    if (want_db && !colsum) st = launch_colsum<bf16_t>(s, dY, part, dbias, M, out, out, accumulate);
+    return st;
+}
+
 // dT = dY U, dX = dT V^T on the same kernel (stage 1 weights = U^T re-ordered, stage 2 weights = V[in][r] in
 // place); then both factor gradients in one launch, their group sums, and the bias gradient.
 static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const bf16_t *X, const bf16_t *V,
@@ -313,25 +344,8 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
         st = launch_linear_chain(s, "linear_bwd_data_fused", a, r);
     }
     if (st != PF_OK) return st;
-    const int tiles = (M + 63) / 64;
-    float *part_dU = part, *part_dV = part + (size_t)p.wg_groups * r * out;
-    const bf16_t *Tt = T_saved ? T_saved : T16;
-    WgradArgs a1{(const uint16_t *)Tt, (const uint16_t *)dY, dU ? part_dU : nullptr, r, out, 8, 8, tiles, p.wg_ipg,
-                 p.wg_groups,          d->M};
-    WgradArgs a2{(const uint16_t *)dT16, (const uint16_t *)X, dV ? part_dV : nullptr, r, in, 8, 8, tiles, p.wg_ipg,
-                 p.wg_groups,            d->M};
-    st = launch_linear_wgrad_pair(s, a1, a2, p.wg_cols);
-    if (st != PF_OK) return st;
-    WgradReduceArgs r0{part_dU, dU, p.wg_groups, 1, r, out, 1, r, 0, accumulate};
-    WgradReduceArgs r1{part_dV, dV, p.wg_groups, 1, r, in, 1, r, 0, accumulate};
-    // (the chain kernel left two rows of column sums of dY per 32-row tile: the bias gradient rides along)
-    const ColsumTilesArgs cs{colsum, dbias, 2 * ((M + LC_ROWS - 1) / LC_ROWS), out, accumulate};
-    st = launch_wgrad_reduce(s, r0, r1, want_db && p.chain2 ? &cs : nullptr);
-    if (st != PF_OK) return st;
-    if (want_db && !p.chain2) st = launch_colsum<bf16_t>(s, dY, part, dbias, M, out, out, accumulate);
-    return st;
+    return linear_wgrads_fused(d, p, X, dY, T_saved ? T_saved : T16, dT16, dU, dV, dbias, colsum, accumulate, part, s);
 }
-
 
 // ------------------------------------------------------------- fp32, few rows
 static int linear_T_skinny(const pf_linear_desc *d, const float *X, const float *V, float *T, float *part, hipStream_t s)
@@ -459,32 +473,99 @@ static int dense_linear_bwd_t(const pf_linear_desc *d, const T *X, const T *W, c
     return st;
 }
 
+// ------------------------------------------------- projections that share their input
+template <typename T>
+__global__ void add_into_kernel(T *dst, const T *src, i64 count)
+{
+    const i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = from_float<T>(to_float(dst[i]) + to_float(src[i]));
+}
+
+template <typename T>
+static int launch_add_into(hipStream_t s, T *dst, const T *src, i64 count)
+{
+    int st = PF_OK;
+    if (count <= 0) return st;
+    PF_LAUNCH(st, "add_into", add_into_kernel<T>, dim3((unsigned)((count + 255) / 256)), dim3(256), s, dst, src, count);
+    return st;
+}
+
+struct SharedPlan {
+    pf_linear_desc one; // one of the G layers
+    LinearPlan p;
+    bool fused_fwd, fused_bwd; // the groups run inside one launch of the chain kernel
+    size_t n_colsum, fwd_bytes, bwd_bytes;
+};
+
+static int check_shared_desc(const pf_linear_shared_desc *d, pf_linear_desc *one)
+{
+    if (!d) return PF_ERR_NULL;
+    *one = pf_linear_desc{d->M, d->n_in, d->n_out, d->r, d->dtype, d->has_bias};
+    int st = check_linear_desc(one);
+    if (st != PF_OK) return st;
+    if (d->groups <= 0 || d->groups > 64) return PF_ERR_SHAPE;
+    const i64 lim = 0x7fffffffLL;
+    if (d->groups * d->M * d->n_out > (lim << 4)) return PF_ERR_SHAPE;
+    return PF_OK;
+}
+
+static SharedPlan plan_shared(const pf_linear_shared_desc *d, const pf_linear_desc &one)
+{
+    SharedPlan sp;
+    sp.one = one;
+    sp.p = plan_linear(&one);
+    const int G = d->groups;
+    const bool bf = d->dtype == PF_BF16 && sp.p.chain2 && d->M > 0 && G > 1;
+    sp.fused_fwd = bf && linear_chain2_multi_supported(d->n_in, d->n_out, d->r, G, false);
+    sp.fused_bwd = bf && linear_chain2_multi_supported(d->n_out, d->n_in, d->r, G, true);
+    sp.n_colsum = (size_t)(2 * ((d->M + LC_ROWS - 1) / LC_ROWS)) * d->n_out;
+    const size_t el = d->dtype == PF_BF16 ? 2 : 4;
+    sp.fwd_bytes = sp.p.fwd_bytes;
+    // one layer's workspace, then: dT and (recomputed) T of all groups, their column sums, one more dX
+    sp.bwd_bytes = sp.p.bwd_bytes + 2 * align_up((size_t)G * sp.p.n_T * 2) + align_up((size_t)G * sp.n_colsum * 4) +
+                   align_up((size_t)(d->M * d->n_in) * el);
+    return sp;
+}
+
+// Alignment a layer's slice of the stacked operands is held to: 16 bytes where the 16-byte-load kernels may run
+// (their shapes make every slice a multiple of 16 bytes anyway), else that of an element or of the 4-byte loads
+// of the few-row fp32 kernels.
+static int layer_align(const SharedPlan &sp, size_t el) { return sp.p.fused ? 16 : (int)(el < 4 ? el : 4); }
+
+template <typename T>
+static int shared_bwd_loop(const pf_linear_shared_desc *d, const SharedPlan &sp, const T *X, const T *V, const T *U,
+                           const T *dY, const T *T_saved, T *dX, float *dU, float *dV, float *dbias, int accumulate,
+                           void *workspace, size_t workspace_bytes, hipStream_t s)
+{
+    // layer by layer; the input gradients of the layers after the first go to a spare buffer and are added
+    const i64 M = d->M, in = d->n_in, out = d->n_out, r = d->r;
+    T *spare = (T *)((char *)workspace + sp.p.bwd_bytes);
+    int st = PF_OK;
+    for (int g = 0; g < d->groups && st == PF_OK; ++g) {
+        T *dXg = !dX ? nullptr : g == 0 ? dX : spare;
+        st = linear_bwd_entry(&sp.one, X, V + g * in * r, U + g * out * r, dY + g * M * out,
+                              T_saved ? T_saved + g * M * r : nullptr, dXg, dU ? dU + g * out * r : nullptr,
+                              dV ? dV + g * in * r : nullptr, dbias ? dbias + g * out : nullptr, accumulate, workspace,
+                              workspace_bytes, s, layer_align(sp, sizeof(T)));
+        if (st == PF_OK && dX && g > 0) st = launch_add_into<T>(s, dX, spare, M * in);
+    }
+    return st;
+}
+
 } // namespace pf
 
 using namespace pf;
 
-extern "C" {
-
-size_t pf_lowrank_linear_fwd_workspace_bytes(const pf_linear_desc *d)
-{
-    if (check_linear_desc(d) != PF_OK) return 0;
-    return plan_linear(d).fwd_bytes;
-}
-
-size_t pf_lowrank_linear_bwd_workspace_bytes(const pf_linear_desc *d)
-{
-    if (check_linear_desc(d) != PF_OK) return 0;
-    return plan_linear(d).bwd_bytes;
-}
-
-int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias,
-                          void *Y, void *T_save, void *workspace, size_t workspace_bytes, void *stream)
+// `align`: what the data pointers must be multiples of (16 for callers; the layers of a shared-input call may
+// start anywhere an element does when their shape is one the element-wise kernels take)
+int pf::linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias,
+                         void *Y, void *T_save, void *workspace, size_t workspace_bytes, void *stream, int align)
 {
     int st = check_linear_desc(d);
     if (st != PF_OK) return st;
     if (!V || !U || (d->has_bias && !bias)) return PF_ERR_NULL;
     if (d->M > 0 && (!X || !Y)) return PF_ERR_NULL;
-    if (any_misaligned({X, V, U, bias, Y, T_save}, 16)) return PF_ERR_UNSUPPORTED;
+    if (any_misaligned({X, V, U, bias, Y, T_save}, align)) return PF_ERR_UNSUPPORTED;
     const size_t need = plan_linear(d).fwd_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     if (d->M == 0) return PF_OK;
@@ -503,15 +584,15 @@ int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V,
                                       (const bf16_t *)bias, (bf16_t *)Y, (bf16_t *)T_save, ws, s);
 }
 
-int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
-                          const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate,
-                          void *workspace, size_t workspace_bytes, void *stream)
+int pf::linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
+                         const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate,
+                         void *workspace, size_t workspace_bytes, void *stream, int align)
 {
     int st = check_linear_desc(d);
     if (st != PF_OK) return st;
     if (!V || !U) return PF_ERR_NULL;
     if (d->M > 0 && (!X || !dY)) return PF_ERR_NULL;
-    if (any_misaligned({X, V, U, dY, T_saved, dX}, 16) || any_misaligned({dU, dV, dbias}, 4)) return PF_ERR_UNSUPPORTED;
+    if (any_misaligned({X, V, U, dY, T_saved, dX}, align) || any_misaligned({dU, dV, dbias}, 4)) return PF_ERR_UNSUPPORTED;
     const size_t need = plan_linear(d).bwd_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
     Workspace ws(workspace, workspace_bytes);
@@ -532,6 +613,34 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
     return linear_bwd_generic<bf16_t>(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U,
                                       (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dU,
                                       (float *)dV, (float *)dbias, accumulate, ws, s);
+}
+
+extern "C" {
+
+size_t pf_lowrank_linear_fwd_workspace_bytes(const pf_linear_desc *d)
+{
+    if (check_linear_desc(d) != PF_OK) return 0;
+    return plan_linear(d).fwd_bytes;
+}
+
+size_t pf_lowrank_linear_bwd_workspace_bytes(const pf_linear_desc *d)
+{
+    if (check_linear_desc(d) != PF_OK) return 0;
+    return plan_linear(d).bwd_bytes;
+}
+
+int pf_lowrank_linear_fwd(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias,
+                          void *Y, void *T_save, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return pf::linear_fwd_entry(d, X, V, U, bias, Y, T_save, workspace, workspace_bytes, stream, 16);
+}
+
+int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
+                          const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    return pf::linear_bwd_entry(d, X, V, U, dY, T_saved, dX, dU, dV, dbias, accumulate, workspace, workspace_bytes,
+                                stream, 16);
 }
 
 size_t pf_dense_linear_workspace_bytes(const pf_linear_desc *d)
@@ -572,6 +681,118 @@ int pf_dense_linear_bwd(const pf_linear_desc *d, const void *X, const void *W, c
                                          (float *)dW, (float *)dbias, accumulate, ws, s);
     return dense_linear_bwd_t<bf16_t>(d, (const bf16_t *)X, (const bf16_t *)W, (const bf16_t *)dY, (bf16_t *)dX,
                                       (float *)dW, (float *)dbias, accumulate, ws, s);
+}
+
+size_t pf_lowrank_linear_shared_fwd_workspace_bytes(const pf_linear_shared_desc *d)
+{
+    pf_linear_desc one;
+    if (check_shared_desc(d, &one) != PF_OK) return 0;
+    return plan_shared(d, one).fwd_bytes;
+}
+
+size_t pf_lowrank_linear_shared_bwd_workspace_bytes(const pf_linear_shared_desc *d)
+{
+    pf_linear_desc one;
+    if (check_shared_desc(d, &one) != PF_OK) return 0;
+    return plan_shared(d, one).bwd_bytes;
+}
+
+int pf_lowrank_linear_shared_fwd(const pf_linear_shared_desc *d, const void *X, const void *V, const void *U,
+                                 const void *bias, void *Y, void *T_save, void *workspace, size_t workspace_bytes,
+                                 void *stream)
+{
+    pf_linear_desc one;
+    int st = check_shared_desc(d, &one);
+    if (st != PF_OK) return st;
+    if (!V || !U || (d->has_bias && !bias)) return PF_ERR_NULL;
+    if (d->M > 0 && (!X || !Y)) return PF_ERR_NULL;
+    if (any_misaligned({X, V, U, bias, Y, T_save}, 16)) return PF_ERR_UNSUPPORTED;
+    const SharedPlan sp = plan_shared(d, one);
+    if (sp.fwd_bytes > 0 && (!workspace || workspace_bytes < sp.fwd_bytes)) return PF_ERR_WORKSPACE;
+    if (d->M == 0) return PF_OK;
+    const i64 M = d->M, in = d->n_in, out = d->n_out, r = d->r;
+    hipStream_t s = (hipStream_t)stream;
+    if (sp.fused_fwd) {
+        LinChainArgs c{(const uint16_t *)X, (const uint16_t *)V, (const uint16_t *)U,
+                       d->has_bias ? (const uint16_t *)bias : nullptr, (uint16_t *)Y, (uint16_t *)T_save, nullptr,
+                       M, (int)in, (int)out};
+        c.groups = d->groups;
+        c.gs_W1 = in * r;
+        c.gs_W2 = out * r;
+        c.gs_bias = out;
+        c.gs_out = M * out;
+        c.gs_mid = M * r;
+        return launch_linear_chain2(s, "linear_shared_fwd_fused", c);
+    }
+    const size_t el = d->dtype == PF_BF16 ? 2 : 4;
+    for (int g = 0; g < d->groups && st == PF_OK; ++g)
+        st = linear_fwd_entry(&one, X, (const char *)V + g * in * r * el, (const char *)U + g * out * r * el,
+                              bias ? (const char *)bias + g * out * el : nullptr, (char *)Y + g * M * out * el,
+                              T_save ? (char *)T_save + g * M * r * el : nullptr, workspace, workspace_bytes, stream,
+                              layer_align(sp, el));
+    return st;
+}
+
+int pf_lowrank_linear_shared_bwd(const pf_linear_shared_desc *d, const void *X, const void *V, const void *U,
+                                 const void *dY, const void *T_saved, void *dX, void *dU, void *dV, void *dbias,
+                                 int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+{
+    pf_linear_desc one;
+    int st = check_shared_desc(d, &one);
+    if (st != PF_OK) return st;
+    if (!V || !U) return PF_ERR_NULL;
+    if (d->M > 0 && (!X || !dY)) return PF_ERR_NULL;
+    if (any_misaligned({X, V, U, dY, T_saved, dX}, 16) || any_misaligned({dU, dV, dbias}, 4)) return PF_ERR_UNSUPPORTED;
+    const SharedPlan sp = plan_shared(d, one);
+    if (!workspace || workspace_bytes < sp.bwd_bytes) return PF_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const i64 M = d->M, in = d->n_in, out = d->n_out, r = d->r;
+    const int G = d->groups;
+    if (!(sp.fused_bwd && dX)) {
+        if (d->dtype == PF_F32)
+            return shared_bwd_loop<float>(d, sp, (const float *)X, (const float *)V, (const float *)U, (const float *)dY,
+                                          (const float *)T_saved, (float *)dX, (float *)dU, (float *)dV,
+                                          (float *)dbias, accumulate, workspace, workspace_bytes, s);
+        return shared_bwd_loop<bf16_t>(d, sp, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U,
+                                       (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dU,
+                                       (float *)dV, (float *)dbias, accumulate, workspace, workspace_bytes, s);
+    }
+    // fused: every group's dT = dY_g U_g and the sum dX = sum_g dT_g V_g^T in one launch, then the factor
+    // gradients layer by layer
+    Workspace ws(workspace, workspace_bytes);
+    const size_t grads = (size_t)sp.p.wg_groups * r * (in + out);
+    float *part = ws.take<float>(grads > sp.p.n_part ? grads : sp.p.n_part);
+    bf16_t *dT16 = ws.take<bf16_t>((size_t)G * sp.p.n_T);
+    bf16_t *T16 = ws.take<bf16_t>((size_t)G * sp.p.n_T);
+    float *colsum = ws.take<float>((size_t)G * sp.n_colsum);
+    const bool want_db = d->has_bias && dbias;
+    const bf16_t *Xb = (const bf16_t *)X, *Vb = (const bf16_t *)V, *Ub = (const bf16_t *)U, *dYb = (const bf16_t *)dY;
+    const bf16_t *Tb = (const bf16_t *)T_saved;
+    if (dU && !Tb) { // T was not saved: recompute it
+        for (int g = 0; g < G && st == PF_OK; ++g)
+            st = launch_gemm_generic<bf16_t, true, false>(
+                "linear_T=X*V", s, GemmShape{(int)M, (int)r, (int)in, 1, 1}, OpA_RowMajor<bf16_t>{Xb, (int)in, 0},
+                OpB_KN<bf16_t>{Vb + g * in * r, (int)r, 0, 0},
+                EpiRowMajor<bf16_t, bf16_t>{T16 + g * M * r, nullptr, (int)r, nullptr, 0});
+        if (st != PF_OK) return st;
+        Tb = T16;
+    }
+    LinChainArgs c{(const uint16_t *)dYb, (const uint16_t *)Ub, (const uint16_t *)Vb, nullptr, (uint16_t *)dX,
+                   (uint16_t *)dT16, want_db ? colsum : nullptr, M, (int)out, (int)in};
+    c.groups = G;
+    c.sum_out = 1;
+    c.gs_in = M * out;
+    c.gs_W1 = out * r;
+    c.gs_W2 = in * r;
+    c.gs_mid = M * r;
+    c.gs_colsum = (i64)sp.n_colsum;
+    st = launch_linear_chain2(s, "linear_shared_bwd_data_fused", c);
+    for (int g = 0; g < G && st == PF_OK; ++g)
+        st = linear_wgrads_fused(&one, sp.p, Xb, dYb + g * M * out, Tb ? Tb + g * M * r : nullptr, dT16 + g * M * r,
+                                 dU ? (float *)dU + g * out * r : nullptr, dV ? (float *)dV + g * in * r : nullptr,
+                                 dbias ? (float *)dbias + g * out : nullptr, want_db ? colsum + g * sp.n_colsum : nullptr,
+                                 accumulate, part, s);
+    return st;
 }
 
 } // extern "C"

@@ -21,12 +21,21 @@ struct LinChainArgs {
     float *colsum;        // [2 * row tiles][C1] column sums of `in` per 16 rows, nullable
     i64 rows;
     int C1, C2;
+    // Several layers of the same shape in one launch (groups > 1; 0 or 1: a single layer).  Each pointer above
+    // moves by its stride (in elements) from one group to the next; a stride of 0 shares the operand.  With
+    // sum_out the groups write ONE output, the sum of their stage-2 products (no bias then): the backward-data
+    // pass of projections that share their input.
+    int groups, sum_out;
+    i64 gs_in, gs_W1, gs_W2, gs_bias, gs_out, gs_mid, gs_colsum;
 };
 
 constexpr int LC_ROWS = 32; // rows per workgroup
 
 // R == 128, C1 and C2 multiples of 256
 bool linear_chain2_supported(i64 n_in, i64 n_out, i64 r);
+// groups > 1: at most LC_MAX_GROUPS; with sum_out also C2 <= 512 (the sums stay in registers)
+constexpr int LC_MAX_GROUPS = 8;
+bool linear_chain2_multi_supported(i64 n_in, i64 n_out, i64 r, int groups, bool sum_out);
 int launch_linear_chain2(hipStream_t s, const char *name, const LinChainArgs &a);
 
 } // namespace pf

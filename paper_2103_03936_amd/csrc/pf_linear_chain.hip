@@ -31,8 +31,10 @@ __device__ __forceinline__ bf16x8_t lc_as_bf16x8(u32x4_t v) { return __builtin_b
 
 // NP: pairs of output blocks per wavefront (C2 / 256) when it is one of 1, 2, 4, 8 -- then stage 2 is fully
 // unrolled and its W2 fragments are fetched two pairs ahead, the first two during stage 1; NP == 0: any C2.
-template <int NP>
-__global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
+// MODE 0: one layer.  MODE 1: the groups of LinChainArgs run one after the other in the same workgroup (same
+// rows), each with its own output.  MODE 2: the same, but the groups' stage-2 products are summed into one output.
+template <int NP, int MODE = 0>
+__global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args)
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][LC_ROWS * LC_XP];
     __shared__ __attribute__((aligned(16))) uint16_t Vs[2][LC_KC * LC_VP];
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, col = lane & 31;
     const i64 row0 = (i64)blockIdx.x * LC_ROWS;
-    const int C1 = a.C1, C2 = a.C2;
+    const int C1 = args.C1, C2 = args.C2;
     const int nch = C1 / LC_KC;
 
     struct XR { // a chunk of the input rows in flight (per thread)
@@ -57,6 +59,31 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
 
     // ---- copy roles: thread -> (row or k, 16-byte column) of a chunk
     const int cr = tid >> 4, co = tid & 15; // 16 threads per 128-element row; 16 rows per pass
+
+    constexpr bool MULTI = MODE != 0, summing = MODE == 2;
+    const int G = MULTI ? args.groups : 1;
+    constexpr int NSUM = summing ? NP : 1;
+    static_assert(!summing || NP == 1 || NP == 2, "the sums of all output blocks stay in registers");
+    f32x16_t ysum[NSUM][2]; // stage-2 sums over the groups (summing only)
+#pragma unroll
+    for (int i = 0; i < NSUM; ++i)
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ysum[i][bi][v] = 0.f;
+
+    for (int gi = 0; gi < G; ++gi) {
+    LinChainArgs a = args;
+    if (MULTI) {
+        a.in += gi * args.gs_in;
+        a.W1 += gi * args.gs_W1;
+        a.W2 += gi * args.gs_W2;
+        if (a.bias) a.bias += gi * args.gs_bias;
+        a.out += gi * args.gs_out;
+        if (a.mid_save) a.mid_save += gi * args.gs_mid;
+        if (a.colsum) a.colsum += gi * args.gs_colsum;
+        if (gi > 0) __syncthreads(); // the LDS tiles of the previous group are free
+    }
     const uint16_t *xsrc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -216,7 +243,7 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) y[bi][v] = 0.f;
+            for (int v = 0; v < 16; ++v) y[bi][v] = summing ? ysum[g < NSUM ? g : 0][bi][v] : 0.f;
         // rows -> MFMA fragments through this wavefront's patch of LDS (the W1 buffers are free by now)
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi)
@@ -232,6 +259,11 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
                 y[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(uf, tf[ks], y[bi], 0, 0, 0);
             }
         __builtin_amdgcn_wave_barrier();
+        if (summing && gi + 1 < G) { // (uniform) not the last group: keep the sums, nothing leaves yet
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi) ysum[g < NSUM ? g : 0][bi] = y[bi];
+            return;
+        }
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi) {
             // lane holds row `col`, outputs o = 32 (ob0 + bi) + 8 q + 4 half + 0..3
@@ -270,6 +302,13 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs a)
             load_u(ur[1], g + 3);
         }
     }
+    } // groups
+}
+
+bool linear_chain2_multi_supported(i64 n_in, i64 n_out, i64 r, int groups, bool sum_out)
+{
+    if (!linear_chain2_supported(n_in, n_out, r) || groups < 1 || groups > LC_MAX_GROUPS) return false;
+    return !sum_out || n_out == 256 || n_out == 512;
 }
 
 bool linear_chain2_supported(i64 n_in, i64 n_out, i64 r)
@@ -286,6 +325,25 @@ int launch_linear_chain2(hipStream_t s, const char *name, const LinChainArgs &a)
     const i64 tiles = (a.rows + LC_ROWS - 1) / LC_ROWS;
     if (tiles > 0x7fffffffLL) return PF_ERR_SHAPE;
     const dim3 grid((unsigned)tiles), block(256);
+    if (a.groups > 1) {
+        if (!linear_chain2_multi_supported(a.C1, a.C2, LC_R, a.groups, a.sum_out != 0)) return PF_ERR_UNSUPPORTED;
+        if (a.sum_out) {
+            if (a.C2 == 256) {
+                PF_LAUNCH(st, name, (linear_chain2_kernel<1, 2>), grid, block, s, a);
+            } else {
+                PF_LAUNCH(st, name, (linear_chain2_kernel<2, 2>), grid, block, s, a);
+            }
+            return st;
+        }
+        switch (a.C2 / 256) {
+        case 1: PF_LAUNCH(st, name, (linear_chain2_kernel<1, 1>), grid, block, s, a); break;
+        case 2: PF_LAUNCH(st, name, (linear_chain2_kernel<2, 1>), grid, block, s, a); break;
+        case 4: PF_LAUNCH(st, name, (linear_chain2_kernel<4, 1>), grid, block, s, a); break;
+        case 8: PF_LAUNCH(st, name, (linear_chain2_kernel<8, 1>), grid, block, s, a); break;
+        default: PF_LAUNCH(st, name, (linear_chain2_kernel<0, 1>), grid, block, s, a); break;
+        }
+        return st;
+    }
     switch (a.C2 / 256) {
     case 1: PF_LAUNCH(st, name, linear_chain2_kernel<1>, grid, block, s, a); break;
     case 2: PF_LAUNCH(st, name, linear_chain2_kernel<2>, grid, block, s, a); break;

@@ -67,6 +67,29 @@ def test_linear_validation():
     assert pf.lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(_lin(r=64))) >= 0
 
 
+def test_linear_shared_validation():
+    f = pf.lib.pf_lowrank_linear_shared_fwd
+    b = pf.lib.pf_lowrank_linear_shared_bwd
+    z = ctypes.c_size_t(0)
+
+    def d(M=4, n_in=5, n_out=3, r=2, G=3, dtype=0, bias=0):
+        return ctypes.byref(pf.pf_linear_shared_desc(M, n_in, n_out, r, G, dtype, bias))
+
+    assert f(None, FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
+    assert f(d(G=0), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
+    assert f(d(G=65), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
+    assert f(d(n_out=0), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
+    assert f(d(dtype=4), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 3
+    assert f(d(bias=1), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
+    assert f(d(), P(260), FAKE, FAKE, None, FAKE, None, None, z, None) == 3
+    assert f(d(M=0), None, FAKE, FAKE, None, None, None, None, z, None) == 0
+    assert b(d(), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, None, 0, FAKE, z, None) == 1
+    assert b(d(), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 4
+    need = pf.lib.pf_lowrank_linear_shared_bwd_workspace_bytes(d())
+    assert need > pf.lib.pf_lowrank_linear_bwd_workspace_bytes(ctypes.byref(_lin()))
+    assert b(d(), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, 0, FAKE, ctypes.c_size_t(need - 1), None) == 4
+
+
 def _conv(N=2, C=3, H=5, W=5, Cout=4, r=2, k=3, s=1, p=1, dtype=0):
     return pf.pf_conv_desc(N, C, H, W, Cout, r, k, s, p, dtype)
 

@@ -110,3 +110,26 @@ def test_parameter_counts_table1():
     m = n = 512
     r = 128
     assert r * (m + n) == 131072 and m * n == 262144
+
+
+@pytest.mark.parametrize("M,n_in,n_out,r,G", [(3, 5, 4, 2, 3), (9, 6, 7, 5, 2), (4, 3, 3, 3, 1)])
+def test_shared_input_projections_match_torch_autograd(M, n_in, n_out, r, G):
+    """Q, K, V style projections of one input (Section 2.4) against autograd of the block written as ONE layer:
+    the factors V_g side by side, the factors U_g on a block diagonal.  A dropped term in the sum over the
+    projections, or gradients filed under the wrong projection, fail here."""
+    X, V, U, b, dY = (_rand(s, 20 + i) for i, s in enumerate(
+        [(M, n_in), (G, n_in, r), (G, n_out, r), (G, n_out), (G, M, n_out)]))
+    tX, tV, tU, tb = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (X, V, U, b))
+    Vcat = torch.cat([tV[g] for g in range(G)], dim=1)                      # [in, G r]
+    Ublk = torch.block_diag(*[tU[g] for g in range(G)])                     # [G out, G r]
+    Ycat = (tX @ Vcat) @ Ublk.T + tb.reshape(-1)                            # [M, G out]
+    Ycat.backward(torch.tensor(np.concatenate([dY[g] for g in range(G)], axis=1)))
+    Y, T = oracle.lowrank_linear_shared_fwd(X, V, U, b)
+    assert Y.shape == (G, M, n_out) and T.shape == (G, M, r)
+    np.testing.assert_allclose(np.concatenate([Y[g] for g in range(G)], axis=1), Ycat.detach().numpy(),
+                               rtol=1e-11, atol=1e-11)
+    dX, dU, dV, db = oracle.lowrank_linear_shared_bwd(X, V, U, dY)
+    np.testing.assert_allclose(dX, tX.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(dU, tU.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(dV, tV.grad.numpy(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-11, atol=1e-11)

@@ -74,6 +74,20 @@ def linear_inputs(M, n_in, n_out, r, dtype="f32", seed=0, bias=False):
     return d
 
 
+def linear_shared_inputs(M, n_in, n_out, r, groups, dtype="f32", seed=0, bias=False):
+    """`groups` projections of one input (Q, K, V): X ~ N(0,1); V[G,in,r] ~ N(0, 1/in); U[G,out,r] ~ N(0, 1/r);
+    dY[G,M,out] ~ N(0,1)."""
+    s = Stream(SEED_BASE + seed, dtype)
+    d = dict(
+        X=s.normal((M, n_in)),
+        V=s.normal((groups, n_in, r), 1.0 / np.sqrt(max(n_in, 1))),
+        U=s.normal((groups, n_out, r), 1.0 / np.sqrt(max(r, 1))),
+        dY=s.normal((groups, M, n_out)),
+    )
+    d["bias"] = s.normal((groups, n_out)) if bias else None
+    return d
+
+
 def conv_inputs(N, C, H, W, Cout, r, k, stride=1, pad=0, dtype="f32", seed=0):
     """X ~ N(0,1) NCHW; Uk[r,C,k,k] ~ N(0, 1/(C k^2)); Vp[Cout,r] ~ N(0, 1/r); dY ~ N(0,1)."""
     s = Stream(SEED_BASE + seed, dtype)
@@ -150,6 +164,10 @@ CONFIGS = {
     "transformer_block_bf16": dict(kind="linear_set", dtype="bf16", M=64 * 128, seed=3, layers=dict(
         wq=(512, 512, 128), wk=(512, 512, 128), wv=(512, 512, 128), wo=(512, 512, 128),
         ffn1=(512, 2048, 128), ffn2=(2048, 512, 128))),
+    # the same block with the query, key and value projections (one input) through the shared-input entry points
+    "transformer_block_qkv_bf16": dict(kind="linear_set", dtype="bf16", M=64 * 128, seed=3, shared=("wq", "wk", "wv"),
+                                       layers=dict(wq=(512, 512, 128), wk=(512, 512, 128), wv=(512, 512, 128),
+                                                   wo=(512, 512, 128), ffn1=(512, 2048, 128), ffn2=(2048, 512, 128))),
     "resnet50_conv5_bf16": dict(kind="conv_set", dtype="bf16", N=256, H=7, W=7, seed=4, layers=dict(
         conv1=(2048, 512, 128, 1, 0), conv2=(512, 512, 128, 3, 1), conv3=(512, 2048, 128, 1, 0))),
 }
