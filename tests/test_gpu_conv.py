@@ -73,6 +73,9 @@ FUSED_SHAPES = [
     (2, 256, 4, 4, 512, 128, 1, 1, 0),
     (7, 512, 2, 3, 256, 64, 1, 1, 0),
     (1, 256, 1, 1, 256, 64, 3, 1, 1),
+    (37, 256, 8, 8, 256, 64, 3, 1, 1),   # image groups of unequal length
+    (29, 512, 7, 7, 512, 128, 3, 1, 1),
+    (45, 1024, 7, 7, 256, 128, 1, 1, 0),
 ]
 
 
