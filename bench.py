@@ -497,7 +497,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import torch
     import workloads
