@@ -361,32 +361,30 @@ __global__ __launch_bounds__(WG_THREADS, 1) void conv_wgrad_pair_kernel(WgradArg
 }
 
 // out[m * s_m + n * s_n + tap * s_tap] (+)= sum_g partial[g][tap][m][n]; four consecutive n per output
-// The blocks past blocks01 add up per-tile column sums instead (a bias gradient): 32 columns per block,
-// eight threads per column take every eighth tile, and their sums are added in a fixed order.
+// The blocks past blocks01 add up per-tile column sums instead (a bias gradient): 16 columns per block,
+// sixteen threads per column take every sixteenth tile, and their sums are added in a fixed order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, WgradReduceArgs r1, int blocks0,
                                                             ColsumTilesArgs cs, int blocks01)
 {
     if ((int)blockIdx.x >= blocks01) {
-        __shared__ float part[8][32];
-        const int tc = threadIdx.x & 31, tg = threadIdx.x >> 5;
-        const int colm = (blockIdx.x - blocks01) * 32 + tc;
+        __shared__ float part[16][16];
+        const int tc = threadIdx.x & 15, tg = threadIdx.x >> 4;
+        const int colm = (blockIdx.x - blocks01) * 16 + tc;
         const float *p = cs.partial + colm;
         float acc = 0.f;
-        int t = tg;
-        for (; t + 56 < cs.tiles; t += 64) { // eight loads in flight
-            float v[8];
+        for (int t = tg; t < cs.tiles; t += 256) { // sixteen loads in flight (tiles past the end repeat the last, unused)
+            float v[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = p[(i64)(t + 8 * u) * cs.cols];
+            for (int u = 0; u < 16; ++u) v[u] = p[(i64)min(t + 16 * u, cs.tiles - 1) * cs.cols];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
+            for (int u = 0; u < 16; ++u) acc += t + 16 * u < cs.tiles ? v[u] : 0.f;
         }
-        for (; t < cs.tiles; t += 8) acc += p[(i64)t * cs.cols];
         part[tg][tc] = acc;
         __syncthreads();
         if (tg == 0) {
             float sum = 0.f;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) sum += part[u][tc];
+            for (int u = 0; u < 16; ++u) sum += part[u][tc];
             cs.out[colm] = cs.accumulate ? cs.out[colm] + sum : sum;
         }
         return;
@@ -512,8 +510,8 @@ int launch_wgrad_reduce(hipStream_t s, const WgradReduceArgs &r0, const WgradRed
     const int b0 = (int)((c0 / 4 + 63) / 64), b1 = (int)((c1 / 4 + 63) / 64);
     ColsumTilesArgs c = {};
     if (cs && cs->out && cs->tiles > 0) c = *cs;
-    if (c.cols % 32 != 0) return PF_ERR_UNSUPPORTED;
-    const int b2 = c.cols / 32;
+    if (c.cols % 16 != 0) return PF_ERR_UNSUPPORTED;
+    const int b2 = c.cols / 16;
     if (b0 + b1 + b2 == 0) return st;
     PF_LAUNCH(st, "wgrad_reduce", wgrad_reduce_kernel, dim3(b0 + b1 + b2), dim3(256), s, r0, r1, b0, c, b0 + b1);
     return st;
