@@ -10,6 +10,7 @@ constexpr int CH_XLD = CH_SUB + 8;   // row stride (elements) of the staged inpu
 constexpr int CH_PLD = CH_PIX + 1;   // row stride (floats) of a partial-sum tile
 
 typedef uint4 __attribute__((may_alias)) uint4_alias;
+typedef uint32_t X16a2 __attribute__((ext_vector_type(4), aligned(2))); // 16 bytes at any 2-byte aligned address
 
 // 16-byte LDS fragment read that may alias the 2-byte stores which filled the tile
 __device__ __forceinline__ uint4 lds_read16(const uint16_t *p) { return *(const uint4_alias *)p; }
@@ -57,6 +58,15 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 
     // One staging item = one pixel x 8 consecutive channels (one 16-byte LDS row segment); a lane owns
     // items lane, lane + 64, ...; neighbouring lanes read neighbouring pixels, so the 2-byte loads coalesce.
+    //
+    // XT: a 1x1 first stage of an 8 x 8 or 7 x 7 image needs no shifted reads, so the 64 planes of a round stay
+    // as they are in memory -- tile row = channel, 64 pixel slots (pitch CH_XLD) -- copied with 16-byte loads
+    // in memory order, and the transposing LDS read turns them into MFMA fragments (the pixel-by-pixel gather
+    // costs eight 2-byte loads per item on the unit that also carries the weight stream).  A 7 x 7 plane is 98
+    // bytes: one unaligned load per group of 8 slots, the last group read from further back so that it stays
+    // in the plane.
+    constexpr bool XT = !CL && KS1 == 1 && ((HC == 8 && WC == 8) || (HC == 7 && WC == 7));
+    constexpr int XG = HC == 8 ? 8 : 7; // 16-byte items per plane
     uint4 xv[NXV];
     const int nitem = 8 * HW;
     auto load_x = [&](int sub) __attribute__((always_inline)) {
@@ -71,6 +81,19 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             return;
         }
         const uint16_t *src = a.in + ((i64)n * C1 + w * cw + sub * CH_SUB) * HW;
+        if (XT) {
+#pragma unroll
+            for (int i = 0; i < NXV; ++i) {
+                const int it = min(lane + 64 * i, CH_SUB * XG - 1), ch = it / XG, j = it - ch * XG;
+                if (XG == 8) {
+                    xv[i] = *(const uint4 *)(src + ch * 64 + 8 * j);
+                } else {
+                    const X16a2 t = *(const X16a2 *)(src + ch * 49 + 8 * j - (j == 6 ? 7 : 0));
+                    xv[i] = make_uint4(t.x, t.y, t.z, t.w);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NXV; ++i) {
             const int it = lane + 64 * i;
@@ -93,6 +116,18 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             for (int i = 0; i < NXV; ++i) {
                 const int it = lane + 64 * i, m = it >> 3, o = it & 7;
                 *(uint4_alias *)&xs[m * CH_XLD + 8 * o] = xv[i];
+            }
+            return;
+        }
+        if (XT) {
+#pragma unroll
+            for (int i = 0; i < NXV; ++i) {
+                const int it = lane + 64 * i, ch = it / XG, j = it - ch * XG;
+                if (it < CH_SUB * XG) {
+                    uint4 v = xv[i];
+                    if (XG == 7 && j == 6) v = make_uint4(v.w >> 16, 0u, 0u, 0u); // pixel 48, then empty slots
+                    *(uint4_alias *)&xs[ch * CH_XLD + 8 * j] = v;
+                }
             }
             return;
         }
@@ -163,20 +198,32 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         if (KS1 == 3) return ((gi % 3) * Wp1 + t) * CH_XLD + 16 * (gi / 3);
         return 16 * t;
     };
+    // input fragment of pixel block pb: 8 consecutive channels of this lane's pixel
+    auto xfrag = [&](int pb, int gi, int t) __attribute__((always_inline)) {
+        if (XT) { // (slots past the image hold zeros)
+            union {
+                bf16x8_t b;
+                uint4 u;
+            } c;
+            c.b = lds_frag_tr(xs, CH_XLD, 16 * t, 32 * pb, lane);
+            return c.u;
+        }
+        return lds_read16(&xs[base1[pb] + (valid[pb] ? xoff(gi, t) : 0)]);
+    };
     // multiply group g (fragments in cur) while fetching the fragments of group gn into nxt
     auto run_group = [&](const uint4(&cur)[GS1][RB], uint4(&nxt)[GS1][RB], int g, int gn) __attribute__((always_inline)) {
         const int gi = g % GPS;
         const uint4 *src = w1s + (i64)gn * GS1 * RB * 64;
         uint4 bc[2], bn[2];
 #pragma unroll
-        for (int pb = 0; pb < 2; ++pb) bc[pb] = lds_read16(&xs[base1[pb] + (valid[pb] ? xoff(gi, 0) : 0)]);
+        for (int pb = 0; pb < 2; ++pb) bc[pb] = xfrag(pb, gi, 0);
 #pragma unroll
         for (int t = 0; t < GS1; ++t) {
 #pragma unroll
             for (int b = 0; b < RB; ++b) nxt[t][b] = src[(t * RB + b) * 64];
             if (t + 1 < GS1) {
 #pragma unroll
-                for (int pb = 0; pb < 2; ++pb) bn[pb] = lds_read16(&xs[base1[pb] + (valid[pb] ? xoff(gi, t + 1) : 0)]);
+                for (int pb = 0; pb < 2; ++pb) bn[pb] = xfrag(pb, gi, t + 1);
             }
 #pragma unroll
             for (int b = 0; b < RB; ++b)
@@ -192,10 +239,12 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     // entered at their first group because the rotation is a whole number of rounds when nsub > 1)
     auto next_round = [&](int g) __attribute__((always_inline)) {
         if ((g + 1) % GPS == 0 && g + 1 < ngroups) {
-            __syncthreads();
+            // (the tile belongs to this wavefront alone, and a wavefront's LDS accesses are performed in the
+            // order it issues them: no workgroup barrier, the four wavefronts drift apart freely in stage 1)
+            __builtin_amdgcn_wave_barrier();
             store_x();
             if (g + 1 + GPS < ngroups) load_x(grp(g + 1 + GPS) / GPS);
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
         }
     };
 
