@@ -163,12 +163,12 @@ static ConvPlan plan_conv(const ConvGeom &g, int dtype)
         // with g groups it runs units * g workgroups of ceil(N / g) images each and writes g partial sums.  Both
         // problems should fit the chip in one round (one workgroup per compute unit) and finish together, and
         // every extra group costs a partial sum to write and to add up.  Costs in thousands of cycles, from
-        // traces of the kernel: an image of a 3x3 stage 1.4, of a 1x1 stage 1.0 (rank 64) or 2.0 (rank 128);
+        // traces of the kernel: an image of a 3x3 block 0.7 (rank 64) or 1.4, of a 1x1 block 1.0 (rank 64) or 2.0;
         // a megabyte of partial sums 1.0.  The search is tiny: every g1, and for it the fewest groups g2 that
         // do not make problem 2 the longer one.
-        const int units1 = (g.C / wgrad_nchunk(g.r, g.k, 1)) * ((g.k == 3 && g.r == 128) ? 2 : 1);
+        const int units1 = (g.C / wgrad_nchunk(g.r, g.k, 1)) * (g.k == 3 ? 2 : 1);
         const int units2 = g.Cout / wgrad_nchunk(g.r, 1, 2);
-        const double c1 = g.k == 3 ? 1.4 : g.r == 128 ? 2.0 : 1.0, c2 = g.r == 128 ? 2.0 : 1.0;
+        const double c1 = g.k == 3 ? (g.r == 128 ? 1.4 : 0.7) : g.r == 128 ? 2.0 : 1.0, c2 = g.r == 128 ? 2.0 : 1.0;
         const double mb1 = 1.0e-6 * 4.0 * g.r * g.C * g.k * g.k, mb2 = 1.0e-6 * 4.0 * g.r * g.Cout;
         const int budget = 256;
         double best = 1e30;

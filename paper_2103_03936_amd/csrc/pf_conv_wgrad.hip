@@ -68,14 +68,15 @@ __device__ __forceinline__ u32x4 row_fix(u32x4 v, int y, int H)
 //
 // Eight wavefronts (two per SIMD, so that one multiplies while the other waits for LDS or the barrier) split
 // an image three ways.  kh = w & 1 takes k-steps 2 kh, 2 kh + 1 (image rows 4 kh .. 4 kh + 3, or pixels
-// 32 kh .. 32 kh + 31 of a 1x1 stage); mq = (w >> 1) & 1 takes half of the m blocks and pq = w >> 2 half of
-// the (n block, tap) pairs.  At the end the two k halves trade half of their tiles through LDS, add, and each
+// 32 kh .. 32 kh + 31 of a 1x1 stage); the other four pairs of wavefronts split the m blocks in two (when there
+// are at least two) and the (n block, tap) pairs in two or four.  At the end the two k halves trade half of their tiles through LDS, add, and each
 // stores the half it kept.
 template <int TAPS, int MB, int NBLK, int HC, int WC>
 struct WgCfg {
     static constexpr int M = 32 * MB, NCH = 32 * NBLK, NPAIR = NBLK * TAPS;
-    static constexpr int MBW = MB / 2;          // m blocks per wavefront
-    static constexpr int PWN = (NPAIR + 1) / 2; // pairs per wavefront
+    static constexpr int MQ = MB >= 2 ? 2 : 1, PQ = 4 / MQ; // ways the m blocks / the pairs are split
+    static constexpr int MBW = MB / MQ;                     // m blocks per wavefront
+    static constexpr int PWN = (NPAIR + PQ - 1) / PQ;       // pairs per wavefront
     static constexpr int TILES = MBW * PWN, KEEP = (TILES + 1) / 2;
     static constexpr bool AL8 = HC == 8 && WC == 8; // planes of 64 pixels: rows are aligned 16-byte pieces
     // LDS copies of the A block / B slab of one image: 64 pixel slots per plane, plane pitch 144 bytes (against
@@ -101,7 +102,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
-    const int kh = w & 1, mb0 = MBW * ((w >> 1) & 1), p0 = PWN * (w >> 2);
+    const int kh = w & 1, mb0 = MBW * ((w >> 1) % C::MQ), p0 = PWN * ((w >> 1) / C::MQ);
     const int H = HC ? HC : a.H, W = WC ? WC : a.W, HW = H * W;
     const int n0 = bx * NCH; // first B channel of this workgroup
     const int img0 = g * a.imgs_per_group;
@@ -110,7 +111,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
     // 16-byte items of the A block / the B slab of one image (7x7: one per 8-pixel slot group of a plane)
     const int apieces = SQ7 ? M * 7 : M * HW / 8, bpieces = SQ7 ? NCH * 7 : NCH * HW / 8;
     constexpr int NT = WG_THREADS;
-    constexpr int APT = MB * 256 / NT, BPT = TAPS == 9 ? 1 : NBLK * 256 / NT; // items per thread (at most; HW <= 64)
+    constexpr int APT = (MB * 256 + NT - 1) / NT, BPT = TAPS == 9 ? 1 : NBLK * 256 / NT; // items per thread (at most)
 
     auto a_buf = [&](int buf) __attribute__((always_inline)) { return lds + buf * (C::A_BYTES + C::B_BYTES); };
     auto b_buf = [&](int buf) __attribute__((always_inline)) { return a_buf(buf) + C::A_BYTES; };
@@ -246,7 +247,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int ks = 2 * kh + kk;
-            if ((TAPS == 9 ? 2 * ks : 16 * ks) < (TAPS == 9 ? H : HW)) { // (uniform) this k-step has pixels
+            if ((TAPS == 9 ? 2 * ks : 16 * ks) < (TAPS == 9 ? H : HW) && p0 < NPAIR) { // (uniform) pixels and pairs to do
                 u32x4 af[MBW], bf[PWN];
 #pragma unroll
                 for (int b = 0; b < MBW; ++b) af[b] = raw_frag(As, 32 * (mb0 + b) + col, ks);
@@ -343,8 +344,9 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
 
 // One launch computes both filter gradients: the first nwg1 workgroups work on problem 1 (taps T1: the
 // k x k stage), the others on problem 2 (always a 1x1 stage).  Each problem has its own image grouping.
-// MB1 / MB2: 32-row blocks of m one workgroup of problem 1 / 2 takes; a 3x3 stage at rank 128 runs as two
-// workgroups of 64 rows (the accumulators of all nine taps and 128 rows do not fit one register file).
+// MB1 / MB2: 32-row blocks of m one workgroup of problem 1 / 2 takes; a 3x3 stage runs as two workgroups of
+// half the rows each (nine taps each): more, shorter workgroups for the same partial-sum traffic, and at rank
+// 128 the accumulators of all nine taps and 128 rows would not fit one register file.
 template <int T1, int MB1, int MB2, int HC, int WC>
 __global__ __launch_bounds__(WG_THREADS, 1) void conv_wgrad_pair_kernel(WgradArgs a1, WgradArgs a2, int nx1, int nx2, int nwg1)
 {
@@ -473,7 +475,7 @@ int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const Wgr
     if (a1.N_img <= 0) return st;
     const int M = a1.M;
     if ((M != 64 && M != 128) || a2.M != M || (k1 != 1 && k1 != 3)) return PF_ERR_UNSUPPORTED;
-    const int mb1 = (k1 == 3 || M == 64) ? 2 : 4; // 32-row blocks per workgroup of problem 1
+    const int mb1 = k1 == 3 ? M / 64 : M / 32; // 32-row blocks per workgroup of problem 1 (3x3: half the rows)
     const int nx1 = a1.partial ? a1.Nc / wgrad_nchunk(M, k1, 1) : 0;
     const int nx2 = a2.partial ? a2.Nc / wgrad_nchunk(M, 1, 2) : 0;
     const int nwg1 = nx1 * a1.groups * (M / (32 * mb1)), nwg2 = nx2 * a2.groups;
@@ -495,7 +497,7 @@ int launch_conv_wgrad_pair(hipStream_t s, const WgradArgs &a1, int k1, const Wgr
         }                                                                                                          \
         return st;                                                                                                 \
     }
-    PF_WGRAD_CASE(9, 2, 2)
+    PF_WGRAD_CASE(9, 1, 2)
     PF_WGRAD_CASE(9, 2, 4)
     PF_WGRAD_CASE(1, 2, 2)
     PF_WGRAD_CASE(1, 4, 4)
