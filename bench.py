@@ -267,12 +267,14 @@ class LstmWorkload:
     def __init__(self, name, cfg, groups=1):
         self.name, self.dtype, self.cfg, self.groups = name, "f32", cfg, groups
         self.seq = bool(cfg.get("seq"))  # sequence-level entry points instead of one call per cell
+        self.stack = bool(cfg.get("stack"))  # all layers in one call per direction
 
     def describe(self):
         c = self.cfg
         return {"workload": self.name, "seq_len": c["T"], "batch": c["B"], "layers": c["layers"], "d": c["d"],
                 "h": c["h"], "r": c["r"], "groups": self.groups,
-                "calls": "pf_lowrank_lstm_seq_*, one per layer and direction" if self.seq else
+                "calls": "pf_lowrank_lstm_stack_*, one per direction" if self.stack else
+                         "pf_lowrank_lstm_seq_*, one per layer and direction" if self.seq else
                          "pf_lowrank_lstm_cell_*, one per time step, layer and direction"}
 
     def flops(self):
@@ -309,7 +311,18 @@ class LstmWorkload:
             above, _, _, _ = pf.pf_lowrank_lstm_seq_bwd(xin, g["zero"], g["zero"], h_all, c_all, gates_all, Tx_all, Th_all,
                                                         p["Vx"], p["Ux"], p["Vh"], p["Uh"], above, None, None, groups)
 
+    def step_stack(self, pf, s):
+        g = s["lm"]
+        L, groups = len(g["P"]), self.groups
+        col = lambda k: [p[k] for p in g["P"]]
+        zero = [g["zero"]] * L
+        Vx, Ux, Vh, Uh = col("Vx"), col("Ux"), col("Vh"), col("Uh")
+        saved = pf.pf_lowrank_lstm_stack_fwd(g["x"], zero, zero, Vx, Ux, Vh, Uh, col("bias"), groups)
+        pf.pf_lowrank_lstm_stack_bwd(g["x"], zero, zero, *saved, Vx, Ux, Vh, Uh, g["dH"], None, None, groups)
+
     def step(self, pf, s):
+        if self.stack:
+            return self.step_stack(pf, s)
         if self.seq:
             return self.step_seq(pf, s)
         g = s["lm"]
@@ -343,6 +356,20 @@ class LstmWorkload:
         c = self.cfg
         B, d, h, r, g = c["B"], c["d"], c["h"], c["r"], self.groups
         gr, cells = g * r, c["T"] * c["layers"]
+        if self.stack:  # one launch per diagonal and product kind, all active layers inside
+            Mt, L = c["T"] * B, c["layers"]
+            slots, up = c["T"] + L - 1, (L - 1) * c["T"]  # launches; layer-to-layer products ride along
+            ws = {
+                "lstm_stack_T": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * h + B * gr) * (cells + up), slots),
+                "lstm_stack_z": (2.0 * B * 4 * h * r * (cells + up),
+                                 4 * (4 * h * r + B * gr + 2 * B * 4 * h) * (cells + up), slots),
+                "lstm_stack_dT": (2.0 * B * 4 * h * r * (cells + up), 4 * (4 * h * r + B * 4 * h + B * gr) * (cells + up),
+                                  slots),
+                "lstm_stack_dh": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * gr + B * h) * (cells + up), slots),
+                "lstm_stack_grads": (2.0 * Mt * (8 * h * r + gr * (d + h)) * L,
+                                     4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)) * L, 2 * L),
+            }
+            return {k: [f, b, n] for k, (f, b, n) in ws.items()}
         if self.seq:  # per-step hidden-path launches, and the batched gradient launch (one per layer)
             Mt, L = c["T"] * B, c["layers"]
             ws = {

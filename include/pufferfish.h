@@ -273,6 +273,69 @@ int pf_lowrank_lstm_seq_bwd(const pf_lstm_seq_desc *d, const void *x,
                             void *stream);
 
 /* ------------------------------------------------------------------ */
+/* A stack of `layers` factorized LSTM layers over a sequence (the      */
+/* 2-layer language model of Appendix D; eq. (2) per layer, layer l > 0 */
+/* reading h_all of layer l - 1).  The result is that of running        */
+/* pf_lowrank_lstm_seq_* layer after layer; the steps are scheduled     */
+/* along the diagonals l + t = const, which shortens the chain of       */
+/* dependent launches from T * layers steps to T + layers - 1.          */
+/* Layer 0 has d_in inputs, the others h; every layer has the same h, r */
+/* and groups.  fp32, B <= 32, 1 <= layers <= 4, every extent >= 4.     */
+/* Per-layer tensors are passed as HOST arrays of `layers` DEVICE       */
+/* pointers (the arrays are read during the call only); shapes per      */
+/* layer as for the sequence entry points.                              */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t T, B, d_in, h, r;
+    int groups;   /* 1 or 4 */
+    int layers;   /* 1..4 */
+    int dtype;    /* PF_F32 */
+    int has_bias;
+} pf_lstm_stack_desc;
+
+size_t pf_lowrank_lstm_stack_fwd_workspace_bytes(const pf_lstm_stack_desc *d);
+size_t pf_lowrank_lstm_stack_bwd_workspace_bytes(const pf_lstm_stack_desc *d);
+
+/* x[T,B,d_in] device.  h0, c0, Vx, Ux, Vh, Uh, bias (array nullable when
+ * has_bias == 0): inputs per layer; h_all, c_all, gates_all, Tx_all, Th_all:
+ * outputs per layer (h_all[layers-1] is the output of the stack).  T == 0 or
+ * B == 0: nothing is done.  Errors as for the cell. */
+int pf_lowrank_lstm_stack_fwd(const pf_lstm_stack_desc *d, const void *x,
+                              const void *const *h0, const void *const *c0,
+                              const void *const *Vx, const void *const *Ux,
+                              const void *const *Vh, const void *const *Uh,
+                              const void *const *bias /* nullable */,
+                              void *const *h_all, void *const *c_all,
+                              void *const *gates_all, void *const *Tx_all,
+                              void *const *Th_all, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* dh_top[T,B,h] = dL/dh_t of the LAST layer arriving from above at every
+ * step; dhT, dcT (arrays and entries nullable = 0): gradients arriving at each
+ * layer's final state.  Outputs: dx_all[T,B,d_in] (nullable), dh0, dc0 per
+ * layer, and the float parameter gradients per layer (dbias array nullable),
+ * overwritten or accumulated. */
+int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x,
+                              const void *const *h0, const void *const *c0,
+                              const void *const *h_all,
+                              const void *const *c_all,
+                              const void *const *gates_all,
+                              const void *const *Tx_all,
+                              const void *const *Th_all,
+                              const void *const *Vx, const void *const *Ux,
+                              const void *const *Vh, const void *const *Uh,
+                              const void *dh_top,
+                              const void *const *dhT /* nullable */,
+                              const void *const *dcT /* nullable */,
+                              void *dx_all /* nullable */, void *const *dh0,
+                              void *const *dc0, void *const *dVx,
+                              void *const *dUx, void *const *dVh,
+                              void *const *dUh,
+                              void *const *dbias /* nullable */,
+                              int accumulate, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ */
 /* Truncated-SVD factor initialisation (Algorithm 1, the step before    */
 /* the factorized layers are trained): W[m x n] (fp32, row-major) ->    */
 /*   U[m x r] = Ut_r S_r^(1/2),  V[n x r] = Vt_r S_r^(1/2)  (fp32),     */

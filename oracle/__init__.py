@@ -315,6 +315,37 @@ def lowrank_lstm_seq_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx,
     return dx_all, dh, dc, grads
 
 
+def lowrank_lstm_stack_fwd(x, h0, c0, Vx, Ux, Vh, Uh, bias=None, groups=1):
+    """Stacked factorized LSTM layers (the 2-layer language model of Appendix D): layer 0 reads x, layer l > 0
+    reads the hidden states of layer l - 1; one layer after the other.  Per-layer arguments are lists.
+    Returns lists (h_all, c_all, gates_all, Tx_all, Th_all)."""
+    outs = ([], [], [], [], [])
+    inp = x
+    for l in range(len(Ux)):
+        res = lowrank_lstm_seq_fwd(inp, h0[l], c0[l], Vx[l], Ux[l], Vh[l], Uh[l], None if bias is None else bias[l],
+                                   groups)
+        for lst, v in zip(outs, res):
+            lst.append(v)
+        inp = res[0]
+    return outs
+
+
+def lowrank_lstm_stack_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux, Vh, Uh, dh_top, dhT=None,
+                           dcT=None, groups=1):
+    """Backward of lowrank_lstm_stack_fwd, the layers taken from the last to the first: the dx_all of layer l
+    is the gradient arriving from above at every step of layer l - 1.  dh_top[T,B,h] arrives at the last
+    layer.  Returns (dx_all, dh0 list, dc0 list, grads list)."""
+    L = len(Ux)
+    dh0, dc0, grads = [None] * L, [None] * L, [None] * L
+    d_above = dh_top
+    for l in range(L - 1, -1, -1):
+        inp = x if l == 0 else h_all[l - 1]
+        d_above, dh0[l], dc0[l], grads[l] = lowrank_lstm_seq_bwd(
+            inp, h0[l], c0[l], h_all[l], c_all[l], gates_all[l], Tx_all[l], Th_all[l], Vx[l], Ux[l], Vh[l], Uh[l],
+            d_above, None if dhT is None else dhT[l], None if dcT is None else dcT[l], groups)
+    return d_above, dh0, dc0, grads
+
+
 # ------------------------------------------------------------------- SVD
 
 def svd_split(W, r):

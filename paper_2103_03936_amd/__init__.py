@@ -48,6 +48,12 @@ class pf_lstm_seq_desc(ctypes.Structure):
                 ("r", ctypes.c_int64), ("groups", ctypes.c_int), ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
 
 
+class pf_lstm_stack_desc(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("B", ctypes.c_int64), ("d_in", ctypes.c_int64), ("h", ctypes.c_int64),
+                ("r", ctypes.c_int64), ("groups", ctypes.c_int), ("layers", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("has_bias", ctypes.c_int)]
+
+
 class pf_svd_desc(ctypes.Structure):
     _fields_ = [("m", ctypes.c_int64), ("n", ctypes.c_int64), ("r", ctypes.c_int64)]
 
@@ -64,6 +70,8 @@ EXPORTS = [
     "pf_lowrank_lstm_cell_fwd", "pf_lowrank_lstm_cell_bwd",
     "pf_lowrank_lstm_seq_fwd_workspace_bytes", "pf_lowrank_lstm_seq_bwd_workspace_bytes",
     "pf_lowrank_lstm_seq_fwd", "pf_lowrank_lstm_seq_bwd",
+    "pf_lowrank_lstm_stack_fwd_workspace_bytes", "pf_lowrank_lstm_stack_bwd_workspace_bytes",
+    "pf_lowrank_lstm_stack_fwd", "pf_lowrank_lstm_stack_bwd",
     "pf_svd_split_workspace_bytes", "pf_svd_split",
     "pf_dense_linear_workspace_bytes", "pf_dense_linear_fwd", "pf_dense_linear_bwd",
     "pf_dense_conv_workspace_bytes", "pf_dense_conv_fwd", "pf_dense_conv_bwd",
@@ -406,6 +414,67 @@ def pf_lowrank_lstm_seq_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, 
         _ptr(grads["dVx"], f32), _ptr(grads["dUx"], f32), _ptr(grads["dVh"], f32), _ptr(grads["dUh"], f32),
         _ptr(grads["dbias"], f32), ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()),
         _stream()), "pf_lowrank_lstm_seq_bwd")
+    return dx_all, dh0, dc0, grads
+
+
+def _ptr_array(ts, dtype=None):
+    """A host array of device pointers, one per layer (None: a NULL array)."""
+    if ts is None:
+        return None
+    return (ctypes.c_void_p * len(ts))(*[_ptr(t, dtype).value for t in ts])
+
+
+def _lstm_stack_desc(x, h0, Ux, groups, has_bias):
+    T, B, d_in = x.shape
+    return pf_lstm_stack_desc(T, B, d_in, h0[0].shape[1], Ux[0].shape[1], groups, len(Ux), _dtype_code(x),
+                              1 if has_bias else 0)
+
+
+def pf_lowrank_lstm_stack_fwd(x, h0, c0, Vx, Ux, Vh, Uh, bias=None, groups=1):
+    """A stack of factorized LSTM layers over a sequence x[T,B,d]; h0, c0, Vx, Ux, Vh, Uh, bias are lists with one
+    tensor per layer.  Returns lists (h_all, c_all, gates_all, Tx_all, Th_all), one tensor per layer."""
+    d = _lstm_stack_desc(x, h0, Ux, groups, bias is not None)
+    f32 = torch.float32
+    dev = x.device
+    L = d.layers
+    new = lambda n: [torch.empty((d.T, d.B, n), dtype=f32, device=dev) for _ in range(L)]
+    h_all, c_all, gates_all = new(d.h), new(d.h), new(4 * d.h)
+    Tx_all, Th_all = new(groups * d.r), new(groups * d.r)
+    ws = _workspace(lib.pf_lowrank_lstm_stack_fwd_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_lowrank_lstm_stack_fwd(
+        ctypes.byref(d), _ptr(x, f32), _ptr_array(h0, f32), _ptr_array(c0, f32), _ptr_array(Vx, f32),
+        _ptr_array(Ux, f32), _ptr_array(Vh, f32), _ptr_array(Uh, f32), _ptr_array(bias, f32), _ptr_array(h_all),
+        _ptr_array(c_all), _ptr_array(gates_all), _ptr_array(Tx_all), _ptr_array(Th_all), _ptr(ws),
+        ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_lstm_stack_fwd")
+    return h_all, c_all, gates_all, Tx_all, Th_all
+
+
+def pf_lowrank_lstm_stack_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux, Vh, Uh, dh_top, dhT=None,
+                              dcT=None, groups=1, need_dx=True, grads=None):
+    """Back-propagation through time and depth.  dh_top[T,B,h] arrives at the last layer; dhT, dcT: optional
+    lists (entries may be None).  Returns (dx_all, dh0, dc0, grads) with dh0, dc0 lists and grads a list of dicts
+    per layer; if `grads` is given the parameter gradients are accumulated into it."""
+    d = _lstm_stack_desc(x, h0, Ux, groups, True)
+    f32 = torch.float32
+    dev = x.device
+    L = d.layers
+    dx_all = torch.empty_like(x) if need_dx else None
+    dh0 = [torch.empty_like(t) for t in h0]
+    dc0 = [torch.empty_like(t) for t in c0]
+    accumulate = grads is not None
+    if grads is None:
+        grads = [dict(dVx=torch.empty_like(Vx[l]), dUx=torch.empty_like(Ux[l]), dVh=torch.empty_like(Vh[l]),
+                      dUh=torch.empty_like(Uh[l]), dbias=torch.empty((4 * d.h,), dtype=f32, device=dev))
+                 for l in range(L)]
+    col = lambda k: _ptr_array([g[k] for g in grads], f32)
+    ws = _workspace(lib.pf_lowrank_lstm_stack_bwd_workspace_bytes(ctypes.byref(d)), dev)
+    _check(lib.pf_lowrank_lstm_stack_bwd(
+        ctypes.byref(d), _ptr(x, f32), _ptr_array(h0, f32), _ptr_array(c0, f32), _ptr_array(h_all, f32),
+        _ptr_array(c_all, f32), _ptr_array(gates_all, f32), _ptr_array(Tx_all, f32), _ptr_array(Th_all, f32),
+        _ptr_array(Vx, f32), _ptr_array(Ux, f32), _ptr_array(Vh, f32), _ptr_array(Uh, f32), _ptr(dh_top, f32),
+        _ptr_array(dhT, f32), _ptr_array(dcT, f32), _ptr(dx_all), _ptr_array(dh0), _ptr_array(dc0), col("dVx"),
+        col("dUx"), col("dVh"), col("dUh"), col("dbias"), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
+        ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_lstm_stack_bwd")
     return dx_all, dh0, dc0, grads
 
 

@@ -44,7 +44,7 @@ struct SliceSumArgs {
     SliceSumSeg s[4];
     int nseg;
 };
-int launch_slice_sum(hipStream_t s, const SliceSumArgs &a);
+int launch_slice_sum(hipStream_t s, const SliceSumArgs &a, const char *name = "slice_sum");
 
 inline SkinnyProb skinny_prob(int M, const float *A, i64 lda, const float *W, i64 ldw, int K, int N, int ldp,
                               i64 pcount)

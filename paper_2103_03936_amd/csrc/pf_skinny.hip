@@ -247,12 +247,12 @@ static int slice_sum_blocks(const SliceSumArgs &a)
     return (int)nb;
 }
 
-int launch_slice_sum(hipStream_t s, const SliceSumArgs &a)
+int launch_slice_sum(hipStream_t s, const SliceSumArgs &a, const char *name)
 {
     int st = PF_OK;
     const int nb = slice_sum_blocks(a);
     if (nb <= 0) return st;
-    PF_LAUNCH(st, "slice_sum", slice_sum_kernel, dim3(nb), dim3(256), s, a);
+    PF_LAUNCH(st, name, slice_sum_kernel, dim3(nb), dim3(256), s, a);
     return st;
 }
 

@@ -237,3 +237,61 @@ def test_sequence_matches_torch_lstm_and_autograd(groups):
     np.testing.assert_allclose(dc0, tc0.grad.numpy(), rtol=1e-9, atol=1e-9)
     for name, tv in (("dVx", tVx), ("dUx", tUx), ("dVh", tVh), ("dUh", tUh), ("dbias", tb)):
         np.testing.assert_allclose(grads[name], tv.grad.numpy(), rtol=1e-9, atol=1e-9, err_msg=name)
+
+
+@pytest.mark.parametrize("groups", [1, 4])
+def test_stack_matches_two_layer_torch_lstm_and_autograd(groups):
+    """The stacked oracle (layer after layer, backward from the last layer to the first) against a 2-layer
+    torch.nn.LSTM with W = U V^T and torch autograd through the factors (library routines)."""
+    T, B, d, h, r, L = 4, 3, 5, 6, 2, 2
+    rng = np.random.default_rng(91 + groups)
+    gr = groups * r
+    x = rng.standard_normal((T, B, d))
+    h0 = [rng.standard_normal((B, h)) * 0.5 for _ in range(L)]
+    c0 = [rng.standard_normal((B, h)) * 0.5 for _ in range(L)]
+    Vx = [rng.standard_normal((d if l == 0 else h, gr)) * 0.4 for l in range(L)]
+    Ux = [rng.standard_normal((4 * h, r)) * 0.4 for _ in range(L)]
+    Vh = [rng.standard_normal((h, gr)) * 0.4 for _ in range(L)]
+    Uh = [rng.standard_normal((4 * h, r)) * 0.4 for _ in range(L)]
+    bias = [rng.standard_normal((4 * h,)) * 0.3 for _ in range(L)]
+    G = rng.standard_normal((T, B, h))
+    GhT = [rng.standard_normal((B, h)) for _ in range(L)]
+    GcT = [rng.standard_normal((B, h)) for _ in range(L)]
+
+    h_all, c_all, gates_all, Tx_all, Th_all = oracle.lowrank_lstm_stack_fwd(x, h0, c0, Vx, Ux, Vh, Uh, bias, groups)
+    dx_all, dh0, dc0, grads = oracle.lowrank_lstm_stack_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux,
+                                                           Vh, Uh, G, GhT, GcT, groups)
+
+    tt = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    tx = tt(x)
+    th0, tc0, tVx, tUx, tVh, tUh, tb = ([tt(a) for a in lst] for lst in (h0, c0, Vx, Ux, Vh, Uh, bias))
+
+    def dense(U, V):
+        blocks = []
+        for g in range(4):
+            Vg = V[:, g * r:(g + 1) * r] if groups == 4 else V
+            blocks.append(U[g * h:(g + 1) * h] @ Vg.T)
+        return torch.cat(blocks, 0)
+
+    lstm = torch.nn.LSTM(d, h, num_layers=L, bias=True, dtype=torch.float64)
+    params = {}
+    for l in range(L):
+        params[f"weight_ih_l{l}"] = dense(tUx[l], tVx[l])
+        params[f"weight_hh_l{l}"] = dense(tUh[l], tVh[l])
+        params[f"bias_ih_l{l}"] = tb[l]
+        params[f"bias_hh_l{l}"] = torch.zeros(4 * h, dtype=torch.float64)
+    out, (hT, cT) = torch.func.functional_call(lstm, params, (tx, (torch.stack(th0), torch.stack(tc0))))
+    np.testing.assert_allclose(h_all[L - 1], out.detach().numpy(), rtol=1e-10, atol=1e-10)
+    for l in range(L):
+        np.testing.assert_allclose(h_all[l][-1], hT[l].detach().numpy(), rtol=1e-10, atol=1e-10)
+        np.testing.assert_allclose(c_all[l][-1], cT[l].detach().numpy(), rtol=1e-10, atol=1e-10)
+    loss = (out * torch.tensor(G)).sum()
+    for l in range(L):
+        loss = loss + (hT[l] * torch.tensor(GhT[l])).sum() + (cT[l] * torch.tensor(GcT[l])).sum()
+    loss.backward()
+    np.testing.assert_allclose(dx_all, tx.grad.numpy(), rtol=1e-9, atol=1e-9)
+    for l in range(L):
+        np.testing.assert_allclose(dh0[l], th0[l].grad.numpy(), rtol=1e-9, atol=1e-9)
+        np.testing.assert_allclose(dc0[l], tc0[l].grad.numpy(), rtol=1e-9, atol=1e-9)
+        for name, tv in (("dVx", tVx), ("dUx", tUx), ("dVh", tVh), ("dUh", tUh), ("dbias", tb)):
+            np.testing.assert_allclose(grads[l][name], tv[l].grad.numpy(), rtol=1e-9, atol=1e-9, err_msg=f"{name}{l}")

@@ -157,6 +157,9 @@ CONFIGS = {
     # the same model through the sequence-level entry points (one call per layer and direction)
     "lstm_lm_seq_f32": dict(kind="lstm", dtype="f32", vocab=33278, d=1500, h=1500, r=375, layers=2,
                             T=35, B=20, seed=2, seq=True),
+    # the same model through the stack entry points (one call per direction, layers on the diagonals l + t)
+    "lstm_lm_stack_f32": dict(kind="lstm", dtype="f32", vocab=33278, d=1500, h=1500, r=375, layers=2,
+                              T=35, B=20, seed=2, stack=True),
     # Algorithm 1's factor initialisation for one layer of each model family (dense weight -> balanced factors)
     "svd_split_f32": dict(kind="svd", dtype="f32", seed=5, layers=dict(
         vgg_fc=(512, 512, 128), resnet18_conv4=(2304, 256, 64), transformer_ffn=(2048, 512, 128),
