@@ -243,12 +243,7 @@ __global__ __launch_bounds__(256) void lstm_slices_pointwise_fwd_kernel(const fl
     const i64 base = (i64)b * 4 * h + j;
     float z[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) z[g] = 0.f;
-    for (int sl = 0; sl < nslices; ++sl) {
-        const float *p = P + (i64)sl * pcount + base;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) z[g] += p[(i64)g * h];
-    }
+    for (int g = 0; g < 4; ++g) z[g] = slices_at(P, nslices, pcount, base + (i64)g * h);
     if (bias) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) z[g] += bias[j + (i64)g * h];
@@ -477,9 +472,7 @@ __global__ __launch_bounds__(256) void lstm_seq_pointwise_bwd_kernel(const float
     const int b = (int)(idx / h), j = (int)(idx % h);
     const i64 base = (i64)b * 4 * h + j;
     float dhv = dh_a[idx] + (dh_b ? dh_b[idx] : 0.f);
-    float sl = 0.f;
-    for (int q = 0; q < nslices; ++q) sl += P[(i64)q * pcount + idx];
-    dhv += sl;
+    dhv += slices_at(P, nslices, pcount, idx);
     const float ig = gates[base], fg = gates[base + h], gg = gates[base + 2 * (i64)h], og = gates[base + 3 * (i64)h];
     const float tc = tanhf(c_out[idx]);
     const float dc = (dc_next ? dc_next[idx] : 0.f) + dhv * og * (1.f - tc * tc);

@@ -40,12 +40,9 @@ __global__ __launch_bounds__(256) void lstm_stack_gates_fwd_kernel(StackGatesFwd
     if (idx >= (i64)a.B * h) return;
     const int b = (int)(idx / h), j = (int)(idx % h);
     const i64 base = (i64)b * 4 * h + j, pcount = (i64)a.B * 4 * h;
-    float z[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int sl = 0; sl < a.nslices[q]; ++sl) {
-        const float *p = a.P[q] + (i64)sl * pcount + base;
+    float z[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) z[g] += p[(i64)g * h];
-    }
+    for (int g = 0; g < 4; ++g) z[g] = slices_at(a.P[q], a.nslices[q], pcount, base + (i64)g * h);
     if (a.bias[q]) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) z[g] += a.bias[q][j + (i64)g * h];
@@ -85,10 +82,7 @@ __global__ __launch_bounds__(256) void lstm_stack_gates_bwd_kernel(StackGatesBwd
     const int b = (int)(idx / h), j = (int)(idx % h);
     const i64 base = (i64)b * 4 * h + j, pc = (i64)a.B * h;
     float dhv = (a.dh_a[q] ? a.dh_a[q][idx] : 0.f) + (a.dh_b[q] ? a.dh_b[q][idx] : 0.f);
-    float s1 = 0.f, s2 = 0.f;
-    for (int k = 0; k < a.n1[q]; ++k) s1 += a.P1[q][(i64)k * pc + idx];
-    for (int k = 0; k < a.n2[q]; ++k) s2 += a.P2[q][(i64)k * pc + idx];
-    dhv += s1 + s2;
+    dhv += slices_at(a.P1[q], a.n1[q], pc, idx) + slices_at(a.P2[q], a.n2[q], pc, idx);
     const float *gt = a.gates[q];
     const float ig = gt[base], fg = gt[base + h], gg = gt[base + 2 * (i64)h], og = gt[base + 3 * (i64)h];
     const float tc = tanhf(a.c_out[q][idx]);
@@ -118,7 +112,7 @@ struct SkBatch {
     void add(const SkinnyProb &p, int region, i64 coloff = 0) { items.push_back(SkItem{p, region, coloff}); }
     // Plans every launch (at most SK_MAX_PROB problems each, regions kept whole), places the slices from `part`
     // on (NULL: sizes only; cap floats are there) and launches unless dry.  *used: the floats of `part` taken.
-    int run(hipStream_t s, const char *name, bool nk, float *part, size_t cap, bool dry, size_t *used)
+    int run(hipStream_t s, const char *name, bool nk, float *part, size_t cap, bool dry, size_t *used, bool packed = true)
     {
         region_off.assign(nregions, 0);
         region_len.assign(nregions, 0);
@@ -159,7 +153,8 @@ struct SkBatch {
         if (dry) return PF_OK;
         if (!part || off > cap) return PF_ERR_WORKSPACE;
         int st = PF_OK;
-        for (size_t q = 0; q < launches.size() && st == PF_OK; ++q) st = launch_skinny_gemm(s, name, launches[q], nk);
+        for (size_t q = 0; q < launches.size() && st == PF_OK; ++q)
+            st = packed ? launch_skinny_gemm_packed(s, name, launches[q]) : launch_skinny_gemm(s, name, launches[q], nk);
         return st;
     }
 };
@@ -252,9 +247,59 @@ struct StackPtrs {
         *Th_all[ST_MAX_LAYERS];
 };
 
+// The factors in the order the streaming kernel reads them (see skinny_packed_floats), copied once per call: every
+// one of the T + L - 1 slots reuses them.  Forward roles: T = a V (contraction over V's rows), z = T U^T (over U's
+// columns); backward roles: dT = dz U (over U's rows), dh = dT V^T (over V's columns).
+struct StackPacked {
+    const float *Vh[ST_MAX_LAYERS], *Vx[ST_MAX_LAYERS];       // Vx: layers above the first only
+    const float *Uh[ST_MAX_LAYERS][4], *Ux[ST_MAX_LAYERS][4]; // per gate block when every gate has its own pair
+};
+// Places the copies from buf on (NULL: sizes only), launches the copy kernels unless dry; returns the floats taken.
+static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float *buf, StackPacked *out, bool dry,
+                         hipStream_t s, int *status)
+{
+    const int h = g.h, r = g.r, gr = g.gr, nq = g.G == 1 ? 1 : 4;
+    size_t off = 0;
+    int st = PF_OK;
+    SkinnyPackArgs pa = {};
+    auto flush = [&]() {
+        if (!dry && st == PF_OK && pa.n > 0) st = launch_skinny_pack(s, pa);
+        pa = SkinnyPackArgs{};
+    };
+    auto add = [&](const float *src, i64 sk, i64 sn, int K, int N) -> const float * {
+        float *dst = buf ? buf + off : nullptr;
+        off += skinny_packed_floats(K, N);
+        if (!dry) {
+            skinny_pack_add(pa, src, sk, sn, K, N, dst);
+            if (pa.n == SK_MAX_PACK) flush();
+        }
+        return dst;
+    };
+    for (int l = 0; l < g.L; ++l) {
+        for (int path = 0; path < 2; ++path) { // 0: hidden path, 1: input path (hoisted for the first layer)
+            if (path == 1 && l == 0) continue;
+            const float *V = dry ? nullptr : (path ? p.Vx[l] : p.Vh[l]), *U = dry ? nullptr : (path ? p.Ux[l] : p.Uh[l]);
+            // V is [h x gr]: forward contracts over its rows, backward over its columns
+            const float *pv = bwd ? add(V, 1, gr, gr, h) : add(V, gr, 1, h, gr);
+            if (out) (path ? out->Vx : out->Vh)[l] = pv;
+            for (int q = 0; q < nq; ++q) {
+                // U (or its gate block q) is [rows x r] with rows = 4h or h
+                const int rows = g.G == 1 ? 4 * h : h;
+                const float *Uq = U ? U + (i64)q * h * r : nullptr;
+                const float *pu = bwd ? add(Uq, r, 1, rows, r) : add(Uq, 1, r, r, rows);
+                if (out) (path ? out->Ux : out->Uh)[l][q] = pu;
+            }
+        }
+    }
+    flush();
+    if (status) *status = st;
+    return off;
+}
+
 // ---- forward slot: products and gates of the layers in `mask` (layer l at time t = slot - l) ----
 // part (NULL: sizes only) holds the slices of one launch group at a time.
-static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const float *zx0, int slot, float *part, size_t cap,
+static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const StackPacked &pk, const float *zx0, int slot,
+                          float *part, size_t cap,
                           bool dry, hipStream_t s, size_t *need)
 {
     const int B = g.B, h = g.h, r = g.r, G = g.G, gr = g.gr;
@@ -270,11 +315,10 @@ static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const float *z
         if (t < 0 || t >= g.T) continue;
         const float *hp = dry ? nullptr : (t ? p.h_all[l] + (i64)(t - 1) * Bh : p.h0[l]);
         reg_th[l] = kn.new_region();
-        kn.add(skinny_prob(B, hp, h, dry ? nullptr : p.Vh[l], gr, h, gr, gr, (i64)B * gr), reg_th[l]);
+        kn.add(skinny_prob(B, hp, h, pk.Vh[l], gr, h, gr, gr, (i64)B * gr), reg_th[l]);
         if (l > 0) {
             reg_tx[l] = kn.new_region();
-            kn.add(skinny_prob(B, dry ? nullptr : p.h_all[l - 1] + (i64)t * Bh, h, dry ? nullptr : p.Vx[l], gr, h, gr, gr,
-                               (i64)B * gr),
+            kn.add(skinny_prob(B, dry ? nullptr : p.h_all[l - 1] + (i64)t * Bh, h, pk.Vx[l], gr, h, gr, gr, (i64)B * gr),
                    reg_tx[l]);
         }
     }
@@ -299,14 +343,12 @@ static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const float *z
     SkBatch nk;
     int reg_zh[ST_MAX_LAYERS], reg_zx[ST_MAX_LAYERS];
     const i64 pcz = (i64)B * 4 * h;
-    auto add_z = [&](int region, const float *Tm, const float *U) {
+    auto add_z = [&](int region, const float *Tm, const float *const *U) { // U: the packed gate blocks
         if (G == 1) {
-            nk.add(skinny_prob(B, Tm, gr, U, r, r, 4 * h, 4 * h, pcz), region);
+            nk.add(skinny_prob(B, Tm, gr, U[0], r, r, 4 * h, 4 * h, pcz), region);
         } else {
             for (int q = 0; q < 4; ++q)
-                nk.add(skinny_prob(B, Tm ? Tm + (i64)q * r : nullptr, gr, U ? U + (i64)q * h * r : nullptr, r, r, h, 4 * h,
-                                   pcz),
-                       region, (i64)q * h);
+                nk.add(skinny_prob(B, Tm ? Tm + (i64)q * r : nullptr, gr, U[q], r, r, h, 4 * h, pcz), region, (i64)q * h);
         }
     };
     for (int l = 0; l < g.L; ++l) {
@@ -314,10 +356,10 @@ static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const float *z
         reg_zh[l] = reg_zx[l] = -1;
         if (t < 0 || t >= g.T) continue;
         reg_zh[l] = nk.new_region();
-        add_z(reg_zh[l], dry ? nullptr : p.Th_all[l] + (i64)t * B * gr, dry ? nullptr : p.Uh[l]);
+        add_z(reg_zh[l], dry ? nullptr : p.Th_all[l] + (i64)t * B * gr, pk.Uh[l]);
         if (l > 0) {
             reg_zx[l] = nk.new_region();
-            add_z(reg_zx[l], dry ? nullptr : p.Tx_all[l] + (i64)t * B * gr, dry ? nullptr : p.Ux[l]);
+            add_z(reg_zx[l], dry ? nullptr : p.Tx_all[l] + (i64)t * B * gr, pk.Ux[l]);
         }
     }
     st = nk.run(s, "lstm_stack_z", true, part, cap, dry, &used);
@@ -348,7 +390,7 @@ static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const float *z
 }
 
 struct StackPlan {
-    size_t n_zx0, n_part, n_part2, n_dT, n_dz, fwd_bytes, bwd_bytes;
+    size_t n_zx0, n_part, n_part2, n_dT, n_dz, n_pack_f, n_pack_b, fwd_bytes, bwd_bytes;
 };
 
 // per-layer tensors of the backward pass
@@ -366,7 +408,8 @@ struct StackCarry {
     const float *P1[ST_MAX_LAYERS], *P2[ST_MAX_LAYERS]; // for layer l: recurrent slices / slices from layer l + 1
     int n1[ST_MAX_LAYERS], n2[ST_MAX_LAYERS];
 };
-static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackBwdPtrs &b, const float *dh_top, int u,
+static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackPacked &pk, const StackBwdPtrs &b,
+                          const float *dh_top, int u,
                           float *part, size_t cap, float *part2, size_t cap2, StackCarry &carry, bool dry, hipStream_t s,
                           size_t *need, size_t *need2)
 {
@@ -407,14 +450,13 @@ static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackBwd
     SkBatch kn;
     int reg_h[ST_MAX_LAYERS], reg_x[ST_MAX_LAYERS];
     const i64 pcT = (i64)B * gr;
-    auto add_dT = [&](int region, const float *dz, const float *U) {
+    auto add_dT = [&](int region, const float *dz, const float *const *U) { // U: the packed gate blocks
         if (G == 1) {
-            kn.add(skinny_prob(B, dz, 4 * (i64)h, U, r, 4 * h, r, gr, pcT), region);
+            kn.add(skinny_prob(B, dz, 4 * (i64)h, U[0], r, 4 * h, r, gr, pcT), region);
         } else {
             for (int q = 0; q < 4; ++q)
-                kn.add(skinny_prob(B, dz ? dz + (i64)q * h : nullptr, 4 * (i64)h, U ? U + (i64)q * h * r : nullptr, r, h, r,
-                                   gr, pcT),
-                       region, (i64)q * r);
+                kn.add(skinny_prob(B, dz ? dz + (i64)q * h : nullptr, 4 * (i64)h, U[q], r, h, r, gr, pcT), region,
+                       (i64)q * r);
         }
     };
     for (int l = 0; l < L; ++l) {
@@ -423,10 +465,10 @@ static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackBwd
         const int t = time_of(l);
         const float *dz = dry ? nullptr : b.dz_all[l] + (i64)t * pcz;
         reg_h[l] = kn.new_region();
-        add_dT(reg_h[l], dz, dry ? nullptr : p.Uh[l]);
+        add_dT(reg_h[l], dz, pk.Uh[l]);
         if (l > 0) {
             reg_x[l] = kn.new_region();
-            add_dT(reg_x[l], dz, dry ? nullptr : p.Ux[l]);
+            add_dT(reg_x[l], dz, pk.Ux[l]);
         }
     }
     size_t used = 0;
@@ -455,11 +497,11 @@ static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackBwd
         if (!active(l)) continue;
         const int t = time_of(l);
         reg_dh[l] = nk.new_region();
-        nk.add(skinny_prob(B, dry ? nullptr : b.dTh_all[l] + (i64)t * pcT, gr, dry ? nullptr : p.Vh[l], gr, gr, h, h, Bh),
+        nk.add(skinny_prob(B, dry ? nullptr : b.dTh_all[l] + (i64)t * pcT, gr, pk.Vh[l], gr, gr, h, h, Bh),
                reg_dh[l]);
         if (l > 0) {
             reg_dx[l] = nk.new_region();
-            nk.add(skinny_prob(B, dry ? nullptr : b.dTx_all[l] + (i64)t * pcT, gr, dry ? nullptr : p.Vx[l], gr, gr, h, h, Bh),
+            nk.add(skinny_prob(B, dry ? nullptr : b.dTx_all[l] + (i64)t * pcT, gr, pk.Vx[l], gr, gr, h, h, Bh),
                    reg_dx[l]);
         }
     }
@@ -502,25 +544,29 @@ static int plan_stack(const StackGeom &g, StackPlan *out)
     upd(st_tall_part(Mt, g.G == 1 ? 4 * g.h : g.h, g.r));  // dTx = dz Ux
     upd(st_tall_part(Mt, g.gr, g.din));                    // dx = dTx Vx^T
     StackPtrs none = {};
+    StackPacked nonep = {};
     StackBwdPtrs noneb = {};
     StackCarry carry = {};
     for (int slot = 0; slot < g.T + g.L - 1; ++slot) {
         // the sets of active layers repeat: every slot in the middle has all of them
         if (slot >= g.L && slot < g.T - 1) continue;
         size_t need = 0, need2 = 0;
-        int st = stack_fwd_slot(g, none, nullptr, slot, nullptr, 0, true, nullptr, &need);
+        int st = stack_fwd_slot(g, none, nonep, nullptr, slot, nullptr, 0, true, nullptr, &need);
         if (st != PF_OK) return st;
         upd(need);
-        st = stack_bwd_slot(g, none, noneb, nullptr, slot, nullptr, 0, nullptr, 0, carry, true, nullptr, &need, &need2);
+        st = stack_bwd_slot(g, none, nonep, noneb, nullptr, slot, nullptr, 0, nullptr, 0, carry, true, nullptr, &need, &need2);
         if (st != PF_OK) return st;
         upd(need);
         if (need2 > m2) m2 = need2;
     }
     p.n_part = m;
     p.n_part2 = m2;
-    p.fwd_bytes = align_up(p.n_zx0 * sizeof(float)) + align_up(p.n_part * sizeof(float));
+    p.n_pack_f = stack_pack(g, none, false, nullptr, nullptr, true, nullptr, nullptr);
+    p.n_pack_b = stack_pack(g, none, true, nullptr, nullptr, true, nullptr, nullptr);
+    p.fwd_bytes = align_up(p.n_zx0 * sizeof(float)) + align_up(p.n_part * sizeof(float)) + align_up(p.n_pack_f * sizeof(float));
     p.bwd_bytes = (size_t)g.L * (align_up(p.n_dz * sizeof(float)) + 2 * align_up(p.n_dT * sizeof(float))) +
-                  align_up(p.n_part * sizeof(float)) + align_up(p.n_part2 * sizeof(float));
+                  align_up(p.n_part * sizeof(float)) + align_up(p.n_part2 * sizeof(float)) +
+                  align_up(p.n_pack_b * sizeof(float));
     *out = p;
     return PF_OK;
 }
@@ -591,6 +637,10 @@ int pf_lowrank_lstm_stack_fwd(const pf_lstm_stack_desc *d, const void *x, const 
     hipStream_t s = (hipStream_t)stream;
     float *zx0 = ws.take<float>(pl.n_zx0);
     float *part = ws.take<float>(pl.n_part);
+    float *packed = ws.take<float>(pl.n_pack_f);
+    StackPacked pk = {};
+    stack_pack(g, p, false, packed, &pk, false, s, &st);
+    if (st != PF_OK) return st;
     const i64 Mt = (i64)g.T * g.B;
     const int h = g.h, r = g.r, gr = g.gr;
     // the input path of the first layer for every time step at once
@@ -606,7 +656,7 @@ int pf_lowrank_lstm_stack_fwd(const pf_lstm_stack_desc *d, const void *x, const 
                          h, zx0 + (i64)q * h, 4 * (i64)h, p.bias[0] ? p.bias[0] + (i64)q * h : nullptr, part);
     }
     for (int slot = 0; slot < g.T + g.L - 1 && st == PF_OK; ++slot)
-        st = stack_fwd_slot(g, p, zx0, slot, part, pl.n_part, false, s, nullptr);
+        st = stack_fwd_slot(g, p, pk, zx0, slot, part, pl.n_part, false, s, nullptr);
     return st;
 }
 
@@ -685,10 +735,14 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x, const 
     }
     float *part = ws.take<float>(pl.n_part);
     float *part2 = ws.take<float>(pl.n_part2);
+    float *packed = ws.take<float>(pl.n_pack_b);
+    StackPacked pk = {};
+    stack_pack(g, p, true, packed, &pk, false, s, &st);
+    if (st != PF_OK) return st;
     StackCarry carry = {};
     for (int u = 0; u < T + L - 1 && st == PF_OK; ++u)
-        st = stack_bwd_slot(g, p, b, (const float *)dh_top, u, part, pl.n_part, part2, pl.n_part2, carry, false, s, nullptr,
-                            nullptr);
+        st = stack_bwd_slot(g, p, pk, b, (const float *)dh_top, u, part, pl.n_part, part2, pl.n_part2, carry, false, s,
+                            nullptr, nullptr);
     if (st != PF_OK) return st;
     // the input path of the first layer for all steps at once
     const i64 Mt = (i64)T * B;

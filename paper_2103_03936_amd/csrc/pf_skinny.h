@@ -32,6 +32,28 @@ int skinny_ksplit(i64 K, i64 total_tiles, int target = 256);
 inline i64 skinny_tiles(i64 N) { return (N + SK_TILE_N - 1) / SK_TILE_N; }
 int launch_skinny_gemm(hipStream_t s, const char *name, const SkinnyArgs &a, bool nk);
 
+// Weights that many launches reuse (a layer's factors over the steps of a sequence) can be copied once into the
+// order the kernel consumes them in: for column tile `tile` and the eight contraction indices 8 S .. 8 S + 7, the
+// 16 bytes of lane l for column sub-tile e are the four values W(k = 8 S + 4 (l / 32) + 0..3, n = 128 tile + 32 e
+// + l % 32) at float offset (((tile * ceil(K / 8) + S) * 4 + e) * 64 + l) * 4, zero past K and N.  A wavefront's
+// load is then one aligned kilobyte.  With such a copy W of a problem points at it and ldw is not used.
+inline size_t skinny_packed_floats(int K, int N) { return (size_t)skinny_tiles(N) * (size_t)((K + 7) / 8) * 1024; }
+struct SkinnyPackItem {
+    const float *src; // element (k, n) at src[k * sk + n * sn]
+    float *dst;
+    i64 sk, sn, item0; // item0: the first 16-byte item of this matrix among all of the launch
+    int K, N;
+};
+constexpr int SK_MAX_PACK = 8;
+struct SkinnyPackArgs {
+    SkinnyPackItem m[SK_MAX_PACK];
+    int n;
+    i64 items;
+};
+void skinny_pack_add(SkinnyPackArgs &a, const float *src, i64 sk, i64 sn, int K, int N, float *dst);
+int launch_skinny_pack(hipStream_t s, const SkinnyPackArgs &a);
+int launch_skinny_gemm_packed(hipStream_t s, const char *name, const SkinnyArgs &a);
+
 // out[m * ldo + n] = bias[n] + sum over ks < ksplit of P[ks * pcount + m * ldp + n], m < M; several segments in
 // one launch (bias nullable)
 struct SliceSumSeg {
@@ -45,6 +67,25 @@ struct SliceSumArgs {
     int nseg;
 };
 int launch_slice_sum(hipStream_t s, const SliceSumArgs &a, const char *name = "slice_sum");
+
+// For kernels that add the slices up themselves: the sum over n slices of P[k * pcount + idx], in order, eight
+// loads in flight at a time (slices past the end add zero).
+__device__ __forceinline__ float slices_at(const float *P, int n, i64 pcount, i64 idx)
+{
+    float s = 0.f;
+    for (int k0 = 0; k0 < n; k0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u;
+            const float x = P[(i64)(k < n ? k : 0) * pcount + idx];
+            v[u] = k < n ? x : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    return s;
+}
 
 inline SkinnyProb skinny_prob(int M, const float *A, i64 lda, const float *W, i64 ldw, int K, int N, int ldp,
                               i64 pcount)

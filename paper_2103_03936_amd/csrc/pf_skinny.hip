@@ -35,9 +35,12 @@ __device__ __forceinline__ f32x4_t ld4n(const float *p, int n)
     return r;
 }
 
-template <bool NK>
+// MODE 0: KN weights, 1: NK weights, 2: weights copied into the kernel's own order by skinny_pack_kernel
+template <int MODE>
 __global__ __launch_bounds__(256, 1) void skinny_gemm_kernel(SkinnyArgs a)
 {
+    constexpr bool NK = MODE != 0; // the packed order keeps NK's assignment of columns to lanes
+    constexpr bool PK = MODE == 2;
     // partial tiles of the four wavefronts, two column tiles at a time
     __shared__ float red[4][2][16][64];
 
@@ -81,8 +84,31 @@ __global__ __launch_bounds__(256, 1) void skinny_gemm_kernel(SkinnyArgs a)
             const int kk = kA + 32 * c + 8 * q + 4 * half; // this lane's k values: kk .. kk + 3
             const int kc = min(kk, K - 4);                 // where they are read from
             st.act[q] = ld4(Ap + kc); // masked when it is used
+            if (!NK) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) st.wv[q][e] = NK ? ld4(W + nrow[e] + kc) : ld4(W + (i64)(kc + e) * ldw + nbase);
+                for (int e = 0; e < 4; ++e) st.wv[q][e] = ld4(W + (i64)(kc + e) * ldw + nbase);
+            }
+        }
+        if (PK) {
+            const i64 S_total = (K + 7) / 8;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const i64 S = min((i64)((kA + 32 * c + 8 * q) >> 3), S_total - 1); // past K: loaded, never used
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    st.wv[q][e] = *(const f32x4_t *)(W + ((((i64)tile * S_total + S) * 4 + e) * 64 + lane) * 4);
+            }
+        }
+        // NK: a lane's loads of one column are neighbours in memory (32 k = one 128-byte stretch per chunk); issued
+        // back to back they meet in the cache instead of fetching the line once per super-step
+        if (NK && !PK) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int kc = min(kA + 32 * c + 8 * q + 4 * half, K - 4);
+                    st.wv[q][e] = ld4(W + nrow[e] + kc);
+                }
         }
     };
 
@@ -107,7 +133,16 @@ __global__ __launch_bounds__(256, 1) void skinny_gemm_kernel(SkinnyArgs a)
                 const int kk = kA + 32 * c + 8 * q + 4 * half, kc = min(kk, K - 4);
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const float av = (row_ok && kc + s >= kk && kc + s < kB) ? st.act[q][s] : 0.f;
+                    // KN / NK: weights and activations were read from kc, so element s stands for k = kc + s.
+                    // Packed weights sit at their own k = kk + s: the activation is taken from where that k landed.
+                    float av;
+                    if (PK) {
+                        const int idx = kk - kc + s;
+                        const float pick = idx == 0 ? st.act[q][0] : idx == 1 ? st.act[q][1] : idx == 2 ? st.act[q][2] : st.act[q][3];
+                        av = (row_ok && kk + s < kB) ? pick : 0.f;
+                    } else {
+                        av = (row_ok && kc + s >= kk && kc + s < kB) ? st.act[q][s] : 0.f;
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         cur[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, NK ? st.wv[q][j][s] : st.wv[q][s][j], cur[j], 0,
@@ -188,10 +223,70 @@ int launch_skinny_gemm(hipStream_t s, const char *name, const SkinnyArgs &a, boo
             a.p[q].ldw < (nk ? a.p[q].K : a.p[q].N))
             return PF_ERR_UNSUPPORTED;
     if (nk) {
-        PF_LAUNCH(st, name, skinny_gemm_kernel<true>, dim3(a.nwg), dim3(256), s, a);
+        PF_LAUNCH(st, name, skinny_gemm_kernel<1>, dim3(a.nwg), dim3(256), s, a);
     } else {
-        PF_LAUNCH(st, name, skinny_gemm_kernel<false>, dim3(a.nwg), dim3(256), s, a);
+        PF_LAUNCH(st, name, skinny_gemm_kernel<0>, dim3(a.nwg), dim3(256), s, a);
     }
+    return st;
+}
+
+int launch_skinny_gemm_packed(hipStream_t s, const char *name, const SkinnyArgs &a)
+{
+    int st = PF_OK;
+    if (a.nwg <= 0 || a.nprob <= 0) return st;
+    if (a.nprob > SK_MAX_PROB) return PF_ERR_UNSUPPORTED;
+    for (int q = 0; q < a.nprob; ++q)
+        if (a.p[q].M < 1 || a.p[q].M > SK_MAX_ROWS || a.p[q].K < 4 || a.p[q].N < 4 || a.p[q].lda < a.p[q].K ||
+            ((uintptr_t)a.p[q].W & 15))
+            return PF_ERR_UNSUPPORTED;
+    PF_LAUNCH(st, name, skinny_gemm_kernel<2>, dim3(a.nwg), dim3(256), s, a);
+    return st;
+}
+
+// one thread per 16-byte item of the packed order
+__global__ __launch_bounds__(256) void skinny_pack_kernel(SkinnyPackArgs a)
+{
+    const i64 g = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (g >= a.items) return;
+    int pi = 0;
+#pragma unroll
+    for (int q = 1; q < SK_MAX_PACK; ++q)
+        if (q < a.n && g >= a.m[q].item0) pi = q;
+    const SkinnyPackItem &m = a.m[pi];
+    const i64 it = g - m.item0, S_total = (m.K + 7) / 8;
+    const int lane = (int)(it & 63), e = (int)((it >> 6) & 3);
+    const i64 S = (it >> 8) % S_total, tile = (it >> 8) / S_total;
+    const i64 n = tile * SK_TILE_N + 32 * e + (lane & 31);
+    f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const i64 k = 8 * S + 4 * (lane >> 5) + s;
+        if (k < m.K && n < m.N) v[s] = m.src[k * m.sk + n * m.sn];
+    }
+    *(f32x4_t *)(m.dst + it * 4) = v;
+}
+
+void skinny_pack_add(SkinnyPackArgs &a, const float *src, i64 sk, i64 sn, int K, int N, float *dst)
+{
+    if (a.n >= SK_MAX_PACK) return;
+    SkinnyPackItem &m = a.m[a.n++];
+    m.src = src;
+    m.dst = dst;
+    m.sk = sk;
+    m.sn = sn;
+    m.K = K;
+    m.N = N;
+    m.item0 = a.items;
+    a.items += (i64)(skinny_packed_floats(K, N) / 4);
+}
+
+int launch_skinny_pack(hipStream_t s, const SkinnyPackArgs &a)
+{
+    int st = PF_OK;
+    if (a.n <= 0 || a.items <= 0) return st;
+    for (int q = 0; q < a.n; ++q)
+        if (!a.m[q].src || !a.m[q].dst || ((uintptr_t)a.m[q].dst & 15)) return PF_ERR_UNSUPPORTED;
+    PF_LAUNCH(st, "skinny_pack", skinny_pack_kernel, dim3((unsigned)((a.items + 255) / 256)), dim3(256), s, a);
     return st;
 }
 
@@ -218,7 +313,17 @@ __device__ __forceinline__ void slice_sum_block(const SliceSumArgs &a, int block
 #pragma unroll
                 for (int u = 0; u < 8; ++u) acc += v[u];
             }
-            for (; ks < sg_.ksplit; ks += 4) acc += p[(i64)ks * sg_.pcount];
+            { // the last round, again with every load in flight before the first add (slices past the end add zero)
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = ks + 4 * u;
+                    const float x = p[(i64)(k < sg_.ksplit ? k : 0) * sg_.pcount];
+                    v[u] = k < sg_.ksplit ? x : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += v[u];
+            }
             __syncthreads();
             sh[threadIdx.x] = acc;
             __syncthreads();
