@@ -363,6 +363,10 @@ class LstmWorkload:
                 "lstm_stack_T": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * h + B * gr) * (cells + up), slots),
                 "lstm_stack_z": (2.0 * B * 4 * h * r * (cells + up),
                                  4 * (4 * h * r + B * gr + 2 * B * 4 * h) * (cells + up), slots),
+                # pre-activations of both paths and the gates in one launch (one factor pair per path)
+                "lstm_stack_z_gates": (2.0 * B * 4 * h * r * (cells + up),
+                                       4 * ((4 * h * r + B * gr) * (cells + up) + (B * 4 * h * 2 + 3 * B * h) * cells),
+                                       slots),
                 "lstm_stack_dT": (2.0 * B * 4 * h * r * (cells + up), 4 * (4 * h * r + B * 4 * h + B * gr) * (cells + up),
                                   slots),
                 "lstm_stack_dh": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * gr + B * h) * (cells + up), slots),

@@ -95,6 +95,275 @@ __global__ __launch_bounds__(256) void lstm_stack_gates_bwd_kernel(StackGatesBwd
     dz[base + 3 * (i64)h] = dhv * tc * og * (1.f - og);
 }
 
+// ---- z = Th Uh^T (+ Tx Ux^T) and the gates in one kernel (one factor pair per path) ----
+// A workgroup owns ZG_HU hidden units of one layer, i.e. 4 ZG_HU = 64 pre-activation columns, and the whole
+// contraction, so no slice sums leave the chip and eq. (2) is applied where z is formed.  The rank-r activations of
+// both paths are staged in LDS once (rows past B and columns past r as zeros: no masks in the loop); the factors
+// come from a copy in the kernel's own order (lstm_zg_pack_kernel).  Column i of MFMA sub-tile e is gate
+// 2 e + i / 16 of unit u0 + i % 16.  With both paths the wavefronts take (path, half of r), with one path a
+// quarter of r each; their accumulators meet in LDS, in a fixed order.
+constexpr int ZG_HU = 16;
+constexpr int ZG_MAXR8 = 512;            // r rounded up to 8 may not exceed this
+constexpr int ZG_MAXP = ZG_MAXR8 + 4;    // LDS row pitch in floats: r8 + 4
+constexpr int ZG_CH = 4;                 // super-steps (of eight contraction indices) per prefetch stage
+constexpr int ZG_NST = 4;                // prefetch stages
+
+inline size_t zg_packed_floats(int h, int r) { return (size_t)((h + ZG_HU - 1) / ZG_HU) * (size_t)((r + 7) / 8) * 512; }
+
+struct ZgPackArgs {
+    const float *src[2 * ST_MAX_LAYERS]; // U[4h][r]
+    float *dst[2 * ST_MAX_LAYERS];
+    int n, h, r;
+};
+// one thread per 16-byte item: (tile, S, e, lane) -> U[(gate h + unit) r + 8 S + 4 (lane / 32) + 0..3]
+__global__ __launch_bounds__(256) void lstm_zg_pack_kernel(ZgPackArgs a)
+{
+    const int S_total = (a.r + 7) / 8, tiles = (a.h + ZG_HU - 1) / ZG_HU;
+    const i64 per = (i64)tiles * S_total * 128, g = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (g >= per * a.n) return;
+    const int mi = (int)(g / per);
+    const i64 it = g % per;
+    const int lane = (int)(it & 63), e = (int)((it >> 6) & 1);
+    const int S = (int)((it >> 7) % S_total), tile = (int)((it >> 7) / S_total);
+    const int i = lane & 31, gate = 2 * e + (i >> 4), unit = tile * ZG_HU + (i & 15);
+    f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int k = 8 * S + 4 * (lane >> 5) + s4;
+        if (k < a.r && unit < a.h) v[s4] = a.src[mi][((i64)gate * a.h + unit) * a.r + k];
+    }
+    *(f32x4_t *)(a.dst[mi] + it * 4) = v;
+}
+
+struct ZgLayer {
+    const float *A[2];  // [B x r] activations of the hidden path and (above the first layer) the input path
+    const float *W[2];  // their factors, packed
+    const float *bias, *zadd, *c_prev; // bias, zadd nullable
+    float *h_out, *c_out, *gates;
+    int nseg, wg0;
+};
+struct ZgArgs {
+    ZgLayer l[ST_MAX_LAYERS];
+    int n, B, h, r, tiles;
+};
+
+// NRI: rows a wavefront stages, ceil(B / 4) rounded up to 5 or 8
+template <int NRI>
+__global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float lds[2 * 32 * ZG_MAXP];
+    int li = 0;
+#pragma unroll
+    for (int x = 1; x < ST_MAX_LAYERS; ++x)
+        if (x < a.n && (int)blockIdx.x >= a.l[x].wg0) li = x;
+    const ZgLayer &L = a.l[li];
+    const int tile = blockIdx.x - L.wg0;
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, i = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // wavefront index, known to be uniform
+    const int B = a.B, h = a.h, r = a.r, r8 = (r + 7) & ~7, P = r8 + 4, S_total = r8 / 8;
+
+    // this wavefront's path and range of super-steps
+    int seg, S0, S1;
+    if (L.nseg == 2) {
+        const int per = (S_total + 1) / 2;
+        seg = w >> 1;
+        S0 = (w & 1) * per;
+        S1 = min(S_total, S0 + per);
+    } else {
+        const int per = (S_total + 3) / 4;
+        seg = 0;
+        S0 = w * per;
+        S1 = min(S_total, S0 + per);
+    }
+    // both paths' pointers are read once as scalars and chosen per lane (indexing the argument block with a
+    // per-lane index would turn every use into a dependent memory read)
+    const float *A0 = L.A[0], *A1 = L.nseg == 2 ? L.A[1] : L.A[0];
+    const float *W0 = L.W[0], *W1 = L.nseg == 2 ? L.W[1] : L.W[0];
+    const float *Wp = (seg ? W1 : W0) + (i64)tile * S_total * 512 + lane * 4; // + (S * 2 + e) * 256
+    const float *Al = lds + (seg * 32 + i) * P + 4 * half;             // + 8 S
+
+    struct Stage {
+        f32x4_t wv[ZG_CH][2];
+    };
+    auto load = [&](Stage &st, int c, bool always) __attribute__((always_inline)) {
+        if (!always && S0 + c * ZG_CH >= S1) return;
+#pragma unroll
+        for (int q = 0; q < ZG_CH; ++q) {
+            const int S = min(S0 + c * ZG_CH + q, S_total - 1); // past the range: loaded, never used
+#pragma unroll
+            for (int e = 0; e < 2; ++e) st.wv[q][e] = *(const f32x4_t *)(Wp + ((i64)S * 2 + e) * 256);
+        }
+    };
+    f32x16_t tot[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[e][v] = 0.f;
+    // The activation fragments of a stage are read from LDS one stage ahead of their use; super-steps past the
+    // wavefront's range read a valid address and multiply by zero.  A fresh accumulator per stage (32 contraction
+    // indices) is added to the running total.
+    auto lds_read = [&](f32x4_t(&av)[ZG_CH], int c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < ZG_CH; ++q) {
+            const int S = S0 + c * ZG_CH + q;
+            const f32x4_t t = *(const f32x4_t *)(Al + 8 * min(S, S_total - 1));
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) av[q][s4] = S < S1 ? t[s4] : 0.f;
+        }
+    };
+    auto compute = [&](const Stage &st, const f32x4_t(&av)[ZG_CH], int c) __attribute__((always_inline)) {
+        if (S0 + c * ZG_CH >= S1) return;
+        f32x16_t cur[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) cur[e][v] = 0.f;
+#pragma unroll
+        for (int q = 0; q < ZG_CH; ++q)
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    cur[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][s4], st.wv[q][e][s4], cur[e], 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) tot[e] += cur[e];
+    };
+    const int nch = S1 > S0 ? (S1 - S0 + ZG_CH - 1) / ZG_CH : 0;
+    // activations -> LDS, 16 bytes per item (rows are only 4-byte aligned in memory): wavefront w takes rows
+    // w, w + 4, ..., a lane the items lane and lane + 64 of a row (r8 <= 512 floats = 128 items).  Items inside a
+    // row are loaded whole; the one item per row that straddles its end is filled float by float; rows past B and
+    // columns past r are written as zeros.
+    struct __attribute__((packed, aligned(4))) F4 {
+        float f[4];
+    };
+    auto stage_load = [&](f32x4_t(&v)[2 * NRI], const float *A) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ri = 0; ri < NRI; ++ri)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = w + 4 * ri, k4 = 4 * (lane + 64 * j);
+                const bool inside = row < B && k4 + 3 < r;
+                const F4 t = *(const F4 *)(A + (inside ? (i64)row * r + k4 : 0));
+                v[2 * ri + j] = f32x4_t{t.f[0], t.f[1], t.f[2], t.f[3]};
+            }
+    };
+    auto stage_store = [&](const f32x4_t(&v)[2 * NRI], int sg) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ri = 0; ri < NRI; ++ri)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = w + 4 * ri, k4 = 4 * (lane + 64 * j);
+                const bool inside = row < B && k4 + 3 < r, straddles = row < B && k4 < r && k4 + 3 >= r;
+                f32x4_t o;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o[c] = inside ? v[2 * ri + j][c] : 0.f;
+                if (k4 < r8 && !straddles) *(f32x4_t *)&lds[(sg * 32 + row) * P + k4] = o;
+            }
+    };
+    // Every wavefront has the compute unit's SIMD to itself and only its loads hide the memory latency, so all of
+    // them are requested before the first wait: a ring of ZG_NST stages of factors (16 super-steps; the first fill
+    // is unconditional so that the loads in flight can be counted exactly), the activations (both paths when a
+    // wavefront stages at most five rows, i.e. B <= 20) and the item that straddles the end of a row.
+    Stage st[ZG_NST];
+    {
+        constexpr bool BOTH = NRI <= 5;
+        f32x4_t v[2 * NRI], v2[BOTH ? 2 * NRI : 1];
+#pragma unroll
+        for (int d = 0; d < ZG_NST; ++d) load(st[d], d, true);
+        stage_load(v, A0);
+        if constexpr (BOTH) stage_load(v2, A1); // (with one path A1 == A0: loaded, not stored)
+        const int k4t = r & ~3; // the straddling item of a row, if r is not a multiple of four
+        const bool fix = tid < L.nseg * 32 && (tid & 31) < B && k4t < r;
+        const float *src = ((tid >> 5) && L.nseg == 2 ? A1 : A0) + (fix ? (i64)(tid & 31) * r + k4t : 0);
+        f32x4_t o = {src[0], 0.f, 0.f, 0.f};
+        const float o1 = src[fix && k4t + 1 < r ? 1 : 0], o2 = src[fix && k4t + 2 < r ? 2 : 0];
+        stage_store(v, 0);
+        if (L.nseg == 2) {
+            if constexpr (!BOTH) {
+                stage_load(v, A1);
+                stage_store(v, 1);
+            } else {
+                stage_store(v2, 1);
+            }
+        }
+        // rows this wavefront does not reach with NRI rows (none when NRI covers ceil(B / 4)) stay unwritten only
+        // if they are past row 4 NRI + 3: write their zeros
+        for (int row = 4 * NRI + w; row < 32; row += 4)
+            for (int sg = 0; sg < L.nseg; ++sg)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int k4 = 4 * (lane + 64 * j);
+                    if (k4 < r8) *(f32x4_t *)&lds[(sg * 32 + row) * P + k4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                }
+        if (fix) {
+            o[1] = k4t + 1 < r ? o1 : 0.f;
+            o[2] = k4t + 2 < r ? o2 : 0.f;
+            *(f32x4_t *)&lds[((tid >> 5) * 32 + (tid & 31)) * P + k4t] = o;
+        }
+    }
+    __syncthreads(); // the staged activations are complete
+    static_assert(ZG_NST % 2 == 0, "the two fragment buffers alternate with the stage index");
+    f32x4_t av[2][ZG_CH];
+    lds_read(av[0], 0);
+    for (int c = 0; c < nch; c += ZG_NST) {
+#pragma unroll
+        for (int d = 0; d < ZG_NST; ++d) {
+            lds_read(av[(d + 1) & 1], c + d + 1);
+            compute(st[d], av[d & 1], c + d);
+            load(st[d], c + d + ZG_NST, false);
+        }
+    }
+
+    // the operands of the gate arithmetic are fetched while the tiles are exchanged (at most two elements per thread)
+    float pre_c[2], pre_b[2][4], pre_z[2][4];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int el = tid + 256 * it, m = el / ZG_HU, unit = tile * ZG_HU + el % ZG_HU;
+        const bool ok = el < B * ZG_HU && unit < h;
+        const i64 base = ok ? (i64)m * 4 * h + unit : 0, idx = ok ? (i64)m * h + unit : 0;
+        pre_c[it] = L.c_prev[idx];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            pre_b[it][g] = L.bias ? L.bias[(i64)g * h + (ok ? unit : 0)] : 0.f;
+            pre_z[it][g] = L.zadd ? L.zadd[base + (i64)g * h] : 0.f;
+        }
+    }
+    // the four wavefronts' tiles meet in LDS (the activations are no longer needed)
+    __syncthreads();
+    float *red = lds; // [4 wavefronts][2 sub-tiles][16][64]
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[((w * 2 + e) * 16 + v) * 64 + lane] = tot[e][v];
+    __syncthreads();
+    // accumulator element v of lane l is row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int el = tid + 256 * it, m = el / ZG_HU, u = el % ZG_HU, unit = tile * ZG_HU + u;
+        if (el >= B * ZG_HU || unit >= h) continue;
+        const int v = ((m >> 3) << 2) | (m & 3), hf = (m >> 2) & 1;
+        const i64 base = (i64)m * 4 * h + unit, idx = (i64)m * h + unit;
+        float z[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int at = (((g >> 1)) * 16 + v) * 64 + hf * 32 + (g & 1) * 16 + u;
+            z[g] = (red[at] + red[2 * 16 * 64 + at]) + (red[4 * 16 * 64 + at] + red[6 * 16 * 64 + at]);
+            z[g] += pre_b[it][g];
+            z[g] += pre_z[it][g];
+        }
+        const float ig = st_sigmoid(z[0]), fg = st_sigmoid(z[1]), gg = tanhf(z[2]), og = st_sigmoid(z[3]);
+        const float c = fg * pre_c[it] + ig * gg;
+        L.gates[base] = ig;
+        L.gates[base + h] = fg;
+        L.gates[base + 2 * (i64)h] = gg;
+        L.gates[base + 3 * (i64)h] = og;
+        L.c_out[idx] = c;
+        L.h_out[idx] = og * tanhf(c);
+    }
+}
+
+static bool zg_supported(int G, int r) { return G == 1 && ((r + 7) & ~7) <= ZG_MAXR8; }
+
 // ---- a launch (or a few) of skinny products whose slice sums are laid out region by region ----
 // Problems of one region write different columns of the same slices (the four gate blocks of a z product), so
 // they must get the same slicing: same K, same launch.
@@ -253,12 +522,16 @@ struct StackPtrs {
 struct StackPacked {
     const float *Vh[ST_MAX_LAYERS], *Vx[ST_MAX_LAYERS];       // Vx: layers above the first only
     const float *Uh[ST_MAX_LAYERS][4], *Ux[ST_MAX_LAYERS][4]; // per gate block when every gate has its own pair
+    const float *zg[ST_MAX_LAYERS][2];                        // forward, fused z + gates: Uh and Ux in that kernel's order
+    bool fused_z;
 };
 // Places the copies from buf on (NULL: sizes only), launches the copy kernels unless dry; returns the floats taken.
 static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float *buf, StackPacked *out, bool dry,
                          hipStream_t s, int *status)
 {
     const int h = g.h, r = g.r, gr = g.gr, nq = g.G == 1 ? 1 : 4;
+    const bool fused_z = !bwd && zg_supported(g.G, r);
+    if (out) out->fused_z = fused_z;
     size_t off = 0;
     int st = PF_OK;
     SkinnyPackArgs pa = {};
@@ -282,7 +555,7 @@ static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float
             // V is [h x gr]: forward contracts over its rows, backward over its columns
             const float *pv = bwd ? add(V, 1, gr, gr, h) : add(V, gr, 1, h, gr);
             if (out) (path ? out->Vx : out->Vh)[l] = pv;
-            for (int q = 0; q < nq; ++q) {
+            for (int q = 0; q < nq && !fused_z; ++q) {
                 // U (or its gate block q) is [rows x r] with rows = 4h or h
                 const int rows = g.G == 1 ? 4 * h : h;
                 const float *Uq = U ? U + (i64)q * h * r : nullptr;
@@ -292,6 +565,25 @@ static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float
         }
     }
     flush();
+    if (fused_z) {
+        ZgPackArgs za = {};
+        za.h = h;
+        za.r = r;
+        for (int l = 0; l < g.L; ++l)
+            for (int path = 0; path < (l ? 2 : 1); ++path) {
+                float *dst = buf ? buf + off : nullptr;
+                off += zg_packed_floats(h, r);
+                if (out) out->zg[l][path] = dst;
+                if (!dry) {
+                    za.src[za.n] = path ? p.Ux[l] : p.Uh[l];
+                    za.dst[za.n++] = dst;
+                }
+            }
+        if (!dry && st == PF_OK && za.n > 0) {
+            const i64 items = (i64)(zg_packed_floats(h, r) / 4) * za.n;
+            PF_LAUNCH(st, "lstm_zg_pack", lstm_zg_pack_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), s, za);
+        }
+    }
     if (status) *status = st;
     return off;
 }
@@ -338,6 +630,40 @@ static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const StackPac
         }
         st = st_slice_sums(s, segs, "lstm_stack_T_sum");
         if (st != PF_OK) return st;
+    }
+    if (pk.fused_z) { // z and the gates in one launch, one workgroup per ZG_HU hidden units of a layer
+        if (need) *need = most;
+        if (dry) return st;
+        ZgArgs za = {};
+        za.B = B;
+        za.h = h;
+        za.r = r;
+        za.tiles = (h + ZG_HU - 1) / ZG_HU;
+        int wg = 0;
+        for (int l = 0; l < g.L; ++l) {
+            const int t = slot - l;
+            if (t < 0 || t >= g.T) continue;
+            ZgLayer &zl = za.l[za.n++];
+            zl.nseg = l > 0 ? 2 : 1;
+            zl.A[0] = p.Th_all[l] + (i64)t * B * gr;
+            zl.W[0] = pk.zg[l][0];
+            zl.A[1] = l > 0 ? p.Tx_all[l] + (i64)t * B * gr : nullptr;
+            zl.W[1] = l > 0 ? pk.zg[l][1] : nullptr;
+            zl.bias = (l > 0 && g.has_bias) ? p.bias[l] : nullptr; // the first layer's bias is inside zx0
+            zl.zadd = l == 0 ? zx0 + (i64)t * B * 4 * h : nullptr;
+            zl.c_prev = t ? p.c_all[l] + (i64)(t - 1) * Bh : p.c0[l];
+            zl.h_out = p.h_all[l] + (i64)t * Bh;
+            zl.c_out = p.c_all[l] + (i64)t * Bh;
+            zl.gates = p.gates_all[l] + (i64)t * B * 4 * h;
+            zl.wg0 = wg;
+            wg += za.tiles;
+        }
+        if (B <= 20) {
+            PF_LAUNCH(st, "lstm_stack_z_gates", lstm_zgates_kernel<5>, dim3((unsigned)wg), dim3(256), s, za);
+        } else {
+            PF_LAUNCH(st, "lstm_stack_z_gates", lstm_zgates_kernel<8>, dim3((unsigned)wg), dim3(256), s, za);
+        }
+        return st;
     }
     // z slices = Th Uh^T (and Tx Ux^T above the first layer), one region per product, a layer's regions adjacent
     SkBatch nk;
@@ -545,6 +871,7 @@ static int plan_stack(const StackGeom &g, StackPlan *out)
     upd(st_tall_part(Mt, g.gr, g.din));                    // dx = dTx Vx^T
     StackPtrs none = {};
     StackPacked nonep = {};
+    nonep.fused_z = zg_supported(g.G, g.r);
     StackBwdPtrs noneb = {};
     StackCarry carry = {};
     for (int slot = 0; slot < g.T + g.L - 1; ++slot) {

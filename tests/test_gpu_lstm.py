@@ -305,6 +305,7 @@ STACKS = [
     (4, 20, 70, 50, 13, 3),
     (3, 32, 37, 29, 7, 2),
     (3, 6, 130, 260, 129, 2),  # several column tiles and contraction slices, all with tails
+    (2, 4, 16, 24, 516, 2),    # a rank beyond what the fused pre-activation + gate kernel stages on chip
 ]
 
 
