@@ -82,3 +82,31 @@ def test_lstm_cell_graph_replay():
         return h, c, dx, dhp, dcp, gr["dVx"], gr["dUx"], gr["dVh"], gr["dUh"], gr["dbias"]
 
     _replay_matches_eager(make, run, ("h", "c", "dx", "dh_prev", "dc_prev", "dVx", "dUx", "dVh", "dUh", "dbias"))
+
+
+@pytest.mark.parametrize("groups", [1, 4])
+def test_lstm_stack_graph_replay(groups):
+    """Two stacked layers over a short sequence (groups = 1: the fused pre-activation + gate kernel and the packed
+    factors; groups = 4: the unfused launches), forward and backward in one graph."""
+    import paper_2103_03936_amd as pf
+    T, B, d, h, r, L = 5, 20, 72, 80, 20, 2
+
+    def make(seed):
+        s = workloads.Stream(workloads.SEED_BASE + 700 + seed, "f32")
+        out = {"x": to_gpu(s.normal((T, B, d))), "dh_top": to_gpu(s.normal((T, B, h)))}
+        for l in range(L):
+            a = workloads.lstm_cell_inputs(B, d if l == 0 else h, h, r, groups=groups, seed=10 * seed + l)
+            for k in ("h_prev", "c_prev", "Vx", "Ux", "Vh", "Uh", "bias"):
+                out[f"{k}{l}"] = to_gpu(a[k])
+        return out
+
+    def run(g):
+        col = lambda k: [g[f"{k}{l}"] for l in range(L)]
+        saved = pf.pf_lowrank_lstm_stack_fwd(g["x"], col("h_prev"), col("c_prev"), col("Vx"), col("Ux"), col("Vh"),
+                                             col("Uh"), col("bias"), groups)
+        dx, dh0, dc0, gr = pf.pf_lowrank_lstm_stack_bwd(g["x"], col("h_prev"), col("c_prev"), *saved, col("Vx"),
+                                                        col("Ux"), col("Vh"), col("Uh"), g["dh_top"], None, None, groups)
+        return (saved[0][L - 1], saved[1][0], dx, dh0[0], dc0[1], gr[0]["dVx"], gr[0]["dUh"], gr[1]["dUx"], gr[1]["dVh"],
+                gr[1]["dbias"])
+
+    _replay_matches_eager(make, run, ("h_top", "c_0", "dx", "dh0_0", "dc0_1", "dVx_0", "dUh_0", "dUx_1", "dVh_1", "dbias_1"))
