@@ -200,8 +200,9 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) tot[e][v] = 0.f;
     // The activation fragments of a stage are read from LDS one stage ahead of their use; super-steps past the
-    // wavefront's range read a valid address and multiply by zero.  A fresh accumulator per stage (32 contraction
-    // indices) is added to the running total.
+    // wavefront's range read a valid address and multiply by zero.  A wavefront adds up at most 256 contraction
+    // indices (half of r <= 512) in its accumulators, and the MFMAs follow each other without a pause: moving
+    // accumulators out to add them elsewhere would leave the matrix unit idle for as long as eight MFMAs.
     auto lds_read = [&](f32x4_t(&av)[ZG_CH], int c) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < ZG_CH; ++q) {
@@ -212,21 +213,13 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
         }
     };
     auto compute = [&](const Stage &st, const f32x4_t(&av)[ZG_CH], int c) __attribute__((always_inline)) {
-        if (S0 + c * ZG_CH >= S1) return;
-        f32x16_t cur[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) cur[e][v] = 0.f;
 #pragma unroll
         for (int q = 0; q < ZG_CH; ++q)
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
                 for (int e = 0; e < 2; ++e)
-                    cur[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][s4], st.wv[q][e][s4], cur[e], 0, 0, 0);
-#pragma unroll
-        for (int e = 0; e < 2; ++e) tot[e] += cur[e];
+                    tot[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][s4], st.wv[q][e][s4], tot[e], 0, 0, 0);
     };
     const int nch = S1 > S0 ? (S1 - S0 + ZG_CH - 1) / ZG_CH : 0;
     // activations -> LDS, 16 bytes per item (rows are only 4-byte aligned in memory): wavefront w takes rows
@@ -308,9 +301,24 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
     for (int c = 0; c < nch; c += ZG_NST) {
 #pragma unroll
         for (int d = 0; d < ZG_NST; ++d) {
-            lds_read(av[(d + 1) & 1], c + d + 1);
-            compute(st[d], av[d & 1], c + d);
-            load(st[d], c + d + ZG_NST, false);
+            if (c + d < nch) { // uniform; the body is one straight run of instructions
+                // next stage's fragments, this stage's 32 MFMAs, and the refill of this stage's registers (past
+                // the range: a repeat of the last valid address).  Program order would issue the reads and the
+                // refill after the last MFMA and leave the matrix unit idle meanwhile: the groups below ask the
+                // scheduler to deal them out between the MFMAs instead.
+                lds_read(av[(d + 1) & 1], c + d + 1);
+                Stage nx;
+                load(nx, c + d + ZG_NST, true);
+                compute(st[d], av[d & 1], c + d);
+                st[d] = nx;
+#define ZG_DEAL(ds)                                       \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);    \
+    __builtin_amdgcn_sched_group_barrier(0x100, ds, 0);   \
+    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);    \
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(0) ZG_DEAL(0) ZG_DEAL(0) ZG_DEAL(0)
+#undef ZG_DEAL
+            }
         }
     }
 
