@@ -578,7 +578,7 @@ static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float
         za.h = h;
         za.r = r;
         for (int l = 0; l < g.L; ++l)
-            for (int path = 0; path < (l ? 2 : 1); ++path) {
+            for (int path = 0; path < 2; ++path) { // both paths of every layer, the first one's input path too
                 float *dst = buf ? buf + off : nullptr;
                 off += zg_packed_floats(h, r);
                 if (out) out->zg[l][path] = dst;
@@ -652,13 +652,16 @@ static int stack_fwd_slot(const StackGeom &g, const StackPtrs &p, const StackPac
             const int t = slot - l;
             if (t < 0 || t >= g.T) continue;
             ZgLayer &zl = za.l[za.n++];
-            zl.nseg = l > 0 ? 2 : 1;
+            // Both paths for every layer: the first layer's Tx is known for all steps beforehand, but forming its
+            // share of z here costs nothing extra (its workgroups would otherwise finish before the others) and
+            // spares the product over all T B rows.
+            zl.nseg = 2;
             zl.A[0] = p.Th_all[l] + (i64)t * B * gr;
             zl.W[0] = pk.zg[l][0];
-            zl.A[1] = l > 0 ? p.Tx_all[l] + (i64)t * B * gr : nullptr;
-            zl.W[1] = l > 0 ? pk.zg[l][1] : nullptr;
-            zl.bias = (l > 0 && g.has_bias) ? p.bias[l] : nullptr; // the first layer's bias is inside zx0
-            zl.zadd = l == 0 ? zx0 + (i64)t * B * 4 * h : nullptr;
+            zl.A[1] = p.Tx_all[l] + (i64)t * B * gr;
+            zl.W[1] = pk.zg[l][1];
+            zl.bias = g.has_bias ? p.bias[l] : nullptr;
+            zl.zadd = nullptr;
             zl.c_prev = t ? p.c_all[l] + (i64)(t - 1) * Bh : p.c0[l];
             zl.h_out = p.h_all[l] + (i64)t * Bh;
             zl.c_out = p.c_all[l] + (i64)t * Bh;
@@ -982,7 +985,9 @@ int pf_lowrank_lstm_stack_fwd(const pf_lstm_stack_desc *d, const void *x, const 
     st = st_tall(s, "lstm_stack_Tx0=X*Vx", false, Mt, (const float *)x, g.din, p.Vx[0], gr, g.din, gr, p.Tx_all[0], gr,
                  nullptr, part);
     if (st != PF_OK) return st;
-    if (g.G == 1) {
+    if (pk.fused_z) {
+        // z of the first layer's input path is formed inside the fused kernel, step by step
+    } else if (g.G == 1) {
         st = st_tall(s, "lstm_stack_zx0=Tx*Uxt", true, Mt, p.Tx_all[0], gr, p.Ux[0], r, r, 4 * h, zx0, 4 * (i64)h,
                      p.bias[0], part);
     } else {
