@@ -370,6 +370,10 @@ class LstmWorkload:
                 "lstm_stack_dT": (2.0 * B * 4 * h * r * (cells + up), 4 * (4 * h * r + B * 4 * h + B * gr) * (cells + up),
                                   slots),
                 "lstm_stack_dh": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * gr + B * h) * (cells + up), slots),
+                # dh from both products and the gate derivatives in one launch (one factor pair per path)
+                "lstm_stack_dh_gates": (2.0 * B * gr * h * (cells + up),
+                                        4 * ((gr * h + B * gr) * (cells + up) + (B * 4 * h * 2 + 5 * B * h) * cells),
+                                        slots + 1),
                 "lstm_stack_grads": (2.0 * Mt * (8 * h * r + gr * (d + h)) * L,
                                      4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)) * L, 2 * L),
             }

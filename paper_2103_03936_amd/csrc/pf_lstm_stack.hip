@@ -108,63 +108,60 @@ constexpr int ZG_MAXP = ZG_MAXR8 + 4;    // LDS row pitch in floats: r8 + 4
 constexpr int ZG_CH = 4;                 // super-steps (of eight contraction indices) per prefetch stage
 constexpr int ZG_NST = 4;                // prefetch stages
 
-inline size_t zg_packed_floats(int h, int r) { return (size_t)((h + ZG_HU - 1) / ZG_HU) * (size_t)((r + 7) / 8) * 512; }
+// Packed order of the fused kernels: for a workgroup's column tile and the eight contraction indices 8 S .. 8 S + 7,
+// the 16 bytes of lane l for MFMA sub-tile e hold k = 8 S + 4 (l / 32) + 0..3 of one column, at float offset
+// (((tile * ceil(r / 8) + S) * E + e) * 64 + l) * 4.  Source matrices are [columns][r] row-major.
+//   mode 0 (E = 2, U[4h][r]): column l % 32 of sub-tile e is gate 2 e + (l % 32) / 16 of unit 16 tile + l % 16
+//   mode 1 (E = 1, V[h][r]):  column l % 32 is unit 32 tile + l % 32
+inline size_t zg_packed_floats(int h, int r, int mode)
+{
+    const int tiles = mode == 0 ? (h + ZG_HU - 1) / ZG_HU : (h + 31) / 32, E = mode == 0 ? 2 : 1;
+    return (size_t)tiles * (size_t)((r + 7) / 8) * 256 * E;
+}
 
 struct ZgPackArgs {
-    const float *src[2 * ST_MAX_LAYERS]; // U[4h][r]
+    const float *src[2 * ST_MAX_LAYERS];
     float *dst[2 * ST_MAX_LAYERS];
-    int n, h, r;
+    int n, h, r, mode;
 };
-// one thread per 16-byte item: (tile, S, e, lane) -> U[(gate h + unit) r + 8 S + 4 (lane / 32) + 0..3]
+// one thread per 16-byte item
 __global__ __launch_bounds__(256) void lstm_zg_pack_kernel(ZgPackArgs a)
 {
-    const int S_total = (a.r + 7) / 8, tiles = (a.h + ZG_HU - 1) / ZG_HU;
-    const i64 per = (i64)tiles * S_total * 128, g = (i64)blockIdx.x * 256 + threadIdx.x;
+    const int S_total = (a.r + 7) / 8, E = a.mode == 0 ? 2 : 1;
+    const int tiles = a.mode == 0 ? (a.h + ZG_HU - 1) / ZG_HU : (a.h + 31) / 32;
+    const i64 per = (i64)tiles * S_total * 64 * E, g = (i64)blockIdx.x * 256 + threadIdx.x;
     if (g >= per * a.n) return;
     const int mi = (int)(g / per);
     const i64 it = g % per;
-    const int lane = (int)(it & 63), e = (int)((it >> 6) & 1);
-    const int S = (int)((it >> 7) % S_total), tile = (int)((it >> 7) / S_total);
-    const int i = lane & 31, gate = 2 * e + (i >> 4), unit = tile * ZG_HU + (i & 15);
+    const int lane = (int)(it & 63), e = (int)((it >> 6) % E);
+    const int S = (int)((it / (64 * E)) % S_total), tile = (int)((it / (64 * E)) / S_total);
+    const int i = lane & 31;
+    const int unit = a.mode == 0 ? tile * ZG_HU + (i & 15) : tile * 32 + i;
+    const i64 row = a.mode == 0 ? (i64)(2 * e + (i >> 4)) * a.h + unit : unit;
     f32x4_t v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
         const int k = 8 * S + 4 * (lane >> 5) + s4;
-        if (k < a.r && unit < a.h) v[s4] = a.src[mi][((i64)gate * a.h + unit) * a.r + k];
+        if (k < a.r && unit < a.h) v[s4] = a.src[mi][row * a.r + k];
     }
     *(f32x4_t *)(a.dst[mi] + it * 4) = v;
 }
 
-struct ZgLayer {
-    const float *A[2];  // [B x r] activations of the hidden path and (above the first layer) the input path
-    const float *W[2];  // their factors, packed
-    const float *bias, *zadd, *c_prev; // bias, zadd nullable
-    float *h_out, *c_out, *gates;
-    int nseg, wg0;
-};
-struct ZgArgs {
-    ZgLayer l[ST_MAX_LAYERS];
-    int n, B, h, r, tiles;
-};
-
-// NRI: rows a wavefront stages, ceil(B / 4) rounded up to 5 or 8
-template <int NRI>
-__global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
+// The products of a fused kernel: tot[e] += A_seg[32 x r] * W_seg(tile) over this wavefront's share of the
+// contraction, for up to two (activations, factor) pairs.  NRI: rows a wavefront stages, ceil(B / 4) rounded up to
+// 5 or 8; E: MFMA sub-tiles (32 columns each) of the workgroup's tile.  With two pairs the wavefronts take
+// (pair, half of r), with one a quarter of r each, with none nothing.  Ends with the activations' LDS free again.
+template <int NRI, int E>
+__device__ __forceinline__ void fused_products(const float *A0, const float *A1, const float *W0, const float *W1,
+                                               int nseg, int tile, int B, int r, float *lds, f32x16_t (&tot)[E])
 {
-    __shared__ __attribute__((aligned(16))) float lds[2 * 32 * ZG_MAXP];
-    int li = 0;
-#pragma unroll
-    for (int x = 1; x < ST_MAX_LAYERS; ++x)
-        if (x < a.n && (int)blockIdx.x >= a.l[x].wg0) li = x;
-    const ZgLayer &L = a.l[li];
-    const int tile = blockIdx.x - L.wg0;
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, i = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // wavefront index, known to be uniform
-    const int B = a.B, h = a.h, r = a.r, r8 = (r + 7) & ~7, P = r8 + 4, S_total = r8 / 8;
+    const int r8 = (r + 7) & ~7, P = r8 + 4, S_total = r8 / 8;
 
-    // this wavefront's path and range of super-steps
+    // this wavefront's pair and range of super-steps
     int seg, S0, S1;
-    if (L.nseg == 2) {
+    if (nseg == 2) {
         const int per = (S_total + 1) / 2;
         seg = w >> 1;
         S0 = (w & 1) * per;
@@ -173,30 +170,24 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
         const int per = (S_total + 3) / 4;
         seg = 0;
         S0 = w * per;
-        S1 = min(S_total, S0 + per);
+        S1 = nseg == 0 ? S0 : min(S_total, S0 + per);
     }
-    // both paths' pointers are read once as scalars and chosen per lane (indexing the argument block with a
-    // per-lane index would turn every use into a dependent memory read)
-    const float *A0 = L.A[0], *A1 = L.nseg == 2 ? L.A[1] : L.A[0];
-    const float *W0 = L.W[0], *W1 = L.nseg == 2 ? L.W[1] : L.W[0];
-    const float *Wp = (seg ? W1 : W0) + (i64)tile * S_total * 512 + lane * 4; // + (S * 2 + e) * 256
-    const float *Al = lds + (seg * 32 + i) * P + 4 * half;             // + 8 S
+    const float *Wp = (seg ? W1 : W0) + (i64)tile * S_total * (256 * E) + lane * 4; // + (S * E + e) * 256
+    const float *Al = lds + (seg * 32 + i) * P + 4 * half;                          // + 8 S
 
     struct Stage {
-        f32x4_t wv[ZG_CH][2];
+        f32x4_t wv[ZG_CH][E];
     };
-    auto load = [&](Stage &st, int c, bool always) __attribute__((always_inline)) {
-        if (!always && S0 + c * ZG_CH >= S1) return;
+    auto load = [&](Stage &st, int c) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < ZG_CH; ++q) {
             const int S = min(S0 + c * ZG_CH + q, S_total - 1); // past the range: loaded, never used
 #pragma unroll
-            for (int e = 0; e < 2; ++e) st.wv[q][e] = *(const f32x4_t *)(Wp + ((i64)S * 2 + e) * 256);
+            for (int e = 0; e < E; ++e) st.wv[q][e] = *(const f32x4_t *)(Wp + ((i64)S * E + e) * 256);
         }
     };
-    f32x16_t tot[2];
 #pragma unroll
-    for (int e = 0; e < 2; ++e)
+    for (int e = 0; e < E; ++e)
 #pragma unroll
         for (int v = 0; v < 16; ++v) tot[e][v] = 0.f;
     // The activation fragments of a stage are read from LDS one stage ahead of their use; super-steps past the
@@ -212,13 +203,13 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
             for (int s4 = 0; s4 < 4; ++s4) av[q][s4] = S < S1 ? t[s4] : 0.f;
         }
     };
-    auto compute = [&](const Stage &st, const f32x4_t(&av)[ZG_CH], int c) __attribute__((always_inline)) {
+    auto compute = [&](const Stage &st, const f32x4_t(&av)[ZG_CH]) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < ZG_CH; ++q)
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
-                for (int e = 0; e < 2; ++e)
+                for (int e = 0; e < E; ++e)
                     tot[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][s4], st.wv[q][e][s4], tot[e], 0, 0, 0);
     };
     const int nch = S1 > S0 ? (S1 - S0 + ZG_CH - 1) / ZG_CH : 0;
@@ -255,23 +246,23 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
     };
     // Every wavefront has the compute unit's SIMD to itself and only its loads hide the memory latency, so all of
     // them are requested before the first wait: a ring of ZG_NST stages of factors (16 super-steps; the first fill
-    // is unconditional so that the loads in flight can be counted exactly), the activations (both paths when a
+    // is unconditional so that the loads in flight can be counted exactly), the activations (both pairs when a
     // wavefront stages at most five rows, i.e. B <= 20) and the item that straddles the end of a row.
     Stage st[ZG_NST];
     {
         constexpr bool BOTH = NRI <= 5;
         f32x4_t v[2 * NRI], v2[BOTH ? 2 * NRI : 1];
 #pragma unroll
-        for (int d = 0; d < ZG_NST; ++d) load(st[d], d, true);
+        for (int d = 0; d < ZG_NST; ++d) load(st[d], d);
         stage_load(v, A0);
-        if constexpr (BOTH) stage_load(v2, A1); // (with one path A1 == A0: loaded, not stored)
+        if constexpr (BOTH) stage_load(v2, A1); // (with fewer than two pairs A1 == A0: loaded, not stored)
         const int k4t = r & ~3; // the straddling item of a row, if r is not a multiple of four
-        const bool fix = tid < L.nseg * 32 && (tid & 31) < B && k4t < r;
-        const float *src = ((tid >> 5) && L.nseg == 2 ? A1 : A0) + (fix ? (i64)(tid & 31) * r + k4t : 0);
+        const bool fix = tid < nseg * 32 && (tid & 31) < B && k4t < r;
+        const float *src = ((tid >> 5) && nseg == 2 ? A1 : A0) + (fix ? (i64)(tid & 31) * r + k4t : 0);
         f32x4_t o = {src[0], 0.f, 0.f, 0.f};
         const float o1 = src[fix && k4t + 1 < r ? 1 : 0], o2 = src[fix && k4t + 2 < r ? 2 : 0];
         stage_store(v, 0);
-        if (L.nseg == 2) {
+        if (nseg == 2) {
             if constexpr (!BOTH) {
                 stage_load(v, A1);
                 stage_store(v, 1);
@@ -282,7 +273,7 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
         // rows this wavefront does not reach with NRI rows (none when NRI covers ceil(B / 4)) stay unwritten only
         // if they are past row 4 NRI + 3: write their zeros
         for (int row = 4 * NRI + w; row < 32; row += 4)
-            for (int sg = 0; sg < L.nseg; ++sg)
+            for (int sg = 0; sg < nseg; ++sg)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int k4 = 4 * (lane + 64 * j);
@@ -302,25 +293,80 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
 #pragma unroll
         for (int d = 0; d < ZG_NST; ++d) {
             if (c + d < nch) { // uniform; the body is one straight run of instructions
-                // next stage's fragments, this stage's 32 MFMAs, and the refill of this stage's registers (past
-                // the range: a repeat of the last valid address).  Program order would issue the reads and the
+                // next stage's fragments, this stage's MFMAs, and the refill of this stage's registers (past the
+                // range: a repeat of the last valid address).  Program order would issue the reads and the
                 // refill after the last MFMA and leave the matrix unit idle meanwhile: the groups below ask the
                 // scheduler to deal them out between the MFMAs instead.
                 lds_read(av[(d + 1) & 1], c + d + 1);
                 Stage nx;
-                load(nx, c + d + ZG_NST, true);
-                compute(st[d], av[d & 1], c + d);
+                load(nx, c + d + ZG_NST);
+                compute(st[d], av[d & 1]);
                 st[d] = nx;
 #define ZG_DEAL(ds)                                       \
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);    \
     __builtin_amdgcn_sched_group_barrier(0x100, ds, 0);   \
     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);    \
     __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-                ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(0) ZG_DEAL(0) ZG_DEAL(0) ZG_DEAL(0)
+                ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(1) ZG_DEAL(1)
+                if constexpr (E == 2) {
+                    ZG_DEAL(0) ZG_DEAL(0) ZG_DEAL(0) ZG_DEAL(0)
+                }
 #undef ZG_DEAL
             }
         }
     }
+}
+
+// The four wavefronts' tiles meet in LDS as red[4][E][16][64] (accumulator element v of lane l is row
+// 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32); the sum of a (row m, sub-tile e, column i) over the wavefronts, in
+// a fixed order, is fused_sum.
+template <int E>
+__device__ __forceinline__ void fused_exchange(float *lds, const f32x16_t (&tot)[E])
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    __syncthreads(); // the activations are no longer needed
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) lds[((w * E + e) * 16 + v) * 64 + lane] = tot[e][v];
+    __syncthreads();
+}
+template <int E>
+__device__ __forceinline__ float fused_sum(const float *red, int m, int e, int i)
+{
+    const int at = (e * 16 + (((m >> 3) << 2) | (m & 3))) * 64 + ((m >> 2) & 1) * 32 + i;
+    return (red[at] + red[E * 1024 + at]) + (red[2 * E * 1024 + at] + red[3 * E * 1024 + at]);
+}
+
+struct ZgLayer {
+    const float *A[2];  // [B x r] activations of the hidden path and of the input path
+    const float *W[2];  // their factors, packed (mode 0)
+    const float *bias, *zadd, *c_prev; // bias, zadd nullable
+    float *h_out, *c_out, *gates;
+    int nseg, wg0;
+};
+struct ZgArgs {
+    ZgLayer l[ST_MAX_LAYERS];
+    int n, B, h, r, tiles;
+};
+
+template <int NRI>
+__global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float lds[2 * 32 * ZG_MAXP];
+    int li = 0;
+#pragma unroll
+    for (int x = 1; x < ST_MAX_LAYERS; ++x)
+        if (x < a.n && (int)blockIdx.x >= a.l[x].wg0) li = x;
+    const ZgLayer &L = a.l[li];
+    const int tile = blockIdx.x - L.wg0, tid = threadIdx.x;
+    const int B = a.B, h = a.h;
+    // both paths' pointers are read once as scalars and chosen per lane (indexing the argument block with a
+    // per-lane index would turn every use into a dependent memory read)
+    const float *A0 = L.A[0], *A1 = L.nseg == 2 ? L.A[1] : L.A[0];
+    const float *W0 = L.W[0], *W1 = L.nseg == 2 ? L.W[1] : L.W[0];
+    f32x16_t tot[2];
+    fused_products<NRI, 2>(A0, A1, W0, W1, L.nseg, tile, B, a.r, lds, tot);
 
     // the operands of the gate arithmetic are fetched while the tiles are exchanged (at most two elements per thread)
     float pre_c[2], pre_b[2][4], pre_z[2][4];
@@ -336,29 +382,15 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
             pre_z[it][g] = L.zadd ? L.zadd[base + (i64)g * h] : 0.f;
         }
     }
-    // the four wavefronts' tiles meet in LDS (the activations are no longer needed)
-    __syncthreads();
-    float *red = lds; // [4 wavefronts][2 sub-tiles][16][64]
-#pragma unroll
-    for (int e = 0; e < 2; ++e)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) red[((w * 2 + e) * 16 + v) * 64 + lane] = tot[e][v];
-    __syncthreads();
-    // accumulator element v of lane l is row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
+    fused_exchange<2>(lds, tot);
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int el = tid + 256 * it, m = el / ZG_HU, u = el % ZG_HU, unit = tile * ZG_HU + u;
         if (el >= B * ZG_HU || unit >= h) continue;
-        const int v = ((m >> 3) << 2) | (m & 3), hf = (m >> 2) & 1;
         const i64 base = (i64)m * 4 * h + unit, idx = (i64)m * h + unit;
         float z[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int at = (((g >> 1)) * 16 + v) * 64 + hf * 32 + (g & 1) * 16 + u;
-            z[g] = (red[at] + red[2 * 16 * 64 + at]) + (red[4 * 16 * 64 + at] + red[6 * 16 * 64 + at]);
-            z[g] += pre_b[it][g];
-            z[g] += pre_z[it][g];
-        }
+        for (int g = 0; g < 4; ++g) z[g] = (fused_sum<2>(lds, m, g >> 1, (g & 1) * 16 + u) + pre_b[it][g]) + pre_z[it][g];
         const float ig = st_sigmoid(z[0]), fg = st_sigmoid(z[1]), gg = tanhf(z[2]), og = st_sigmoid(z[3]);
         const float c = fg * pre_c[it] + ig * gg;
         L.gates[base] = ig;
@@ -367,6 +399,78 @@ __global__ __launch_bounds__(256, 1) void lstm_zgates_kernel(ZgArgs a)
         L.gates[base + 3 * (i64)h] = og;
         L.c_out[idx] = c;
         L.h_out[idx] = og * tanhf(c);
+    }
+}
+
+// ---- backward: dh_t = (what arrives from above and from the final state) + dTh_{t+1} Vh^T + dTx^{above}_t Vx^{above T},
+// then the gate derivatives, in one kernel.  A workgroup owns 32 hidden units of a layer and the whole contraction of
+// both products; the rank-r gradients are tensors by then (their slice sums were formed in the slot before).  With
+// dh_out set the sum is written there instead (the gradient that reaches a layer's initial state).
+struct DgLayer {
+    const float *A[2];  // [B x r]: this layer's dTh at t + 1 and / or the dTx of the layer above at t (nseg of them)
+    const float *W[2];  // packed (mode 1) Vh of this layer / Vx of the layer above
+    const float *dh_a, *dh_b;                       // [B x h] addends, nullable
+    const float *gates, *c_prev, *c_out, *dc_next;  // dc_next nullable
+    float *dz, *dc_prev, *dh_out;
+    int nseg, wg0;
+};
+struct DgArgs {
+    DgLayer l[ST_MAX_LAYERS];
+    int n, B, h, r, tiles;
+};
+
+template <int NRI>
+__global__ __launch_bounds__(256, 1) void lstm_dhgates_kernel(DgArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float lds[2 * 32 * ZG_MAXP];
+    int li = 0;
+#pragma unroll
+    for (int x = 1; x < ST_MAX_LAYERS; ++x)
+        if (x < a.n && (int)blockIdx.x >= a.l[x].wg0) li = x;
+    const DgLayer &L = a.l[li];
+    const int tile = blockIdx.x - L.wg0, tid = threadIdx.x;
+    const int B = a.B, h = a.h;
+    const float *A0 = L.A[0], *A1 = L.nseg == 2 ? L.A[1] : L.A[0];
+    const float *W0 = L.W[0], *W1 = L.nseg == 2 ? L.W[1] : L.W[0];
+    f32x16_t tot[1];
+    fused_products<NRI, 1>(A0, A1, W0, W1, L.nseg, tile, B, a.r, lds, tot);
+
+    // operands of the gate derivatives, fetched while the tiles are exchanged (B * 32 <= 1024 elements: four per thread)
+    const bool gates_on = L.dh_out == nullptr;
+    float pa[4], pg[4][4], pcp[4], pco[4], pdc[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int el = tid + 256 * it, m = el >> 5, unit = tile * 32 + (el & 31);
+        const bool ok = el < B * 32 && unit < h;
+        const i64 base = ok ? (i64)m * 4 * h + unit : 0, idx = ok ? (i64)m * h + unit : 0;
+        pa[it] = (L.dh_a ? L.dh_a[idx] : 0.f) + (L.dh_b ? L.dh_b[idx] : 0.f);
+        if (gates_on) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) pg[it][g] = L.gates[base + (i64)g * h];
+            pcp[it] = L.c_prev[idx];
+            pco[it] = L.c_out[idx];
+            pdc[it] = L.dc_next ? L.dc_next[idx] : 0.f;
+        }
+    }
+    fused_exchange<1>(lds, tot);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int el = tid + 256 * it, m = el >> 5, u = el & 31, unit = tile * 32 + u;
+        if (el >= B * 32 || unit >= h) continue;
+        const i64 base = (i64)m * 4 * h + unit, idx = (i64)m * h + unit;
+        const float dhv = pa[it] + fused_sum<1>(lds, m, 0, u);
+        if (!gates_on) {
+            L.dh_out[idx] = dhv;
+            continue;
+        }
+        const float ig = pg[it][0], fg = pg[it][1], gg = pg[it][2], og = pg[it][3];
+        const float tc = tanhf(pco[it]);
+        const float dc = pdc[it] + dhv * og * (1.f - tc * tc);
+        L.dc_prev[idx] = dc * fg;
+        L.dz[base] = dc * gg * ig * (1.f - ig);
+        L.dz[base + h] = dc * pcp[it] * fg * (1.f - fg);
+        L.dz[base + 2 * (i64)h] = dc * ig * (1.f - gg * gg);
+        L.dz[base + 3 * (i64)h] = dhv * tc * og * (1.f - og);
     }
 }
 
@@ -531,15 +635,16 @@ struct StackPacked {
     const float *Vh[ST_MAX_LAYERS], *Vx[ST_MAX_LAYERS];       // Vx: layers above the first only
     const float *Uh[ST_MAX_LAYERS][4], *Ux[ST_MAX_LAYERS][4]; // per gate block when every gate has its own pair
     const float *zg[ST_MAX_LAYERS][2];                        // forward, fused z + gates: Uh and Ux in that kernel's order
-    bool fused_z;
+    const float *dg[ST_MAX_LAYERS][2];                        // backward, fused dh + gates: Vh and Vx in that kernel's order
+    bool fused_z;                                             // either direction: the fused kernel of that direction is used
 };
 // Places the copies from buf on (NULL: sizes only), launches the copy kernels unless dry; returns the floats taken.
 static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float *buf, StackPacked *out, bool dry,
                          hipStream_t s, int *status)
 {
     const int h = g.h, r = g.r, gr = g.gr, nq = g.G == 1 ? 1 : 4;
-    const bool fused_z = !bwd && zg_supported(g.G, r);
-    if (out) out->fused_z = fused_z;
+    const bool fused = zg_supported(g.G, r); // forward: U in the fused kernel's order; backward: V
+    if (out) out->fused_z = fused;
     size_t off = 0;
     int st = PF_OK;
     SkinnyPackArgs pa = {};
@@ -561,9 +666,11 @@ static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float
             if (path == 1 && l == 0) continue;
             const float *V = dry ? nullptr : (path ? p.Vx[l] : p.Vh[l]), *U = dry ? nullptr : (path ? p.Ux[l] : p.Uh[l]);
             // V is [h x gr]: forward contracts over its rows, backward over its columns
-            const float *pv = bwd ? add(V, 1, gr, gr, h) : add(V, gr, 1, h, gr);
-            if (out) (path ? out->Vx : out->Vh)[l] = pv;
-            for (int q = 0; q < nq && !fused_z; ++q) {
+            if (!(bwd && fused)) {
+                const float *pv = bwd ? add(V, 1, gr, gr, h) : add(V, gr, 1, h, gr);
+                if (out) (path ? out->Vx : out->Vh)[l] = pv;
+            }
+            for (int q = 0; q < nq && !(!bwd && fused); ++q) {
                 // U (or its gate block q) is [rows x r] with rows = 4h or h
                 const int rows = g.G == 1 ? 4 * h : h;
                 const float *Uq = U ? U + (i64)q * h * r : nullptr;
@@ -573,22 +680,26 @@ static size_t stack_pack(const StackGeom &g, const StackPtrs &p, bool bwd, float
         }
     }
     flush();
-    if (fused_z) {
+    if (fused) {
         ZgPackArgs za = {};
         za.h = h;
         za.r = r;
+        za.mode = bwd ? 1 : 0;
         for (int l = 0; l < g.L; ++l)
-            for (int path = 0; path < 2; ++path) { // both paths of every layer, the first one's input path too
+            for (int path = 0; path < 2; ++path) {
+                // forward: both paths of every layer (the first layer's input path too);
+                // backward: Vh of every layer, Vx of the layers above the first
+                if (bwd && path == 1 && l == 0) continue;
                 float *dst = buf ? buf + off : nullptr;
-                off += zg_packed_floats(h, r);
-                if (out) out->zg[l][path] = dst;
+                off += zg_packed_floats(h, r, za.mode);
+                if (out) (bwd ? out->dg : out->zg)[l][path] = dst;
                 if (!dry) {
-                    za.src[za.n] = path ? p.Ux[l] : p.Uh[l];
+                    za.src[za.n] = bwd ? (path ? p.Vx[l] : p.Vh[l]) : (path ? p.Ux[l] : p.Uh[l]);
                     za.dst[za.n++] = dst;
                 }
             }
         if (!dry && st == PF_OK && za.n > 0) {
-            const i64 items = (i64)(zg_packed_floats(h, r) / 4) * za.n;
+            const i64 items = (i64)(zg_packed_floats(h, r, za.mode) / 4) * za.n;
             PF_LAUNCH(st, "lstm_zg_pack", lstm_zg_pack_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), s, za);
         }
     }
@@ -758,7 +869,58 @@ static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackPac
         const int t = time_of(l);
         return t >= 0 && t < T;
     };
-    if (!dry) {
+    const i64 pcT = (i64)B * gr;
+    if (pk.fused_z && !dry) {
+        // dh (both products, whole contraction) and the gate derivatives in one launch, one workgroup per 32 hidden
+        // units of a layer; a layer whose step 0 was the slot before gets its dh_{-1} = dTh_0 Vh^T here
+        DgArgs da = {};
+        da.B = B;
+        da.h = h;
+        da.r = r;
+        da.tiles = (h + 31) / 32;
+        int wg = 0;
+        for (int l = 0; l < L; ++l) {
+            const int t = time_of(l);
+            if (t < -1 || t >= T) continue;
+            DgLayer &dl = da.l[da.n++];
+            if (t + 1 < T) { // this layer's own step t + 1
+                dl.A[dl.nseg] = b.dTh_all[l] + (i64)(t + 1) * pcT;
+                dl.W[dl.nseg++] = pk.dg[l][0];
+            }
+            if (t >= 0 && l + 1 < L) { // the layer above at the same step
+                dl.A[dl.nseg] = b.dTx_all[l + 1] + (i64)t * pcT;
+                dl.W[dl.nseg++] = pk.dg[l + 1][1];
+            }
+            if (dl.nseg == 0) { // nothing to multiply: valid operands of the right size, never used
+                dl.A[0] = p.Th_all[l] + (i64)t * pcT;
+                dl.W[0] = pk.dg[l][0];
+            }
+            if (t < 0) {
+                dl.dh_out = b.dh0[l];
+            } else {
+                dl.dh_a = l == L - 1 ? dh_top + (i64)t * Bh : nullptr; // the top layer's dL/dh_t comes from outside
+                dl.dh_b = t == T - 1 ? b.dhT[l] : nullptr;
+                dl.gates = p.gates_all[l] + (i64)t * pcz;
+                dl.c_prev = t ? p.c_all[l] + (i64)(t - 1) * Bh : p.c0[l];
+                dl.c_out = p.c_all[l] + (i64)t * Bh;
+                // dc_t lives in dc0 between the steps of a layer (each element is read, then rewritten, by its own thread)
+                dl.dc_next = t == T - 1 ? b.dcT[l] : b.dc0[l];
+                dl.dz = b.dz_all[l] + (i64)t * pcz;
+                dl.dc_prev = b.dc0[l];
+            }
+            dl.wg0 = wg;
+            wg += da.tiles;
+        }
+        if (da.n > 0) {
+            if (B <= 20) {
+                PF_LAUNCH(st, "lstm_stack_dh_gates", lstm_dhgates_kernel<5>, dim3((unsigned)wg), dim3(256), s, da);
+            } else {
+                PF_LAUNCH(st, "lstm_stack_dh_gates", lstm_dhgates_kernel<8>, dim3((unsigned)wg), dim3(256), s, da);
+            }
+            if (st != PF_OK) return st;
+        }
+    }
+    if (!pk.fused_z && !dry) {
         StackGatesBwd ga = {};
         ga.B = B;
         ga.h = h;
@@ -786,7 +948,6 @@ static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackPac
     // dTh = dz Uh, and above the first layer dTx = dz Ux (layer 0's input path is done for all steps at the end)
     SkBatch kn;
     int reg_h[ST_MAX_LAYERS], reg_x[ST_MAX_LAYERS];
-    const i64 pcT = (i64)B * gr;
     auto add_dT = [&](int region, const float *dz, const float *const *U) { // U: the packed gate blocks
         if (G == 1) {
             kn.add(skinny_prob(B, dz, 4 * (i64)h, U[0], r, 4 * h, r, gr, pcT), region);
@@ -825,6 +986,10 @@ static int stack_bwd_slot(const StackGeom &g, const StackPtrs &p, const StackPac
         }
         st = st_slice_sums(s, segs, "lstm_stack_dT_sum");
         if (st != PF_OK) return st;
+    }
+    if (pk.fused_z) { // the dh products are part of the next slot's fused launch
+        if (need2) *need2 = 0;
+        return st;
     }
     // slices of dh_{t-1} = dTh Vh^T for the layer itself and of dx_t = dTx Vx^T for the layer below
     SkBatch nk;
@@ -1080,7 +1245,7 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x, const 
     stack_pack(g, p, true, packed, &pk, false, s, &st);
     if (st != PF_OK) return st;
     StackCarry carry = {};
-    for (int u = 0; u < T + L - 1 && st == PF_OK; ++u)
+    for (int u = 0; u < T + L - 1 + (pk.fused_z ? 1 : 0) && st == PF_OK; ++u) // fused: one more slot for the first layer's dh0
         st = stack_bwd_slot(g, p, pk, b, (const float *)dh_top, u, part, pl.n_part, part2, pl.n_part2, carry, false, s,
                             nullptr, nullptr);
     if (st != PF_OK) return st;
