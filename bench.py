@@ -356,39 +356,30 @@ class LstmWorkload:
         c = self.cfg
         B, d, h, r, g = c["B"], c["d"], c["h"], c["r"], self.groups
         gr, cells = g * r, c["T"] * c["layers"]
-        if self.stack:  # one launch per diagonal and product kind, all active layers inside
+        if self.stack or self.seq:
+            # one call per direction for the whole stack, or (sequence entry points) per layer: a slot holds every
+            # layer of the call that has a step on its diagonal
             Mt, L = c["T"] * B, c["layers"]
-            slots, up = c["T"] + L - 1, (L - 1) * c["T"]  # launches; layer-to-layer products ride along
+            calls, lay = (1, L) if self.stack else (L, 1)
+            slots = calls * (c["T"] + lay - 1)
+            up = (lay - 1) * c["T"] * calls  # layer-to-layer products that ride in the slots
+            prods = cells + up
             ws = {
-                "lstm_stack_T": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * h + B * gr) * (cells + up), slots),
-                "lstm_stack_z": (2.0 * B * 4 * h * r * (cells + up),
-                                 4 * (4 * h * r + B * gr + 2 * B * 4 * h) * (cells + up), slots),
+                "lstm_stack_T": (2.0 * B * gr * h * prods, 4 * (gr * h + B * h + B * gr) * prods, slots),
+                "lstm_stack_z": (2.0 * B * 4 * h * r * prods, 4 * (4 * h * r + B * gr + 2 * B * 4 * h) * prods, slots),
                 # pre-activations of both paths and the gates in one launch (one factor pair per path)
-                "lstm_stack_z_gates": (2.0 * B * 4 * h * r * (cells + up),
-                                       4 * ((4 * h * r + B * gr) * (cells + up) + (B * 4 * h * 2 + 3 * B * h) * cells),
-                                       slots),
-                "lstm_stack_dT": (2.0 * B * 4 * h * r * (cells + up), 4 * (4 * h * r + B * 4 * h + B * gr) * (cells + up),
-                                  slots),
-                "lstm_stack_dh": (2.0 * B * gr * h * (cells + up), 4 * (gr * h + B * gr + B * h) * (cells + up), slots),
+                "lstm_stack_z_gates": (2.0 * B * 4 * h * r * 2 * cells,
+                                       4 * ((4 * h * r + B * gr) * 2 * cells + (B * 4 * h + 3 * B * h) * cells), slots),
+                "lstm_stack_dT": (2.0 * B * 4 * h * r * prods, 4 * (4 * h * r + B * 4 * h + B * gr) * prods, slots),
+                "lstm_stack_dh": (2.0 * B * gr * h * prods, 4 * (gr * h + B * gr + B * h) * prods, slots),
                 # dh from both products and the gate derivatives in one launch (one factor pair per path)
-                "lstm_stack_dh_gates": (2.0 * B * gr * h * (cells + up),
-                                        4 * ((gr * h + B * gr) * (cells + up) + (B * 4 * h * 2 + 5 * B * h) * cells),
-                                        slots + 1),
+                "lstm_stack_dh_gates": (2.0 * B * gr * h * prods,
+                                        4 * ((gr * h + B * gr) * prods + (B * 4 * h * 2 + 5 * B * h) * cells),
+                                        slots + calls),
                 "lstm_stack_grads": (2.0 * Mt * (8 * h * r + gr * (d + h)) * L,
                                      4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)) * L, 2 * L),
             }
             return {k: [f, b, n] for k, (f, b, n) in ws.items()}
-        if self.seq:  # per-step hidden-path launches, and the batched gradient launch (one per layer)
-            Mt, L = c["T"] * B, c["layers"]
-            ws = {
-                "lstm_seq_Th=h*Vh": (2.0 * B * gr * h, 4 * (gr * h + B * h + B * gr), cells),
-                "lstm_seq_zh=Th*Uht": (2.0 * B * 4 * h * r, 4 * (4 * h * r + B * gr + 2 * B * 4 * h), cells),
-                "lstm_seq_dTh=dz*Uh": (2.0 * B * 4 * h * r, 4 * (4 * h * r + B * 4 * h + B * gr), cells),
-                "lstm_seq_dh=dTh*Vht": (2.0 * B * gr * h, 4 * (gr * h + B * gr + B * h), cells),
-                "lstm_seq_grads": (2.0 * Mt * (8 * h * r + gr * (d + h)),
-                                   4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)), 2 * L),
-            }
-            return {k: [f * n, b * n, n] for k, (f, b, n) in ws.items()}
         w = {
             "lstm_T=[x*Vx|h*Vh]": (2.0 * B * gr * (d + h), 4 * (gr * (d + h) + B * (d + h) + 2 * B * gr)),
             "lstm_z=[Tx|Th]*[Ux|Uh]t": (2.0 * B * 4 * h * 2 * r, 4 * (8 * h * r + 2 * B * gr + B * 4 * h)),

@@ -459,280 +459,6 @@ static int lstm_bwd_skinny(const pf_lstm_desc *d, const float *x, const float *h
 }
 
 
-// ------------------------------------------------------------------ whole sequences (B <= 32)
-// dh_t = dh_a (+ dh_b) (+ slices of dTh_{t+1} Vh^T), then as lstm_pointwise_bwd_kernel
-__global__ __launch_bounds__(256) void lstm_seq_pointwise_bwd_kernel(const float *gates, const float *c_prev,
-                                                                      const float *c_out, const float *dh_a,
-                                                                      const float *dh_b, const float *P, int nslices,
-                                                                      i64 pcount, const float *dc_next, float *dz,
-                                                                      float *dc_prev, int B, int h)
-{
-    const i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (i64)B * h) return;
-    const int b = (int)(idx / h), j = (int)(idx % h);
-    const i64 base = (i64)b * 4 * h + j;
-    float dhv = dh_a[idx] + (dh_b ? dh_b[idx] : 0.f);
-    dhv += slices_at(P, nslices, pcount, idx);
-    const float ig = gates[base], fg = gates[base + h], gg = gates[base + 2 * (i64)h], og = gates[base + 3 * (i64)h];
-    const float tc = tanhf(c_out[idx]);
-    const float dc = (dc_next ? dc_next[idx] : 0.f) + dhv * og * (1.f - tc * tc);
-    dc_prev[idx] = dc * fg;
-    dz[base] = dc * gg * ig * (1.f - ig);
-    dz[base + h] = dc * c_prev[idx] * fg * (1.f - fg);
-    dz[base + 2 * (i64)h] = dc * ig * (1.f - gg * gg);
-    dz[base + 3 * (i64)h] = dhv * tc * og * (1.f - og);
-}
-
-static int check_lstm_seq_desc(const pf_lstm_seq_desc *d, pf_lstm_desc *cell)
-{
-    if (!d) return PF_ERR_NULL;
-    if (d->T < 0) return PF_ERR_SHAPE;
-    pf_lstm_desc c = {d->B, d->d_in, d->h, d->r, d->groups, d->dtype, d->has_bias};
-    const int st = check_lstm_desc(&c);
-    if (st != PF_OK) return st;
-    const i64 lim = 0x7fffffffLL;
-    if (d->T > lim || d->T * d->B > lim || d->T * d->B * d->h * 4 > (lim << 3) || d->T * d->B * d->d_in > (lim << 3))
-        return PF_ERR_SHAPE;
-    if (!lstm_skinny_ok(&c) && d->T > 0 && d->B > 0) return PF_ERR_UNSUPPORTED; // built for small batches
-    if (cell) *cell = c;
-    return PF_OK;
-}
-
-constexpr int SEQ_ROWS = SK_MAX_ROWS * SK_MAX_PROB; // rows one launch of a tall product takes
-
-// C[Mt x N] = A[Mt x K] W (+ bias) for Mt = T B rows, SEQ_ROWS rows per launch pair (product + slice sums)
-static int tall_product(hipStream_t s, const char *name, bool nk, i64 Mt, const float *A, i64 lda, const float *W,
-                        i64 ldw, int K, int N, float *out, i64 ldo, const float *bias, float *part)
-{
-    int st = PF_OK;
-    for (i64 m0 = 0; m0 < Mt && st == PF_OK; m0 += SEQ_ROWS) {
-        const int Mg = (int)(Mt - m0 < SEQ_ROWS ? Mt - m0 : SEQ_ROWS);
-        SkinnyArgs a;
-        skinny_rows(Mg, A + m0 * lda, lda, W, ldw, K, N, part, a);
-        st = launch_skinny_gemm(s, name, a, nk);
-        if (st != PF_OK) break;
-        SliceSumArgs ss = {};
-        ss.s[ss.nseg++] = skinny_rows_seg(a, Mg, out + m0 * ldo, ldo, bias);
-        st = launch_slice_sum(s, ss);
-    }
-    return st;
-}
-// floats of slice sums tall_product needs: the larger of a full launch and the last, shorter one
-static size_t tall_part(i64 Mt, int K, int N)
-{
-    SkinnyArgs a;
-    size_t m = 0;
-    const int full = (int)(Mt < SEQ_ROWS ? Mt : SEQ_ROWS), last = (int)(Mt % SEQ_ROWS);
-    if (full > 0) m = skinny_rows(full, nullptr, K, nullptr, N, K, N, nullptr, a);
-    if (last > 0) {
-        const size_t v = skinny_rows(last, nullptr, K, nullptr, N, K, N, nullptr, a);
-        if (v > m) m = v;
-    }
-    return m;
-}
-
-
-// The hidden-path products of one time step on their own (the input path is hoisted out of the recurrence).
-static size_t build_zh(const pf_lstm_desc *d, const float *Th, const float *Uh, float *part, SkinnyArgs &a)
-{
-    const int B = (int)d->B, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
-    a = SkinnyArgs{};
-    const i64 pc = (i64)B * 4 * h;
-    if (G == 1) {
-        a.p[a.nprob++] = skinny_prob(B, Th, gr, Uh, r, r, 4 * h, 4 * h, pc);
-    } else {
-        for (int g = 0; g < 4; ++g)
-            a.p[a.nprob++] = skinny_prob(B, Th ? Th + (i64)g * r : nullptr, gr, Uh ? Uh + (i64)g * h * r : nullptr, r, r,
-                                         h, 4 * h, pc);
-    }
-    skinny_plan(a);
-    for (int q = 0; q < a.nprob; ++q) a.p[q].P = part ? part + (G == 4 ? (i64)q * h : 0) : nullptr;
-    return (size_t)(a.p[0].ksplit * pc);
-}
-static size_t build_dTh(const pf_lstm_desc *d, const float *dz, const float *Uh, float *part, SkinnyArgs &a)
-{
-    const int B = (int)d->B, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
-    a = SkinnyArgs{};
-    const i64 pc = (i64)B * gr;
-    if (G == 1) {
-        a.p[a.nprob++] = skinny_prob(B, dz, 4 * (i64)h, Uh, r, 4 * h, r, gr, pc);
-    } else {
-        for (int g = 0; g < 4; ++g)
-            a.p[a.nprob++] = skinny_prob(B, dz ? dz + (i64)g * h : nullptr, 4 * (i64)h, Uh ? Uh + (i64)g * h * r : nullptr,
-                                         r, h, r, gr, pc);
-    }
-    skinny_plan(a);
-    for (int q = 0; q < a.nprob; ++q) a.p[q].P = part ? part + (G == 4 ? (i64)q * r : 0) : nullptr;
-    return (size_t)(a.p[0].ksplit * pc);
-}
-
-struct SeqPlan {
-    size_t n_zx, n_part, n_part_dh, n_dT, fwd_bytes, bwd_bytes;
-};
-static SeqPlan plan_lstm_seq(const pf_lstm_seq_desc *d, const pf_lstm_desc *c)
-{
-    SeqPlan p = {};
-    const i64 Mt = d->T * d->B;
-    const int h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r, din = (int)d->d_in;
-    if (Mt == 0) return p;
-    p.n_zx = (size_t)(Mt * 4 * h);
-    p.n_dT = (size_t)(Mt * gr);
-    SkinnyArgs a;
-    size_t m = skinny_rows((int)d->B, nullptr, h, nullptr, gr, h, gr, nullptr, a); // Th = h Vh
-    auto upd = [&](size_t v) {
-        if (v > m) m = v;
-    };
-    upd(build_zh(c, nullptr, nullptr, nullptr, a));
-    upd(build_dTh(c, nullptr, nullptr, nullptr, a));
-    upd(tall_part(Mt, din, gr));                    // Tx_all = X Vx
-    upd(tall_part(Mt, r, G == 1 ? 4 * h : h));      // zx_all = Tx_all Ux^T
-    upd(tall_part(Mt, G == 1 ? 4 * h : h, r));      // dTx_all = dz_all Ux
-    upd(tall_part(Mt, gr, din));                    // dx_all = dTx_all Vx^T
-    p.n_part = m;
-    p.n_part_dh = build_dxh(c, false, nullptr, nullptr, nullptr, nullptr, nullptr, a);
-    p.fwd_bytes = align_up(p.n_zx * sizeof(float)) + align_up(p.n_part * sizeof(float));
-    p.bwd_bytes = align_up(p.n_zx * sizeof(float)) + 2 * align_up(p.n_dT * sizeof(float)) +
-                  align_up(p.n_part * sizeof(float)) + align_up(p.n_part_dh * sizeof(float));
-    return p;
-}
-
-static int lstm_seq_fwd_impl(const pf_lstm_seq_desc *d, const pf_lstm_desc *c, const float *x, const float *h0,
-                             const float *c0, const float *Vx, const float *Ux, const float *Vh, const float *Uh,
-                             const float *bias, float *h_all, float *c_all, float *gates_all, float *Tx_all,
-                             float *Th_all, Workspace &ws, hipStream_t s)
-{
-    const int T = (int)d->T, B = (int)d->B, din = (int)d->d_in, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
-    const i64 Mt = (i64)T * B;
-    const SeqPlan p = plan_lstm_seq(d, c);
-    float *zx = ws.take<float>(p.n_zx);
-    float *part = ws.take<float>(p.n_part);
-    // the input path of every time step at once (it does not depend on the recurrence)
-    int st = tall_product(s, "lstm_seq_Tx=X*Vx", false, Mt, x, din, Vx, gr, din, gr, Tx_all, gr, nullptr, part);
-    if (st != PF_OK) return st;
-    if (G == 1) {
-        st = tall_product(s, "lstm_seq_zx=Tx*Uxt", true, Mt, Tx_all, gr, Ux, r, r, 4 * h, zx, 4 * (i64)h,
-                          d->has_bias ? bias : nullptr, part);
-    } else {
-        for (int g = 0; g < 4 && st == PF_OK; ++g)
-            st = tall_product(s, "lstm_seq_zx=Tx*Uxt", true, Mt, Tx_all + (i64)g * r, gr, Ux + (i64)g * h * r, r, r, h,
-                              zx + (i64)g * h, 4 * (i64)h, d->has_bias ? bias + (i64)g * h : nullptr, part);
-    }
-    if (st != PF_OK) return st;
-    // the recurrence: per step Th = h_{t-1} Vh, z = zx_t + Th Uh^T, gates
-    const dim3 grid((unsigned)(((i64)B * h + 255) / 256));
-    for (int t = 0; t < T; ++t) {
-        const float *hp = t ? h_all + (i64)(t - 1) * B * h : h0, *cp = t ? c_all + (i64)(t - 1) * B * h : c0;
-        float *Th = Th_all + (i64)t * B * gr;
-        SkinnyArgs a;
-        skinny_rows(B, hp, h, Vh, gr, h, gr, part, a);
-        st = launch_skinny_gemm(s, "lstm_seq_Th=h*Vh", a, false);
-        if (st != PF_OK) return st;
-        SliceSumArgs ss = {};
-        ss.s[ss.nseg++] = skinny_rows_seg(a, B, Th, gr, nullptr);
-        st = launch_slice_sum(s, ss);
-        if (st != PF_OK) return st;
-        SkinnyArgs ah;
-        build_zh(c, Th, Uh, part, ah);
-        st = launch_skinny_gemm(s, "lstm_seq_zh=Th*Uht", ah, true);
-        if (st != PF_OK) return st;
-        PF_LAUNCH(st, "lstm_pointwise_fwd", lstm_slices_pointwise_fwd_kernel, grid, dim3(256), s, part, ah.p[0].ksplit,
-                  (i64)B * 4 * h, (const float *)nullptr, zx + (i64)t * B * 4 * h, cp, h_all + (i64)t * B * h,
-                  c_all + (i64)t * B * h, gates_all + (i64)t * B * 4 * h, B, h);
-        if (st != PF_OK) return st;
-    }
-    return st;
-}
-
-static int lstm_seq_bwd_impl(const pf_lstm_seq_desc *d, const pf_lstm_desc *c, const float *x, const float *h0,
-                             const float *c0, const float *h_all, const float *c_all, const float *gates_all,
-                             const float *Tx_all, const float *Th_all, const float *Vx, const float *Ux,
-                             const float *Vh, const float *Uh, const float *dh_all, const float *dhT, const float *dcT,
-                             float *dx_all, float *dh0, float *dc0, float *dVx, float *dUx, float *dVh, float *dUh,
-                             float *dbias, int accumulate, Workspace &ws, hipStream_t s)
-{
-    const int T = (int)d->T, B = (int)d->B, din = (int)d->d_in, h = (int)d->h, r = (int)d->r, G = d->groups, gr = G * r;
-    const i64 Mt = (i64)T * B;
-    const SeqPlan p = plan_lstm_seq(d, c);
-    float *dz_all = ws.take<float>(p.n_zx);
-    float *dTh_all = ws.take<float>(p.n_dT);
-    float *dTx_all = ws.take<float>(p.n_dT);
-    float *part = ws.take<float>(p.n_part);
-    float *part_dh = ws.take<float>(p.n_part_dh);
-    int st = PF_OK;
-    const dim3 grid((unsigned)(((i64)B * h + 255) / 256));
-    int dh_slices = 0; // slices of dTh_{t+1} Vh^T waiting in part_dh
-    i64 dh_pcount = (i64)B * h;
-    for (int t = T - 1; t >= 0; --t) {
-        const float *cp = t ? c_all + (i64)(t - 1) * B * h : c0;
-        float *dz = dz_all + (i64)t * B * 4 * h, *dTh = dTh_all + (i64)t * B * gr;
-        // dc_t lives in dc0 between steps (each element is read, then rewritten, by its own thread)
-        PF_LAUNCH(st, "lstm_pointwise_bwd", lstm_seq_pointwise_bwd_kernel, grid, dim3(256), s,
-                  gates_all + (i64)t * B * 4 * h, cp, c_all + (i64)t * B * h, dh_all + (i64)t * B * h,
-                  t == T - 1 ? dhT : (const float *)nullptr, part_dh, dh_slices, dh_pcount,
-                  t == T - 1 ? dcT : (const float *)dc0, dz, dc0, B, h);
-        if (st != PF_OK) return st;
-        SkinnyArgs a, ah;
-        build_dTh(c, dz, Uh, part, ah);
-        st = launch_skinny_gemm(s, "lstm_seq_dTh=dz*Uh", ah, false);
-        if (st != PF_OK) return st;
-        SliceSumArgs ss = {};
-        ss.s[ss.nseg++] = slice_seg(ah.p[0], dTh, gr, gr);
-        st = launch_slice_sum(s, ss);
-        if (st != PF_OK) return st;
-        // slices of dh_{t-1} = dTh Vh^T, added up by the next step's gate kernel
-        build_dxh(c, false, nullptr, dTh, nullptr, Vh, part_dh, a);
-        st = launch_skinny_gemm(s, "lstm_seq_dh=dTh*Vht", a, true);
-        if (st != PF_OK) return st;
-        dh_slices = a.p[0].ksplit;
-        dh_pcount = a.p[0].pcount;
-        if (t == 0) {
-            ss = SliceSumArgs{};
-            ss.s[ss.nseg++] = slice_seg(a.p[0], dh0, h, h);
-            st = launch_slice_sum(s, ss);
-            if (st != PF_OK) return st;
-        }
-    }
-    // the input path and all parameter gradients, once over all T B rows
-    if (G == 1) {
-        st = tall_product(s, "lstm_seq_dTx=dz*Ux", false, Mt, dz_all, 4 * (i64)h, Ux, r, 4 * h, r, dTx_all, gr, nullptr,
-                          part);
-    } else {
-        for (int g = 0; g < 4 && st == PF_OK; ++g)
-            st = tall_product(s, "lstm_seq_dTx=dz*Ux", false, Mt, dz_all + (i64)g * h, 4 * (i64)h, Ux + (i64)g * h * r, r,
-                              h, r, dTx_all + (i64)g * r, gr, nullptr, part);
-    }
-    if (st != PF_OK) return st;
-    if (dx_all) {
-        st = tall_product(s, "lstm_seq_dx=dTx*Vxt", true, Mt, dTx_all, gr, Vx, gr, gr, din, dx_all, din, nullptr, part);
-        if (st != PF_OK) return st;
-    }
-    RankArgs ra = {};
-    ra.M = (int)Mt;
-    ra.accumulate = accumulate;
-    for (int path = 0; path < 2; ++path) {
-        const float *Tm = path ? Th_all : Tx_all;
-        float *dU = path ? dUh : dUx;
-        if (G == 1) {
-            rank_add(ra, dz_all, 4 * (i64)h, Tm, gr, dU, r, 4 * h, r);
-        } else {
-            for (int g = 0; g < 4; ++g)
-                rank_add(ra, dz_all + (i64)g * h, 4 * (i64)h, Tm + (i64)g * r, gr, dU + (i64)g * h * r, r, h, r);
-        }
-    }
-    rank_add(ra, x, din, dTx_all, gr, dVx, gr, din, gr);
-    // dVh = sum_t h_{t-1}^T dTh_t: the rows t >= 1 here, the h0 row block in a second launch below
-    if (T > 1) rank_add(ra, h_all, h, dTh_all + (i64)B * gr, gr, dVh, gr, h, gr, (int)(Mt - B));
-    if (dbias) rank_add(ra, dz_all, 4 * (i64)h, nullptr, 0, dbias, 1, 4 * h, 1);
-    SliceSumArgs none = {};
-    st = launch_rank_update(s, "lstm_seq_grads", ra, none);
-    if (st != PF_OK) return st;
-    RankArgs rb = {};
-    rb.M = B;
-    rb.accumulate = (T > 1) ? 1 : accumulate;
-    rank_add(rb, h0, h, dTh_all, gr, dVh, gr, h, gr);
-    return launch_rank_update(s, "lstm_seq_grads", rb, none);
-}
-
 } // namespace pf
 
 using namespace pf;
@@ -811,82 +537,6 @@ int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x, const void *h
                             (const float *)dh, (const float *)dc_next, (float *)dx, (float *)dh_prev, (float *)dc_prev,
                             (float *)dVx, (float *)dUx, (float *)dVh, (float *)dUh, (float *)dbias, accumulate, ws,
                             (hipStream_t)stream);
-}
-
-size_t pf_lowrank_lstm_seq_fwd_workspace_bytes(const pf_lstm_seq_desc *d)
-{
-    pf_lstm_desc c;
-    if (check_lstm_seq_desc(d, &c) != PF_OK) return 0;
-    return plan_lstm_seq(d, &c).fwd_bytes;
-}
-
-size_t pf_lowrank_lstm_seq_bwd_workspace_bytes(const pf_lstm_seq_desc *d)
-{
-    pf_lstm_desc c;
-    if (check_lstm_seq_desc(d, &c) != PF_OK) return 0;
-    return plan_lstm_seq(d, &c).bwd_bytes;
-}
-
-int pf_lowrank_lstm_seq_fwd(const pf_lstm_seq_desc *d, const void *x, const void *h0, const void *c0, const void *Vx,
-                            const void *Ux, const void *Vh, const void *Uh, const void *bias, void *h_all, void *c_all,
-                            void *gates_all, void *Tx_all, void *Th_all, void *workspace, size_t workspace_bytes,
-                            void *stream)
-{
-    pf_lstm_desc c;
-    int st = check_lstm_seq_desc(d, &c);
-    if (st != PF_OK) return st;
-    if (!Vx || !Ux || !Vh || !Uh || (d->has_bias && !bias)) return PF_ERR_NULL;
-    if (any_misaligned({x, h0, c0, Vx, Ux, Vh, Uh, bias, h_all, c_all, gates_all, Tx_all, Th_all}, 16))
-        return PF_ERR_UNSUPPORTED;
-    if (d->T == 0 || d->B == 0) return PF_OK;
-    if (!x || !h0 || !c0 || !h_all || !c_all || !gates_all || !Tx_all || !Th_all) return PF_ERR_NULL;
-    const size_t need = plan_lstm_seq(d, &c).fwd_bytes;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
-    Workspace ws(workspace, workspace_bytes);
-    return lstm_seq_fwd_impl(d, &c, (const float *)x, (const float *)h0, (const float *)c0, (const float *)Vx,
-                             (const float *)Ux, (const float *)Vh, (const float *)Uh, (const float *)bias,
-                             (float *)h_all, (float *)c_all, (float *)gates_all, (float *)Tx_all, (float *)Th_all, ws,
-                             (hipStream_t)stream);
-}
-
-int pf_lowrank_lstm_seq_bwd(const pf_lstm_seq_desc *d, const void *x, const void *h0, const void *c0, const void *h_all,
-                            const void *c_all, const void *gates_all, const void *Tx_all, const void *Th_all,
-                            const void *Vx, const void *Ux, const void *Vh, const void *Uh, const void *dh_all,
-                            const void *dhT, const void *dcT, void *dx_all, void *dh0, void *dc0, void *dVx, void *dUx,
-                            void *dVh, void *dUh, void *dbias, int accumulate, void *workspace, size_t workspace_bytes,
-                            void *stream)
-{
-    pf_lstm_desc c;
-    int st = check_lstm_seq_desc(d, &c);
-    if (st != PF_OK) return st;
-    if (!Vx || !Ux || !Vh || !Uh || !dVx || !dUx || !dVh || !dUh) return PF_ERR_NULL;
-    if (any_misaligned({x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all, Vx, Ux, Vh, Uh, dh_all, dhT, dcT, dx_all,
-                        dh0, dc0}, 16) ||
-        any_misaligned({dVx, dUx, dVh, dUh, dbias}, 4))
-        return PF_ERR_UNSUPPORTED;
-    if (d->T == 0 || d->B == 0) { // no rows: the gradients this call owns are zero
-        if (!accumulate) {
-            hipStream_t s = (hipStream_t)stream;
-            const i64 gr = (i64)d->groups * d->r;
-            st = launch_zero_f32(s, (float *)dVx, d->d_in * gr);
-            if (st == PF_OK) st = launch_zero_f32(s, (float *)dVh, d->h * gr);
-            if (st == PF_OK) st = launch_zero_f32(s, (float *)dUx, 4 * d->h * d->r);
-            if (st == PF_OK) st = launch_zero_f32(s, (float *)dUh, 4 * d->h * d->r);
-            if (st == PF_OK) st = launch_zero_f32(s, (float *)dbias, 4 * d->h);
-        }
-        return st;
-    }
-    if (!x || !h0 || !c0 || !h_all || !c_all || !gates_all || !Tx_all || !Th_all || !dh_all || !dh0 || !dc0)
-        return PF_ERR_NULL;
-    const size_t need = plan_lstm_seq(d, &c).bwd_bytes;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
-    Workspace ws(workspace, workspace_bytes);
-    return lstm_seq_bwd_impl(d, &c, (const float *)x, (const float *)h0, (const float *)c0, (const float *)h_all,
-                             (const float *)c_all, (const float *)gates_all, (const float *)Tx_all,
-                             (const float *)Th_all, (const float *)Vx, (const float *)Ux, (const float *)Vh,
-                             (const float *)Uh, (const float *)dh_all, (const float *)dhT, (const float *)dcT,
-                             (float *)dx_all, (float *)dh0, (float *)dc0, (float *)dVx, (float *)dUx, (float *)dVh,
-                             (float *)dUh, (float *)dbias, accumulate, ws, (hipStream_t)stream);
 }
 
 } // extern "C"

@@ -1298,4 +1298,61 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x, const 
     return st;
 }
 
+// ---- one layer over a sequence: a stack of one layer ----
+static pf_lstm_stack_desc seq_as_stack(const pf_lstm_seq_desc *d)
+{
+    pf_lstm_stack_desc sd = {};
+    if (d) {
+        sd.T = d->T;
+        sd.B = d->B;
+        sd.d_in = d->d_in;
+        sd.h = d->h;
+        sd.r = d->r;
+        sd.groups = d->groups;
+        sd.layers = 1;
+        sd.dtype = d->dtype;
+        sd.has_bias = d->has_bias;
+    }
+    return sd;
+}
+
+size_t pf_lowrank_lstm_seq_fwd_workspace_bytes(const pf_lstm_seq_desc *d)
+{
+    if (!d) return 0;
+    const pf_lstm_stack_desc sd = seq_as_stack(d);
+    return pf_lowrank_lstm_stack_fwd_workspace_bytes(&sd);
+}
+
+size_t pf_lowrank_lstm_seq_bwd_workspace_bytes(const pf_lstm_seq_desc *d)
+{
+    if (!d) return 0;
+    const pf_lstm_stack_desc sd = seq_as_stack(d);
+    return pf_lowrank_lstm_stack_bwd_workspace_bytes(&sd);
+}
+
+int pf_lowrank_lstm_seq_fwd(const pf_lstm_seq_desc *d, const void *x, const void *h0, const void *c0, const void *Vx,
+                            const void *Ux, const void *Vh, const void *Uh, const void *bias, void *h_all, void *c_all,
+                            void *gates_all, void *Tx_all, void *Th_all, void *workspace, size_t workspace_bytes,
+                            void *stream)
+{
+    if (!d) return PF_ERR_NULL;
+    const pf_lstm_stack_desc sd = seq_as_stack(d);
+    return pf_lowrank_lstm_stack_fwd(&sd, x, &h0, &c0, &Vx, &Ux, &Vh, &Uh, &bias, &h_all, &c_all, &gates_all, &Tx_all,
+                                     &Th_all, workspace, workspace_bytes, stream);
+}
+
+int pf_lowrank_lstm_seq_bwd(const pf_lstm_seq_desc *d, const void *x, const void *h0, const void *c0, const void *h_all,
+                            const void *c_all, const void *gates_all, const void *Tx_all, const void *Th_all,
+                            const void *Vx, const void *Ux, const void *Vh, const void *Uh, const void *dh_all,
+                            const void *dhT, const void *dcT, void *dx_all, void *dh0, void *dc0, void *dVx, void *dUx,
+                            void *dVh, void *dUh, void *dbias, int accumulate, void *workspace, size_t workspace_bytes,
+                            void *stream)
+{
+    if (!d) return PF_ERR_NULL;
+    const pf_lstm_stack_desc sd = seq_as_stack(d);
+    return pf_lowrank_lstm_stack_bwd(&sd, x, &h0, &c0, &h_all, &c_all, &gates_all, &Tx_all, &Th_all, &Vx, &Ux, &Vh, &Uh,
+                                     dh_all, &dhT, &dcT, dx_all, &dh0, &dc0, &dVx, &dUx, &dVh, &dUh, &dbias, accumulate,
+                                     workspace, workspace_bytes, stream);
+}
+
 } // extern "C"
