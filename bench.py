@@ -586,7 +586,7 @@ def main():
             roofline["algorithmic_GBps"] = kbytes / step_s / 1e9
 
     dense = None
-    if not args.no_dense:
+    if not args.no_dense and hasattr(wl, "dense_prepare"):  # (the LSTM workloads have no dense comparator)
         for s in sets:
             wl.dense_prepare(s, torch)
         if args.no_graph:
