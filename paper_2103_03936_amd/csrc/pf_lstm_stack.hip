@@ -5,11 +5,14 @@
 // the mirror image).  A step of the recurrence is a chain of short, latency-bound launches; the wavefront makes
 // that chain T + L - 1 slots long instead of T L.
 //
-// Per forward slot: one launch for all T = (h Vh | x Vx) products, one for their slice sums, one for all
-// z = T U^T products, one for the gates of all active layers.  The input path of layer 0 does not depend on any
-// recurrence and is computed for all time steps up front; the input path of a higher layer reads the layer
-// below at the same time step and rides in the slot's launches.  All parameter gradients are formed once per
-// layer over all T B rows after the backward wavefront.
+// General schedule (any factor layout): per forward slot one launch for all T = (h Vh | x Vx) products, one for
+// their slice sums, one for all z = T U^T products, one for the gates of all active layers; the input path of layer 0
+// does not depend on any recurrence and is computed for all time steps up front; the input path of a higher layer
+// reads the layer below at the same time step and rides in the slot's launches.  With one factor pair per path and
+// r <= 512 the products that follow the slice sums and the gate arithmetic are one kernel in either direction
+// (lstm_zgates_kernel, lstm_dhgates_kernel): three launches per slot.  All parameter gradients are formed once per
+// layer over all T B rows after the backward wavefront.  The factors are copied once per call into the order the
+// kernels read them in.  A single layer over a sequence (pf_lowrank_lstm_seq_*) is a stack of one layer.
 #include <vector>
 
 #include "pf_gemm.h"
