@@ -152,6 +152,43 @@ def test_lstm_seq_validation():
     assert ws > 0
 
 
+def test_lstm_stack_validation():
+    f = pf.lib.pf_lowrank_lstm_stack_fwd
+    z = ctypes.c_size_t(0)
+    mk = lambda T=3, B=2, d=8, h=8, r=4, groups=1, layers=2, dtype=0, bias=1: pf.pf_lstm_stack_desc(
+        T, B, d, h, r, groups, layers, dtype, bias)
+    arr = lambda n=2, v=256: (ctypes.c_void_p * n)(*([v] * n))  # host arrays of never-dereferenced device pointers
+    per_layer = lambda: [arr() for _ in range(12)]
+    assert f(None, FAKE, *per_layer(), None, z, None) == 1
+    assert f(ctypes.byref(mk(layers=0)), FAKE, *per_layer(), None, z, None) == 2
+    assert f(ctypes.byref(mk(layers=5)), FAKE, *per_layer(), None, z, None) == 2
+    assert f(ctypes.byref(mk(groups=2)), FAKE, *per_layer(), None, z, None) == 3
+    assert f(ctypes.byref(mk(dtype=1)), FAKE, *per_layer(), None, z, None) == 3
+    assert f(ctypes.byref(mk(B=33)), FAKE, *per_layer(), None, z, None) == 3      # built for small batches
+    assert f(ctypes.byref(mk(r=2)), FAKE, *per_layer(), None, z, None) == 3       # every extent at least 4
+    args = per_layer()
+    args[2] = None                                                                  # the Vx array itself
+    assert f(ctypes.byref(mk()), FAKE, *args, None, z, None) == 1
+    args = per_layer()
+    args[4] = arr(v=None)                                                           # a layer's Vh pointer
+    assert f(ctypes.byref(mk()), FAKE, *args, None, z, None) == 1
+    args = per_layer()
+    args[7] = arr(v=260)                                                            # h_all not 16-byte aligned
+    assert f(ctypes.byref(mk()), FAKE, *args, None, z, None) == 3
+    assert f(ctypes.byref(mk()), None, *per_layer(), None, z, None) == 1            # x
+    assert f(ctypes.byref(mk()), FAKE, *per_layer(), None, z, None) == 4            # workspace missing
+    assert f(ctypes.byref(mk(T=0)), FAKE, *per_layer(), None, z, None) == 0
+    assert f(ctypes.byref(mk(B=0)), FAKE, *per_layer(), None, z, None) == 0
+    for q in (pf.lib.pf_lowrank_lstm_stack_fwd_workspace_bytes, pf.lib.pf_lowrank_lstm_stack_bwd_workspace_bytes):
+        assert q(ctypes.byref(mk())) > 0
+        assert q(ctypes.byref(mk(groups=4, r=600, h=700, d=700, B=20, T=5))) > 0   # the unfused schedule
+        assert q(ctypes.byref(mk(layers=9))) == 0
+    # one factor pair per path takes the fused schedule, whose packed copies differ in size from the general one
+    fused = pf.lib.pf_lowrank_lstm_stack_fwd_workspace_bytes(ctypes.byref(mk(B=20, d=64, h=64, r=16, T=4)))
+    general = pf.lib.pf_lowrank_lstm_stack_fwd_workspace_bytes(ctypes.byref(mk(B=20, d=64, h=64, r=16, T=4, groups=4)))
+    assert fused > 0 and general > 0 and fused != general
+
+
 def test_svd_validation():
     f = pf.lib.pf_svd_split
     z = ctypes.c_size_t(0)
