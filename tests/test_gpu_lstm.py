@@ -400,3 +400,28 @@ def test_layer_stack_matches_sequence_layers_full_size():
         for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
             assert_close(gr[l][k], grs[k].double().cpu().numpy(), "f32", f"full size {k}{l}")
     assert_close(dx, above.double().cpu().numpy(), "f32", "full size dx")
+
+
+def test_layer_stack_full_size_against_oracle():
+    """The language model's two layers over all 35 steps at batch 20 (Appendix D), forward and back-propagation
+    through time and depth, directly against the fp64 oracle."""
+    import paper_2103_03936_amd as pf
+    T, B, d, h, r, L = 35, 20, 1500, 1500, 375, 2
+    a = _stack_inputs(T, B, d, h, r, 1, L, seed=21)
+    ho, co, go, Txo, Tho = oracle.lowrank_lstm_stack_fwd(a["x"], a["h0"], a["c0"], a["Vx"], a["Ux"], a["Vh"], a["Uh"],
+                                                         a["bias"], 1)
+    dxo, dh0o, dc0o, gro = oracle.lowrank_lstm_stack_bwd(a["x"], a["h0"], a["c0"], ho, co, go, Txo, Tho, a["Vx"],
+                                                        a["Ux"], a["Vh"], a["Uh"], a["dh_top"], a["dhT"], a["dcT"], 1)
+    g = _gpu_lists(a)
+    outs = pf.pf_lowrank_lstm_stack_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["bias"], 1)
+    dx, dh0, dc0, gr = pf.pf_lowrank_lstm_stack_bwd(g["x"], g["h0"], g["c0"], *outs, g["Vx"], g["Ux"], g["Vh"], g["Uh"],
+                                                    g["dh_top"], g["dhT"], g["dcT"], 1)
+    for l in range(L):
+        for name, got, want in (("h", outs[0], ho), ("c", outs[1], co), ("gates", outs[2], go), ("Tx", outs[3], Txo),
+                                ("Th", outs[4], Tho)):
+            assert_close(got[l], want[l], "f32", f"full size {name}{l}")
+        assert_close(dh0[l], dh0o[l], "f32", f"full size dh0 {l}")
+        assert_close(dc0[l], dc0o[l], "f32", f"full size dc0 {l}")
+        for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
+            assert_close(gr[l][k], gro[l][k], "f32", f"full size {k}{l}")
+    assert_close(dx, dxo, "f32", "full size dx")
