@@ -425,3 +425,32 @@ def test_layer_stack_full_size_against_oracle():
         for k in ("dVx", "dUx", "dVh", "dUh", "dbias"):
             assert_close(gr[l][k], gro[l][k], "f32", f"full size {k}{l}")
     assert_close(dx, dxo, "f32", "full size dx")
+
+
+def test_layer_stack_random_shapes():
+    """Twelve seeded random geometries (steps, batch, widths, rank, depth, factor layout, bias) against the oracle."""
+    import paper_2103_03936_amd as pf
+    rng = np.random.default_rng(2103)
+    for case in range(12):
+        T, B, L = int(rng.integers(1, 6)), int(rng.integers(1, 33)), int(rng.integers(1, 5))
+        G, bias = int(rng.choice([1, 4])), bool(rng.integers(0, 2))
+        d, h, r = int(rng.integers(4, 80)), int(rng.integers(4, 80)), int(rng.integers(4, 40))
+        a = _stack_inputs(T, B, d, h, r, G, L, seed=100 + case)
+        if not bias:
+            a["bias"] = None
+        tag = f"random stack {case}: T={T} B={B} d={d} h={h} r={r} L={L} groups={G} bias={bias}"
+        o = oracle.lowrank_lstm_stack_fwd(a["x"], a["h0"], a["c0"], a["Vx"], a["Ux"], a["Vh"], a["Uh"], a["bias"], G)
+        ob = oracle.lowrank_lstm_stack_bwd(a["x"], a["h0"], a["c0"], *o, a["Vx"], a["Ux"], a["Vh"], a["Uh"], a["dh_top"],
+                                           a["dhT"], a["dcT"], G)
+        g = {k: (None if v is None else _gpu_lists({k: v})[k]) for k, v in a.items()}
+        outs = pf.pf_lowrank_lstm_stack_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["bias"], G)
+        dx, dh0, dc0, gr = pf.pf_lowrank_lstm_stack_bwd(g["x"], g["h0"], g["c0"], *outs, g["Vx"], g["Ux"], g["Vh"],
+                                                        g["Uh"], g["dh_top"], g["dhT"], g["dcT"], G)
+        assert_close(dx, ob[0], "f32", tag + " dx")
+        for l in range(L):
+            for i, name in enumerate(("h", "c", "gates", "Tx", "Th")):
+                assert_close(outs[i][l], o[i][l], "f32", f"{tag} {name}{l}")
+            assert_close(dh0[l], ob[1][l], "f32", f"{tag} dh0 {l}")
+            assert_close(dc0[l], ob[2][l], "f32", f"{tag} dc0 {l}")
+            for k in ("dVx", "dUx", "dVh", "dUh") + (("dbias",) if bias else ()):
+                assert_close(gr[l][k], ob[3][l][k], "f32", f"{tag} {k}{l}")
