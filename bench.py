@@ -453,7 +453,7 @@ def svd_bench(args, torch, pf, workloads):
         "cpu_baseline": cpu}))
 
 
-def make_workload(name):
+def make_workload(name, lstm_groups=1):
     import workloads
     cfg = workloads.CONFIGS[name]
     if cfg["kind"] in ("conv", "conv_set"):
@@ -461,7 +461,7 @@ def make_workload(name):
     if cfg["kind"] in ("linear", "linear_set"):
         return LinearWorkload(name, cfg)
     if cfg["kind"] == "lstm":
-        return LstmWorkload(name, cfg)
+        return LstmWorkload(name, cfg, groups=lstm_groups)
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -521,6 +521,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy, so that byte counters of a profiler run can be scaled")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--lstm-groups", type=int, default=1, choices=(1, 4),
+                    help="LSTM workloads: 1 = one factor pair per path, 4 = one pair per gate and path (Appendix D's table)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
@@ -534,7 +536,7 @@ def main():
     torch.cuda.set_device(0)
     if workloads.CONFIGS[args.workload]["kind"] == "svd":
         return svd_bench(args, torch, pf, workloads)
-    wl = make_workload(args.workload)
+    wl = make_workload(args.workload, args.lstm_groups)
 
     one = wl.make_set(0, torch, workloads)
     set_bytes = sum(t.numel() * t.element_size() for g in one.values() for t in g.values() if hasattr(t, "numel"))
