@@ -137,7 +137,7 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
     p.fwd_bytes = align_up(p.n_T * sizeof(float));
     p.bwd_bytes = align_up(p.n_T * sizeof(float)) + align_up(p.n_dT * sizeof(float)) + align_up(p.n_part * sizeof(float));
     p.fused = d->dtype == PF_BF16 && linear_chain_supported(d->in, d->out, d->r);
-    p.skinny = d->dtype == PF_F32 && d->M > 0 && d->M <= SK_MAX_ROWS * SK_MAX_PROB / 2 && d->in >= 4 && d->out >= 4 &&
+    p.skinny = d->dtype == PF_F32 && d->M > 0 && d->M <= 4 * SK_MAX_ROWS && d->in >= 4 && d->out >= 4 &&
                d->r >= 4;
     p.n_part_sk = 0;
     if (p.skinny) {

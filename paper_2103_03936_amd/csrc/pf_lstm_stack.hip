@@ -566,7 +566,7 @@ static int check_stack_desc(const pf_lstm_stack_desc *d, StackGeom *g)
     return PF_OK;
 }
 
-// C[Mt x N] = A[Mt x K] W (+ bias) for Mt = T B rows, 256 rows per launch pair (product + slice sums)
+// C[Mt x N] = A[Mt x K] W (+ bias) for Mt = T B rows, 512 rows per launch pair (product + slice sums)
 constexpr int ST_ROWS = SK_MAX_ROWS * SK_MAX_PROB;
 static int st_tall(hipStream_t s, const char *name, bool nk, i64 Mt, const float *A, i64 lda, const float *W, i64 ldw,
                    int K, int N, float *out, i64 ldo, const float *bias, float *part)

@@ -11,7 +11,7 @@ namespace pf {
 
 constexpr int SK_MAX_ROWS = 32;  // activation rows one MFMA tile holds
 constexpr int SK_TILE_N = 128;   // output columns per workgroup
-constexpr int SK_MAX_PROB = 8;
+constexpr int SK_MAX_PROB = 16;
 
 struct SkinnyProb {
     const float *A; // activations, A[m * lda + k]
@@ -23,6 +23,8 @@ struct SkinnyProb {
 };
 struct SkinnyArgs {
     SkinnyProb p[SK_MAX_PROB];
+    int wg0[SK_MAX_PROB]; // first workgroup of every problem once more, side by side: one scalar load finds a
+                          // workgroup's problem (filled by skinny_plan; INT_MAX-like past nprob)
     int nprob, nwg;
 };
 // Chooses the slicing of every problem (about `target` workgroups in all) and numbers the workgroups.

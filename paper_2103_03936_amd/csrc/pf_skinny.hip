@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, 1) void skinny_gemm_kernel(SkinnyArgs a)
     int pi = 0;
 #pragma unroll
     for (int q = 1; q < SK_MAX_PROB; ++q)
-        if (q < a.nprob && (int)blockIdx.x >= a.p[q].wg0) pi = q;
+        if ((int)blockIdx.x >= a.wg0[q]) pi = q;
     const SkinnyProb &pb = a.p[pi];
     const float *__restrict__ A = pb.A;
     const float *__restrict__ W = pb.W;
@@ -209,6 +209,7 @@ void skinny_plan(SkinnyArgs &a, int target)
         p.wg0 = wg;
         wg += p.ntiles * p.ksplit;
     }
+    for (int q = 0; q < SK_MAX_PROB; ++q) a.wg0[q] = q < a.nprob ? a.p[q].wg0 : 0x7fffffff;
     a.nwg = wg;
 }
 
