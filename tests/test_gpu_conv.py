@@ -156,3 +156,23 @@ def test_resnet50_conv5_full_size(layer):
     c = workloads.CONFIGS["resnet50_conv5_bf16"]
     Cin, Cout, r, k, p = c["layers"][layer]
     _run((16, Cin, c["H"], c["W"], Cout, r, k, 1, p), c["dtype"], seed=c["seed"], saved_W=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_geometries(dtype):
+    """Sixteen seeded random geometries (generic path, and the fused path where a drawn shape qualifies)."""
+    rng = np.random.default_rng(3936)
+    for case in range(16):
+        k = int(rng.choice([1, 3, 5]))
+        s = int(rng.choice([1, 2]))
+        p = int(rng.integers(0, k // 2 + 1))
+        N, C, Cout, r = int(rng.integers(1, 6)), int(rng.integers(1, 40)), int(rng.integers(1, 48)), int(rng.integers(1, 20))
+        H, W = int(rng.integers(k, 13)), int(rng.integers(k, 13))
+        _run((N, C, H, W, Cout, r, k, s, p), dtype, saved_T=bool(rng.integers(0, 2)), seed=300 + case,
+             saved_W=bool(rng.integers(0, 2)))
+    # channel counts the fused kernels take (multiples of 64, rank 64 or 128, small images)
+    for case in range(4):
+        C, Cout = 64 * int(rng.integers(1, 4)), 64 * int(rng.integers(1, 4))
+        r, k = int(rng.choice([64, 128])), int(rng.choice([1, 3]))
+        H = int(rng.choice([7, 8]))
+        _run((int(rng.integers(1, 9)), C, H, H, Cout, r, k, 1, k // 2), dtype, seed=400 + case, saved_W=True)

@@ -117,3 +117,15 @@ def test_transformer_block_full_size(layer):
     cfg = workloads.CONFIGS["transformer_block_bf16"]
     n_in, n_out, r = cfg["layers"][layer]
     _run(cfg["M"], n_in, n_out, r, "bf16", True, True, seed=cfg["seed"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_geometries(dtype):
+    """Sixteen seeded random geometries, with and without bias and saved T (few-row, generic and fused paths)."""
+    rng = np.random.default_rng(2103)
+    for case in range(16):
+        M = int(rng.choice([1, 7, 33, 129, 300]))
+        n_in, n_out, r = int(rng.integers(1, 200)), int(rng.integers(1, 200)), int(rng.integers(1, 64))
+        if case >= 12:  # shapes of the fused bf16 kernel
+            n_in, n_out, r = 256 * int(rng.integers(1, 4)), 256 * int(rng.integers(1, 4)), 128
+        _run(M, n_in, n_out, r, dtype, bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), seed=500 + case)
