@@ -132,6 +132,14 @@ static int do_slice_sum(const SliceSumArgs &a)
 int emu_slice_sum_kernel(dim3, const SliceSumArgs &a) { return do_slice_sum(a); }
 int emu_rank_update_kernel(dim3 grid, const RankArgs &a, const SliceSumArgs &seg, int nsb)
 {
+    const int TI = 32; // rows of an output tile
+    int tiles = 0;
+    for (int q = 0; q < a.nprob; ++q) {
+        const RankProb &p = a.p[q];
+        if (p.wg0 != tiles) { g_err = "rank update: first workgroup of a problem"; return PF_ERR_LAUNCH; }
+        tiles += ((p.I + TI - 1) / TI) * ((p.J + 127) / 128);
+    }
+    if (tiles != a.nwg || (int)grid.x != a.nwg + nsb) { g_err = "rank update: grid"; return PF_ERR_LAUNCH; }
     for (int q = 0; q < a.nprob; ++q) {
         const RankProb &p = a.p[q];
         for (int b = 0; b < p.M; ++b) {

@@ -90,6 +90,7 @@ CASES = [
     (3, 32, 37, 29, 7, 2, 1, True),     # a full MFMA tile of rows
     (3, 6, 130, 260, 129, 2, 1, True),  # several column tiles and contraction slices
     (2, 4, 16, 24, 516, 2, 1, True),    # rank beyond the fused kernels: general schedule
+    (9, 32, 70, 50, 13, 2, 1, True),    # 288 rows summed in the weight gradients
     (1, 3, 8, 8, 4, 2, 4, True),
     (6, 5, 40, 36, 10, 2, 4, False),
     (4, 20, 70, 50, 13, 3, 4, True),
