@@ -22,6 +22,7 @@
 namespace pf {
 
 constexpr int ST_MAX_LAYERS = 4;
+constexpr int ST_RANK_MMA_ROWS = 128; // T B from which the weight gradients go to the matrix unit
 
 __device__ __forceinline__ float st_sigmoid(float z) { return 1.0f / (1.0f + expf(-z)); }
 
@@ -1273,6 +1274,28 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x, const 
     for (int l = 0; l < L && st == PF_OK; ++l) {
         const float *xin = l ? p.h_all[l - 1] : (const float *)x;
         const int din = l ? h : g.din;
+        if (Mt >= ST_RANK_MMA_ROWS) {
+            // enough rows for the matrix unit; the bias gradient rides on the input path's dU
+            RankMmaArgs rm = {};
+            rm.accumulate = accumulate;
+            bool ok = true;
+            for (int path = 0; path < 2; ++path) {
+                const float *Tm = path ? p.Th_all[l] : p.Tx_all[l];
+                float *dU = path ? b.dUh[l] : b.dUx[l];
+                for (int q = 0; q < g.G; ++q)
+                    ok = ok && rank_mma_add(rm, nullptr, 0, b.dz_all[l] + (i64)q * h, 4 * (i64)h, Tm + (i64)q * r, gr,
+                                            dU + (i64)q * h * r, r, g.G == 1 ? 4 * h : h, r, (int)Mt,
+                                            path == 0 && b.dbias[l] ? b.dbias[l] + (i64)q * h : nullptr);
+            }
+            ok = ok && rank_mma_add(rm, nullptr, 0, xin, din, b.dTx_all[l], gr, b.dVx[l], gr, din, gr, (int)Mt);
+            // dVh = sum_t h_{t-1}^T dTh_t: the left operand is h0, then h_0 .. h_{T-2}
+            ok = ok && rank_mma_add(rm, p.h0[l], B, p.h_all[l], h, b.dTh_all[l], gr, b.dVh[l], gr, h, gr, (int)Mt);
+            if (ok) {
+                st = launch_rank_mma(s, "lstm_stack_grads", rm);
+                continue;
+            }
+            // (a dimension below four: the general kernel below takes the layer)
+        }
         RankArgs ra = {};
         ra.M = (int)Mt;
         ra.accumulate = accumulate;

@@ -162,4 +162,47 @@ void rank_add(RankArgs &a, const float *A, i64 lda, const float *Bm, i64 ldb, fl
 // seg: optional slice sums done by extra workgroups of the same launch (nseg == 0: none)
 int launch_rank_update(hipStream_t s, const char *name, const RankArgs &a, const SliceSumArgs &seg);
 
+struct __attribute__((packed, aligned(4))) F4u {
+    float v[4];
+};
+
+// four floats at a 4-byte aligned address
+__device__ __forceinline__ f32x4_t ld4(const float *p)
+{
+    const F4u t = *(const F4u *)p;
+    f32x4_t r = {t.v[0], t.v[1], t.v[2], t.v[3]};
+    return r;
+}
+// the first n of four floats (n <= 0: none), zero elsewhere; only the first n are touched
+__device__ __forceinline__ f32x4_t ld4n(const float *p, int n)
+{
+    if (n >= 4) return ld4(p);
+    f32x4_t r = {0.f, 0.f, 0.f, 0.f};
+    if (n > 0) r[0] = p[0];
+    if (n > 1) r[1] = p[1];
+    if (n > 2) r[2] = p[2];
+    return r;
+}
+
+// out (+)= [A0; A]^T * Bm on the matrix unit, for sums over hundreds of rows (the weight gradients of a whole
+// sequence): out[i * ldo + j] (+)= sum_{b < M0} A0[b * lda + i] * Bm[b * ldb + j]
+//                                + sum_{M0 <= b < M} A[(b - M0) * lda + i] * Bm[b * ldb + j].
+// The two-part left operand is the hidden state one step back: h0, then h_0 .. h_{T-2}.
+// colsum (optional): colsum[i] (+)= sum_b A[b][i], a bias gradient.
+struct RankMmaProb {
+    const float *A0, *A, *Bm;
+    float *out, *colsum;
+    i64 lda, ldb, ldo;
+    int M0, M, I, J, wg0, jt, ntile, nwg; // jt = column tiles; nwg = ntile rounded up to a multiple of eight
+};
+constexpr int RM_MAX_PROB = 12;
+struct RankMmaArgs {
+    RankMmaProb p[RM_MAX_PROB];
+    int nprob, accumulate, nwg, xi; // nwg, xi (tile height / 64) and the problems' tile fields: set by the launch
+};
+// false: the kernel does not take this problem (a row shorter than four floats, too many problems); out == NULL: skipped
+bool rank_mma_add(RankMmaArgs &a, const float *A0, int M0, const float *A, i64 lda, const float *Bm, i64 ldb,
+                  float *out, i64 ldo, int I, int J, int M, float *colsum = nullptr);
+int launch_rank_mma(hipStream_t s, const char *name, const RankMmaArgs &a);
+
 } // namespace pf

@@ -13,28 +13,6 @@
 
 namespace pf {
 
-struct __attribute__((packed, aligned(4))) F4u {
-    float v[4];
-};
-
-// four floats at a 4-byte aligned address
-__device__ __forceinline__ f32x4_t ld4(const float *p)
-{
-    const F4u t = *(const F4u *)p;
-    f32x4_t r = {t.v[0], t.v[1], t.v[2], t.v[3]};
-    return r;
-}
-// the first n of four floats (n <= 0: none), zero elsewhere; only the first n are touched
-__device__ __forceinline__ f32x4_t ld4n(const float *p, int n)
-{
-    if (n >= 4) return ld4(p);
-    f32x4_t r = {0.f, 0.f, 0.f, 0.f};
-    if (n > 0) r[0] = p[0];
-    if (n > 1) r[1] = p[1];
-    if (n > 2) r[2] = p[2];
-    return r;
-}
-
 // MODE 0: KN weights, 1: NK weights, 2: weights copied into the kernel's own order by skinny_pack_kernel
 template <int MODE>
 __global__ __launch_bounds__(256, 1) void skinny_gemm_kernel(SkinnyArgs a)

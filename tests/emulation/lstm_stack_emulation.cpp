@@ -41,6 +41,7 @@ template <int MODE> int emu_skinny_gemm_kernel(dim3 grid, const SkinnyArgs &a);
 int emu_skinny_pack_kernel(dim3 grid, const SkinnyPackArgs &a);
 int emu_slice_sum_kernel(dim3 grid, const SliceSumArgs &a);
 int emu_rank_update_kernel(dim3 grid, const RankArgs &a, const SliceSumArgs &seg, int nsb);
+template <int XI> int emu_rank_mma_kernel(dim3 grid, const RankMmaArgs &a);
 int launch_zero_f32(hipStream_t, float *out, i64 count)
 {
     if (count <= 0 || !out) return PF_OK;
@@ -54,6 +55,7 @@ int launch_zero_f32(hipStream_t, float *out, i64 count)
     do { if ((st) == PF_OK) { ++g_launches; (st) = emu_##kernel(grid, __VA_ARGS__); } } while (0)
 
 #include "pf_skinny.hip"
+#include "pf_rank_mma.hip"
 #include "pf_lstm_stack.hip"
 
 namespace pf {
@@ -156,6 +158,45 @@ int emu_rank_update_kernel(dim3 grid, const RankArgs &a, const SliceSumArgs &seg
         }
     }
     return nsb ? do_slice_sum(seg) : PF_OK;
+}
+template <int XI> int emu_rank_mma_kernel(dim3 grid, const RankMmaArgs &a)
+{
+    const int TI = 64 * XI;
+    if (a.xi != XI) { g_err = "rank mma: tile height"; return PF_ERR_LAUNCH; }
+    int tiles = 0;
+    for (int q = 0; q < a.nprob; ++q) {
+        const RankMmaProb &p = a.p[q];
+        if (p.wg0 != tiles) { g_err = "rank mma: first workgroup of a problem"; return PF_ERR_LAUNCH; }
+        if (p.M0 < 0 || p.M0 > p.M || p.M < 1) { g_err = "rank mma: rows"; return PF_ERR_LAUNCH; }
+        if (p.I < 4 || p.J < 4) { g_err = "rank mma: a row shorter than four floats"; return PF_ERR_LAUNCH; }
+        const int nt = ((p.I + TI - 1) / TI) * ((p.J + 127) / 128);
+        if (p.ntile != nt || p.nwg != (nt + 7) / 8 * 8 || p.jt != (p.J + 127) / 128) { g_err = "rank mma: tiles of a problem"; return PF_ERR_LAUNCH; }
+        tiles += p.nwg;
+    }
+    if (tiles != a.nwg || (int)grid.x != a.nwg) { g_err = "rank mma: grid"; return PF_ERR_LAUNCH; }
+    for (int q = 0; q < a.nprob; ++q) {
+        const RankMmaProb &p = a.p[q];
+        auto row = [&](int b) { return b < p.M0 ? p.A0 + (i64)b * p.lda : p.A + (i64)(b - p.M0) * p.lda; };
+        for (int b = 0; b < p.M; ++b) {
+            CHK(row(b), p.I, "rank mma A");
+            CHK(p.Bm + (i64)b * p.ldb, p.J, "rank mma B");
+        }
+        if (p.colsum) CHK(p.colsum, p.I, "rank mma column sums");
+        for (int i = 0; i < p.I; ++i) {
+            CHK(p.out + (i64)i * p.ldo, p.J, "rank mma out");
+            for (int j = 0; j < p.J; ++j) {
+                double acc = a.accumulate ? p.out[(i64)i * p.ldo + j] : 0.0;
+                for (int b = 0; b < p.M; ++b) acc += (double)row(b)[i] * p.Bm[(i64)b * p.ldb + j];
+                p.out[(i64)i * p.ldo + j] = (float)acc;
+            }
+            if (p.colsum) {
+                double acc = a.accumulate ? p.colsum[i] : 0.0;
+                for (int b = 0; b < p.M; ++b) acc += row(b)[i];
+                p.colsum[i] = (float)acc;
+            }
+        }
+    }
+    return PF_OK;
 }
 static double sg(double z) { return 1.0 / (1.0 + exp(-z)); }
 int emu_lstm_zg_pack_kernel(dim3 grid, const ZgPackArgs &a)

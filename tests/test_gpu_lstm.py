@@ -306,6 +306,8 @@ STACKS = [
     (3, 32, 37, 29, 7, 2),
     (3, 6, 130, 260, 129, 2),  # several column tiles and contraction slices, all with tails
     (2, 4, 16, 24, 516, 2),    # a rank beyond what the fused pre-activation + gate kernel stages on chip
+    (9, 20, 70, 150, 37, 2),   # 180 rows: weight gradients on the matrix unit, ragged last chunk and tiles
+    (5, 32, 200, 130, 140, 2), # 160 rows = whole chunks; more than one column tile
 ]
 
 

@@ -95,6 +95,7 @@ CASES = [
     (6, 5, 40, 36, 10, 2, 4, False),
     (4, 20, 70, 50, 13, 3, 4, True),
     (3, 6, 130, 260, 129, 2, 4, True),
+    (7, 20, 40, 36, 10, 2, 4, False),   # 140 rows, one factor pair per gate
 ]
 
 
