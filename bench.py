@@ -377,7 +377,8 @@ class LstmWorkload:
                                         4 * ((gr * h + B * gr) * prods + (B * 4 * h * 2 + 5 * B * h) * cells),
                                         slots + calls),
                 "lstm_stack_grads": (2.0 * Mt * (8 * h * r + gr * (d + h)) * L,
-                                     4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)) * L, 2 * L),
+                                     4 * ((8 * h * r + gr * (d + h) + 4 * h) + Mt * (4 * h + 2 * gr + d + h)) * L,
+                                     L if Mt >= 128 else 2 * L),  # one launch per layer from 128 rows on
             }
             return {k: [f, b, n] for k, (f, b, n) in ws.items()}
         w = {
