@@ -456,3 +456,52 @@ def test_layer_stack_random_shapes():
             assert_close(dc0[l], ob[2][l], "f32", f"{tag} dc0 {l}")
             for k in ("dVx", "dUx", "dVh", "dUh") + (("dbias",) if bias else ()):
                 assert_close(gr[l][k], ob[3][l][k], "f32", f"{tag} {k}{l}")
+
+
+def _check_stack_case(pf, T, B, d, h, r, L, G, bias, seed, tag):
+    a = _stack_inputs(T, B, d, h, r, G, L, seed=seed)
+    if not bias:
+        a["bias"] = None
+    o = oracle.lowrank_lstm_stack_fwd(a["x"], a["h0"], a["c0"], a["Vx"], a["Ux"], a["Vh"], a["Uh"], a["bias"], G)
+    ob = oracle.lowrank_lstm_stack_bwd(a["x"], a["h0"], a["c0"], *o, a["Vx"], a["Ux"], a["Vh"], a["Uh"], a["dh_top"],
+                                       a["dhT"], a["dcT"], G)
+    g = {k: (None if v is None else _gpu_lists({k: v})[k]) for k, v in a.items()}
+    outs = pf.pf_lowrank_lstm_stack_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["bias"], G)
+    dx, dh0, dc0, gr = pf.pf_lowrank_lstm_stack_bwd(g["x"], g["h0"], g["c0"], *outs, g["Vx"], g["Ux"], g["Vh"],
+                                                    g["Uh"], g["dh_top"], g["dhT"], g["dcT"], G)
+    assert_close(dx, ob[0], "f32", tag + " dx")
+    for l in range(L):
+        assert_close(dh0[l], ob[1][l], "f32", f"{tag} dh0 {l}")
+        assert_close(dc0[l], ob[2][l], "f32", f"{tag} dc0 {l}")
+        for k in ("dVx", "dUx", "dVh", "dUh") + (("dbias",) if bias else ()):
+            assert_close(gr[l][k], ob[3][l][k], "f32", f"{tag} {k}{l}")
+    # a second call accumulates onto the first
+    _, _, _, gr2 = pf.pf_lowrank_lstm_stack_bwd(g["x"], g["h0"], g["c0"], *outs, g["Vx"], g["Ux"], g["Vh"], g["Uh"],
+                                                g["dh_top"], g["dhT"], g["dcT"], G, grads=gr)
+    for l in range(L):
+        for k in ("dVx", "dUx", "dVh", "dUh") + (("dbias",) if bias else ()):
+            assert_close(gr2[l][k], 2 * ob[3][l][k], "f32", f"{tag} accumulated {k}{l}")
+
+
+def test_layer_stack_long_sequences_random_shapes():
+    """Seeded random geometries with T B between 128 and 512, where the weight gradients are summed on the matrix
+    unit: widths and ranks around its 64- and 128-wide tiles, both factor layouts, with and without bias, written
+    and accumulated."""
+    import paper_2103_03936_amd as pf
+    rng = np.random.default_rng(3936)
+    for case in range(10):
+        T, B, L = int(rng.integers(8, 17)), int(rng.integers(16, 33)), int(rng.integers(1, 3))
+        G, bias = int(rng.choice([1, 4])), bool(rng.integers(0, 2))
+        d, h, r = int(rng.integers(4, 200)), int(rng.integers(4, 150)), int(rng.integers(4, 140))
+        tag = f"long random stack {case}: T={T} B={B} d={d} h={h} r={r} L={L} groups={G} bias={bias}"
+        _check_stack_case(pf, T, B, d, h, r, L, G, bias, 300 + case, tag)
+
+
+@pytest.mark.parametrize("shape", [(4, 32, 64, 64, 128, 1, 1), (32, 4, 20, 12, 6, 2, 1), (16, 8, 4, 4, 4, 1, 4),
+                                   (16, 8, 4, 4, 4, 2, 1), (5, 32, 7, 33, 129, 1, 1)])
+def test_layer_stack_long_sequences_edges(shape):
+    """T B >= 128 at the edges of the matrix-unit weight-gradient kernel: exactly one full tile and whole chunks,
+    many short steps, the smallest extents the entry points take (rows of four floats), one column past a tile."""
+    import paper_2103_03936_amd as pf
+    T, B, d, h, r, L, G = shape
+    _check_stack_case(pf, T, B, d, h, r, L, G, True, 77, f"long stack edge {shape}")
