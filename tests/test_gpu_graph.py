@@ -84,12 +84,14 @@ def test_lstm_cell_graph_replay():
     _replay_matches_eager(make, run, ("h", "c", "dx", "dh_prev", "dc_prev", "dVx", "dUx", "dVh", "dUh", "dbias"))
 
 
+@pytest.mark.parametrize("T", [5, 9])
 @pytest.mark.parametrize("groups", [1, 4])
-def test_lstm_stack_graph_replay(groups):
+def test_lstm_stack_graph_replay(groups, T):
     """Two stacked layers over a short sequence (groups = 1: the fused pre-activation + gate kernel and the packed
-    factors; groups = 4: the unfused launches), forward and backward in one graph."""
+    factors; groups = 4: the unfused launches), forward and backward in one graph.  T = 9 gives 180 rows, from
+    where the weight gradients are summed on the matrix unit."""
     import paper_2103_03936_amd as pf
-    T, B, d, h, r, L = 5, 20, 72, 80, 20, 2
+    B, d, h, r, L = 20, 72, 80, 20, 2
 
     def make(seed):
         s = workloads.Stream(workloads.SEED_BASE + 700 + seed, "f32")
