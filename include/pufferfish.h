@@ -4,15 +4,19 @@
  * replaced by rank-r factors U V^T.
  *
  * General rules
- *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     never allocates, frees or synchronises; work is enqueued on `stream`
- *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The layer
+ *     entry points never allocate, free or synchronise; work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream).
+ *     The one exception is the benchmark-only pf_timing_* group at the end of
+ *     this file, which creates HIP events while enabled and waits for them in
+ *     pf_timing_collect(); with timing disabled (the default) nothing of the
+ *     kind happens.
  *   - Descriptors are small HOST structs passed by pointer.
  *   - Arrays are dense row-major, last index fastest.
  *   - `dtype` PF_F32: all tensors float.  PF_BF16: activations and factors are
  *     bfloat16, products accumulate in float, activation outputs (Y, dX, T_save)
  *     are rounded to bfloat16.  Parameter gradients (dU, dV, dbias, ...) are
- *     ALWAYS float.
+ *     ALWAYS float: descriptors that carry a `wgrad_dtype` accept PF_F32 only.
  *   - Activations, factors, biases and saved tensors must be 16-byte aligned
  *     (any device allocation is); parameter-gradient outputs need only 4-byte
  *     alignment, so they may be slices of ONE flat float buffer laid out back
@@ -21,8 +25,10 @@
  *   - `accumulate` != 0 adds parameter gradients to what the buffers hold
  *     (gradient accumulation, back-propagation through time); 0 overwrites.
  *   - Scratch memory comes from the caller: ask pf_*_workspace_bytes(desc),
- *     pass at least that many bytes, 256-byte aligned.  A NULL workspace is
- *     accepted when the query returns 0.
+ *     pass at least that many bytes, 256-byte aligned (PF_ERR_UNSUPPORTED
+ *     otherwise).  A NULL workspace is accepted when the query returns 0.
+ *     The queries return 0 also for a descriptor the entry point would
+ *     reject; the entry point then reports why.
  *   - Every call returns a pf_status.  Arguments are validated on the host
  *     before anything is launched: PF_ERR_NULL (a required pointer is NULL),
  *     PF_ERR_SHAPE (a dimension is not positive, or a convolution has no
@@ -52,6 +58,8 @@ typedef enum {
 } pf_status;
 
 typedef enum { PF_F32 = 0, PF_BF16 = 1 } pf_dtype;
+/* Activation layouts of the convolution entry points (only NCHW is built). */
+typedef enum { PF_NCHW = 0, PF_NHWC = 1 } pf_layout;
 
 const char *pf_status_string(int status);
 /* hipError_t of the last failed launch on the calling thread (0 = none). */
@@ -68,8 +76,9 @@ int pf_version(void);
 /* ------------------------------------------------------------------ */
 typedef struct {
     int64_t M, in, out, r;
-    int dtype;    /* pf_dtype */
-    int has_bias; /* bias[out] is read (fwd) / dbias[out] is written (bwd) */
+    int dtype;       /* pf_dtype */
+    int wgrad_dtype; /* pf_dtype of dU, dV, dbias: PF_F32 (anything else: PF_ERR_UNSUPPORTED) */
+    int has_bias;    /* bias[out] is read (fwd) / dbias[out] is written (bwd) */
 } pf_linear_desc;
 
 size_t pf_lowrank_linear_fwd_workspace_bytes(const pf_linear_desc *d);
@@ -142,7 +151,9 @@ int pf_lowrank_linear_shared_bwd(const pf_linear_shared_desc *d, const void *X,
 typedef struct {
     int64_t N, Cin, H, W, Cout, r;
     int k, stride, pad;
-    int dtype; /* pf_dtype */
+    int layout;      /* pf_layout of X, T, Y and their gradients: PF_NCHW (anything else: PF_ERR_UNSUPPORTED) */
+    int dtype;       /* pf_dtype */
+    int wgrad_dtype; /* pf_dtype of dUk, dVp: PF_F32 (anything else: PF_ERR_UNSUPPORTED) */
 } pf_conv_desc;
 
 size_t pf_lowrank_conv_fwd_workspace_bytes(const pf_conv_desc *d);
@@ -231,6 +242,11 @@ int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x,
 /* does not depend on the recurrence and is computed for all time steps */
 /* at once, and the parameter gradients are formed once over all steps. */
 /*   x[T,B,d_in]; h0, c0 [B,h]; factors and bias as for the cell.       */
+/* These run on the small-batch schedule of the stack entry points      */
+/* below (a sequence is a stack of one layer) and share its limits:     */
+/* B <= 32 and d_in, h, r >= 4, otherwise PF_ERR_UNSUPPORTED -- larger   */
+/* batches go step by step through the cell entry points, which take    */
+/* any B.                                                               */
 /* ------------------------------------------------------------------ */
 typedef struct {
     int64_t T, B, d_in, h, r;
@@ -245,7 +261,7 @@ size_t pf_lowrank_lstm_seq_bwd_workspace_bytes(const pf_lstm_seq_desc *d);
 /* Outputs h_all, c_all [T,B,h] (h_all[t] = h_t); saved for backward:
  * gates_all[T,B,4h] (activated i|f|g|o), Tx_all, Th_all [T,B,groups r].  All
  * device pointers, all required (bias nullable); T == 0 or B == 0: nothing is
- * done.  Errors as for the cell. */
+ * done.  Errors as for the cell, plus the limits stated above. */
 int pf_lowrank_lstm_seq_fwd(const pf_lstm_seq_desc *d, const void *x,
                             const void *h0, const void *c0, const void *Vx,
                             const void *Ux, const void *Vh, const void *Uh,
@@ -345,6 +361,13 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x,
 /* the sign of each column pair.  r <= min(m, n) <= 8192 (else          */
 /* PF_ERR_SHAPE / PF_ERR_UNSUPPORTED).  For a convolution unroll        */
 /* W[c_out, c_in, k, k] to [c_in k^2, c_out] first (Section 2.2).       */
+/* Sweeps stop once a whole sweep found every column pair orthogonal to */
+/* min(m,n)-independent rounding level (max(m,n) * 2^-52 relative); at  */
+/* most 24 sweeps run.  The call is asynchronous, so convergence cannot */
+/* come back in the status: info (nullable, DEVICE int[2]) receives     */
+/* info[0] = sweeps that ran, info[1] = rotations applied in the last   */
+/* of them -- 0 means converged; anything else means the 24 sweeps did  */
+/* not suffice and the factors are approximate.                         */
 /* ------------------------------------------------------------------ */
 typedef struct {
     int64_t m, n, r;
@@ -352,8 +375,8 @@ typedef struct {
 
 size_t pf_svd_split_workspace_bytes(const pf_svd_desc *d);
 int pf_svd_split(const pf_svd_desc *d, const void *W, void *U, void *V,
-                 void *sigma /* nullable */, void *workspace,
-                 size_t workspace_bytes, void *stream);
+                 void *sigma /* nullable */, void *info /* nullable */,
+                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ */
 /* Dense (un-factorized) comparators, for benchmarks only: the layers   */
@@ -379,6 +402,9 @@ int pf_dense_conv_bwd(const pf_conv_desc *d, const void *X, const void *Wd,
 /* ------------------------------------------------------------------ */
 /* Per-kernel timing (HIP events recorded around every kernel launch on */
 /* the launch stream while enabled).  Not thread-safe; for benchmarks.  */
+/* While enabled every launch creates two hipEvents (host objects), so  */
+/* do not enable it under stream capture; pf_timing_collect() blocks    */
+/* the calling thread until the recorded events have completed.         */
 /* ------------------------------------------------------------------ */
 void pf_timing_enable(int on);
 /* Synchronises the recorded events, adds them to the totals and returns the

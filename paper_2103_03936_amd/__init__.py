@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpufferfish.so")
 
 PF_F32, PF_BF16 = 0, 1
+PF_NCHW, PF_NHWC = 0, 1
 
 
 class PfError(RuntimeError):
@@ -24,7 +25,7 @@ class PfError(RuntimeError):
 
 class pf_linear_desc(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int64), ("n_in", ctypes.c_int64), ("n_out", ctypes.c_int64), ("r", ctypes.c_int64),
-                ("dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
+                ("dtype", ctypes.c_int), ("wgrad_dtype", ctypes.c_int), ("has_bias", ctypes.c_int)]
 
 
 class pf_linear_shared_desc(ctypes.Structure):
@@ -35,7 +36,7 @@ class pf_linear_shared_desc(ctypes.Structure):
 class pf_conv_desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("Cin", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
                 ("Cout", ctypes.c_int64), ("r", ctypes.c_int64), ("k", ctypes.c_int), ("stride", ctypes.c_int),
-                ("pad", ctypes.c_int), ("dtype", ctypes.c_int)]
+                ("pad", ctypes.c_int), ("layout", ctypes.c_int), ("dtype", ctypes.c_int), ("wgrad_dtype", ctypes.c_int)]
 
 
 class pf_lstm_desc(ctypes.Structure):
@@ -123,13 +124,20 @@ def _stream():
 
 
 _ws_cache = {}
+_ws_retired = []  # outgrown buffers: a HIP graph captured earlier may still hold their addresses, so they stay allocated
 
 
 def _workspace(nbytes, device):
-    """A reusable byte buffer of at least nbytes on `device` (grown, never shrunk)."""
-    key = (device.type, device.index)
+    """A reusable byte buffer of at least nbytes for torch's current stream on `device` (grown, never shrunk).
+
+    One buffer per (device, stream): calls enqueued on one stream are ordered, so they may share scratch memory;
+    calls on different streams get different buffers.  A buffer that is outgrown is kept alive rather than freed,
+    so graphs captured through these wrappers stay valid when a later call needs more."""
+    key = (device.type, device.index, torch.cuda.current_stream(device).cuda_stream)
     buf = _ws_cache.get(key)
     if buf is None or buf.numel() < nbytes:
+        if buf is not None:
+            _ws_retired.append(buf)
         buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
         _ws_cache[key] = buf
     return buf
@@ -140,7 +148,7 @@ def _workspace(nbytes, device):
 def _linear_desc(X, U, bias_flag):
     M, n_in = X.shape
     n_out, r = U.shape
-    return pf_linear_desc(M, n_in, n_out, r, _dtype_code(X), 1 if bias_flag else 0)
+    return pf_linear_desc(M, n_in, n_out, r, _dtype_code(X), PF_F32, 1 if bias_flag else 0)
 
 
 def pf_lowrank_linear_fwd(X, V, U, bias=None, save_T=True):
@@ -224,7 +232,7 @@ def pf_lowrank_linear_shared_bwd(X, V, U, dY, T_saved=None, need_dX=True, has_bi
 def pf_dense_linear_fwd(X, W, bias=None):
     M, n_in = X.shape
     n_out = W.shape[0]
-    d = pf_linear_desc(M, n_in, n_out, 1, _dtype_code(X), 1 if bias is not None else 0)
+    d = pf_linear_desc(M, n_in, n_out, 1, _dtype_code(X), PF_F32, 1 if bias is not None else 0)
     Y = torch.empty((M, n_out), dtype=X.dtype, device=X.device)
     ws = _workspace(256, X.device)
     _check(lib.pf_dense_linear_fwd(ctypes.byref(d), _ptr(X), _ptr(W, X.dtype), _ptr(bias, X.dtype), _ptr(Y),
@@ -235,7 +243,7 @@ def pf_dense_linear_fwd(X, W, bias=None):
 def pf_dense_linear_bwd(X, W, dY, has_bias=False):
     M, n_in = X.shape
     n_out = W.shape[0]
-    d = pf_linear_desc(M, n_in, n_out, 1, _dtype_code(X), 1 if has_bias else 0)
+    d = pf_linear_desc(M, n_in, n_out, 1, _dtype_code(X), PF_F32, 1 if has_bias else 0)
     dX = torch.empty_like(X)
     dW = torch.empty((n_out, n_in), dtype=torch.float32, device=X.device)
     db = torch.empty((n_out,), dtype=torch.float32, device=X.device) if has_bias else None
@@ -251,7 +259,7 @@ def pf_dense_linear_bwd(X, W, dY, has_bias=False):
 def _conv_desc(X, Uk, Vp, stride, pad):
     N, C, H, W = X.shape
     r, _, k, _ = Uk.shape
-    return pf_conv_desc(N, C, H, W, Vp.shape[0], r, k, stride, pad, _dtype_code(X))
+    return pf_conv_desc(N, C, H, W, Vp.shape[0], r, k, stride, pad, PF_NCHW, _dtype_code(X), PF_F32)
 
 
 def conv_out_hw(d):
@@ -297,7 +305,7 @@ def pf_lowrank_conv_bwd(X, Uk, Vp, dY, T_saved=None, stride=1, pad=0, need_dX=Tr
 def pf_dense_conv_fwd(X, Wd, stride=1, pad=0):
     N, C, H, W = X.shape
     Cout, _, k, _ = Wd.shape
-    d = pf_conv_desc(N, C, H, W, Cout, 1, k, stride, pad, _dtype_code(X))
+    d = pf_conv_desc(N, C, H, W, Cout, 1, k, stride, pad, PF_NCHW, _dtype_code(X), PF_F32)
     Ho, Wo = conv_out_hw(d)
     Y = torch.empty((N, Cout, Ho, Wo), dtype=X.dtype, device=X.device)
     ws = _workspace(lib.pf_dense_conv_workspace_bytes(ctypes.byref(d)), X.device)
@@ -309,7 +317,7 @@ def pf_dense_conv_fwd(X, Wd, stride=1, pad=0):
 def pf_dense_conv_bwd(X, Wd, dY, stride=1, pad=0):
     N, C, H, W = X.shape
     Cout, _, k, _ = Wd.shape
-    d = pf_conv_desc(N, C, H, W, Cout, 1, k, stride, pad, _dtype_code(X))
+    d = pf_conv_desc(N, C, H, W, Cout, 1, k, stride, pad, PF_NCHW, _dtype_code(X), PF_F32)
     dX = torch.empty_like(X)
     dW = torch.empty(Wd.shape, dtype=torch.float32, device=X.device)
     ws = _workspace(lib.pf_dense_conv_workspace_bytes(ctypes.byref(d)), X.device)
@@ -478,9 +486,10 @@ def pf_lowrank_lstm_stack_bwd(x, h0, c0, h_all, c_all, gates_all, Tx_all, Th_all
     return dx_all, dh0, dc0, grads
 
 
-def pf_svd_split(W, r):
+def pf_svd_split(W, r, return_info=False):
     """Algorithm 1's factor initialisation: W[m, n] float32 -> (U[m, r], V[n, r], sigma[min(m, n)]) with
-    U V^T the best rank-r approximation of W and the singular values split evenly between the factors."""
+    U V^T the best rank-r approximation of W and the singular values split evenly between the factors.
+    With return_info also the int32 device tensor [sweeps run, rotations in the last sweep (0 = converged)]."""
     if W.dtype != torch.float32 or W.dim() != 2:
         raise PfError("pf_svd_split takes a 2-D float32 matrix")
     W = W.contiguous()
@@ -490,10 +499,11 @@ def pf_svd_split(W, r):
     U = torch.empty((m, r), dtype=torch.float32, device=dev)
     V = torch.empty((n, r), dtype=torch.float32, device=dev)
     sigma = torch.empty((min(m, n),), dtype=torch.float32, device=dev)
+    info = torch.empty((2,), dtype=torch.int32, device=dev) if return_info else None
     ws = _workspace(lib.pf_svd_split_workspace_bytes(ctypes.byref(d)), dev)
-    _check(lib.pf_svd_split(ctypes.byref(d), _ptr(W), _ptr(U), _ptr(V), _ptr(sigma), _ptr(ws),
+    _check(lib.pf_svd_split(ctypes.byref(d), _ptr(W), _ptr(U), _ptr(V), _ptr(sigma), _ptr(info), _ptr(ws),
                             ctypes.c_size_t(ws.numel()), _stream()), "pf_svd_split")
-    return U, V, sigma
+    return (U, V, sigma, info) if return_info else (U, V, sigma)
 
 
 def pf_svd_split_conv(Wd, r):

@@ -111,6 +111,8 @@ struct Workspace {
         used += bytes;
         return r;
     }
+    // false once the pieces handed out exceed the buffer: a plan and its call disagree
+    bool ok() const { return used <= size; }
 };
 
 } // namespace pf

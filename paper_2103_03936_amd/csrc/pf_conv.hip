@@ -120,6 +120,7 @@ static int check_conv_desc(const pf_conv_desc *d, ConvGeom *g)
 {
     if (!d) return PF_ERR_NULL;
     if (d->dtype != PF_F32 && d->dtype != PF_BF16) return PF_ERR_UNSUPPORTED;
+    if (d->layout != PF_NCHW || d->wgrad_dtype != PF_F32) return PF_ERR_UNSUPPORTED;
     if (d->N < 0 || d->Cin <= 0 || d->H <= 0 || d->W <= 0 || d->Cout <= 0 || d->r <= 0) return PF_ERR_SHAPE;
     if (d->k <= 0 || d->stride <= 0 || d->pad < 0 || d->k > 15) return PF_ERR_SHAPE;
     const i64 Ho = (d->H + 2 * (i64)d->pad - d->k) / d->stride + 1, Wo = (d->W + 2 * (i64)d->pad - d->k) / d->stride + 1;
@@ -446,6 +447,7 @@ int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, co
     if (any_misaligned({X, Uk, Vp, Y, T_save, W_save}, 16)) return PF_ERR_UNSUPPORTED;
     const ConvPlan p = plan_conv(g, d->dtype);
     if (p.fwd_bytes > 0 && (!workspace || workspace_bytes < p.fwd_bytes)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     if (g.N == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
@@ -471,6 +473,7 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, co
     if (any_misaligned({X, Uk, Vp, dY, T_saved, W_saved, dX}, 16) || any_misaligned({dUk, dVp}, 4)) return PF_ERR_UNSUPPORTED;
     const ConvPlan p = plan_conv(g, d->dtype);
     if (p.bwd_bytes > 0 && (!workspace || workspace_bytes < p.bwd_bytes)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     if (g.N == 0) {
@@ -526,6 +529,7 @@ int pf_dense_conv_bwd(const pf_conv_desc *d, const void *X, const void *Wd, cons
     if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
     const size_t need = plan_dense_conv(g).bytes;
     if (!workspace || workspace_bytes < need) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     if (d->dtype == PF_F32)

@@ -96,6 +96,7 @@ static int check_linear_desc(const pf_linear_desc *d)
 {
     if (!d) return PF_ERR_NULL;
     if (d->dtype != PF_F32 && d->dtype != PF_BF16) return PF_ERR_UNSUPPORTED;
+    if (d->wgrad_dtype != PF_F32) return PF_ERR_UNSUPPORTED; // parameter gradients are float sums
     if (d->M < 0 || d->in <= 0 || d->out <= 0 || d->r <= 0) return PF_ERR_SHAPE;
     const i64 lim = 0x7fffffffLL;
     if (d->M > lim || d->in > lim || d->out > lim || d->r > lim) return PF_ERR_SHAPE;
@@ -500,7 +501,7 @@ struct SharedPlan {
 static int check_shared_desc(const pf_linear_shared_desc *d, pf_linear_desc *one)
 {
     if (!d) return PF_ERR_NULL;
-    *one = pf_linear_desc{d->M, d->n_in, d->n_out, d->r, d->dtype, d->has_bias};
+    *one = pf_linear_desc{d->M, d->n_in, d->n_out, d->r, d->dtype, PF_F32, d->has_bias};
     int st = check_linear_desc(one);
     if (st != PF_OK) return st;
     if (d->groups <= 0 || d->groups > 64) return PF_ERR_SHAPE;
@@ -568,6 +569,7 @@ int pf::linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, 
     if (any_misaligned({X, V, U, bias, Y, T_save}, align)) return PF_ERR_UNSUPPORTED;
     const size_t need = plan_linear(d).fwd_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     if (d->M == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
@@ -595,6 +597,7 @@ int pf::linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, 
     if (any_misaligned({X, V, U, dY, T_saved, dX}, align) || any_misaligned({dU, dV, dbias}, 4)) return PF_ERR_UNSUPPORTED;
     const size_t need = plan_linear(d).bwd_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     if (d->dtype == PF_F32 && plan_linear(d).skinny)
@@ -674,6 +677,7 @@ int pf_dense_linear_bwd(const pf_linear_desc *d, const void *X, const void *W, c
     if (d->M > 0 && (!X || !dY)) return PF_ERR_NULL;
     const size_t need = plan_dense_linear(d).bytes;
     if (!workspace || workspace_bytes < need) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     if (d->dtype == PF_F32)
@@ -709,6 +713,7 @@ int pf_lowrank_linear_shared_fwd(const pf_linear_shared_desc *d, const void *X, 
     if (any_misaligned({X, V, U, bias, Y, T_save}, 16)) return PF_ERR_UNSUPPORTED;
     const SharedPlan sp = plan_shared(d, one);
     if (sp.fwd_bytes > 0 && (!workspace || workspace_bytes < sp.fwd_bytes)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     if (d->M == 0) return PF_OK;
     const i64 M = d->M, in = d->n_in, out = d->n_out, r = d->r;
     hipStream_t s = (hipStream_t)stream;
@@ -745,6 +750,7 @@ int pf_lowrank_linear_shared_bwd(const pf_linear_shared_desc *d, const void *X, 
     if (any_misaligned({X, V, U, dY, T_saved, dX}, 16) || any_misaligned({dU, dV, dbias}, 4)) return PF_ERR_UNSUPPORTED;
     const SharedPlan sp = plan_shared(d, one);
     if (!workspace || workspace_bytes < sp.bwd_bytes) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     hipStream_t s = (hipStream_t)stream;
     const i64 M = d->M, in = d->n_in, out = d->n_out, r = d->r;
     const int G = d->groups;

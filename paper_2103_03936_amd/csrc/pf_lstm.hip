@@ -492,6 +492,7 @@ int pf_lowrank_lstm_cell_fwd(const pf_lstm_desc *d, const void *x, const void *h
     if (d->B == 0) return PF_OK; // nothing to compute, nothing to check
     const size_t need = pf_lowrank_lstm_cell_fwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     if (lstm_skinny_ok(d))
         return lstm_fwd_skinny(d, (const float *)x, (const float *)h_prev, (const float *)c_prev, (const float *)Vx,
@@ -523,6 +524,7 @@ int pf_lowrank_lstm_cell_bwd(const pf_lstm_desc *d, const void *x, const void *h
         return PF_ERR_UNSUPPORTED;
     const size_t need = pf_lowrank_lstm_cell_bwd_workspace_bytes(d);
     if (need > 0 && (!workspace || workspace_bytes < need)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     if (lstm_skinny_ok(d))
         return lstm_bwd_skinny(d, (const float *)x, (const float *)h_prev, (const float *)c_prev,

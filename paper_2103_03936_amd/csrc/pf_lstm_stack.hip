@@ -1038,8 +1038,9 @@ static int plan_stack(const StackGeom &g, StackPlan *out)
         *out = p;
         return PF_OK;
     }
-    p.n_zx0 = (size_t)(Mt * 4 * g.h);
-    p.n_dz = p.n_zx0;
+    p.n_dz = (size_t)(Mt * 4 * g.h);
+    // pre-activations of the first layer's input path for all steps: the fused schedule forms them step by step
+    p.n_zx0 = zg_supported(g.G, g.r) ? 0 : p.n_dz;
     p.n_dT = (size_t)(Mt * g.gr);
     size_t m = 0, m2 = 0;
     auto upd = [&](size_t v) {
@@ -1140,11 +1141,13 @@ int pf_lowrank_lstm_stack_fwd(const pf_lstm_stack_desc *d, const void *x, const 
     st = plan_stack(g, &pl);
     if (st != PF_OK) return st;
     if (!workspace || workspace_bytes < pl.fwd_bytes) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     float *zx0 = ws.take<float>(pl.n_zx0);
     float *part = ws.take<float>(pl.n_part);
     float *packed = ws.take<float>(pl.n_pack_f);
+    if (!ws.ok()) return PF_ERR_WORKSPACE;
     StackPacked pk = {};
     stack_pack(g, p, false, packed, &pk, false, s, &st);
     if (st != PF_OK) return st;
@@ -1236,6 +1239,7 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x, const 
     st = plan_stack(g, &pl);
     if (st != PF_OK) return st;
     if (!workspace || workspace_bytes < pl.bwd_bytes) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     for (int l = 0; l < L; ++l) {
         b.dz_all[l] = ws.take<float>(pl.n_dz);
@@ -1245,6 +1249,7 @@ int pf_lowrank_lstm_stack_bwd(const pf_lstm_stack_desc *d, const void *x, const 
     float *part = ws.take<float>(pl.n_part);
     float *part2 = ws.take<float>(pl.n_part2);
     float *packed = ws.take<float>(pl.n_pack_b);
+    if (!ws.ok()) return PF_ERR_WORKSPACE;
     StackPacked pk = {};
     stack_pack(g, p, true, packed, &pk, false, s, &st);
     if (st != PF_OK) return st;

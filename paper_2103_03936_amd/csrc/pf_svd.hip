@@ -13,7 +13,14 @@
 namespace pf {
 
 constexpr int SVD_MAX_SWEEPS = 24;
-constexpr double SVD_TOL = 1e-15; // a pair counts as orthogonal when |a_p . a_q| <= tol |a_p| |a_q|
+// A pair counts as orthogonal when |a_p . a_q| <= tol |a_p| |a_q|.  The inner product of two columns of `rows`
+// doubles carries rounding noise of about rows * 2^-53 relative to |a_p| |a_q|, so a tighter threshold never stops
+// the sweeps; rows * 2^-52 still leaves the fp32 factors exact to their last bit.
+static double svd_tolerance(int rows)
+{
+    const double t = (double)rows * 2.220446049250313e-16;
+    return t < 1e-15 ? 1e-15 : t;
+}
 
 __global__ __launch_bounds__(256) void svd_init_kernel(const float *W, double *At, double *Qt, int n, int nr, int nc,
                                                         int transposed)
@@ -27,7 +34,7 @@ __global__ __launch_bounds__(256) void svd_init_kernel(const float *W, double *A
 }
 
 __global__ __launch_bounds__(256) void svd_round_kernel(double *At, double *Qt, int nr, int nc, int npad, int round,
-                                                         int sweep, unsigned *rot)
+                                                         int sweep, unsigned *rot, double tol)
 {
     if (sweep > 0 && rot[sweep - 1] == 0u) return; // the sweep before found every pair orthogonal
     const int k = blockIdx.x, m1 = npad - 1, tid = threadIdx.x;
@@ -65,7 +72,7 @@ __global__ __launch_bounds__(256) void svd_round_kernel(double *At, double *Qt, 
         alpha = red[0][0];
         beta = red[1][0];
         gamma = red[2][0];
-        int doit = !(fabs(gamma) <= SVD_TOL * sqrt(alpha * beta) || gamma == 0.0);
+        int doit = !(fabs(gamma) <= tol * sqrt(alpha * beta) || gamma == 0.0);
         if (doit) {
             const double zeta = (beta - alpha) / (2.0 * gamma);
             const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
@@ -121,8 +128,19 @@ __global__ __launch_bounds__(256) void svd_rank_kernel(const double *sig, int *r
 // column j of A (= sigma_j x left vector) and of Q (right vector) -> column rank[j] of the balanced factors
 __global__ __launch_bounds__(256) void svd_emit_kernel(const double *At, const double *Qt, const double *sig,
                                                         const int *rank, float *U, float *V, float *sigma_out, int nr,
-                                                        int nc, int r, int transposed)
+                                                        int nc, int r, int transposed, const unsigned *rot, int *info)
 {
+    if (info && blockIdx.x == 0 && threadIdx.x == 0) {
+        // sweeps that ran (the first one that rotated nothing ends them) and rotations of the last one
+        int ran = SVD_MAX_SWEEPS;
+        for (int sw = 0; sw < SVD_MAX_SWEEPS; ++sw)
+            if (rot[sw] == 0u) {
+                ran = sw + 1;
+                break;
+            }
+        info[0] = nc > 1 ? ran : 0;
+        info[1] = nc > 1 ? (int)rot[ran - 1] : 0;
+    }
     const int j = blockIdx.x, k = rank[j];
     const double s = sig[j];
     if (threadIdx.x == 0 && sigma_out) sigma_out[k] = (float)s;
@@ -168,14 +186,16 @@ size_t pf_svd_split_workspace_bytes(const pf_svd_desc *d)
     return plan_svd(d, &p) == PF_OK ? p.bytes : 0;
 }
 
-int pf_svd_split(const pf_svd_desc *d, const void *W, void *U, void *V, void *sigma, void *workspace,
+int pf_svd_split(const pf_svd_desc *d, const void *W, void *U, void *V, void *sigma, void *info, void *workspace,
                  size_t workspace_bytes, void *stream)
 {
     SvdPlan p;
     int st = plan_svd(d, &p);
     if (st != PF_OK) return st;
     if (!W || !U || !V) return PF_ERR_NULL;
+    if (any_misaligned({W, U, V, sigma, info}, 4)) return PF_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < p.bytes) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
     double *At = ws.take<double>(p.n_At), *Qt = ws.take<double>(p.n_Qt), *sig = ws.take<double>(p.nc);
@@ -190,13 +210,13 @@ int pf_svd_split(const pf_svd_desc *d, const void *W, void *U, void *V, void *si
         for (int sweep = 0; sweep < SVD_MAX_SWEEPS && st == PF_OK; ++sweep)
             for (int round = 0; round < p.npad - 1 && st == PF_OK; ++round)
                 PF_LAUNCH(st, "svd_jacobi_round", svd_round_kernel, dim3(p.npad / 2), dim3(256), s, At, Qt, p.nr, p.nc,
-                          p.npad, round, sweep, rot);
+                          p.npad, round, sweep, rot, svd_tolerance(p.nr));
     }
     PF_LAUNCH(st, "svd_sigma", svd_sigma_kernel, dim3(p.nc), dim3(256), s, (const double *)At, sig, p.nr);
     PF_LAUNCH(st, "svd_rank", svd_rank_kernel, dim3((p.nc + 255) / 256), dim3(256), s, (const double *)sig, rank, p.nc);
     PF_LAUNCH(st, "svd_emit", svd_emit_kernel, dim3(p.nc), dim3(256), s, (const double *)At, (const double *)Qt,
               (const double *)sig, (const int *)rank, (float *)U, (float *)V, (float *)sigma, p.nr, p.nc, (int)d->r,
-              p.transposed);
+              p.transposed, (const unsigned *)rot, (int *)info);
     return st;
 }
 

@@ -32,8 +32,8 @@ def test_status_strings():
     assert pf.lib.pf_version() >= 1
 
 
-def _lin(M=4, n_in=5, n_out=3, r=2, dtype=0, bias=0):
-    return pf.pf_linear_desc(M, n_in, n_out, r, dtype, bias)
+def _lin(M=4, n_in=5, n_out=3, r=2, dtype=0, bias=0, wgrad_dtype=0):
+    return pf.pf_linear_desc(M, n_in, n_out, r, dtype, wgrad_dtype, bias)
 
 
 def test_linear_validation():
@@ -44,6 +44,10 @@ def test_linear_validation():
     assert f(ctypes.byref(_lin(r=-1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
     assert f(ctypes.byref(_lin(M=-1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 2
     assert f(ctypes.byref(_lin(dtype=7)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 3
+    # parameter gradients come as float only
+    assert f(ctypes.byref(_lin(wgrad_dtype=1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 3
+    assert pf.lib.pf_lowrank_linear_bwd(ctypes.byref(_lin(dtype=1, wgrad_dtype=1)), FAKE, FAKE, FAKE, FAKE, None, FAKE,
+                                        FAKE, FAKE, None, 0, FAKE, ctypes.c_size_t(1 << 30), None) == 3
     assert f(ctypes.byref(_lin()), None, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
     assert f(ctypes.byref(_lin(bias=1)), FAKE, FAKE, FAKE, None, FAKE, None, None, z, None) == 1
     # workspace too small / missing
@@ -63,6 +67,8 @@ def test_linear_validation():
     assert b(ctypes.byref(_lin()), FAKE, FAKE, odd, FAKE, None, FAKE, FAKE, FAKE, None, 0, None, z, None) == 3
     assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, odd2, FAKE, None, 0, None, z, None) == 3
     assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, odd, odd, None, 0, None, z, None) == 4
+    assert b(ctypes.byref(_lin()), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, 0, P(256 + 16),
+             ctypes.c_size_t(1 << 30), None) == 3  # workspace not 256-byte aligned
     # full rank and beyond is legal
     assert pf.lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(_lin(r=64))) >= 0
 
@@ -90,8 +96,8 @@ def test_linear_shared_validation():
     assert b(d(), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, 0, FAKE, ctypes.c_size_t(need - 1), None) == 4
 
 
-def _conv(N=2, C=3, H=5, W=5, Cout=4, r=2, k=3, s=1, p=1, dtype=0):
-    return pf.pf_conv_desc(N, C, H, W, Cout, r, k, s, p, dtype)
+def _conv(N=2, C=3, H=5, W=5, Cout=4, r=2, k=3, s=1, p=1, dtype=0, layout=0, wgrad_dtype=0):
+    return pf.pf_conv_desc(N, C, H, W, Cout, r, k, s, p, layout, dtype, wgrad_dtype)
 
 
 def test_conv_validation():
@@ -102,6 +108,11 @@ def test_conv_validation():
     assert f(ctypes.byref(_conv(s=0)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 2
     assert f(ctypes.byref(_conv(H=2, W=2, k=5, p=0)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 2
     assert f(ctypes.byref(_conv(dtype=9)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 3
+    # NCHW activations and float filter gradients are what is built
+    assert f(ctypes.byref(_conv(layout=pf.PF_NHWC)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 3
+    assert f(ctypes.byref(_conv(wgrad_dtype=pf.PF_BF16)), FAKE, FAKE, FAKE, FAKE, None, None, None, z, None) == 3
+    assert pf.lib.pf_lowrank_conv_bwd(ctypes.byref(_conv(layout=1)), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE,
+                                      0, FAKE, ctypes.c_size_t(1 << 30), None) == 3
     assert f(ctypes.byref(_conv()), FAKE, None, FAKE, FAKE, None, None, None, z, None) == 1
     d = _conv()
     need = pf.lib.pf_lowrank_conv_fwd_workspace_bytes(ctypes.byref(d))
@@ -177,6 +188,7 @@ def test_lstm_stack_validation():
     assert f(ctypes.byref(mk()), FAKE, *args, None, z, None) == 3
     assert f(ctypes.byref(mk()), None, *per_layer(), None, z, None) == 1            # x
     assert f(ctypes.byref(mk()), FAKE, *per_layer(), None, z, None) == 4            # workspace missing
+    assert f(ctypes.byref(mk()), FAKE, *per_layer(), P(256 + 128), ctypes.c_size_t(1 << 30), None) == 3   # misaligned
     assert f(ctypes.byref(mk(T=0)), FAKE, *per_layer(), None, z, None) == 0
     assert f(ctypes.byref(mk(B=0)), FAKE, *per_layer(), None, z, None) == 0
     for q in (pf.lib.pf_lowrank_lstm_stack_fwd_workspace_bytes, pf.lib.pf_lowrank_lstm_stack_bwd_workspace_bytes):
@@ -193,10 +205,13 @@ def test_svd_validation():
     f = pf.lib.pf_svd_split
     z = ctypes.c_size_t(0)
     mk = lambda m=8, n=6, r=3: pf.pf_svd_desc(m, n, r)
-    assert f(None, FAKE, FAKE, FAKE, None, None, z, None) == 1
-    assert f(ctypes.byref(mk(r=7)), FAKE, FAKE, FAKE, None, None, z, None) == 2   # r > min(m, n)
-    assert f(ctypes.byref(mk(m=0)), FAKE, FAKE, FAKE, None, None, z, None) == 2
-    assert f(ctypes.byref(mk(m=20000, n=20000, r=4)), FAKE, FAKE, FAKE, None, None, z, None) == 3
-    assert f(ctypes.byref(mk()), None, FAKE, FAKE, None, None, z, None) == 1
-    assert f(ctypes.byref(mk()), FAKE, FAKE, FAKE, None, None, z, None) == 4      # workspace missing
+    assert f(None, FAKE, FAKE, FAKE, None, None, None, z, None) == 1
+    assert f(ctypes.byref(mk(r=7)), FAKE, FAKE, FAKE, None, None, None, z, None) == 2   # r > min(m, n)
+    assert f(ctypes.byref(mk(m=0)), FAKE, FAKE, FAKE, None, None, None, z, None) == 2
+    assert f(ctypes.byref(mk(m=20000, n=20000, r=4)), FAKE, FAKE, FAKE, None, None, None, z, None) == 3
+    assert f(ctypes.byref(mk()), None, FAKE, FAKE, None, None, None, z, None) == 1
+    assert f(ctypes.byref(mk()), FAKE, FAKE, FAKE, None, None, None, z, None) == 4      # workspace missing
+    assert f(ctypes.byref(mk()), FAKE, FAKE, FAKE, None, P(258), FAKE, ctypes.c_size_t(1 << 30), None) == 3  # info
+    # a workspace that is not 256-byte aligned is refused by every entry point that takes one
+    assert f(ctypes.byref(mk()), FAKE, FAKE, FAKE, None, None, P(256 + 64), ctypes.c_size_t(1 << 30), None) == 3
     assert pf.lib.pf_svd_split_workspace_bytes(ctypes.byref(mk())) > 0

@@ -404,20 +404,22 @@ def test_layer_stack_matches_sequence_layers_full_size():
     assert_close(dx, above.double().cpu().numpy(), "f32", "full size dx")
 
 
-def test_layer_stack_full_size_against_oracle():
+@pytest.mark.parametrize("groups", [1, 4])
+def test_layer_stack_full_size_against_oracle(groups):
     """The language model's two layers over all 35 steps at batch 20 (Appendix D), forward and back-propagation
-    through time and depth, directly against the fp64 oracle."""
+    through time and depth, directly against the fp64 oracle: with one rank-375 factor pair per path (groups = 1,
+    the fused schedule) and with one pair per gate and path (groups = 4, Appendix D's table, the general schedule)."""
     import paper_2103_03936_amd as pf
     T, B, d, h, r, L = 35, 20, 1500, 1500, 375, 2
-    a = _stack_inputs(T, B, d, h, r, 1, L, seed=21)
+    a = _stack_inputs(T, B, d, h, r, groups, L, seed=21)
     ho, co, go, Txo, Tho = oracle.lowrank_lstm_stack_fwd(a["x"], a["h0"], a["c0"], a["Vx"], a["Ux"], a["Vh"], a["Uh"],
-                                                         a["bias"], 1)
+                                                         a["bias"], groups)
     dxo, dh0o, dc0o, gro = oracle.lowrank_lstm_stack_bwd(a["x"], a["h0"], a["c0"], ho, co, go, Txo, Tho, a["Vx"],
-                                                        a["Ux"], a["Vh"], a["Uh"], a["dh_top"], a["dhT"], a["dcT"], 1)
+                                                        a["Ux"], a["Vh"], a["Uh"], a["dh_top"], a["dhT"], a["dcT"], groups)
     g = _gpu_lists(a)
-    outs = pf.pf_lowrank_lstm_stack_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["bias"], 1)
+    outs = pf.pf_lowrank_lstm_stack_fwd(g["x"], g["h0"], g["c0"], g["Vx"], g["Ux"], g["Vh"], g["Uh"], g["bias"], groups)
     dx, dh0, dc0, gr = pf.pf_lowrank_lstm_stack_bwd(g["x"], g["h0"], g["c0"], *outs, g["Vx"], g["Ux"], g["Vh"], g["Uh"],
-                                                    g["dh_top"], g["dhT"], g["dcT"], 1)
+                                                    g["dh_top"], g["dhT"], g["dcT"], groups)
     for l in range(L):
         for name, got, want in (("h", outs[0], ho), ("c", outs[1], co), ("gates", outs[2], go), ("Tx", outs[3], Txo),
                                 ("Th", outs[4], Tho)):

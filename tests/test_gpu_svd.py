@@ -63,6 +63,25 @@ def test_rank_deficient_matrix():
     assert_close(U.double() @ V.double().t(), W.astype(np.float64), "f32", "rank-deficient reconstruction")
 
 
+def test_convergence_is_reported_and_sweeps_stop():
+    """The rounding-level threshold lets a converged sweep end the launches (info[0] well below the 24-sweep cap,
+    info[1] == 0), also for an ill-conditioned matrix (singular values over nine decades) and a rank-deficient one."""
+    import paper_2103_03936_amd as pf
+    q1, _ = np.linalg.qr(_matrix(300, 60, 7).astype(np.float64))
+    q2, _ = np.linalg.qr(_matrix(60, 60, 8).astype(np.float64))
+    ill = ((q1 * np.logspace(0, -9, 60)) @ q2.T).astype(np.float32)
+    deficient = (_matrix(200, 4, 9).astype(np.float64) @ _matrix(4, 90, 10).astype(np.float64)).astype(np.float32)
+    for tag, W, r in (("well conditioned", _matrix(2000, 200, 11), 50), ("ill conditioned", ill, 20),
+                      ("rank deficient", deficient, 6)):
+        U, V, sigma, info = pf.pf_svd_split(to_gpu(W), r, return_info=True)
+        sweeps, last = (int(v) for v in info.cpu())
+        assert last == 0, f"{tag}: {last} rotations in the last of {sweeps} sweeps"
+        assert 1 <= sweeps <= 16, f"{tag}: {sweeps} sweeps"
+        Uo, Vo, so = oracle.svd_split(W.astype(np.float64), r)
+        assert np.max(np.abs(sigma.double().cpu().numpy() - so)) <= 1e-5 * so[0], tag
+        assert_close(U.double() @ V.double().t(), Uo @ Vo.T, "f32", tag + " U V^T")
+
+
 def test_conv_filter_bank():
     """ResNet-18 conv4_x filter bank 256 x 256 x 3 x 3 at rank 64 (Section 2.2 unrolling): the factorized layer's
     composed dense filters equal the oracle's rank-64 truncation."""

@@ -59,6 +59,12 @@ class _Buffers:
         self.lib.emu_register(ctypes.c_void_p(a.ctypes.data), ctypes.c_size_t(a.nbytes))
         return a
 
+    def workspace(self, nbytes):
+        """nbytes of zeroed scratch memory, 256-byte aligned as the entry points require."""
+        raw = np.zeros(nbytes + 256, dtype=np.uint8)
+        off = (-raw.ctypes.data) % 256
+        return self.reg(raw[off:off + nbytes])
+
     def copy(self, a):
         out = self._aligned(a.size).reshape(a.shape)
         out[...] = a
@@ -126,7 +132,7 @@ def test_stack_host_logic_against_oracle(emu, case):
     fb = copies(bs) if bias else None
     outs = [[m.new(T, B, n) for _ in range(L)] for n in (h, h, 4 * h, gr, gr)]
     nbytes = emu.pf_lowrank_lstm_stack_fwd_workspace_bytes(ctypes.byref(desc))
-    ws = m.reg(np.zeros(max(nbytes, 16), dtype=np.uint8))
+    ws = m.workspace(max(nbytes, 16))
     st = emu.pf_lowrank_lstm_stack_fwd(ctypes.byref(desc), _p(fx), _pa(fh0), _pa(fc0), _pa(fVx), _pa(fUx), _pa(fVh),
                                        _pa(fUh), _pa(fb), *[_pa(v) for v in outs], _p(ws), ctypes.c_size_t(nbytes), None)
     assert st == 0, (st, emu.emu_error())
@@ -141,7 +147,7 @@ def test_stack_host_logic_against_oracle(emu, case):
     grads = {k: [m.new(*v[l].shape) for l in range(L)] for k, v in (("dVx", Vx), ("dUx", Ux), ("dVh", Vh), ("dUh", Uh))}
     grads["dbias"] = [m.new(4 * h) for _ in range(L)]
     nbytes = emu.pf_lowrank_lstm_stack_bwd_workspace_bytes(ctypes.byref(desc))
-    ws2 = m.reg(np.zeros(max(nbytes, 16), dtype=np.uint8))
+    ws2 = m.workspace(max(nbytes, 16))
     st = emu.pf_lowrank_lstm_stack_bwd(
         ctypes.byref(desc), _p(fx), _pa(fh0), _pa(fc0), *[_pa(v) for v in outs], _pa(fVx), _pa(fUx), _pa(fVh), _pa(fUh),
         _p(fdtop), _pa(fdhT), _pa(fdcT), _p(dx), _pa(dh0), _pa(dc0), _pa(grads["dVx"]), _pa(grads["dUx"]),
@@ -160,7 +166,7 @@ def test_a_workspace_one_byte_short_is_refused(emu):
     need = emu.pf_lowrank_lstm_stack_fwd_workspace_bytes(ctypes.byref(desc))
     a = lambda n=2: (ctypes.c_void_p * n)(*([256] * n))
     args = [a() for _ in range(12)]
-    ws = m.reg(np.zeros(need, dtype=np.uint8))
+    ws = m.workspace(need)
     st = emu.pf_lowrank_lstm_stack_fwd(ctypes.byref(desc), ctypes.c_void_p(256), *args, _p(ws), ctypes.c_size_t(need - 1),
                                        None)
     assert st == 4
