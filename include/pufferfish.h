@@ -102,6 +102,25 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
                           int accumulate, void *workspace,
                           size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or hand over a         */
+/* workspace (code running under HIP graph capture, tight serving        */
+/* loops, harnesses that forbid hipMalloc): pf_lowrank_linear_bwd with   */
+/* its scratch memory in a device array that is part of the library,     */
+/* PF_STATIC_SCRATCH_BYTES per GPU, held until the process ends.  Same   */
+/* arguments, results and errors as pf_lowrank_linear_bwd minus the      */
+/* workspace; a descriptor whose pf_lowrank_linear_bwd_workspace_bytes   */
+/* exceeds PF_STATIC_SCRATCH_BYTES gets PF_ERR_WORKSPACE.  The call      */
+/* allocates and frees nothing.  All calls on one GPU share that GPU's   */
+/* array: calls enqueued on one stream are ordered and safe, calls that  */
+/* can overlap on one GPU (different streams, different threads) race.   */
+#define PF_STATIC_SCRATCH_BYTES (40u << 20)
+size_t pf_static_scratch_bytes(void);
+int pf_lowrank_linear_bwd_static(const pf_linear_desc *d, const void *X,
+                                 const void *V, const void *U, const void *dY,
+                                 const void *T_saved /* nullable */, void *dX,
+                                 void *dU, void *dV, void *dbias,
+                                 int accumulate, void *stream);
+
 /* ------------------------------------------------------------------ */
 /* Several factorized projections of the same shape that read the SAME */
 /* input, e.g. the query, key and value matrices of an attention block  */

@@ -62,7 +62,7 @@ class pf_svd_desc(ctypes.Structure):
 EXPORTS = [
     "pf_status_string", "pf_last_hip_error", "pf_version",
     "pf_lowrank_linear_fwd_workspace_bytes", "pf_lowrank_linear_bwd_workspace_bytes",
-    "pf_lowrank_linear_fwd", "pf_lowrank_linear_bwd",
+    "pf_lowrank_linear_fwd", "pf_lowrank_linear_bwd", "pf_static_scratch_bytes", "pf_lowrank_linear_bwd_static",
     "pf_lowrank_linear_shared_fwd_workspace_bytes", "pf_lowrank_linear_shared_bwd_workspace_bytes",
     "pf_lowrank_linear_shared_fwd", "pf_lowrank_linear_shared_bwd",
     "pf_lowrank_conv_fwd_workspace_bytes", "pf_lowrank_conv_bwd_workspace_bytes",
@@ -87,7 +87,7 @@ if not os.path.exists(LIB_PATH):
 lib = ctypes.CDLL(LIB_PATH)
 lib.pf_status_string.restype = ctypes.c_char_p
 for _n in EXPORTS:
-    if _n.endswith("_bytes"):
+    if _n.endswith("_bytes"):  # (size_t results)
         getattr(lib, _n).restype = ctypes.c_size_t
 
 
@@ -185,6 +185,19 @@ def pf_lowrank_linear_bwd(X, V, U, dY, T_saved=None, need_dX=True, has_bias=Fals
                                      _ptr(db, torch.float32), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
                                      ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_linear_bwd")
     return dX, dU, dV, db
+
+
+def pf_lowrank_linear_bwd_static(X, V, U, dY, T_saved, dX, dU, dV, dbias=None, accumulate=False):
+    """pf_lowrank_linear_bwd with the library's own scratch array: no workspace and no allocation, so every output
+    tensor is the caller's (dX, dbias nullable).  Raises PfError (workspace status) when the layer needs more scratch
+    memory than the library holds."""
+    d = _linear_desc(X, U, dbias is not None)
+    dt, f32 = X.dtype, torch.float32
+    _check(lib.pf_lowrank_linear_bwd_static(ctypes.byref(d), _ptr(X, dt), _ptr(V, dt), _ptr(U, dt), _ptr(dY, dt),
+                                            _ptr(T_saved, dt), _ptr(dX, dt), _ptr(dU, f32), _ptr(dV, f32),
+                                            _ptr(dbias, f32), ctypes.c_int(1 if accumulate else 0), _stream()),
+           "pf_lowrank_linear_bwd_static")
+    return dX, dU, dV, dbias
 
 
 def _shared_desc(X, U, bias_flag):

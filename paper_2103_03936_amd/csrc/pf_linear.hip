@@ -5,6 +5,7 @@
 #include "pf_linear_chain.h"
 #include "pf_skinny.h"
 #include "pf_conv_wgrad.h"
+#include <mutex>
 #include "pf_gemm.h"
 
 namespace pf {
@@ -644,6 +645,58 @@ int pf_lowrank_linear_bwd(const pf_linear_desc *d, const void *X, const void *V,
 {
     return pf::linear_bwd_entry(d, X, V, U, dY, T_saved, dX, dU, dV, dbias, accumulate, workspace, workspace_bytes,
                                 stream, 16);
+}
+
+} // extern "C"
+
+// ---------------------------------------------------- library-owned scratch
+// Backward for callers that cannot allocate: the partial sums of the factor gradients, the rank-r gradient dT
+// and a recomputed T live in this array instead of a caller's workspace.  Every GPU the library runs on holds
+// its own copy at its own address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[PF_STATIC_SCRATCH_BYTES];
+
+namespace pf {
+constexpr int SCRATCH_MAX_DEVICES = 64;
+static void *g_scratch_addr[SCRATCH_MAX_DEVICES]; // per device, looked up once
+static std::mutex g_scratch_lock;
+
+// Device address of `scratch` on the current device (no allocation: the array came with the code object).
+static int scratch_on_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= SCRATCH_MAX_DEVICES)
+        return set_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_addr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return set_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_scratch_addr[dev] = ptr;
+    }
+    *out = g_scratch_addr[dev];
+    return PF_OK;
+}
+} // namespace pf
+
+extern "C" {
+
+size_t pf_static_scratch_bytes(void) { return (size_t)PF_STATIC_SCRATCH_BYTES; }
+
+int pf_lowrank_linear_bwd_static(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
+                                 const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate,
+                                 void *stream)
+{
+    int st = check_linear_desc(d);
+    if (st != PF_OK) return st;
+    if (plan_linear(d).bwd_bytes > (size_t)PF_STATIC_SCRATCH_BYTES) return PF_ERR_WORKSPACE;
+    void *ptr = nullptr;
+    st = scratch_on_current_device(&ptr);
+    if (st != PF_OK) return st;
+    // nothing in the backward pass reads scratch memory before writing it, so what the last call left is harmless
+    return pf::linear_bwd_entry(d, X, V, U, dY, T_saved, dX, dU, dV, dbias, accumulate, ptr,
+                                (size_t)PF_STATIC_SCRATCH_BYTES, stream, 16);
 }
 
 size_t pf_dense_linear_workspace_bytes(const pf_linear_desc *d)
