@@ -3,14 +3,23 @@
 
 A step is one forward (T saved) plus one backward (dX, both factor gradients) of the
 workload's factorized layer(s) on synthetic inputs that are already resident in HBM.  The
-default workload is the CIFAR ResNet-18 conv4_x factorized 3x3 convolution at batch 128
-(bf16 inputs, fp32 accumulation).  Steps rotate over enough distinct buffer sets to exceed
-the 256 MB last-level cache, so every step reads its activations from HBM.
+headline workload is the largest of the five benchmark configurations, the three
+factorized convolutions of a ResNet-50 conv5_x bottleneck at batch 256 (bf16 inputs, fp32
+accumulation); the other four configurations are measured in the same run and reported
+in the `workloads` list of the same line.  Steps rotate over enough distinct buffer sets
+to exceed the 256 MB last-level cache, so every step reads its activations from HBM.
+
+Exactly --steps steps are timed per repetition (HIP-graph replay); repetitions are added
+until at least 50 ms of GPU time have been measured, and the median repetition is reported
+with the spread.
 
 Prints ONE JSON line: throughput in algorithmic TFLOP/s (6 M r (C k^2 + Cout) per
-factorized layer), the roofline figures of the kernel that takes the most time (timed
-live with HIP events around every launch), the dense un-factorized layer on the same
-tiling code, and the CPU oracle timed on this machine's host cores.
+factorized layer), the fraction of the MFMA peak and of min(peak, intensity x HBM
+bandwidth), the roofline figures of the kernel that takes the most time (timed live with
+HIP events around every launch), the dense un-factorized layer through the vendor
+library, the same factorized layer as two vendor-library launches per direction with the
+rank-r intermediate round-tripping HBM (the unfused leg), and the CPU oracle timed on
+this machine's host cores, all cores and one.
 """
 import argparse
 import json
@@ -70,11 +79,6 @@ class ConvWorkload:
             if "Wd" not in g:
                 g["Wd"] = torch.einsum("oq,qcij->ocij", g["Vp"].float(), g["Uk"].float()).to(g["X"].dtype).contiguous()
 
-    def dense_step(self, pf, s):
-        for g in s.values():
-            pf.pf_dense_conv_fwd(g["X"], g["Wd"], 1, g["pad"])
-            pf.pf_dense_conv_bwd(g["X"], g["Wd"], g["dY"], 1, g["pad"])
-
     def library_dense_prepare(self, s, torch):
         out = []
         for g in s.values():
@@ -117,17 +121,38 @@ class ConvWorkload:
             add("conv_wgrad_pair", f1 + f2, s * (npix * C + npix * Co + 2 * npix * r) + 4 * (r * K + Co * r))
         return out
 
-    def cpu_baseline(self, oracle, workloads, reps=3):
-        inputs = [(workloads.conv_inputs(self.N, C, self.H, self.W, Co, r, k, 1, p, dtype=self.dtype, seed=self.seed), p)
+    def algorithmic_bytes(self):
+        w = self.kernel_work()
+        return sum(w[k][1] for k in ("conv_fwd_fused", "conv_bwd_data_fused", "conv_wgrad_pair"))
+
+    def library_lowrank_prepare(self, s, torch):
+        out = []
+        for g in s.values():
+            leaf = lambda t: t.detach().clone().requires_grad_(True)
+            out.append((leaf(g["X"]), leaf(g["Uk"]), leaf(g["Vp"][:, :, None, None]), g["dY"], g["pad"]))
+        return out
+
+    def library_lowrank_step(self, prep, torch):
+        """The factorized layer as the paper ran it: two library convolutions per direction, T through HBM."""
+        F = torch.nn.functional
+        for X, Uk, Vp, dY, pad in prep:
+            X.grad = Uk.grad = Vp.grad = None
+            F.conv2d(F.conv2d(X, Uk, padding=pad), Vp).backward(dY)
+
+    def cpu_baseline(self, oracle, workloads, images=None):
+        """Seconds of one fwd+bwd of every layer on `images` images of the batch (None = all), and its flops."""
+        n = self.N if images is None else min(images, self.N)
+        inputs = [(workloads.conv_inputs(n, C, self.H, self.W, Co, r, k, 1, p, dtype=self.dtype, seed=self.seed), p)
                   for C, Co, r, k, p in self.layers.values()]
-        times = []
-        for rep in range(reps):
-            t0 = time.perf_counter()
-            for a, p in inputs:
-                oracle.lowrank_conv_fwd(a["X"], a["Uk"], a["Vp"], 1, p)
-                oracle.lowrank_conv_bwd(a["X"], a["Uk"], a["Vp"], a["dY"], 1, p)
-            times.append(time.perf_counter() - t0)
-        return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
+        t0 = time.perf_counter()
+        for a, p in inputs:
+            oracle.lowrank_conv_fwd(a["X"], a["Uk"], a["Vp"], 1, p)
+            oracle.lowrank_conv_bwd(a["X"], a["Uk"], a["Vp"], a["dY"], 1, p)
+        secs = time.perf_counter() - t0
+        return secs, self.flops() * n / self.N, f"fwd+bwd of every layer on {n} of {self.N} images, one run"
+
+    def cpu_single_thread_sample(self):
+        return max(1, self.N // 16)
 
 
 class LinearWorkload:
@@ -188,12 +213,6 @@ class LinearWorkload:
             if "W" not in g:
                 g["W"] = (g["U"].float() @ g["V"].float().transpose(-1, -2)).to(g["X"].dtype).contiguous()
 
-    def dense_step(self, pf, s):
-        for g in s.values():
-            for X, W, b, dY in self._dense_layers(g):
-                pf.pf_dense_linear_fwd(X, W, b)
-                pf.pf_dense_linear_bwd(X, W, dY, has_bias=True)
-
     def library_dense_prepare(self, s, torch):
         out = []
         for g in s.values():
@@ -239,25 +258,49 @@ class LinearWorkload:
                 s * (M * i + G * (M * o + M * r + r * (i + o))))
         return out
 
-    def cpu_baseline(self, oracle, workloads, reps=3):
-        inputs = [workloads.linear_inputs(self.M, i, o, r, dtype=self.dtype, seed=self.seed, bias=True)
+    def algorithmic_bytes(self):
+        w = self.kernel_work()
+        return sum(w[k][1] for k in ("linear_fwd_fused", "linear_bwd_data_fused", "linear_wgrad_pair"))
+
+    def library_lowrank_prepare(self, s, torch):
+        out = []
+        leaf = lambda t: t.detach().clone().requires_grad_(True)
+        for g in s.values():
+            if g["V"].dim() == 3:
+                for k in range(g["V"].shape[0]):
+                    out.append((leaf(g["X"]), leaf(g["V"][k]), leaf(g["U"][k]), leaf(g["bias"][k]), g["dY"][k]))
+            else:
+                out.append((leaf(g["X"]), leaf(g["V"]), leaf(g["U"]), leaf(g["bias"]), g["dY"]))
+        return out
+
+    def library_lowrank_step(self, prep, torch):
+        """The factorized layer as two library GEMMs per direction, T through HBM."""
+        for X, V, U, b, dY in prep:
+            X.grad = V.grad = U.grad = b.grad = None
+            torch.nn.functional.linear(X @ V, U, b).backward(dY)
+
+    def cpu_baseline(self, oracle, workloads, rows=None):
+        """Seconds of one fwd+bwd of every layer on `rows` rows of the batch (None = all), and its flops."""
+        m = self.M if rows is None else min(rows, self.M)
+        inputs = [workloads.linear_inputs(m, i, o, r, dtype=self.dtype, seed=self.seed, bias=True)
                   for n, (i, o, r) in self.layers.items() if n not in self.shared]
         shared = None
         if self.shared:
             i, o, r = self.layers[self.shared[0]]
-            shared = workloads.linear_shared_inputs(self.M, i, o, r, len(self.shared), dtype=self.dtype, seed=self.seed,
+            shared = workloads.linear_shared_inputs(m, i, o, r, len(self.shared), dtype=self.dtype, seed=self.seed,
                                                     bias=True)
-        times = []
-        for rep in range(reps):
-            t0 = time.perf_counter()
-            for a in inputs:
-                oracle.lowrank_linear_fwd(a["X"], a["V"], a["U"], a["bias"])
-                oracle.lowrank_linear_bwd(a["X"], a["V"], a["U"], a["dY"])
-            if shared:
-                oracle.lowrank_linear_shared_fwd(shared["X"], shared["V"], shared["U"], shared["bias"])
-                oracle.lowrank_linear_shared_bwd(shared["X"], shared["V"], shared["U"], shared["dY"])
-            times.append(time.perf_counter() - t0)
-        return statistics.median(times), self.flops(), f"full workload, fwd+bwd, median of {reps} runs"
+        t0 = time.perf_counter()
+        for a in inputs:
+            oracle.lowrank_linear_fwd(a["X"], a["V"], a["U"], a["bias"])
+            oracle.lowrank_linear_bwd(a["X"], a["V"], a["U"], a["dY"])
+        if shared:
+            oracle.lowrank_linear_shared_fwd(shared["X"], shared["V"], shared["U"], shared["bias"])
+            oracle.lowrank_linear_shared_bwd(shared["X"], shared["V"], shared["U"], shared["dY"])
+        secs = time.perf_counter() - t0
+        return secs, self.flops() * m / self.M, f"fwd+bwd of every layer on {m} of {self.M} rows, one run"
+
+    def cpu_single_thread_sample(self):
+        return max(1, self.M // 16)
 
 
 class LstmWorkload:
@@ -391,19 +434,31 @@ class LstmWorkload:
         }
         return {k: [f * cells, b * cells, cells] for k, (f, b) in w.items()}
 
-    def cpu_baseline(self, oracle, workloads, reps=1):
-        import numpy as np
+    def algorithmic_bytes(self):
+        w = self.kernel_work()
+        if self.stack or self.seq:
+            names = (("lstm_stack_T", "lstm_stack_z_gates", "lstm_stack_dT", "lstm_stack_dh_gates", "lstm_stack_grads")
+                     if self.groups == 1 else ("lstm_stack_T", "lstm_stack_z", "lstm_stack_dT", "lstm_stack_dh", "lstm_stack_grads"))
+            return sum(w[k][1] for k in names)
+        return sum(v[1] for v in w.values())
+
+    def cpu_baseline(self, oracle, workloads, cells=8):
+        """Seconds of `cells` cell steps (fwd+bwd) of one layer, and their flops."""
         c = self.cfg
+        n = cells or 8
         a = workloads.lstm_cell_inputs(c["B"], c["d"], c["h"], c["r"], groups=self.groups, seed=c["seed"])
         t0 = time.perf_counter()
-        n = 8
         for _ in range(n):
             ho, co, gates, Tx, Th = oracle.lowrank_lstm_cell_fwd(a["x"], a["h_prev"], a["c_prev"], a["Vx"], a["Ux"],
                                                                  a["Vh"], a["Uh"], a["bias"], self.groups)
             oracle.lowrank_lstm_cell_bwd(a["x"], a["h_prev"], a["c_prev"], co, gates, Tx, Th, a["Vx"], a["Ux"], a["Vh"],
                                          a["Uh"], a["dh"], a["dc"], self.groups)
         secs = time.perf_counter() - t0
-        return secs, self.flops() / (c["T"] * c["layers"]) * n, f"{n} cell steps (fwd+bwd) of one layer; the full workload is {c['T'] * c['layers']} of them"
+        return secs, self.flops() / (c["T"] * c["layers"]) * n, \
+            f"{n} cell steps (fwd+bwd) of one layer; the full workload is {c['T'] * c['layers']} of them"
+
+    def cpu_single_thread_sample(self):
+        return 2
 
 
 def measured_traffic(workload, kernel):
@@ -466,23 +521,42 @@ def make_workload(name, lstm_groups=1):
     raise SystemExit(f"unknown workload {name}")
 
 
+MIN_TIMED_MS = 50.0   # GPU time measured per figure, at least
+MAX_REPEATS = 400
+
+
+def _repeat(torch, run_once, steps):
+    """Times run_once() (exactly `steps` steps) again and again until MIN_TIMED_MS of GPU time are on record; returns
+    the ms/step of every repetition."""
+    per_rep, total = [], 0.0
+    while (total < MIN_TIMED_MS or len(per_rep) < 3) and len(per_rep) < MAX_REPEATS:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run_once()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        per_rep.append(ms / steps)
+        total += ms
+    return per_rep
+
+
 def time_steps(torch, fn, sets, steps, warmup):
+    """Eager launches: `warmup` untimed steps, then repetitions of exactly `steps` timed steps."""
     for i in range(warmup):
         fn(sets[i % len(sets)])
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(steps):
-        fn(sets[i % len(sets)])
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / steps
+
+    def once():
+        for i in range(steps):
+            fn(sets[i % len(sets)])
+    return _repeat(torch, once, steps)
 
 
 def capture_graph(torch, fn, sets, count):
     """One HIP graph holding `count` whole steps (all launches of fwd + bwd), walking the buffer sets in turn."""
     for s in sets:
-        fn(s)  # eager once: sizes the workspace before capture
+        fn(s)  # eager once: output tensors of the right size are in torch's pool before capture
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
@@ -492,33 +566,176 @@ def capture_graph(torch, fn, sets, count):
 
 
 def time_graph_steps(torch, fn, sets, steps, warmup):
-    """Exactly `steps` steps as replays of one graph of len(sets) steps plus one graph for the remainder."""
+    """Exactly `steps` steps per repetition, as replays of one graph of len(sets) steps plus one graph for the
+    remainder."""
     per = len(sets)
-    full = capture_graph(torch, fn, sets, per)
+    full = capture_graph(torch, fn, sets, per) if steps >= per else None
     rem = capture_graph(torch, fn, sets, steps % per) if steps % per else None
     for i in range(max(1, warmup // per)):
-        full.replay()
+        (full or rem).replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(steps // per):
-        full.replay()
-    if rem is not None:
-        rem.replay()
-    e1.record()
+
+    def once():
+        for i in range(steps // per):
+            full.replay()
+        if rem is not None:
+            rem.replay()
+    return _repeat(torch, once, steps)
+
+
+def summary(per_rep):
+    return {"ms_per_step": statistics.median(per_rep), "repeats": len(per_rep), "min_ms_per_step": min(per_rep),
+            "max_ms_per_step": max(per_rep)}
+
+
+def host_description():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"nproc": os.cpu_count(), "cpu_model": model}
+
+
+def cpu_baseline(wl, workloads):
+    """The oracle on this machine's host cores: all threads on (a bounded sample of) the workload, then one thread
+    on a smaller sample of it."""
+    import oracle
+    threads = oracle.num_threads()
+    secs, cflops, sample = wl.cpu_baseline(oracle, workloads)
+    out = {"value": cflops / secs / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle", "sample": sample,
+           "seconds": secs}
+    oracle.set_num_threads(1)
+    try:
+        s1, f1, sample1 = wl.cpu_baseline(oracle, workloads, wl.cpu_single_thread_sample())
+    finally:
+        oracle.set_num_threads(threads)
+    out["single_thread"] = {"value": f1 / s1 / 1e12, "unit": "TFLOP/s", "cores": 1, "sample": sample1, "seconds": s1}
+    out.update(host_description())
+    return out
+
+
+def run_workload(args, torch, pf, workloads, name, lstm_groups=1):
+    """Every figure of one workload, as a dict."""
+    wl = make_workload(name, lstm_groups)
+    one = wl.make_set(0, torch, workloads)
+    set_bytes = sum(t.numel() * t.element_size() for g in one.values() for t in g.values() if hasattr(t, "numel"))
+    nsets = args.buffer_sets or max(2, int(300e6 // max(set_bytes * 2, 1)) + 1)  # x2: outputs are as large as inputs
+    nsets = min(nsets, 64)
+    sets = [one] + [wl.make_set(i, torch, workloads) for i in range(1, nsets)]
+    step = lambda s: wl.step(pf, s)
+
+    eager = summary(time_steps(torch, step, sets, args.steps, args.warmup))
+    if args.no_graph:
+        timed = eager
+        resident = summary(time_steps(torch, step, sets[:1], args.steps, args.warmup))
+    else:
+        # a step is a handful of microsecond kernels, launch-bound from the host, so it is replayed as a HIP graph
+        timed = summary(time_graph_steps(torch, step, sets, args.steps, args.warmup))
+        resident = summary(time_graph_steps(torch, step, sets[:1] * 8, args.steps, args.warmup))
+    ms = timed["ms_per_step"]
+    flops = wl.flops()
+    value = flops / (ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[wl.dtype]
+    ai = flops / wl.algorithmic_bytes()
+    attainable = min(peak, ai * HBM_GBS / 1e3)  # TFLOP/s: min(MFMA peak, intensity x HBM bandwidth)
+
+    # per-kernel durations, HIP events around every launch on the launch stream
+    pf.timing_reset()
+    pf.timing_enable(True)
+    for i in range(max(args.steps, 20)):
+        wl.step(pf, sets[i % len(sets)])
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / steps
+    pf.timing_enable(False)
+    per_kernel = pf.timing_collect()
+    kernels = {k: {"launches": n, "avg_us": 1e3 * t / n} for k, (n, t) in sorted(per_kernel.items(), key=lambda kv: -kv[1][1])}
+    work = wl.kernel_work()
+    roofline = None
+    if kernels:
+        dom = next((k for k in kernels if k in work), next(iter(kernels)))  # the costliest kernel that has a work model
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": None, "peak": peak, "unit": "TFLOP/s", "frac": None,
+                    "traffic": None, "avg_us": kernels[dom]["avg_us"]}
+        if dom in work:
+            kflops, kbytes, per_step = work[dom]
+            step_s = kernels[dom]["avg_us"] * 1e-6 * per_step  # time this kernel takes per step, all layers
+            bound = "mfma" if kflops / kbytes >= peak * 1e12 / (HBM_GBS * 1e9) else "hbm"
+            roofline.update({"bound": bound, "launches_per_step": per_step, "algorithmic_flops_per_step": kflops,
+                             "algorithmic_bytes_per_step": kbytes, "traffic": measured_traffic(wl.name, dom)})
+            if bound == "mfma":
+                roofline.update({"achieved": kflops / step_s / 1e12, "peak": peak, "unit": "TFLOP/s",
+                                 "frac": kflops / step_s / 1e12 / peak})
+            else:
+                roofline.update({"achieved": kbytes / step_s / 1e9, "peak": HBM_GBS, "unit": "GB/s",
+                                 "frac": kbytes / step_s / 1e9 / HBM_GBS})
+            roofline["tflops"] = kflops / step_s / 1e12
+            roofline["algorithmic_GBps"] = kbytes / step_s / 1e9
+
+    def vendor_leg(prepare, run):
+        """ms/step summary of a torch (vendor library) leg: graph-replayed like the factorized path when torch can
+        capture it, else launched eagerly."""
+        prep = [prepare(s_, torch) for s_ in sets[:4]]
+        fn = lambda p: run(p, torch)
+        if not args.no_graph:
+            try:
+                return dict(summary(time_graph_steps(torch, fn, prep, args.steps, 4)), launch="hip_graph")
+            except Exception:
+                torch.cuda.synchronize()
+        return dict(summary(time_steps(torch, fn, prep, args.steps, 5)), launch="eager")
+
+    library = unfused = None
+    if not args.no_dense and hasattr(wl, "library_dense_step"):
+        # the dense layer through the vendor library (torch -> MIOpen / hipBLASLt), as an outside reference
+        try:
+            for s_ in sets[:4]:
+                wl.dense_prepare(s_, torch)
+            lms = vendor_leg(wl.library_dense_prepare, wl.library_dense_step)
+            library = dict(lms, value=wl.dense_flops() / (lms["ms_per_step"] * 1e-3) / 1e12, unit="TFLOP/s (dense flops)",
+                           what=f"torch.nn.functional dense layer fwd+bwd, {wl.dtype}, vendor library kernels",
+                           speedup_of_factorized=lms["ms_per_step"] / ms)
+        except Exception as e:  # the outside reference is optional
+            library = {"error": repr(e)[:200]}
+        # the factorized layer as two library launches per direction: the rank-r intermediate goes through HBM
+        try:
+            ums = vendor_leg(wl.library_lowrank_prepare, wl.library_lowrank_step)
+            unfused = dict(ums, value=flops / (ums["ms_per_step"] * 1e-3) / 1e12, unit="TFLOP/s",
+                           what="the same factorized layer as two vendor-library launches per direction (torch autograd), "
+                                "T written to and read back from HBM",
+                           speedup_of_fused=ums["ms_per_step"] / ms)
+        except Exception as e:
+            unfused = {"error": repr(e)[:200]}
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, workloads)
+    del sets, one
+    torch.cuda.empty_cache()
+    return {
+        "value": value, "unit": "TFLOP/s", "ms_per_step": ms, "dtype": wl.dtype,
+        "config": dict(wl.describe(), buffer_sets=nsets),
+        "timing": timed, "frac_of_mfma_peak": value / peak,
+        "arithmetic_intensity": ai, "attainable_TFLOPs": attainable, "frac_of_min_peak_ai_bw": value / attainable,
+        "launch": "eager" if args.no_graph else "hip_graph", "eager_ms_per_step": eager["ms_per_step"],
+        "cache_resident": {"ms_per_step": resident["ms_per_step"], "value": flops / (resident["ms_per_step"] * 1e-3) / 1e12},
+        "roofline": roofline, "cpu_baseline": cpu, "dense_layer_vendor_library": library,
+        "unfused_vendor_library": unfused, "kernels": kernels,
+    }
+
+
+# the five benchmark configurations, largest first (the first is the headline unless --workload names another)
+FIVE = ["resnet50_conv5_bf16", "transformer_block_bf16", "lstm_lm_stack_f32", "resnet18_conv4_bf16", "linear_fc_f32"]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="resnet18_conv4_bf16")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=FIVE[0])
+    ap.add_argument("--single", action="store_true", help="measure --workload only, not the other four configurations")
     ap.add_argument("--buffer-sets", type=int, default=0, help="distinct input/output sets to rotate over (0 = enough to exceed 256 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-dense", action="store_true", help="skip the vendor-library legs (dense layer, unfused factorized layer)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy, so that byte counters of a profiler run can be scaled")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
@@ -537,86 +754,17 @@ def main():
     torch.cuda.set_device(0)
     if workloads.CONFIGS[args.workload]["kind"] == "svd":
         return svd_bench(args, torch, pf, workloads)
-    wl = make_workload(args.workload, args.lstm_groups)
 
-    one = wl.make_set(0, torch, workloads)
-    set_bytes = sum(t.numel() * t.element_size() for g in one.values() for t in g.values() if hasattr(t, "numel"))
-    nsets = args.buffer_sets or max(2, int(300e6 // max(set_bytes * 2, 1)) + 1)  # x2: outputs are as large as inputs
-    nsets = min(nsets, 64)
-    sets = [one] + [wl.make_set(i, torch, workloads) for i in range(1, nsets)]
-
-    ms_eager = time_steps(torch, lambda s: wl.step(pf, s), sets, args.steps, args.warmup)
-    if args.no_graph:
-        ms = ms_eager
-        ms_resident = time_steps(torch, lambda s: wl.step(pf, s), sets[:1], args.steps, args.warmup)
-    else:
-        # the step is launch-bound (a handful of microsecond kernels), so it is replayed as a HIP graph
-        ms = time_graph_steps(torch, lambda s: wl.step(pf, s), sets, args.steps, args.warmup)
-        ms_resident = time_graph_steps(torch, lambda s: wl.step(pf, s), sets[:1] * 8, args.steps, args.warmup)
-    flops = wl.flops()
-    value = flops / (ms * 1e-3) / 1e12
-
-    # per-kernel durations, HIP events around every launch on the launch stream
-    pf.timing_reset()
-    pf.timing_enable(True)
-    for i in range(min(args.steps, 50)):
-        wl.step(pf, sets[i % len(sets)])
-    torch.cuda.synchronize()
-    pf.timing_enable(False)
-    per_kernel = pf.timing_collect()
-    kernels = {k: {"launches": n, "avg_us": 1e3 * t / n} for k, (n, t) in sorted(per_kernel.items(), key=lambda kv: -kv[1][1])}
-    work = wl.kernel_work()
-    roofline = None
-    if kernels:
-        dom = next((k for k in kernels if k in work), next(iter(kernels)))  # the costliest kernel that has a work model
-        peak = PEAK_TFLOPS[wl.dtype]
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": None, "peak": peak, "unit": "TFLOP/s", "frac": None,
-                    "traffic": None, "avg_us": kernels[dom]["avg_us"]}
-        if dom in work:
-            kflops, kbytes, per_step = work[dom]
-            step_s = kernels[dom]["avg_us"] * 1e-6 * per_step  # time this kernel takes per step, all layers
-            ai = kflops / kbytes
-            bound = "mfma" if ai >= peak * 1e12 / (HBM_GBS * 1e9) else "hbm"
-            roofline.update({"bound": bound, "launches_per_step": per_step, "algorithmic_flops_per_step": kflops,
-                             "algorithmic_bytes_per_step": kbytes, "traffic": measured_traffic(wl.name, dom)})
-            if bound == "mfma":
-                roofline.update({"achieved": kflops / step_s / 1e12, "peak": peak, "unit": "TFLOP/s",
-                                 "frac": kflops / step_s / 1e12 / peak})
-            else:
-                roofline.update({"achieved": kbytes / step_s / 1e9, "peak": HBM_GBS, "unit": "GB/s",
-                                 "frac": kbytes / step_s / 1e9 / HBM_GBS})
-            roofline["tflops"] = kflops / step_s / 1e12
-            roofline["algorithmic_GBps"] = kbytes / step_s / 1e9
-
-    dense = None
-    if not args.no_dense and hasattr(wl, "dense_prepare"):  # (the LSTM workloads have no dense comparator)
-        for s in sets:
-            wl.dense_prepare(s, torch)
-        if args.no_graph:
-            dms = time_steps(torch, lambda s: wl.dense_step(pf, s), sets, max(10, args.steps // 4), max(2, args.warmup // 4))
-        else:
-            dms = time_graph_steps(torch, lambda s: wl.dense_step(pf, s), sets[:4], max(10, args.steps // 4), 4)
-        dense = {"ms_per_step": dms, "value": wl.dense_flops() / (dms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
-                 "speedup_of_factorized": dms / ms}
-
-    library = None
-    if not args.no_dense and hasattr(wl, "library_dense_step"):
-        # the same dense layer through the vendor library (torch -> MIOpen / hipBLASLt), as an outside reference
-        try:
-            prep = [wl.library_dense_prepare(s, torch) for s in sets[:4]]
-            lms = time_steps(torch, lambda p: wl.library_dense_step(p, torch), prep, max(10, args.steps // 4), 5)
-            library = {"ms_per_step": lms, "value": wl.dense_flops() / (lms * 1e-3) / 1e12, "unit": "TFLOP/s (dense flops)",
-                       "what": f"torch.nn.functional dense layer fwd+bwd, {wl.dtype}, vendor library kernels",
-                       "speedup_of_factorized": lms / ms}
-        except Exception as e:  # the reference is optional
-            library = {"error": repr(e)[:200]}
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        secs, cflops, sample = wl.cpu_baseline(oracle, workloads)
-        cpu = {"value": cflops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": sample, "seconds": secs}
+    head = run_workload(args, torch, pf, workloads, args.workload, args.lstm_groups)
+    others = []
+    if not args.single:
+        for name in FIVE:
+            if name == args.workload:
+                continue
+            r = run_workload(args, torch, pf, workloads, name, 1)
+            others.append(r)
+            if workloads.CONFIGS[name]["kind"] == "lstm":  # the paper's own reading: one factor pair per gate and path
+                others.append(run_workload(args, torch, pf, workloads, name, 4))
 
     if args.copy_calibration:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
@@ -625,15 +773,16 @@ def main():
         torch.cuda.synchronize()
 
     out = {
-        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
-        "data": "synthetic", "config": dict(wl.describe(), buffer_sets=nsets),
-        "frac_of_mfma_peak": value / PEAK_TFLOPS[wl.dtype],
-        "launch": "eager" if args.no_graph else "hip_graph", "eager_ms_per_step": ms_eager,
-        "cache_resident": {"ms_per_step": ms_resident, "value": flops / (ms_resident * 1e-3) / 1e12},
-        "roofline": roofline, "cpu_baseline": cpu, "dense_layer": dense, "dense_layer_vendor_library": library,
-        "kernels": kernels,
+        "metric": METRIC, "value": head["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
     }
+    out.update({k: v for k, v in head.items() if k not in out})
+    brief = lambda r: {k: r[k] for k in ("config", "dtype", "ms_per_step", "value", "unit", "timing", "frac_of_mfma_peak",
+                                         "arithmetic_intensity", "attainable_TFLOPs", "frac_of_min_peak_ai_bw",
+                                         "eager_ms_per_step", "roofline", "cpu_baseline", "dense_layer_vendor_library",
+                                         "unfused_vendor_library", "kernels")}
+    out["workloads"] = [brief(head)] + [brief(r) for r in others]
     print(json.dumps(out))
 
 
