@@ -145,6 +145,34 @@ def lowrank_linear_shared_bwd(X, V, U, dY):
     return dX, np.stack(dUs), np.stack(dVs), np.stack(dbs)
 
 
+def lowrank_linear_fwd_ep(X, V, U, bias=None, residual=None, act="none"):
+    """The factorized layer of Section 2.1 with what follows it in a Transformer block (Section 2.4): the bias, an
+    optional residual input R of Y's shape, and the feed-forward network's max(0, .):
+        Z = (X V) U^T + b + R,   Y = max(0, Z) if act == "relu" else Z.
+    FFN(x) = max(0, x W_1 + b_1) W_2 + b_2 is act="relu" on the first layer and act="none" on the second.
+    Returns (Y, T)."""
+    assert act in ("none", "relu")
+    Z, T = lowrank_linear_fwd(X, V, U, bias)
+    if residual is not None:
+        Z = Z + np.asarray(residual, dtype=np.float64)
+    return (np.maximum(Z, 0.0) if act == "relu" else Z), T
+
+
+def lowrank_linear_bwd_ep(X, V, U, dZ, dX_add=None, x_is_relu=False):
+    """Backward of lowrank_linear_fwd_ep from dZ = dL/dZ (the gradient of the pre-activation; for act == "none"
+    that is dL/dY, and a residual input receives dZ unchanged).  The layer's own input may be the output of a
+    max(0, .) and may also feed a skip connection:
+        dX = (dZ U V^T + dX_add) * [X > 0]      (the mask only when x_is_relu; dX_add optional),
+    i.e. dX is dL/d(pre-activation of the layer below).  dU, dV, db as in lowrank_linear_bwd with dY = dZ.
+    Returns (dX, dU, dV, db)."""
+    dX, dU, dV, db = lowrank_linear_bwd(X, V, U, dZ)
+    if dX_add is not None:
+        dX = dX + np.asarray(dX_add, dtype=np.float64)
+    if x_is_relu:
+        dX = dX * (np.asarray(X, dtype=np.float64) > 0.0)
+    return dX, dU, dV, db
+
+
 # ------------------------------------------------------------------ conv
 
 def dense_conv_fwd(X, Wd, stride=1, pad=0):
@@ -196,6 +224,39 @@ def lowrank_conv_bwd(X, Uk, Vp, dY, stride=1, pad=0):
 
 
 # ------------------------------------------------------------------ LSTM
+
+def lowrank_conv_fwd_ep(X, Uk, Vp, scale=None, shift=None, residual=None, act="none", stride=1, pad=0):
+    """The factorized convolution of Section 2.2 followed by what Appendix D puts after every convolution: batch
+    normalisation (here with fixed statistics, i.e. a per-channel scale and shift: scale = gamma / sqrt(var + eps),
+    shift = beta - mean * scale), the residual input of a ResNet block, and ReLU:
+        P = Vp * (Uk * X),  Z[n,o,y,x] = scale[o] P[n,o,y,x] + shift[o] + R[n,o,y,x],  Y = max(0, Z) or Z.
+    Returns (Y, T)."""
+    assert act in ("none", "relu")
+    P, T = lowrank_conv_fwd(X, Uk, Vp, stride, pad)
+    Z = P
+    if scale is not None:
+        Z = Z * np.asarray(scale, dtype=np.float64)[None, :, None, None]
+    if shift is not None:
+        Z = Z + np.asarray(shift, dtype=np.float64)[None, :, None, None]
+    if residual is not None:
+        Z = Z + np.asarray(residual, dtype=np.float64)
+    return (np.maximum(Z, 0.0) if act == "relu" else Z), T
+
+
+def lowrank_conv_bwd_ep(X, Uk, Vp, scale, dZ, stride=1, pad=0, dX_add=None, x_is_relu=False):
+    """Backward of lowrank_conv_fwd_ep from dZ = dL/dZ:  dP = scale * dZ (per output channel), dshift[o] = the sum
+    of dZ over batch and pixels, dT, dVp, dUk from dP as in lowrank_conv_bwd, and
+        dX = (transposed convolution of dT + dX_add) * [X > 0]   (mask only when x_is_relu; dX_add optional).
+    The scale is a constant (fixed statistics), so it has no gradient.  Returns (dX, dUk, dVp, dshift)."""
+    dZ = np.asarray(dZ, dtype=np.float64)
+    dP = dZ if scale is None else dZ * np.asarray(scale, dtype=np.float64)[None, :, None, None]
+    dX, dUk, dVp = lowrank_conv_bwd(X, Uk, Vp, dP, stride, pad)
+    if dX_add is not None:
+        dX = dX + np.asarray(dX_add, dtype=np.float64)
+    if x_is_relu:
+        dX = dX * (np.asarray(X, dtype=np.float64) > 0.0)
+    return dX, dUk, dVp, dZ.sum(axis=(0, 2, 3))
+
 
 def dense_lstm_cell_fwd(x, hprev, cprev, Wx, Wh, bias=None):
     """Eq. (1): returns (h, c)."""
