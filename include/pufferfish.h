@@ -205,6 +205,74 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk,
                         size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ */
+/* Layer epilogues: what the paper's models put directly after a        */
+/* factorized layer, applied where the layer's output is formed, and    */
+/* the matching step of the backward pass.                              */
+/*                                                                      */
+/* Linear (Section 2.4: FFN(x) = max(0, x W1 + b1) W2 + b2; each        */
+/* sub-layer of a Transformer block sits inside a residual connection): */
+/*   Z = (X V) U^T + bias + residual,   Y = act(Z)                      */
+/*   residual: nullable, [M x out] in dtype.  act: pf_activation.       */
+/* Backward takes dZ = dL/dZ where pf_lowrank_linear_bwd takes dY (for  */
+/* PF_ACT_NONE they are the same tensor; a residual input receives dZ   */
+/* as it is) and forms the gradient the layer BELOW needs:              */
+/*   dX = (dZ U V^T + dX_add) * [X > 0]                                 */
+/*   dX_add: nullable [M x in] (the gradient arriving over a skip       */
+/*   connection that branches off X); the mask only when x_is_relu != 0 */
+/*   (X is the output of a ReLU: dX is then dL/dZ of the layer below).  */
+/*   dU, dV, dbias as in pf_lowrank_linear_bwd with dY = dZ.            */
+/*                                                                      */
+/* Convolution (Appendix D: a batch-norm layer after every convolution, */
+/* ReLU after it, the shortcut of a ResNet block added before the last  */
+/* ReLU), with the statistics fixed (running mean and variance): the    */
+/* normalisation is then a per-channel scale and shift,                 */
+/*   scale = gamma / sqrt(var + eps), shift = beta - mean * scale:      */
+/*   Z[n,o,y,x] = scale[o] (Vp * (Uk * X))[n,o,y,x] + shift[o] + R,     */
+/*   Y = act(Z);  scale, shift: float[Cout], each nullable (1 and 0).   */
+/* Backward from dZ:  dP = scale dZ, dT = Vp^T dP, dVp = dP T^T,        */
+/*   dshift[o] = sum over n,y,x of dZ (float[Cout], nullable),          */
+/*   dX = (transposed convolution of dT + dX_add) * [X > 0].            */
+/* The scale is a constant here and has no gradient.                    */
+/*                                                                      */
+/* Workspace: the *_fwd_ep calls and pf_lowrank_linear_bwd_ep need what */
+/* the plain calls need; pf_lowrank_conv_bwd_ep has its own query.      */
+/* Errors as for the plain calls; an unknown act: PF_ERR_UNSUPPORTED.   */
+/* ------------------------------------------------------------------ */
+typedef enum { PF_ACT_NONE = 0, PF_ACT_RELU = 1 } pf_activation;
+
+int pf_lowrank_linear_fwd_ep(const pf_linear_desc *d, const void *X, const void *V,
+                             const void *U, const void *bias /* nullable */,
+                             const void *residual /* nullable */, int act,
+                             void *Y, void *T_save /* nullable */,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream);
+int pf_lowrank_linear_bwd_ep(const pf_linear_desc *d, const void *X, const void *V,
+                             const void *U, const void *dZ,
+                             const void *T_saved /* nullable */,
+                             const void *dX_add /* nullable */, int x_is_relu,
+                             void *dX, void *dU, void *dV, void *dbias,
+                             int accumulate, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+size_t pf_lowrank_conv_bwd_ep_workspace_bytes(const pf_conv_desc *d);
+int pf_lowrank_conv_fwd_ep(const pf_conv_desc *d, const void *X, const void *Uk,
+                           const void *Vp, const void *scale /* nullable */,
+                           const void *shift /* nullable */,
+                           const void *residual /* nullable */, int act,
+                           void *Y, void *T_save /* nullable */,
+                           void *W_save /* nullable */, void *workspace,
+                           size_t workspace_bytes, void *stream);
+int pf_lowrank_conv_bwd_ep(const pf_conv_desc *d, const void *X, const void *Uk,
+                           const void *Vp, const void *scale /* nullable */,
+                           const void *dZ, const void *T_saved /* nullable */,
+                           const void *W_saved /* nullable */,
+                           const void *dX_add /* nullable */, int x_is_relu,
+                           void *dX, void *dUk, void *dVp,
+                           void *dshift /* nullable */, int accumulate,
+                           void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/* ------------------------------------------------------------------ */
 /* LSTM cell (paper Section 2.3, eq. (2); architecture table of the     */
 /* low-rank LSTM in Appendix D).  One time step for a batch of B rows:  */
 /*   Tx = x Vx, Th = h_prev Vh,                                        */

@@ -17,6 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libpufferfish.so")
 
 PF_F32, PF_BF16 = 0, 1
 PF_NCHW, PF_NHWC = 0, 1
+PF_ACT_NONE, PF_ACT_RELU = 0, 1
+_ACT = {None: 0, "none": 0, "relu": 1}
 
 
 class PfError(RuntimeError):
@@ -67,6 +69,8 @@ EXPORTS = [
     "pf_lowrank_linear_shared_fwd", "pf_lowrank_linear_shared_bwd",
     "pf_lowrank_conv_fwd_workspace_bytes", "pf_lowrank_conv_bwd_workspace_bytes",
     "pf_lowrank_conv_saved_weights_bytes", "pf_lowrank_conv_fwd", "pf_lowrank_conv_bwd",
+    "pf_lowrank_linear_fwd_ep", "pf_lowrank_linear_bwd_ep", "pf_lowrank_conv_bwd_ep_workspace_bytes",
+    "pf_lowrank_conv_fwd_ep", "pf_lowrank_conv_bwd_ep",
     "pf_lowrank_lstm_cell_fwd_workspace_bytes", "pf_lowrank_lstm_cell_bwd_workspace_bytes",
     "pf_lowrank_lstm_cell_fwd", "pf_lowrank_lstm_cell_bwd",
     "pf_lowrank_lstm_seq_fwd_workspace_bytes", "pf_lowrank_lstm_seq_bwd_workspace_bytes",
@@ -200,6 +204,41 @@ def pf_lowrank_linear_bwd_static(X, V, U, dY, T_saved, dX, dU, dV, dbias=None, a
     return dX, dU, dV, dbias
 
 
+def pf_lowrank_linear_fwd_ep(X, V, U, bias=None, residual=None, act="none", save_T=True):
+    """Y = act((X V) U^T + bias + residual); returns (Y, T)."""
+    d = _linear_desc(X, U, bias is not None)
+    dt = X.dtype
+    Y = torch.empty((d.M, d.n_out), dtype=dt, device=X.device)
+    T = torch.empty((d.M, d.r), dtype=dt, device=X.device) if save_T else None
+    ws = _workspace(lib.pf_lowrank_linear_fwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_linear_fwd_ep(ctypes.byref(d), _ptr(X, dt), _ptr(V, dt), _ptr(U, dt), _ptr(bias, dt),
+                                        _ptr(residual, dt), ctypes.c_int(_ACT[act]), _ptr(Y), _ptr(T), _ptr(ws),
+                                        ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_linear_fwd_ep")
+    return Y, T
+
+
+def pf_lowrank_linear_bwd_ep(X, V, U, dZ, T_saved=None, dX_add=None, x_is_relu=False, need_dX=True, has_bias=False,
+                             grads=None):
+    """From dZ = dL/d(pre-activation): (dX, dU, dV, dbias) with dX = (dZ U V^T + dX_add) * [X > 0 if x_is_relu]."""
+    d = _linear_desc(X, U, has_bias)
+    dt, f32 = X.dtype, torch.float32
+    dX = torch.empty_like(X) if need_dX else None
+    accumulate = grads is not None
+    if grads is None:
+        dU = torch.empty((d.n_out, d.r), dtype=f32, device=X.device)
+        dV = torch.empty((d.n_in, d.r), dtype=f32, device=X.device)
+        db = torch.empty((d.n_out,), dtype=f32, device=X.device) if has_bias else None
+    else:
+        dU, dV, db = grads
+    ws = _workspace(lib.pf_lowrank_linear_bwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_linear_bwd_ep(ctypes.byref(d), _ptr(X, dt), _ptr(V, dt), _ptr(U, dt), _ptr(dZ, dt),
+                                        _ptr(T_saved, dt), _ptr(dX_add, dt), ctypes.c_int(1 if x_is_relu else 0),
+                                        _ptr(dX), _ptr(dU, f32), _ptr(dV, f32), _ptr(db, f32),
+                                        ctypes.c_int(1 if accumulate else 0), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                                        _stream()), "pf_lowrank_linear_bwd_ep")
+    return dX, dU, dV, db
+
+
 def _shared_desc(X, U, bias_flag):
     M, n_in = X.shape
     G, n_out, r = U.shape
@@ -313,6 +352,48 @@ def pf_lowrank_conv_bwd(X, Uk, Vp, dY, T_saved=None, stride=1, pad=0, need_dX=Tr
                                    _ptr(dVp, torch.float32), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
                                    ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_conv_bwd")
     return dX, dUk, dVp
+
+
+def pf_lowrank_conv_fwd_ep(X, Uk, Vp, scale=None, shift=None, residual=None, act="none", stride=1, pad=0, save_T=True,
+                           save_W=False):
+    """Y = act(scale[o] (Vp * (Uk * X)) + shift[o] + residual); scale, shift float32 [Cout].  Returns (Y, T) or
+    (Y, T, W_save)."""
+    d = _conv_desc(X, Uk, Vp, stride, pad)
+    dt, f32 = X.dtype, torch.float32
+    Ho, Wo = conv_out_hw(d)
+    Y = torch.empty((d.N, d.Cout, Ho, Wo), dtype=dt, device=X.device)
+    T = torch.empty((d.N, d.r, Ho, Wo), dtype=dt, device=X.device) if save_T else None
+    nW = lib.pf_lowrank_conv_saved_weights_bytes(ctypes.byref(d)) if save_W else 0
+    Wsv = torch.empty((nW,), dtype=torch.uint8, device=X.device) if nW else None
+    ws = _workspace(lib.pf_lowrank_conv_fwd_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_conv_fwd_ep(ctypes.byref(d), _ptr(X), _ptr(Uk, dt), _ptr(Vp, dt), _ptr(scale, f32),
+                                      _ptr(shift, f32), _ptr(residual, dt), ctypes.c_int(_ACT[act]), _ptr(Y), _ptr(T),
+                                      _ptr(Wsv), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()),
+           "pf_lowrank_conv_fwd_ep")
+    return (Y, T, Wsv) if save_W else (Y, T)
+
+
+def pf_lowrank_conv_bwd_ep(X, Uk, Vp, scale, dZ, T_saved=None, stride=1, pad=0, dX_add=None, x_is_relu=False,
+                           need_dX=True, need_dshift=True, grads=None, W_saved=None):
+    """From dZ = dL/d(pre-activation): (dX, dUk, dVp, dshift), dX = (conv^T(dT) + dX_add) * [X > 0 if x_is_relu];
+    `grads` = (dUk, dVp, dshift) accumulates."""
+    d = _conv_desc(X, Uk, Vp, stride, pad)
+    dt, f32 = X.dtype, torch.float32
+    dX = torch.empty_like(X) if need_dX else None
+    accumulate = grads is not None
+    if grads is None:
+        dUk = torch.empty(Uk.shape, dtype=f32, device=X.device)
+        dVp = torch.empty(Vp.shape, dtype=f32, device=X.device)
+        dsh = torch.empty((d.Cout,), dtype=f32, device=X.device) if need_dshift else None
+    else:
+        dUk, dVp, dsh = grads
+    ws = _workspace(lib.pf_lowrank_conv_bwd_ep_workspace_bytes(ctypes.byref(d)), X.device)
+    _check(lib.pf_lowrank_conv_bwd_ep(ctypes.byref(d), _ptr(X), _ptr(Uk, dt), _ptr(Vp, dt), _ptr(scale, f32),
+                                      _ptr(dZ, dt), _ptr(T_saved, dt), _ptr(W_saved), _ptr(dX_add, dt),
+                                      ctypes.c_int(1 if x_is_relu else 0), _ptr(dX), _ptr(dUk, f32), _ptr(dVp, f32),
+                                      _ptr(dsh, f32), ctypes.c_int(1 if accumulate else 0), _ptr(ws),
+                                      ctypes.c_size_t(ws.numel()), _stream()), "pf_lowrank_conv_bwd_ep")
+    return dX, dUk, dVp, dsh
 
 
 def pf_dense_conv_fwd(X, Wd, stride=1, pad=0):

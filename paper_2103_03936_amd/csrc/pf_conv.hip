@@ -4,7 +4,7 @@
 // stage as an implicit GEMM (operands gathered by functors) on the guarded tile GEMM.
 #include "pf_conv_chain.h"
 #include "pf_conv_wgrad.h"
-#include "pf_gemm.h"
+#include "pf_epilogue.h"
 
 namespace pf {
 
@@ -540,3 +540,29 @@ int pf_dense_conv_bwd(const pf_conv_desc *d, const void *X, const void *Wd, cons
 }
 
 } // extern "C"
+
+// ------------------------------------------------ entry points with an epilogue
+// (the element-wise part is applied by the caller when *fused stays false)
+int pf::conv_fwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const float *scale,
+                          const float *shift, const void *residual, int act, void *Y, void *T_save, void *W_save,
+                          void *workspace, size_t workspace_bytes, void *stream, bool *fused)
+{
+    (void)scale;
+    (void)shift;
+    (void)residual;
+    (void)act;
+    *fused = false;
+    return pf_lowrank_conv_fwd(d, X, Uk, Vp, Y, T_save, W_save, workspace, workspace_bytes, stream);
+}
+
+int pf::conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dZ,
+                          const void *T_saved, const void *W_saved, const void *dX_add, int x_is_relu, void *dX,
+                          void *dUk, void *dVp, int accumulate, void *workspace, size_t workspace_bytes, void *stream,
+                          bool *fused)
+{
+    (void)dX_add;
+    (void)x_is_relu;
+    *fused = false;
+    return pf_lowrank_conv_bwd(d, X, Uk, Vp, dZ, T_saved, W_saved, dX, dUk, dVp, accumulate, workspace, workspace_bytes,
+                               stream);
+}

@@ -7,6 +7,7 @@
 #include "pf_conv_wgrad.h"
 #include <mutex>
 #include "pf_gemm.h"
+#include "pf_epilogue.h"
 
 namespace pf {
 
@@ -855,3 +856,27 @@ int pf_lowrank_linear_shared_bwd(const pf_linear_shared_desc *d, const void *X, 
 }
 
 } // extern "C"
+
+// ------------------------------------------------ entry points with an epilogue
+// (the element-wise part is applied by the caller when *fused stays false)
+int pf::linear_fwd_entry_ep(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias,
+                            const void *residual, int act, void *Y, void *T_save, void *workspace,
+                            size_t workspace_bytes, void *stream, bool *fused)
+{
+    (void)residual;
+    (void)act;
+    *fused = false;
+    return pf::linear_fwd_entry(d, X, V, U, bias, Y, T_save, workspace, workspace_bytes, stream, 16);
+}
+
+int pf::linear_bwd_entry_ep(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dZ,
+                            const void *T_saved, const void *dX_add, int x_is_relu, void *dX, void *dU, void *dV,
+                            void *dbias, int accumulate, void *workspace, size_t workspace_bytes, void *stream,
+                            bool *fused)
+{
+    (void)dX_add;
+    (void)x_is_relu;
+    *fused = false;
+    return pf::linear_bwd_entry(d, X, V, U, dZ, T_saved, dX, dU, dV, dbias, accumulate, workspace, workspace_bytes,
+                                stream, 16);
+}
