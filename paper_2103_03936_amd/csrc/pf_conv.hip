@@ -292,31 +292,40 @@ static int conv_bwd_generic(const ConvGeom &g, const ConvPlan &p, const T *X, co
 }
 
 // ----------------------------------------------------- fused small-image path (bf16)
+// What the chain kernel applies as it stores its output (all optional): forward scale / shift / residual / ReLU,
+// backward the gradient arriving over a skip connection and the mask of a ReLU input.
+struct ConvEpilogue {
+    const float *scale, *shift;
+    const void *add, *mask;
+    int relu;
+};
+
 static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X, const bf16_t *Uk, const bf16_t *Vp,
-                          bf16_t *Y, bf16_t *T_save, void *W_save, Workspace &ws, hipStream_t s)
+                          bf16_t *Y, bf16_t *T_save, void *W_save, Workspace &ws, hipStream_t s, const ConvEpilogue &ep)
 {
     const int T = g.k * g.k;
     uint16_t *w1 = ws.take<uint16_t>(p.n_w1);
     uint16_t *w2 = ws.take<uint16_t>(p.n_w2);
-    // only the thin k x k filters need re-ordering; the 1x1 filters Vp[Cout][r] are read in place.  The same
-    // launch can re-order both factors the way the backward pass wants them (W_save), which saves that pass a
-    // launch of its own.
+    // Both factors are re-ordered into MFMA fragment order by one small launch (read in place, one lane per row,
+    // the 1x1 filters Vp[Cout][r] reach the compute unit at a quarter of the rate).  The same launch can re-order
+    // both factors the way the backward pass wants them (W_save), which saves that pass a launch of its own.
     uint16_t *s1 = (uint16_t *)W_save, *s2 = W_save ? (uint16_t *)((char *)W_save + align_up(p.n_w1b * 2)) : nullptr;
     int st = launch_pack_chain(
         s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1),
         make_pack_w2(W_save ? (const uint16_t *)Uk : nullptr, (uint4 *)s2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1),
-        make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0));
+        make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0),
+        make_pack_w2((const uint16_t *)Vp, (uint4 *)w2, g.Cout, g.r, 1, 0, g.r, 1, 0));
     if (st != PF_OK) return st;
-    (void)w2;
-    ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, nullptr, (const uint16_t *)Vp, (uint16_t *)Y,
-                (uint16_t *)T_save,  g.C,               g.Cout,  g.H,                  g.W,
-                0,                   nullptr};
+    ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)Y,
+                (uint16_t *)T_save,  g.C,               g.Cout,            g.H,     g.W,
+                0,                   nullptr,           ep.scale,          ep.shift, (const uint16_t *)ep.add,
+                (const uint16_t *)ep.mask, ep.relu};
     return launch_conv_chain(s, "conv_fwd_fused", a, g.N, g.k, 1, g.r);
 }
 
 static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X, const bf16_t *Uk, const bf16_t *Vp,
                           const bf16_t *dY, const bf16_t *T_saved, const void *W_saved, bf16_t *dX, float *dUk,
-                          float *dVp, int accumulate, Workspace &ws, hipStream_t s)
+                          float *dVp, int accumulate, Workspace &ws, hipStream_t s, const ConvEpilogue &ep)
 {
     const int T = g.k * g.k;
     const uint16_t *w1 = ws.take<uint16_t>(p.n_w1b);
@@ -342,7 +351,8 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
     if (st != PF_OK) return st;
     ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)dX,
                 (uint16_t *)dT16,     g.Cout,            g.C,               g.H,     g.W,
-                0,                    nullptr};
+                0,                    nullptr,           nullptr,           nullptr, (const uint16_t *)ep.add,
+                (const uint16_t *)ep.mask, 0};
     st = launch_conv_chain(s, "conv_bwd_data_fused", a, g.N, 1, g.k, g.r);
     if (st != PF_OK) return st;
     const bf16_t *Tt = T_saved ? T_saved : T16;
@@ -439,61 +449,18 @@ size_t pf_lowrank_conv_saved_weights_bytes(const pf_conv_desc *d)
 int pf_lowrank_conv_fwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, void *Y, void *T_save,
                         void *W_save, void *workspace, size_t workspace_bytes, void *stream)
 {
-    ConvGeom g;
-    int st = check_conv_desc(d, &g);
-    if (st != PF_OK) return st;
-    if (!Uk || !Vp) return PF_ERR_NULL;
-    if (g.N > 0 && (!X || !Y)) return PF_ERR_NULL;
-    if (any_misaligned({X, Uk, Vp, Y, T_save, W_save}, 16)) return PF_ERR_UNSUPPORTED;
-    const ConvPlan p = plan_conv(g, d->dtype);
-    if (p.fwd_bytes > 0 && (!workspace || workspace_bytes < p.fwd_bytes)) return PF_ERR_WORKSPACE;
-    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
-    if (g.N == 0) return PF_OK;
-    Workspace ws(workspace, workspace_bytes);
-    hipStream_t s = (hipStream_t)stream;
-    if (d->dtype == PF_F32)
-        return conv_fwd_generic<float>(g, (const float *)X, (const float *)Uk, (const float *)Vp, (float *)Y,
-                                       (float *)T_save, ws, s);
-    if (p.chain)
-        return conv_fwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
-                              (bf16_t *)T_save, W_save, ws, s);
-    return conv_fwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
-                                    (bf16_t *)T_save, ws, s);
+    bool fused = false;
+    return pf::conv_fwd_entry_ep(d, X, Uk, Vp, nullptr, nullptr, nullptr, PF_ACT_NONE, Y, T_save, W_save, workspace,
+                                 workspace_bytes, stream, &fused);
 }
 
 int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dY,
                         const void *T_saved, const void *W_saved, void *dX, void *dUk, void *dVp, int accumulate,
                         void *workspace, size_t workspace_bytes, void *stream)
 {
-    ConvGeom g;
-    int st = check_conv_desc(d, &g);
-    if (st != PF_OK) return st;
-    if (!Uk || !Vp) return PF_ERR_NULL;
-    if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
-    if (any_misaligned({X, Uk, Vp, dY, T_saved, W_saved, dX}, 16) || any_misaligned({dUk, dVp}, 4)) return PF_ERR_UNSUPPORTED;
-    const ConvPlan p = plan_conv(g, d->dtype);
-    if (p.bwd_bytes > 0 && (!workspace || workspace_bytes < p.bwd_bytes)) return PF_ERR_WORKSPACE;
-    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
-    Workspace ws(workspace, workspace_bytes);
-    hipStream_t s = (hipStream_t)stream;
-    if (g.N == 0) {
-        if (!accumulate) {
-            st = launch_zero_f32(s, (float *)dUk, (i64)g.r * g.C * g.k * g.k);
-            if (st == PF_OK) st = launch_zero_f32(s, (float *)dVp, (i64)g.Cout * g.r);
-        }
-        return st;
-    }
-    if (d->dtype == PF_F32)
-        return conv_bwd_generic<float>(g, p, (const float *)X, (const float *)Uk, (const float *)Vp, (const float *)dY,
-                                       (const float *)T_saved, (float *)dX, (float *)dUk, (float *)dVp, accumulate, ws,
-                                       s);
-    if (p.chain && dX)
-        return conv_bwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
-                              (const bf16_t *)T_saved, p.saved_bytes ? W_saved : nullptr, (bf16_t *)dX, (float *)dUk,
-                              (float *)dVp, accumulate, ws, s);
-    return conv_bwd_generic<bf16_t>(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp,
-                                    (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk,
-                                    (float *)dVp, accumulate, ws, s);
+    bool fused = false;
+    return pf::conv_bwd_entry_ep(d, X, Uk, Vp, dY, T_saved, W_saved, nullptr, 0, dX, dUk, dVp, accumulate, workspace,
+                                 workspace_bytes, stream, &fused);
 }
 
 size_t pf_dense_conv_workspace_bytes(const pf_conv_desc *d)
@@ -547,22 +514,71 @@ int pf::conv_fwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, 
                           const float *shift, const void *residual, int act, void *Y, void *T_save, void *W_save,
                           void *workspace, size_t workspace_bytes, void *stream, bool *fused)
 {
-    (void)scale;
-    (void)shift;
-    (void)residual;
-    (void)act;
-    *fused = false;
-    return pf_lowrank_conv_fwd(d, X, Uk, Vp, Y, T_save, W_save, workspace, workspace_bytes, stream);
+    ConvGeom g;
+    int st = check_conv_desc(d, &g);
+    if (st != PF_OK) return st;
+    if (!Uk || !Vp) return PF_ERR_NULL;
+    if (g.N > 0 && (!X || !Y)) return PF_ERR_NULL;
+    if (any_misaligned({X, Uk, Vp, Y, T_save, W_save}, 16)) return PF_ERR_UNSUPPORTED;
+    const ConvPlan p = plan_conv(g, d->dtype);
+    if (p.fwd_bytes > 0 && (!workspace || workspace_bytes < p.fwd_bytes)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
+    if (g.N == 0) return PF_OK;
+    Workspace ws(workspace, workspace_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32)
+        return conv_fwd_generic<float>(g, (const float *)X, (const float *)Uk, (const float *)Vp, (float *)Y,
+                                       (float *)T_save, ws, s);
+    if (p.chain)
+    {
+        // the kernel applies the epilogue as it stores (its float4 loads of scale and shift need 16-byte alignment)
+        ConvEpilogue ep = {};
+        if (!any_misaligned({scale, shift}, 16)) {
+            ep = ConvEpilogue{scale, shift, residual, nullptr, act == PF_ACT_RELU ? 1 : 0};
+            *fused = true;
+        }
+        return conv_fwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
+                              (bf16_t *)T_save, W_save, ws, s, ep);
+    }
+    return conv_fwd_generic<bf16_t>(g, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (bf16_t *)Y,
+                                    (bf16_t *)T_save, ws, s);
 }
 
-int pf::conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dZ,
+int pf::conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dY,
                           const void *T_saved, const void *W_saved, const void *dX_add, int x_is_relu, void *dX,
                           void *dUk, void *dVp, int accumulate, void *workspace, size_t workspace_bytes, void *stream,
                           bool *fused)
 {
-    (void)dX_add;
-    (void)x_is_relu;
-    *fused = false;
-    return pf_lowrank_conv_bwd(d, X, Uk, Vp, dZ, T_saved, W_saved, dX, dUk, dVp, accumulate, workspace, workspace_bytes,
-                               stream);
+    ConvGeom g;
+    int st = check_conv_desc(d, &g);
+    if (st != PF_OK) return st;
+    if (!Uk || !Vp) return PF_ERR_NULL;
+    if (g.N > 0 && (!X || !dY)) return PF_ERR_NULL;
+    if (any_misaligned({X, Uk, Vp, dY, T_saved, W_saved, dX}, 16) || any_misaligned({dUk, dVp}, 4)) return PF_ERR_UNSUPPORTED;
+    const ConvPlan p = plan_conv(g, d->dtype);
+    if (p.bwd_bytes > 0 && (!workspace || workspace_bytes < p.bwd_bytes)) return PF_ERR_WORKSPACE;
+    if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
+    Workspace ws(workspace, workspace_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    if (g.N == 0) {
+        if (!accumulate) {
+            st = launch_zero_f32(s, (float *)dUk, (i64)g.r * g.C * g.k * g.k);
+            if (st == PF_OK) st = launch_zero_f32(s, (float *)dVp, (i64)g.Cout * g.r);
+        }
+        return st;
+    }
+    if (d->dtype == PF_F32)
+        return conv_bwd_generic<float>(g, p, (const float *)X, (const float *)Uk, (const float *)Vp, (const float *)dY,
+                                       (const float *)T_saved, (float *)dX, (float *)dUk, (float *)dVp, accumulate, ws,
+                                       s);
+    if (p.chain && dX)
+    {
+        *fused = true; // the kernel adds the skip gradient and masks as it stores dX
+        return conv_bwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
+                              (const bf16_t *)T_saved, p.saved_bytes ? W_saved : nullptr, (bf16_t *)dX, (float *)dUk,
+                              (float *)dVp, accumulate, ws, s, ConvEpilogue{nullptr, nullptr, dX_add, x_is_relu ? X : nullptr, 0});
+    }
+    return conv_bwd_generic<bf16_t>(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp,
+                                    (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk,
+                                    (float *)dVp, accumulate, ws, s);
 }

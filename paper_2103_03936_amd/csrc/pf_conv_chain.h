@@ -25,13 +25,20 @@ struct ChainArgs {
     const uint16_t *in;  // [N][C1][HW] bf16
     const uint4 *W1p;    // packed stage-1 weights, see make_pack_w1
     const uint4 *W2p;    // packed stage-2 weights, see make_pack_w2 (unused when W2nat is set)
-    const uint16_t *W2nat; // 1x1 stage 2 only, nullable: weights in their natural [C2][R] layout
+    const uint16_t *W2nat; // 1x1 stage 2 only, nullable: weights in their natural [C2][R] layout (a lane per row:
+                           // slow beyond a few output blocks; the fully connected mode at rank 64 uses it)
     uint16_t *out;       // [N][C2][HW] bf16
     uint16_t *mid_save;  // [N][R][HW] bf16, nullable
     int C1, C2, H, W;
     // fully connected ("channels last") mode only: in = X[rows][C1], out = Y[rows][C2], mid_save = T[rows][R]
     i64 rows;
     const void *bias; // bf16 [C2], nullable
+    // Epilogue applied as the output is stored (image mode only; every member nullable / zero):
+    //   out = mask > 0 ? act(scale[c] * out + shift[c] + add) : 0
+    const float *ep_scale, *ep_shift; // float [C2], 16-byte aligned
+    const uint16_t *ep_add;           // bf16 [N][C2][HW]: a residual input, or a gradient arriving over a skip connection
+    const uint16_t *ep_mask;          // bf16 [N][C2][HW]: the output is zero where this is not positive
+    int ep_relu;                      // act = max(0, .)
 };
 
 // Can the chain kernel take this problem?  (C1, C2: channels in / out of the chain.)
@@ -57,7 +64,8 @@ struct PackW2 {
 };
 PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap);
 PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o, i64 s_rho, i64 s_tap);
-int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3 = PackW1{});
+int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3 = PackW1{},
+                      const PackW2 &p4 = PackW2{});
 // The fully connected layer on the same kernel: Y[rows][C2] = (X[rows][C1] W1^T) W2^T + bias, W2 = a.W2nat.
 bool linear_chain_supported(i64 n_in, i64 n_out, i64 r);
 int launch_linear_chain(hipStream_t s, const char *name, const ChainArgs &a, int R);

@@ -29,7 +29,9 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v)
 // CL ("channels last", the fully connected layer): the input is a row-major matrix X[rows][C1], one tile =
 // 64 consecutive rows standing where the 64 pixels of an image stand; the intermediate and the output are
 // row-major too (T[rows][R], Y[rows][C2]), a bias may be added, and both stages are 1x1.
-template <int KS1, int KS2, int R, int HC, int WC, bool CL = false>
+// EP: the epilogue members of the arguments are honoured (a separate instantiation, so that the plain layer does
+// not carry their registers).
+template <int KS1, int KS2, int R, int HC, int WC, bool CL = false, bool EP = false>
 __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 {
     constexpr int RB = R / 32, R16 = R / 16, T1 = KS1 * KS1, T2 = KS2 * KS2;
@@ -64,7 +66,9 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     // in memory order, and the transposing LDS read turns them into MFMA fragments (the pixel-by-pixel gather
     // costs eight 2-byte loads per item on the unit that also carries the weight stream).  A 7 x 7 plane is 98
     // bytes: one unaligned load per group of 8 slots, the last group read from further back so that it stays
-    // in the plane.
+    // in the plane.  (Aligned loads of the planes laid end to end, written to their slots with 16-byte LDS
+    // stores at 2-byte aligned addresses, were measured: the misaligned LDS stores cost more than the
+    // misaligned global loads, 3.8 k against 2.8 k cycles per 64-channel round.)
     constexpr bool XT = !CL && KS1 == 1 && ((HC == 8 && WC == 8) || (HC == 7 && WC == 7));
     constexpr int XG = HC == 8 ? 8 : 7; // 16-byte items per plane
     uint4 xv[NXV];
@@ -250,7 +254,8 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 
     store_x();
     if (nsub > 1) load_x(grp(GPS) / GPS);
-    __syncthreads();
+    // (the tile is this wavefront's own: no workgroup barrier, which would also wait for the loads just issued)
+    __builtin_amdgcn_wave_barrier();
     for (int g = 0; g < ngroups; g += 2) {
         run_group(afA, afB, grp(g), grp(g + 1));
         next_round(g);
@@ -322,7 +327,11 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                     const i64 row = (i64)n * CH_PIX + pix;
                     if (row < a.rows) *(uint4 *)(a.mid_save + row * R + 64 * rh + r0) = pk;
                 } else if (a.mid_save) {
-                    uint16_t *ms = a.mid_save + ((i64)n * R + 64 * rh + r0) * HW + pix;
+                    // The copy kept for the backward pass is [R][HW]: these 8 rows of it are HW 16-byte pieces in a
+                    // row.  They are put together in this wavefront's idle input tile and leave below as aligned
+                    // 16-byte stores (2-byte stores from here cost the memory pipeline sixteen times as many
+                    // instructions, and the barrier below would wait for them).
+                    uint16_t *ms = xs + (2 * rh + it) * 8 * CH_PIX + pix;
                     const uint32_t d[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
                     for (int e = 0; e < 8; ++e) ms[e * HW] = (uint16_t)(d[e >> 1] >> (16 * (e & 1)));
@@ -331,6 +340,15 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         }
     }
     __syncthreads();
+    if (a.mid_save && !CL) { // rows 64 rh + 8 (w + 4 it) .. + 7 of the intermediate, from this wavefront's tile
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ck = 0; ck < R / 32; ++ck) { // chunk ck = 2 rh + it
+            const int r0 = 64 * (ck >> 1) + 8 * (w + 4 * (ck & 1));
+            uint4 *dst = (uint4 *)(a.mid_save + ((i64)n * R + r0) * HW);
+            if (lane < HW) dst[lane] = *(const uint4_alias *)&xs[ck * 8 * CH_PIX + 8 * lane];
+        }
+    }
 
     // ------------------------------- stage 2 -------------------------------
     f32x16_t acc2[2][2];
@@ -341,8 +359,22 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
 
+    // epilogue operands of the output-block pair in work (16-byte pieces of the pair's 64 x HW block), requested
+    // when the pair starts so that they have arrived when it is stored
+    constexpr int NOV = CH_PIX * CH_PIX / 8 / 64;
+    uint4 epa[NOV], epm[NOV];
+    const bool ep_any = EP && !CL && (a.ep_add || a.ep_mask || a.ep_relu);
     auto run_group2 = [&](const uint4(&cur)[2][R16], uint4(&nxt)[2][R16], int q) __attribute__((always_inline)) {
         const int tap = tap_of(q);
+        if (EP && !CL && q % T2 == 0 && (a.ep_add || a.ep_mask)) {
+            const i64 blk = ((i64)n * C2 + 32 * (2 * w + 8 * (q / T2))) * HW;
+#pragma unroll
+            for (int i = 0; i < NOV; ++i) {
+                const int vi = min(lane + 64 * i, 64 * HW / 8 - 1);
+                if (a.ep_add) epa[i] = ((const uint4 *)(a.ep_add + blk))[vi];
+                if (a.ep_mask) epm[i] = ((const uint4 *)(a.ep_mask + blk))[vi];
+            }
+        }
         const int toff = (KS2 == 3 ? (tap / 3) * Wp2 + (tap % 3) : 0) * TLD;
         const uint4 *src = w2src(q + 1);
         uint4 bc[2], bn[2];
@@ -410,6 +442,23 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                 return;
             }
             uint16_t *ys = xs + (4 * half) * HW + col;
+            if (EP && (a.ep_scale || a.ep_shift)) { // per output channel, in float, before the one rounding to bf16
+#pragma unroll
+                for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const int ch = 32 * ob + 32 * bb + 8 * qd + 4 * half; // four consecutive channels
+                        const float4 sc = a.ep_scale ? *(const float4 *)(a.ep_scale + ch) : make_float4(1.f, 1.f, 1.f, 1.f);
+                        const float4 sh = a.ep_shift ? *(const float4 *)(a.ep_shift + ch) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                        for (int pb = 0; pb < 2; ++pb) {
+                            acc2[bb][pb][4 * qd + 0] = acc2[bb][pb][4 * qd + 0] * sc.x + sh.x;
+                            acc2[bb][pb][4 * qd + 1] = acc2[bb][pb][4 * qd + 1] * sc.y + sh.y;
+                            acc2[bb][pb][4 * qd + 2] = acc2[bb][pb][4 * qd + 2] * sc.z + sh.z;
+                            acc2[bb][pb][4 * qd + 3] = acc2[bb][pb][4 * qd + 3] * sc.w + sh.w;
+                        }
+                    }
+            }
 #pragma unroll
             for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
@@ -430,7 +479,33 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int i = 0; i < CH_PIX * CH_PIX / 8 / 64; ++i) {
                 const int vi = lane + 64 * i;
-                if (vi < nv) dst[vi] = *(const uint4_alias *)&xs[8 * vi];
+                if (vi < nv) {
+                    uint4 y = *(const uint4_alias *)&xs[8 * vi];
+                    if (EP && ep_any) { // (uniform) residual / skip gradient, activation, mask: on the block as it leaves
+                        uint32_t yw[4] = {y.x, y.y, y.z, y.w};
+                        const uint32_t aw[4] = {epa[i].x, epa[i].y, epa[i].z, epa[i].w};
+                        const uint32_t mw[4] = {epm[i].x, epm[i].y, epm[i].z, epm[i].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float lo = bf16_bits_to_float((uint16_t)yw[e]), hi = bf16_bits_to_float((uint16_t)(yw[e] >> 16));
+                            if (a.ep_add) {
+                                lo += bf16_bits_to_float((uint16_t)aw[e]);
+                                hi += bf16_bits_to_float((uint16_t)(aw[e] >> 16));
+                            }
+                            if (a.ep_relu) {
+                                lo = fmaxf(lo, 0.f);
+                                hi = fmaxf(hi, 0.f);
+                            }
+                            if (a.ep_mask) {
+                                lo = bf16_bits_to_float((uint16_t)mw[e]) > 0.f ? lo : 0.f;
+                                hi = bf16_bits_to_float((uint16_t)(mw[e] >> 16)) > 0.f ? hi : 0.f;
+                            }
+                            yw[e] = pack_bf16x2(lo, hi);
+                        }
+                        y = make_uint4(yw[0], yw[1], yw[2], yw[3]);
+                    }
+                    dst[vi] = y;
+                }
             }
         }
     };
@@ -464,7 +539,7 @@ __device__ __forceinline__ void pack_w2_item(const PackW2 &p, int g)
 }
 
 // All weight sets of one call in a single launch (any count may be zero).
-__global__ __launch_bounds__(256) void pack_chain_kernel(PackW1 p1, PackW2 p2, PackW1 p3)
+__global__ __launch_bounds__(256) void pack_chain_kernel(PackW1 p1, PackW2 p2, PackW1 p3, PackW2 p4)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
     if (g < p1.n)
@@ -473,6 +548,8 @@ __global__ __launch_bounds__(256) void pack_chain_kernel(PackW1 p1, PackW2 p2, P
         pack_w2_item(p2, g - p1.n);
     else if (g - p1.n - p2.n < p3.n)
         pack_w1_item(p3, g - p1.n - p2.n);
+    else if (g - p1.n - p2.n - p3.n < p4.n)
+        pack_w2_item(p4, g - p1.n - p2.n - p3.n);
 }
 
 bool chain_supported(int C1, int C2, int R, int H, int W, int k, int stride, int pad)
@@ -517,12 +594,12 @@ PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 b
     return p;
 }
 
-int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3)
+int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3, const PackW2 &p4)
 {
     int st = PF_OK;
-    const int n = p1.n + p2.n + p3.n;
+    const int n = p1.n + p2.n + p3.n + p4.n;
     if (n <= 0) return st;
-    PF_LAUNCH(st, "pack_chain", pack_chain_kernel, dim3((n + 255) / 256), dim3(256), s, p1, p2, p3);
+    PF_LAUNCH(st, "pack_chain", pack_chain_kernel, dim3((n + 255) / 256), dim3(256), s, p1, p2, p3, p4);
     return st;
 }
 
@@ -552,9 +629,16 @@ int launch_conv_chain(hipStream_t s, const char *name, const ChainArgs &a, int N
     if (N <= 0) return st;
     const dim3 grid(N), block(256);
     const int hw = (a.H == 8 && a.W == 8) ? 8 : (a.H == 7 && a.W == 7) ? 7 : 0;
+    const bool ep = a.ep_scale || a.ep_shift || a.ep_add || a.ep_mask || a.ep_relu;
 #define PF_CHAIN_CASE(K1, K2, RR)                                                                    \
     if (k1 == K1 && k2 == K2 && R == RR) {                                                           \
-        if (hw == 8) {                                                                               \
+        if (hw == 8 && ep) {                                                                         \
+            PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 8, 8, false, true>), grid, block, s, a); \
+        } else if (hw == 7 && ep) {                                                                  \
+            PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 7, 7, false, true>), grid, block, s, a); \
+        } else if (ep) {                                                                             \
+            PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 0, 0, false, true>), grid, block, s, a); \
+        } else if (hw == 8) {                                                                        \
             PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 8, 8>), grid, block, s, a);           \
         } else if (hw == 7) {                                                                        \
             PF_LAUNCH(st, name, (conv_chain_kernel<K1, K2, RR, 7, 7>), grid, block, s, a);           \
