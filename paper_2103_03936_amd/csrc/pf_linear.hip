@@ -106,11 +106,19 @@ static int check_linear_desc(const pf_linear_desc *d)
     return PF_OK;
 }
 
+// What the 32-row chain kernel applies as its output leaves (all optional; *used reports that it did).
+struct LinEpilogue {
+    const void *add, *mask;
+    int relu;
+    bool *used;
+};
+
 int linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias, void *Y,
-                     void *T_save, void *workspace, size_t workspace_bytes, void *stream, int align);
+                     void *T_save, void *workspace, size_t workspace_bytes, void *stream, int align,
+                     const LinEpilogue *ep = nullptr);
 int linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
                      const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate, void *workspace,
-                     size_t workspace_bytes, void *stream, int align);
+                     size_t workspace_bytes, void *stream, int align, const LinEpilogue *ep = nullptr);
 
 // ---------------------------------------------------------- workspace plan
 struct LinearPlan {
@@ -268,13 +276,17 @@ static int linear_bwd_generic(const pf_linear_desc *d, const T *X, const T *V, c
 // Y = (X V) U^T + bias on the two-stage chain kernel: stage 1 weights = V^T re-ordered into MFMA fragments,
 // stage 2 weights = U[out][r] read in place.
 static int linear_fwd_fused(const pf_linear_desc *d, const bf16_t *X, const bf16_t *V, const bf16_t *U,
-                            const bf16_t *bias, bf16_t *Y, bf16_t *T_save, Workspace &ws, hipStream_t s)
+                            const bf16_t *bias, bf16_t *Y, bf16_t *T_save, Workspace &ws, hipStream_t s,
+                            const LinEpilogue &ep = LinEpilogue{})
 {
     const int in = (int)d->in, out = (int)d->out, r = (int)d->r;
     if (linear_chain2_supported(in, out, r)) {
         LinChainArgs c{(const uint16_t *)X, (const uint16_t *)V, (const uint16_t *)U,
                        d->has_bias ? (const uint16_t *)bias : nullptr, (uint16_t *)Y, (uint16_t *)T_save, nullptr,
                        d->M, in, out};
+        c.ep_add = (const uint16_t *)ep.add;
+        c.ep_relu = ep.relu;
+        if (ep.used) *ep.used = true;
         return launch_linear_chain2(s, "linear_fwd_fused", c);
     }
     uint16_t *w1 = ws.take<uint16_t>((size_t)(in > out ? in : out) * r);
@@ -316,7 +328,8 @@ static int linear_wgrads_fused(const pf_linear_desc *d, const LinearPlan &p, con
 // place); then both factor gradients in one launch, their group sums, and the bias gradient.
 static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const bf16_t *X, const bf16_t *V,
                             const bf16_t *U, const bf16_t *dY, const bf16_t *T_saved, bf16_t *dX, float *dU, float *dV,
-                            float *dbias, int accumulate, Workspace &ws, hipStream_t s)
+                            float *dbias, int accumulate, Workspace &ws, hipStream_t s,
+                            const LinEpilogue &ep = LinEpilogue{})
 {
     const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
     uint16_t *w1 = ws.take<uint16_t>((size_t)(in > out ? in : out) * r);
@@ -336,6 +349,9 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
     if (p.chain2) {
         LinChainArgs c{(const uint16_t *)dY, (const uint16_t *)U, (const uint16_t *)V, nullptr, (uint16_t *)dX,
                        (uint16_t *)dT16, want_db ? colsum : nullptr, d->M, out, in};
+        c.ep_add = (const uint16_t *)ep.add;
+        c.ep_mask = (const uint16_t *)ep.mask;
+        if (ep.used) *ep.used = true;
         st = launch_linear_chain2(s, "linear_bwd_data_fused", c);
     } else {
         st = launch_pack_chain(s, make_pack_w1((const uint16_t *)U, (uint4 *)w1, out, r, 1, 1, r, 0),
@@ -562,7 +578,8 @@ using namespace pf;
 // `align`: what the data pointers must be multiples of (16 for callers; the layers of a shared-input call may
 // start anywhere an element does when their shape is one the element-wise kernels take)
 int pf::linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *bias,
-                         void *Y, void *T_save, void *workspace, size_t workspace_bytes, void *stream, int align)
+                         void *Y, void *T_save, void *workspace, size_t workspace_bytes, void *stream, int align,
+                         const LinEpilogue *ep)
 {
     int st = check_linear_desc(d);
     if (st != PF_OK) return st;
@@ -583,14 +600,14 @@ int pf::linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, 
                                          (float *)Y, (float *)T_save, ws, s);
     if (plan_linear(d).fused)
         return linear_fwd_fused(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U, (const bf16_t *)bias,
-                                (bf16_t *)Y, (bf16_t *)T_save, ws, s);
+                                (bf16_t *)Y, (bf16_t *)T_save, ws, s, ep ? *ep : LinEpilogue{});
     return linear_fwd_generic<bf16_t>(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U,
                                       (const bf16_t *)bias, (bf16_t *)Y, (bf16_t *)T_save, ws, s);
 }
 
 int pf::linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dY,
                          const void *T_saved, void *dX, void *dU, void *dV, void *dbias, int accumulate,
-                         void *workspace, size_t workspace_bytes, void *stream, int align)
+                         void *workspace, size_t workspace_bytes, void *stream, int align, const LinEpilogue *ep)
 {
     int st = check_linear_desc(d);
     if (st != PF_OK) return st;
@@ -614,7 +631,7 @@ int pf::linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, 
     if (p.fused && dX && d->M > 0)
         return linear_bwd_fused(d, p, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U, (const bf16_t *)dY,
                                 (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dU, (float *)dV, (float *)dbias,
-                                accumulate, ws, s);
+                                accumulate, ws, s, ep ? *ep : LinEpilogue{});
     return linear_bwd_generic<bf16_t>(d, (const bf16_t *)X, (const bf16_t *)V, (const bf16_t *)U,
                                       (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dU,
                                       (float *)dV, (float *)dbias, accumulate, ws, s);
@@ -863,10 +880,9 @@ int pf::linear_fwd_entry_ep(const pf_linear_desc *d, const void *X, const void *
                             const void *residual, int act, void *Y, void *T_save, void *workspace,
                             size_t workspace_bytes, void *stream, bool *fused)
 {
-    (void)residual;
-    (void)act;
     *fused = false;
-    return pf::linear_fwd_entry(d, X, V, U, bias, Y, T_save, workspace, workspace_bytes, stream, 16);
+    const LinEpilogue ep{residual, nullptr, act == PF_ACT_RELU ? 1 : 0, fused};
+    return pf::linear_fwd_entry(d, X, V, U, bias, Y, T_save, workspace, workspace_bytes, stream, 16, &ep);
 }
 
 int pf::linear_bwd_entry_ep(const pf_linear_desc *d, const void *X, const void *V, const void *U, const void *dZ,
@@ -874,9 +890,8 @@ int pf::linear_bwd_entry_ep(const pf_linear_desc *d, const void *X, const void *
                             void *dbias, int accumulate, void *workspace, size_t workspace_bytes, void *stream,
                             bool *fused)
 {
-    (void)dX_add;
-    (void)x_is_relu;
     *fused = false;
+    const LinEpilogue ep{dX_add, x_is_relu ? X : nullptr, 0, fused};
     return pf::linear_bwd_entry(d, X, V, U, dZ, T_saved, dX, dU, dV, dbias, accumulate, workspace, workspace_bytes,
-                                stream, 16);
+                                stream, 16, &ep);
 }

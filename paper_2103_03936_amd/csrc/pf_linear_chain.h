@@ -27,6 +27,11 @@ struct LinChainArgs {
     // pass of projections that share their input.
     int groups, sum_out;
     i64 gs_in, gs_W1, gs_W2, gs_bias, gs_out, gs_mid, gs_colsum;
+    // Epilogue applied as the output leaves (single layer only; every member nullable / zero):
+    //   out = mask > 0 ? act(out + add) : 0
+    const uint16_t *ep_add;  // [rows][C2] bf16: a residual input, or a gradient arriving over a skip connection
+    const uint16_t *ep_mask; // [rows][C2] bf16: the output is zero where this is not positive
+    int ep_relu;             // act = max(0, .)
 };
 
 constexpr int LC_ROWS = 32; // rows per workgroup

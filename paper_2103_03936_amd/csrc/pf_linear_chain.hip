@@ -33,7 +33,9 @@ __device__ __forceinline__ bf16x8_t lc_as_bf16x8(u32x4_t v) { return __builtin_b
 // unrolled and its W2 fragments are fetched two pairs ahead, the first two during stage 1; NP == 0: any C2.
 // MODE 0: one layer.  MODE 1: the groups of LinChainArgs run one after the other in the same workgroup (same
 // rows), each with its own output.  MODE 2: the same, but the groups' stage-2 products are summed into one output.
-template <int NP, int MODE = 0>
+// EP: the epilogue members of the arguments are honoured (MODE 0 only; a separate instantiation, so that the plain
+// layer does not carry their registers).
+template <int NP, int MODE = 0, bool EP = false>
 __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args)
 {
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][LC_ROWS * LC_XP];
@@ -239,6 +241,17 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
     auto pair = [&](const UR &u, int g) __attribute__((always_inline)) {
         if (2 * g >= obw) return;
         const int ob0 = w * obw + 2 * pair_of(g);
+        // epilogue operands of this patch, requested before the products so that they have arrived at the store
+        u32x4_t ea[4], em[4];
+        if (EP && (a.ep_add || a.ep_mask)) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
+                const i64 row = row0 + r < a.rows ? row0 + r : a.rows - 1;
+                if (a.ep_add) ea[i] = *(const uint4_alias *)(a.ep_add + row * C2 + 32 * ob0 + 8 * ch);
+                if (a.ep_mask) em[i] = *(const uint4_alias *)(a.ep_mask + row * C2 + 32 * ob0 + 8 * ch);
+            }
+        }
         f32x16_t y[2];
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi)
@@ -283,7 +296,26 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
-            const u32x4_t v = *(const uint4_alias *)&Ys[w][r * LC_YP + 8 * ch];
+            u32x4_t v = *(const uint4_alias *)&Ys[w][r * LC_YP + 8 * ch];
+            if (EP && (a.ep_add || a.ep_mask || a.ep_relu)) { // (uniform)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float lo = bf16_bits_to_float((uint16_t)v[e]), hi = bf16_bits_to_float((uint16_t)(v[e] >> 16));
+                    if (a.ep_add) {
+                        lo += bf16_bits_to_float((uint16_t)ea[i][e]);
+                        hi += bf16_bits_to_float((uint16_t)(ea[i][e] >> 16));
+                    }
+                    if (a.ep_relu) {
+                        lo = fmaxf(lo, 0.f);
+                        hi = fmaxf(hi, 0.f);
+                    }
+                    if (a.ep_mask) {
+                        lo = bf16_bits_to_float((uint16_t)em[i][e]) > 0.f ? lo : 0.f;
+                        hi = bf16_bits_to_float((uint16_t)(em[i][e] >> 16)) > 0.f ? hi : 0.f;
+                    }
+                    v[e] = pack_bf16x2(lo, hi);
+                }
+            }
             if (row0 + r < a.rows) *(uint4_alias *)(a.out + (row0 + r) * C2 + 32 * ob0 + 8 * ch) = v;
         }
         __builtin_amdgcn_wave_barrier();
@@ -341,6 +373,16 @@ int launch_linear_chain2(hipStream_t s, const char *name, const LinChainArgs &a)
         case 4: PF_LAUNCH(st, name, (linear_chain2_kernel<4, 1>), grid, block, s, a); break;
         case 8: PF_LAUNCH(st, name, (linear_chain2_kernel<8, 1>), grid, block, s, a); break;
         default: PF_LAUNCH(st, name, (linear_chain2_kernel<0, 1>), grid, block, s, a); break;
+        }
+        return st;
+    }
+    if (a.ep_add || a.ep_mask || a.ep_relu) {
+        switch (a.C2 / 256) {
+        case 1: PF_LAUNCH(st, name, (linear_chain2_kernel<1, 0, true>), grid, block, s, a); break;
+        case 2: PF_LAUNCH(st, name, (linear_chain2_kernel<2, 0, true>), grid, block, s, a); break;
+        case 4: PF_LAUNCH(st, name, (linear_chain2_kernel<4, 0, true>), grid, block, s, a); break;
+        case 8: PF_LAUNCH(st, name, (linear_chain2_kernel<8, 0, true>), grid, block, s, a); break;
+        default: PF_LAUNCH(st, name, (linear_chain2_kernel<0, 0, true>), grid, block, s, a); break;
         }
         return st;
     }
