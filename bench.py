@@ -461,6 +461,141 @@ class LstmWorkload:
         return 2
 
 
+class FfnBlockWorkload:
+    """y = x + FFN(x), FFN(x) = max(0, x W1 + b1) W2 + b2 (Section 2.4) with both matrices factorized: two
+    pf_lowrank_linear_fwd_ep calls forward, two pf_lowrank_linear_bwd_ep calls backward (the ReLU mask applied where
+    dH is formed, the skip gradient where dx is formed)."""
+
+    def __init__(self, name, cfg):
+        self.name, self.dtype, self.cfg = name, cfg["dtype"], cfg
+        c = cfg
+        self.inner = LinearWorkload(name, dict(kind="linear_set", dtype=c["dtype"], M=c["M"], seed=c["seed"], layers=dict(
+            ffn1=(c["d"], c["dff"], c["r"]), ffn2=(c["dff"], c["d"], c["r"]))))
+
+    def describe(self):
+        c = self.cfg
+        return {"workload": self.name, "tokens": c["M"], "d_model": c["d"], "d_ff": c["dff"], "r": c["r"],
+                "calls": "pf_lowrank_linear_fwd_ep / pf_lowrank_linear_bwd_ep"}
+
+    def flops(self):
+        return self.inner.flops()
+
+    def dense_flops(self):
+        return self.inner.dense_flops()
+
+    def algorithmic_bytes(self):
+        return self.inner.algorithmic_bytes()
+
+    def kernel_work(self):
+        return self.inner.kernel_work()
+
+    def make_set(self, i, torch, workloads):
+        return self.inner.make_set(i, torch, workloads)
+
+    def step(self, pf, s):
+        g1, g2 = s["ffn1"], s["ffn2"]
+        H, T1 = pf.pf_lowrank_linear_fwd_ep(g1["X"], g1["V"], g1["U"], g1["bias"], act="relu")
+        Y, T2 = pf.pf_lowrank_linear_fwd_ep(H, g2["V"], g2["U"], g2["bias"], residual=g1["X"])
+        dZ1, _, _, _ = pf.pf_lowrank_linear_bwd_ep(H, g2["V"], g2["U"], g2["dY"], T_saved=T2, x_is_relu=True, has_bias=True)
+        pf.pf_lowrank_linear_bwd_ep(g1["X"], g1["V"], g1["U"], dZ1, T_saved=T1, dX_add=g2["dY"], has_bias=True)
+
+    def separate_step(self, pf, s, torch):
+        """The same block with the plain calls and the element-wise steps as separate (torch) kernels."""
+        g1, g2 = s["ffn1"], s["ffn2"]
+        H, T1 = pf.pf_lowrank_linear_fwd(g1["X"], g1["V"], g1["U"], g1["bias"])
+        H = torch.relu_(H)
+        Y, T2 = pf.pf_lowrank_linear_fwd(H, g2["V"], g2["U"], g2["bias"])
+        Y += g1["X"]
+        dH, _, _, _ = pf.pf_lowrank_linear_bwd(H, g2["V"], g2["U"], g2["dY"], T_saved=T2, has_bias=True)
+        dH *= (H > 0)
+        dx, _, _, _ = pf.pf_lowrank_linear_bwd(g1["X"], g1["V"], g1["U"], dH, T_saved=T1, has_bias=True)
+        dx += g2["dY"]
+
+    def cpu_baseline(self, oracle, workloads, rows=None):
+        return self.inner.cpu_baseline(oracle, workloads, rows)
+
+    def cpu_single_thread_sample(self):
+        return self.inner.cpu_single_thread_sample()
+
+
+class BasicBlockWorkload:
+    """A ResNet-18 basic block (Appendix D) of two factorized 3x3 convolutions, batch norm with fixed statistics and
+    ReLU after each, identity shortcut: y1 = relu(bn1(conv1(x))), y2 = relu(bn2(conv2(y1)) + x), through
+    pf_lowrank_conv_fwd_ep / pf_lowrank_conv_bwd_ep."""
+
+    def __init__(self, name, cfg):
+        self.name, self.dtype, self.cfg = name, cfg["dtype"], cfg
+        c = cfg
+        self.inner = ConvWorkload(name, dict(kind="conv_set", dtype=c["dtype"], N=c["N"], H=c["H"], W=c["W"], seed=c["seed"],
+                                             layers=dict(conv1=(c["C"], c["C"], c["r"], c["k"], c["k"] // 2),
+                                                         conv2=(c["C"], c["C"], c["r"], c["k"], c["k"] // 2))))
+
+    def describe(self):
+        d = self.inner.describe()
+        d["calls"] = "pf_lowrank_conv_fwd_ep / pf_lowrank_conv_bwd_ep"
+        return d
+
+    def flops(self):
+        return self.inner.flops()
+
+    def dense_flops(self):
+        return self.inner.dense_flops()
+
+    def algorithmic_bytes(self):
+        return self.inner.algorithmic_bytes()
+
+    def kernel_work(self):
+        return self.inner.kernel_work()
+
+    def make_set(self, i, torch, workloads):
+        s = self.inner.make_set(i, torch, workloads)
+        C = self.cfg["C"]
+        for j, g in enumerate(s.values()):
+            gen = torch.Generator(device="cpu").manual_seed(1000 * i + j)
+            g["scale"] = (0.5 + torch.rand(C, generator=gen)).cuda()
+            g["shift"] = (0.2 * torch.randn(C, generator=gen)).cuda()
+        s["conv1"]["X"] = torch.relu(s["conv1"]["X"])
+        return s
+
+    def step(self, pf, s):
+        g1, g2 = s["conv1"], s["conv2"]
+        p = g1["pad"]
+        y1, T1, W1 = pf.pf_lowrank_conv_fwd_ep(g1["X"], g1["Uk"], g1["Vp"], g1["scale"], g1["shift"], act="relu", stride=1,
+                                               pad=p, save_W=True)
+        y2, T2, W2 = pf.pf_lowrank_conv_fwd_ep(y1, g2["Uk"], g2["Vp"], g2["scale"], g2["shift"], residual=g1["X"], act="relu",
+                                               stride=1, pad=p, save_W=True)
+        dZ2 = g2["dY"]  # (what the block above hands down)
+        dZ1, _, _, _ = pf.pf_lowrank_conv_bwd_ep(y1, g2["Uk"], g2["Vp"], g2["scale"], dZ2, T_saved=T2, stride=1, pad=p,
+                                                 x_is_relu=True, W_saved=W2)
+        pf.pf_lowrank_conv_bwd_ep(g1["X"], g1["Uk"], g1["Vp"], g1["scale"], dZ1, T_saved=T1, stride=1, pad=p, dX_add=dZ2,
+                                  x_is_relu=True, W_saved=W1)
+
+    def separate_step(self, pf, s, torch):
+        g1, g2 = s["conv1"], s["conv2"]
+        p = g1["pad"]
+        bn = lambda y, g: y.mul_(g["scale"].to(y.dtype)[None, :, None, None]).add_(g["shift"].to(y.dtype)[None, :, None, None])
+        y1, T1, W1 = pf.pf_lowrank_conv_fwd(g1["X"], g1["Uk"], g1["Vp"], 1, p, save_W=True)
+        y1 = torch.relu_(bn(y1, g1))
+        y2, T2, W2 = pf.pf_lowrank_conv_fwd(y1, g2["Uk"], g2["Vp"], 1, p, save_W=True)
+        y2 = torch.relu_(bn(y2, g2).add_(g1["X"]))
+        dZ2 = g2["dY"]
+        dP2 = dZ2 * g2["scale"].to(dZ2.dtype)[None, :, None, None]
+        dsh2 = dZ2.float().sum(dim=(0, 2, 3))
+        dy1, _, _ = pf.pf_lowrank_conv_bwd(y1, g2["Uk"], g2["Vp"], dP2, T_saved=T2, stride=1, pad=p, W_saved=W2)
+        dy1 *= (y1 > 0)
+        dP1 = dy1 * g1["scale"].to(dy1.dtype)[None, :, None, None]
+        dsh1 = dy1.float().sum(dim=(0, 2, 3))
+        dx, _, _ = pf.pf_lowrank_conv_bwd(g1["X"], g1["Uk"], g1["Vp"], dP1, T_saved=T1, stride=1, pad=p, W_saved=W1)
+        dx += dZ2
+        dx *= (g1["X"] > 0)
+
+    def cpu_baseline(self, oracle, workloads, images=None):
+        return self.inner.cpu_baseline(oracle, workloads, images)
+
+    def cpu_single_thread_sample(self):
+        return self.inner.cpu_single_thread_sample()
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there is no
     figure or the kernel's source file has changed since the counters were taken."""
@@ -518,6 +653,10 @@ def make_workload(name, lstm_groups=1):
         return LinearWorkload(name, cfg)
     if cfg["kind"] == "lstm":
         return LstmWorkload(name, cfg, groups=lstm_groups)
+    if cfg["kind"] == "ffn_block":
+        return FfnBlockWorkload(name, cfg)
+    if cfg["kind"] == "basic_block":
+        return BasicBlockWorkload(name, cfg)
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -707,6 +846,14 @@ def run_workload(args, torch, pf, workloads, name, lstm_groups=1):
         except Exception as e:
             unfused = {"error": repr(e)[:200]}
 
+    separate = None
+    if hasattr(wl, "separate_step"):
+        sep = lambda s_: wl.separate_step(pf, s_, torch)
+        sms = summary(time_steps(torch, sep, sets, args.steps, args.warmup) if args.no_graph else
+                      time_graph_steps(torch, sep, sets, args.steps, args.warmup))
+        separate = dict(sms, what="the same block through the plain calls, its element-wise steps as separate kernels",
+                        speedup_of_fused_epilogues=sms["ms_per_step"] / ms)
+
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, workloads)
     del sets, one
     torch.cuda.empty_cache()
@@ -718,12 +865,14 @@ def run_workload(args, torch, pf, workloads, name, lstm_groups=1):
         "launch": "eager" if args.no_graph else "hip_graph", "eager_ms_per_step": eager["ms_per_step"],
         "cache_resident": {"ms_per_step": resident["ms_per_step"], "value": flops / (resident["ms_per_step"] * 1e-3) / 1e12},
         "roofline": roofline, "cpu_baseline": cpu, "dense_layer_vendor_library": library,
-        "unfused_vendor_library": unfused, "kernels": kernels,
+        "unfused_vendor_library": unfused, "separate_epilogues": separate, "kernels": kernels,
     }
 
 
 # the five benchmark configurations, largest first (the first is the headline unless --workload names another)
 FIVE = ["resnet50_conv5_bf16", "transformer_block_bf16", "lstm_lm_stack_f32", "resnet18_conv4_bf16", "linear_fc_f32"]
+# two blocks that run the layers with their epilogues (not among the five configurations; reported after them)
+BLOCKS = ["transformer_ffn_block_bf16", "resnet18_basic_block_bf16"]
 
 
 def main():
@@ -765,6 +914,11 @@ def main():
             others.append(r)
             if workloads.CONFIGS[name]["kind"] == "lstm":  # the paper's own reading: one factor pair per gate and path
                 others.append(run_workload(args, torch, pf, workloads, name, 4))
+        saved, args.no_dense, args.no_cpu_baseline = (args.no_dense, args.no_cpu_baseline), True, True
+        for name in BLOCKS:
+            if name != args.workload:
+                others.append(run_workload(args, torch, pf, workloads, name, 1))
+        args.no_dense, args.no_cpu_baseline = saved
 
     if args.copy_calibration:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
@@ -781,7 +935,7 @@ def main():
     brief = lambda r: {k: r[k] for k in ("config", "dtype", "ms_per_step", "value", "unit", "timing", "frac_of_mfma_peak",
                                          "arithmetic_intensity", "attainable_TFLOPs", "frac_of_min_peak_ai_bw",
                                          "eager_ms_per_step", "roofline", "cpu_baseline", "dense_layer_vendor_library",
-                                         "unfused_vendor_library", "kernels")}
+                                         "unfused_vendor_library", "separate_epilogues", "kernels")}
     out["workloads"] = [brief(head)] + [brief(r) for r in others]
     print(json.dumps(out))
 

@@ -232,7 +232,9 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk,
 /* Backward from dZ:  dP = scale dZ, dT = Vp^T dP, dVp = dP T^T,        */
 /*   dshift[o] = sum over n,y,x of dZ (float[Cout], nullable),          */
 /*   dX = (transposed convolution of dT + dX_add) * [X > 0].            */
-/* The scale is a constant here and has no gradient.                    */
+/* The scale is a constant here and has no gradient.  A W_saved handed */
+/* to the backward call must come from pf_lowrank_conv_fwd_ep called   */
+/* with the same scale (the saved copy of the 1x1 filters carries it). */
 /*                                                                      */
 /* Workspace: the *_fwd_ep calls and pf_lowrank_linear_bwd_ep need what */
 /* the plain calls need; pf_lowrank_conv_bwd_ep has its own query.      */

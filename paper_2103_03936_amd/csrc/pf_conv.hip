@@ -313,7 +313,12 @@ static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
     int st = launch_pack_chain(
         s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1),
         make_pack_w2(W_save ? (const uint16_t *)Uk : nullptr, (uint4 *)s2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1),
-        make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0),
+        // (kept for a backward call that is given the same scale: its first stage runs on scale * Vp)
+        [&] {
+            PackW1 q = make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0);
+            q.cscale = ep.scale;
+            return q;
+        }(),
         make_pack_w2((const uint16_t *)Vp, (uint4 *)w2, g.Cout, g.r, 1, 0, g.r, 1, 0));
     if (st != PF_OK) return st;
     ChainArgs a{(const uint16_t *)X, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)Y,
@@ -345,9 +350,11 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
         if (st != PF_OK) return st;
     }
     // stage 1: dT = Vp^T dY (1x1); stage 2: dX = flipped-Uk * dT (k x k)
-    if (!W_saved)
-        st = launch_pack_chain(s, make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0),
-                               make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
+    if (!W_saved) {
+        PackW1 q = make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0);
+        q.cscale = ep.scale; // dT = Vp^T (scale dZ) = (scale Vp)^T dZ
+        st = launch_pack_chain(s, q, make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
+    }
     if (st != PF_OK) return st;
     ChainArgs a{(const uint16_t *)dY, (const uint4 *)w1, (const uint4 *)w2, nullptr, (uint16_t *)dX,
                 (uint16_t *)dT16,     g.Cout,            g.C,               g.H,     g.W,
@@ -364,8 +371,8 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
                   p.wg_ipg2,            p.wg_groups2, 0};
     st = launch_conv_wgrad_pair(s, wa1, g.k, wa2);
     if (st != PF_OK) return st;
-    WgradReduceArgs r0{part_dUk, dUk, p.wg_groups, T, g.r, g.C, (i64)g.C * T, T, 1, accumulate};
-    WgradReduceArgs r1{part_dVp, dVp, p.wg_groups2, 1, g.r, g.Cout, 1, g.r, 0, accumulate};
+    WgradReduceArgs r0{part_dUk, dUk, p.wg_groups, T, g.r, g.C, (i64)g.C * T, T, 1, accumulate, nullptr};
+    WgradReduceArgs r1{part_dVp, dVp, p.wg_groups2, 1, g.r, g.Cout, 1, g.r, 0, accumulate, ep.scale}; // dVp = scale (dZ T^T)
     return launch_wgrad_reduce(s, r0, r1);
 }
 
@@ -459,8 +466,8 @@ int pf_lowrank_conv_bwd(const pf_conv_desc *d, const void *X, const void *Uk, co
                         void *workspace, size_t workspace_bytes, void *stream)
 {
     bool fused = false;
-    return pf::conv_bwd_entry_ep(d, X, Uk, Vp, dY, T_saved, W_saved, nullptr, 0, dX, dUk, dVp, accumulate, workspace,
-                                 workspace_bytes, stream, &fused);
+    return pf::conv_bwd_entry_ep(d, X, Uk, Vp, nullptr, dY, T_saved, W_saved, nullptr, 0, dX, dUk, dVp, accumulate,
+                                 workspace, workspace_bytes, stream, &fused);
 }
 
 size_t pf_dense_conv_workspace_bytes(const pf_conv_desc *d)
@@ -508,6 +515,16 @@ int pf_dense_conv_bwd(const pf_conv_desc *d, const void *X, const void *Wd, cons
 
 } // extern "C"
 
+// Does the backward call for this descriptor run on the chain kernels, which fold a batch-norm scale into their
+// weight re-ordering and into the sum of the filter gradients?  (Otherwise the caller scales beforehand.)
+bool pf::conv_bwd_takes_scale(const pf_conv_desc *d, bool want_dX)
+{
+    ConvGeom g;
+    if (check_conv_desc(d, &g) != PF_OK || d->dtype != PF_BF16 || g.N == 0 || !want_dX) return false;
+    const ConvPlan p = plan_conv(g, d->dtype);
+    return p.chain && p.wgrad;
+}
+
 // ------------------------------------------------ entry points with an epilogue
 // (the element-wise part is applied by the caller when *fused stays false)
 int pf::conv_fwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const float *scale,
@@ -544,10 +561,10 @@ int pf::conv_fwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, 
                                     (bf16_t *)T_save, ws, s);
 }
 
-int pf::conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dY,
-                          const void *T_saved, const void *W_saved, const void *dX_add, int x_is_relu, void *dX,
-                          void *dUk, void *dVp, int accumulate, void *workspace, size_t workspace_bytes, void *stream,
-                          bool *fused)
+int pf::conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const float *scale,
+                          const void *dY, const void *T_saved, const void *W_saved, const void *dX_add, int x_is_relu,
+                          void *dX, void *dUk, void *dVp, int accumulate, void *workspace, size_t workspace_bytes,
+                          void *stream, bool *fused)
 {
     ConvGeom g;
     int st = check_conv_desc(d, &g);
@@ -576,7 +593,7 @@ int pf::conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, 
         *fused = true; // the kernel adds the skip gradient and masks as it stores dX
         return conv_bwd_chain(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp, (const bf16_t *)dY,
                               (const bf16_t *)T_saved, p.saved_bytes ? W_saved : nullptr, (bf16_t *)dX, (float *)dUk,
-                              (float *)dVp, accumulate, ws, s, ConvEpilogue{nullptr, nullptr, dX_add, x_is_relu ? X : nullptr, 0});
+                              (float *)dVp, accumulate, ws, s, ConvEpilogue{scale, nullptr, dX_add, x_is_relu ? X : nullptr, 0});
     }
     return conv_bwd_generic<bf16_t>(g, p, (const bf16_t *)X, (const bf16_t *)Uk, (const bf16_t *)Vp,
                                     (const bf16_t *)dY, (const bf16_t *)T_saved, (bf16_t *)dX, (float *)dUk,

@@ -53,6 +53,7 @@ struct PackW1 {
     uint4 *dst;
     int n, RB, T; // n = number of 16-byte fragment slots
     i64 s_rho, s_c, s_tap;
+    const float *cscale; // nullable: W1(rho, c, tap) is multiplied by cscale[c] (rounded to bf16 once more)
 };
 // W2p[ob][s2][lane][e] = W2(o = 32 ob + lane % 32, tap = s2 / (R / 16), rho = 16 (s2 % (R / 16)) + 8 (lane / 32) + e)
 // with W2(o, tap, rho) = src[base + o * s_o + rho * s_rho + tap * s_tap].

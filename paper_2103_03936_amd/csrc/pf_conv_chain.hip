@@ -524,6 +524,10 @@ __device__ __forceinline__ void pack_w1_item(const PackW1 &p, int g)
     uint32_t e[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) e[i] = p.src[rho * p.s_rho + (c0 + i) * p.s_c + tap * p.s_tap];
+    if (p.cscale) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e[i] = float_to_bf16_bits(bf16_bits_to_float((uint16_t)e[i]) * p.cscale[c0 + i]);
+    }
     p.dst[g] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
 }
 
@@ -576,6 +580,7 @@ PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s
     p.s_rho = s_rho;
     p.s_c = s_c;
     p.s_tap = s_tap;
+    p.cscale = nullptr;
     return p;
 }
 

@@ -19,6 +19,7 @@ struct WgradReduceArgs {
     int groups, taps, M, Nc;
     i64 s_m, s_n, s_tap;
     int accumulate;
+    const float *nscale; // nullable: the sum of column n is multiplied by nscale[n] (a fixed batch-norm scale)
 };
 
 // out[c] (+)= sum over tiles of partial[tile][c]; cols a multiple of 32

@@ -447,7 +447,11 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradReduceArgs r0, W
     const i64 t = i / r.Nc;
     const int m = (int)(t % r.M), tap = (int)(t / r.M);
     float *dst = r.out + m * r.s_m + n * r.s_n + tap * r.s_tap;
-    const float v[4] = {s.x, s.y, s.z, s.w};
+    float v[4] = {s.x, s.y, s.z, s.w};
+    if (r.nscale) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] *= r.nscale[n + e];
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) dst[e * r.s_n] = r.accumulate ? (dst[e * r.s_n] + v[e]) : v[e];
 }

@@ -22,8 +22,11 @@ int linear_bwd_entry_ep(const pf_linear_desc *d, const void *X, const void *V, c
 int conv_fwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const float *scale,
                       const float *shift, const void *residual, int act, void *Y, void *T_save, void *W_save,
                       void *workspace, size_t workspace_bytes, void *stream, bool *fused);
-int conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const void *dZ,
-                      const void *T_saved, const void *W_saved, const void *dX_add, int x_is_relu, void *dX, void *dUk,
-                      void *dVp, int accumulate, void *workspace, size_t workspace_bytes, void *stream, bool *fused);
+// scale: honoured only when conv_bwd_takes_scale(d, dX != NULL); otherwise pass NULL and scale beforehand.
+int conv_bwd_entry_ep(const pf_conv_desc *d, const void *X, const void *Uk, const void *Vp, const float *scale,
+                      const void *dZ, const void *T_saved, const void *W_saved, const void *dX_add, int x_is_relu,
+                      void *dX, void *dUk, void *dVp, int accumulate, void *workspace, size_t workspace_bytes,
+                      void *stream, bool *fused);
+bool conv_bwd_takes_scale(const pf_conv_desc *d, bool want_dX);
 
 } // namespace pf

@@ -138,15 +138,33 @@ __global__ __launch_bounds__(256) void dvp_finish_kernel(const float *raw, const
     }
 }
 
-// out[c] (+)= sum over images and pixels of dZ[n][c][p]: one workgroup per channel, fixed summation order
+// out[c] (+)= sum over images and pixels of dZ[n][c][p]: one workgroup per channel, fixed summation order.
+// Planes that are a whole number of 16-byte pieces are read eight (bf16) or four (float) elements at a time.
 template <typename T>
 __global__ __launch_bounds__(256) void channel_sum_kernel(const T *dZ, float *out, int N, int C, int HW, int accumulate)
 {
     const int c = blockIdx.x, tid = threadIdx.x;
+    constexpr int V = 16 / sizeof(T);
     float acc = 0.f;
-    for (i64 i = tid; i < (i64)N * HW; i += 256) {
-        const int n = (int)(i / HW), p = (int)(i - (i64)n * HW);
-        acc += to_float(dZ[((i64)n * C + c) * HW + p]);
+    if (HW % V == 0) {
+        const int pv = HW / V; // pieces per plane
+        for (i64 i = tid; i < (i64)N * pv; i += 256) {
+            const int n = (int)(i / pv), q = (int)(i - (i64)n * pv);
+            const T *src = dZ + ((i64)n * C + c) * HW + (i64)q * V;
+            if (sizeof(T) == 2) {
+                float f[8];
+                load8<T>(src, f);
+                acc += ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+            } else {
+                const float4 v = *(const float4 *)src;
+                acc += (v.x + v.y) + (v.z + v.w);
+            }
+        }
+    } else {
+        for (i64 i = tid; i < (i64)N * HW; i += 256) {
+            const int n = (int)(i / HW), p = (int)(i - (i64)n * HW);
+            acc += to_float(dZ[((i64)n * C + c) * HW + p]);
+        }
     }
     __shared__ float red[256];
     red[tid] = acc;
@@ -265,7 +283,10 @@ int pf_lowrank_conv_bwd_ep(const pf_conv_desc *d, const void *X, const void *Uk,
     void *dVp_used = dVp;
     float *raw = nullptr;
     int st = PF_OK;
-    const bool scaled = scale && Vp && d->Cout > 0 && d->r > 0 && d->N > 0;
+    // the chain kernels fold the scale into their own weight re-ordering and gradient sum; any other path runs on
+    // a scaled copy of the 1x1 filters and finishes dVp afterwards
+    const bool in_kernel = scale && conv_bwd_takes_scale(d, dX != nullptr);
+    const bool scaled = !in_kernel && scale && Vp && d->Cout > 0 && d->r > 0 && d->N > 0;
     if (scaled) {
         // dT = Vp^T (scale dZ) = (scale Vp)^T dZ: the backward kernels run on a scaled copy of the 1x1 filters,
         // and dVp = scale (dZ T^T) is finished from the unscaled sum.
@@ -294,8 +315,8 @@ int pf_lowrank_conv_bwd_ep(const pf_conv_desc *d, const void *X, const void *Uk,
         W_saved = nullptr; // the forward call's re-ordered copy holds the unscaled filters
     }
     bool fused = false;
-    st = conv_bwd_entry_ep(d, X, Uk, Vp_used, dZ, T_saved, W_saved, dX_add, x_is_relu, dX, dUk, dVp_used, accumulate,
-                           workspace, workspace_bytes, stream, &fused);
+    st = conv_bwd_entry_ep(d, X, Uk, Vp_used, in_kernel ? (const float *)scale : nullptr, dZ, T_saved, W_saved, dX_add,
+                           x_is_relu, dX, dUk, dVp_used, accumulate, workspace, workspace_bytes, stream, &fused);
     if (st != PF_OK) return st;
     const i64 Ho = (d->H + 2 * (i64)d->pad - d->k) / d->stride + 1, Wo = (d->W + 2 * (i64)d->pad - d->k) / d->stride + 1;
     if (scaled && dVp) {

@@ -171,6 +171,11 @@ CONFIGS = {
     "transformer_block_qkv_bf16": dict(kind="linear_set", dtype="bf16", M=64 * 128, seed=3, shared=("wq", "wk", "wv"),
                                        layers=dict(wq=(512, 512, 128), wk=(512, 512, 128), wv=(512, 512, 128),
                                                    wo=(512, 512, 128), ffn1=(512, 2048, 128), ffn2=(2048, 512, 128))),
+    # blocks with the layers' epilogues (bias / fixed-statistics batch norm, ReLU, residual) through the *_ep calls:
+    # the feed-forward network of a Transformer layer with its residual connection (Section 2.4), and a ResNet-18
+    # conv4_x basic block (Appendix D)
+    "transformer_ffn_block_bf16": dict(kind="ffn_block", dtype="bf16", M=64 * 128, d=512, dff=2048, r=128, seed=6),
+    "resnet18_basic_block_bf16": dict(kind="basic_block", dtype="bf16", N=128, C=256, H=8, W=8, r=64, k=3, seed=7),
     "resnet50_conv5_bf16": dict(kind="conv_set", dtype="bf16", N=256, H=7, W=7, seed=4, layers=dict(
         conv1=(2048, 512, 128, 1, 0), conv2=(512, 512, 128, 3, 1), conv3=(512, 2048, 128, 1, 0))),
 }
