@@ -7,7 +7,7 @@ constexpr int CH_PIX = 64;           // pixel slots of one image tile
 constexpr int CH_PP = 101;           // padded positions (up to 10 x 10) plus one all-zero row
 constexpr int CH_SUB = 64;           // channels staged per wavefront at a time
 constexpr int CH_XLD = CH_SUB + 8;   // row stride (elements) of the staged input tile: 144 bytes
-constexpr int CH_PLD = CH_PIX + 1;   // row stride (floats) of a partial-sum tile
+constexpr int CH_PLD = 64 + 4;        // stride (floats) between the pixels of a partial-sum tile [pixel][64 rows of rho]
 
 typedef uint4 __attribute__((may_alias)) uint4_alias;
 typedef uint32_t X16a2 __attribute__((ext_vector_type(4), aligned(2))); // 16 bytes at any 2-byte aligned address
@@ -298,14 +298,18 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
     for (int rh = 0; rh < R / 64; ++rh) {
         if (rh > 0) __syncthreads();
-        float *pw = &P[w][(4 * half) * CH_PLD + col];
+        // a lane holds four consecutive rows of rho per accumulator quad: the tile is pixel-major, so they leave
+        // as one 16-byte store (and come back below as 16-byte loads): a quarter of the LDS instructions
+        float *pw = &P[w][col * CH_PLD + 4 * half];
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    pw[(32 * bb + 8 * (v >> 2) + (v & 3)) * CH_PLD + 32 * pb] = acc[2 * rh + bb][pb][v];
+                for (int q = 0; q < 4; ++q)
+                    *(float4 *)&pw[32 * pb * CH_PLD + 32 * bb + 8 * q] =
+                        make_float4(acc[2 * rh + bb][pb][4 * q], acc[2 * rh + bb][pb][4 * q + 1],
+                                    acc[2 * rh + bb][pb][4 * q + 2], acc[2 * rh + bb][pb][4 * q + 3]);
         __syncthreads();
         const int pix = tid & 63;
         const int py = pix / W, px = pix - py * W;
@@ -315,9 +319,14 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             const int r0 = 8 * ((tid >> 6) + 4 * it);
             float f[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int idx = (r0 + e) * CH_PLD + pix;
-                f[e] = (P[0][idx] + P[1][idx]) + (P[2][idx] + P[3][idx]);
+            for (int h4 = 0; h4 < 2; ++h4) {
+                const int idx = pix * CH_PLD + r0 + 4 * h4;
+                const float4 p0 = *(const float4 *)&P[0][idx], p1 = *(const float4 *)&P[1][idx];
+                const float4 p2 = *(const float4 *)&P[2][idx], p3 = *(const float4 *)&P[3][idx];
+                f[4 * h4 + 0] = (p0.x + p1.x) + (p2.x + p3.x);
+                f[4 * h4 + 1] = (p0.y + p1.y) + (p2.y + p3.y);
+                f[4 * h4 + 2] = (p0.z + p1.z) + (p2.z + p3.z);
+                f[4 * h4 + 3] = (p0.w + p1.w) + (p2.w + p3.w);
             }
             if (pix < HW) {
                 const uint4 pk = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
