@@ -246,6 +246,11 @@ class LinearWorkload:
             add("linear_dX=dT*Vt", 2.0 * M * r * i, s * (i * r + M * i) + 4 * M * r)
             add("linear_dU=dYt*T", 2.0 * M * r * o, s * (M * o + M * r) + 4 * o * r)
             add("linear_dV=Xt*dT", 2.0 * M * r * i, s * M * i + 4 * (M * r + i * r))
+            # fp32 with few rows: slices of the rank-r intermediate, then every product that reads their sum
+            add("linear_T_slices", 2.0 * M * r * i, s * (M * i + i * r + M * r))
+            add("linear_Y=T*Ut+b", 2.0 * M * r * o, s * (M * r + o * r + M * o + M * r))
+            add("linear_dT_slices", 2.0 * M * r * o, s * (M * o + o * r + M * r))
+            add("linear_dX,dU,dV,db", 2.0 * M * r * (2 * i + o), s * (2 * M * r + i * r + M * i + M * o + M * i) + 4 * r * (i + o))
             # fused path
             add("linear_fwd_fused", 2.0 * M * r * (i + o), s * (M * i + M * o + M * r + r * (i + o)))
             add("linear_bwd_data_fused", 2.0 * M * r * (i + o), s * (M * o + M * i + M * r + r * (i + o)))

@@ -4,6 +4,7 @@
 #include "pf_conv_chain.h"
 #include "pf_linear_chain.h"
 #include "pf_skinny.h"
+#include "pf_linear_small.h"
 #include "pf_conv_wgrad.h"
 #include <mutex>
 #include "pf_gemm.h"
@@ -132,6 +133,8 @@ struct LinearPlan {
     int wg_cols;           // columns per workgroup of that kernel
     bool skinny;           // fp32 with at most 128 rows: the weight-streaming kernels of the LSTM cell
     size_t n_part_sk;      // their slice sums, floats
+    bool small;            // fp32 with at most 128 rows and dimensions in whole tiles: two launches per direction
+    size_t n_small;        // slices of the rank-r intermediate(s) between them, floats
 };
 
 static LinearPlan plan_linear(const pf_linear_desc *d)
@@ -164,6 +167,13 @@ static LinearPlan plan_linear(const pf_linear_desc *d)
         const size_t bwd = 2 * align_up(p.n_T * sizeof(float)) + align_up(p.n_part_sk * sizeof(float));
         if (fwd > p.fwd_bytes) p.fwd_bytes = fwd;
         if (bwd > p.bwd_bytes) p.bwd_bytes = bwd;
+    }
+    p.small = d->dtype == PF_F32 && linear_small_supported(d->M, d->in, d->out, d->r);
+    p.n_small = p.small ? (size_t)(8 * d->M * d->r) : 0; // at most eight slices per intermediate
+    if (p.small) {
+        const size_t one = align_up(p.n_small * sizeof(float));
+        if (one > p.fwd_bytes) p.fwd_bytes = one;
+        if (2 * one > p.bwd_bytes) p.bwd_bytes = 2 * one;
     }
     p.chain2 = p.fused && linear_chain2_supported(d->in, d->out, d->r);
     p.n_colsum = p.chain2 ? (size_t)(2 * ((d->M + LC_ROWS - 1) / LC_ROWS)) * d->out : 0;
@@ -364,6 +374,49 @@ static int linear_bwd_fused(const pf_linear_desc *d, const LinearPlan &p, const 
     }
     if (st != PF_OK) return st;
     return linear_wgrads_fused(d, p, X, dY, T_saved ? T_saved : T16, dT16, dU, dV, dbias, colsum, accumulate, part, s);
+}
+
+// --------------------------------------- fp32, few rows, dimensions in whole tiles
+// Two launches per direction: the slices of the rank-r intermediate, then every product that reads their sum.
+static int linear_fwd_small(const pf_linear_desc *d, const LinearPlan &p, const float *X, const float *V, const float *U,
+                            const float *bias, float *Y, float *T_save, Workspace &ws, hipStream_t s)
+{
+    const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    float *P = ws.take<float>(p.n_small);
+    const int S = linear_small_slices(in);
+    int st = launch_ls_slices(s, "linear_T_slices", LsSliceArgs{X, V, P, in, r, M, in, r, S});
+    if (st != PF_OK) return st;
+    LsTileArgs ta = {};
+    ls_add(ta, ls_operand(P, r, LS_MK, S, (i64)M * r), ls_operand(U, r, LS_MK), M, out, r, Y, out,
+           d->has_bias ? bias : nullptr, 0, T_save);
+    return launch_ls_tiles(s, "linear_Y=T*Ut+b", ta);
+}
+
+static int linear_bwd_small(const pf_linear_desc *d, const LinearPlan &p, const float *X, const float *V, const float *U,
+                            const float *dY, const float *T_saved, float *dX, float *dU, float *dV, float *dbias,
+                            int accumulate, Workspace &ws, hipStream_t s)
+{
+    const int M = (int)d->M, in = (int)d->in, out = (int)d->out, r = (int)d->r;
+    float *PdT = ws.take<float>(p.n_small), *PT = ws.take<float>(p.n_small);
+    const int SdT = linear_small_slices(out), ST = linear_small_slices(in);
+    const bool recompute = dU && !T_saved;
+    // dT = dY U in slices and, when T was not kept, T = X V again, in one launch
+    int st = launch_ls_slices(s, "linear_dT_slices", LsSliceArgs{dY, U, PdT, out, r, M, out, r, SdT},
+                              recompute ? LsSliceArgs{X, V, PT, in, r, M, in, r, ST} : LsSliceArgs{});
+    if (st != PF_OK) return st;
+    const LsOperand dT_rows = ls_operand(PdT, r, LS_MK, SdT, (i64)M * r); // (row, rank index)
+    const LsOperand dT_cols = ls_operand(PdT, r, LS_KM, SdT, (i64)M * r); // (rank index, row): contraction over rows
+    const bool want_db = d->has_bias && dbias;
+    LsTileArgs ta = {};
+    if (dX) ls_add(ta, dT_rows, ls_operand(V, r, LS_MK), M, in, r, dX, in, nullptr, 0);
+    if (dU)
+        ls_add(ta, ls_operand(dY, out, LS_KM), recompute ? ls_operand(PT, r, LS_KM, ST, (i64)M * r) : ls_operand(T_saved, r, LS_KM),
+               out, r, M, dU, r, nullptr, accumulate, nullptr, want_db ? dbias : nullptr);
+    else if (want_db) // only the bias gradient of this product is wanted: the column sums of its left operand
+        ls_add(ta, ls_operand(dY, out, LS_KM), ls_operand(dY, out, LS_KM), out, 32, M, nullptr, 0, nullptr, accumulate, nullptr,
+               dbias);
+    if (dV) ls_add(ta, ls_operand(X, in, LS_KM), dT_cols, in, r, M, dV, r, nullptr, accumulate);
+    return launch_ls_tiles(s, "linear_dX,dU,dV,db", ta);
 }
 
 // ------------------------------------------------------------- fp32, few rows
@@ -592,6 +645,9 @@ int pf::linear_fwd_entry(const pf_linear_desc *d, const void *X, const void *V, 
     if (d->M == 0) return PF_OK;
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32 && plan_linear(d).small)
+        return linear_fwd_small(d, plan_linear(d), (const float *)X, (const float *)V, (const float *)U,
+                                (const float *)bias, (float *)Y, (float *)T_save, ws, s);
     if (d->dtype == PF_F32 && plan_linear(d).skinny)
         return linear_fwd_skinny(d, plan_linear(d), (const float *)X, (const float *)V, (const float *)U,
                                  (const float *)bias, (float *)Y, (float *)T_save, ws, s);
@@ -619,6 +675,10 @@ int pf::linear_bwd_entry(const pf_linear_desc *d, const void *X, const void *V, 
     if (pf::any_misaligned({workspace}, 256)) return PF_ERR_UNSUPPORTED; // NULL passes: the size check has caught it
     Workspace ws(workspace, workspace_bytes);
     hipStream_t s = (hipStream_t)stream;
+    if (d->dtype == PF_F32 && plan_linear(d).small)
+        return linear_bwd_small(d, plan_linear(d), (const float *)X, (const float *)V, (const float *)U,
+                                (const float *)dY, (const float *)T_saved, (float *)dX, (float *)dU, (float *)dV,
+                                (float *)dbias, accumulate, ws, s);
     if (d->dtype == PF_F32 && plan_linear(d).skinny)
         return linear_bwd_skinny(d, plan_linear(d), (const float *)X, (const float *)V, (const float *)U,
                                  (const float *)dY, (const float *)T_saved, (float *)dX, (float *)dU, (float *)dV,
