@@ -31,9 +31,15 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v)
 // row-major too (T[rows][R], Y[rows][C2]), a bias may be added, and both stages are 1x1.
 // EP: the epilogue members of the arguments are honoured (a separate instantiation, so that the plain layer does
 // not carry their registers).
-template <int KS1, int KS2, int R, int HC, int WC, bool CL = false, bool EP = false>
+// SPLIT: workgroups per image (1 or 2).  With 2 (a batch that leaves half the chip empty) both run the whole first
+// stage and each takes half of the second stage's output blocks, one block per wavefront step instead of a pair:
+// half the second-stage weights per workgroup, which is what bounds a 3x3 second stage.
+template <int KS1, int KS2, int R, int HC, int WC, bool CL = false, bool EP = false, int SPLIT = 1>
 __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 {
+    constexpr int NB2 = SPLIT == 2 ? 1 : 2;    // output blocks (32 channels) a wavefront works on at a time
+    constexpr int NVW = 4 * SPLIT;             // wavefronts that share an image's second stage
+    static_assert(SPLIT == 1 || (!CL && !EP), "the split kernel is built for the plain image mode");
     constexpr int RB = R / 32, R16 = R / 16, T1 = KS1 * KS1, T2 = KS2 * KS2;
     constexpr int TLD = R + 8; // row stride (elements) of the intermediate tile
     constexpr int S2 = T2 * R16;
@@ -268,7 +274,8 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     // stage-2 weight fragments, one tap (R16 k-steps, two 32-channel output blocks) per group;
     // the first group is requested now so that it arrives during the partial-sum exchange
     const int nb2 = C2 / 32;
-    const int npair = (nb2 / 2 + 3 - w) / 4; // output-block pairs of this wavefront: 2 w, 2 w + 8, ...
+    const int vw = SPLIT == 2 ? w + 4 * (int)blockIdx.y : w; // this wavefront among those of the image
+    const int npair = (nb2 / NB2 + NVW - 1 - vw) / NVW; // output-block pairs (blocks) of this wavefront: NB2 vw, NB2 (vw + NVW), ...
     const int ngroups2 = npair * T2;
     const int rot2 = (int)((n >> 3) % T2);
     auto tap_of = [&](int q) __attribute__((always_inline)) { // taps of a pair are visited in a rotated order
@@ -281,15 +288,15 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const i64 w2bb = w2nat ? 4 * R : (i64)S2 * 64, w2k = w2nat ? 2 : 64; // strides in 16-byte units
     auto w2src = [&](int q) __attribute__((always_inline)) {
         const int qq = q < ngroups2 ? q : ngroups2 - 1;
-        const int ob = 2 * w + 8 * (qq / T2), tap = tap_of(qq);
+        const int ob = NB2 * (vw + NVW * (qq / T2)), tap = tap_of(qq);
         if (w2nat) return (const uint4 *)(a.W2nat + ((i64)(32 * ob + col) * R + 8 * half));
         return a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
     };
-    uint4 bwA[2][R16], bwB[2][R16];
+    uint4 bwA[NB2][R16], bwB[NB2][R16];
     if (ngroups2 > 0) {
         const uint4 *src = w2src(0);
 #pragma unroll
-        for (int bb = 0; bb < 2; ++bb)
+        for (int bb = 0; bb < NB2; ++bb)
 #pragma unroll
             for (int k = 0; k < R16; ++k) bwA[bb][k] = src[bb * w2bb + k * w2k];
     }
@@ -335,7 +342,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                 if (a.mid_save && CL) {
                     const i64 row = (i64)n * CH_PIX + pix;
                     if (row < a.rows) *(uint4 *)(a.mid_save + row * R + 64 * rh + r0) = pk;
-                } else if (a.mid_save) {
+                } else if (a.mid_save && (SPLIT == 1 || blockIdx.y == 0)) {
                     // The copy kept for the backward pass is [R][HW]: these 8 rows of it are HW 16-byte pieces in a
                     // row.  They are put together in this wavefront's idle input tile and leave below as aligned
                     // 16-byte stores (2-byte stores from here cost the memory pipeline sixteen times as many
@@ -349,7 +356,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         }
     }
     __syncthreads();
-    if (a.mid_save && !CL) { // rows 64 rh + 8 (w + 4 it) .. + 7 of the intermediate, from this wavefront's tile
+    if (a.mid_save && !CL && (SPLIT == 1 || blockIdx.y == 0)) { // rows 64 rh + 8 (w + 4 it) .. + 7 of the intermediate, from this wavefront's tile
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int ck = 0; ck < R / 32; ++ck) { // chunk ck = 2 rh + it
@@ -360,9 +367,9 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     }
 
     // ------------------------------- stage 2 -------------------------------
-    f32x16_t acc2[2][2];
+    f32x16_t acc2[NB2][2];
 #pragma unroll
-    for (int bb = 0; bb < 2; ++bb)
+    for (int bb = 0; bb < NB2; ++bb)
 #pragma unroll
         for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
@@ -373,13 +380,13 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     constexpr int NOV = CH_PIX * CH_PIX / 8 / 64;
     uint4 epa[NOV], epm[NOV];
     const bool ep_any = EP && !CL && (a.ep_add || a.ep_mask || a.ep_relu);
-    auto run_group2 = [&](const uint4(&cur)[2][R16], uint4(&nxt)[2][R16], int q) __attribute__((always_inline)) {
+    auto run_group2 = [&](const uint4(&cur)[NB2][R16], uint4(&nxt)[NB2][R16], int q) __attribute__((always_inline)) {
         const int tap = tap_of(q);
         if (EP && !CL && q % T2 == 0 && (a.ep_add || a.ep_mask)) {
-            const i64 blk = ((i64)n * C2 + 32 * (2 * w + 8 * (q / T2))) * HW;
+            const i64 blk = ((i64)n * C2 + 32 * NB2 * (vw + NVW * (q / T2))) * HW;
 #pragma unroll
             for (int i = 0; i < NOV; ++i) {
-                const int vi = min(lane + 64 * i, 64 * HW / 8 - 1);
+                const int vi = min(lane + 64 * i, 32 * NB2 * HW / 8 - 1);
                 if (a.ep_add) epa[i] = ((const uint4 *)(a.ep_add + blk))[vi];
                 if (a.ep_mask) epm[i] = ((const uint4 *)(a.ep_mask + blk))[vi];
             }
@@ -392,15 +399,16 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
         for (int k = 0; k < R16; ++k) {
 #pragma unroll
-            for (int bb = 0; bb < 2; ++bb) nxt[bb][k] = src[bb * w2bb + k * w2k];
+            for (int bb = 0; bb < NB2; ++bb) nxt[bb][k] = src[bb * w2bb + k * w2k];
             if (k + 1 < R16) {
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb) bn[pb] = lds_read16(&Ts[base2[pb] + (valid[pb] ? toff : 0) + 16 * (k + 1)]);
             }
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb) {
-                acc2[0][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[0][k]), as_bf16x8(bc[pb]), acc2[0][pb], 0, 0, 0);
-                acc2[1][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[1][k]), as_bf16x8(bc[pb]), acc2[1][pb], 0, 0, 0);
+#pragma unroll
+                for (int bb = 0; bb < NB2; ++bb)
+                    acc2[bb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cur[bb][k]), as_bf16x8(bc[pb]), acc2[bb][pb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -410,7 +418,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             // The 64 output channels x HW pixels of the pair are one contiguous block of `out`.  Round to
             // bf16 into this wavefront's (now idle) input tile laid out exactly like that block, then
             // copy it out with 16-byte stores.
-            const int ob = 2 * w + 8 * (q / T2);
+            const int ob = NB2 * (vw + NVW * (q / T2));
             if (CL) {
                 // Row-major output: a lane holds 4 consecutive output channels of one row per accumulator
                 // quad.  Stage the 64 rows x 64 channels of the pair in the idle input tile ([row][channel],
@@ -453,7 +461,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             uint16_t *ys = xs + (4 * half) * HW + col;
             if (EP && (a.ep_scale || a.ep_shift)) { // per output channel, in float, before the one rounding to bf16
 #pragma unroll
-                for (int bb = 0; bb < 2; ++bb)
+                for (int bb = 0; bb < NB2; ++bb)
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {
                         const int ch = 32 * ob + 32 * bb + 8 * qd + 4 * half; // four consecutive channels
@@ -469,7 +477,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                     }
             }
 #pragma unroll
-            for (int bb = 0; bb < 2; ++bb)
+            for (int bb = 0; bb < NB2; ++bb)
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb) {
                     if (32 * pb + col < HW) {
@@ -484,7 +492,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                     for (int v = 0; v < 16; ++v) acc2[bb][pb][v] = 0.f;
                 }
             uint4 *dst = (uint4 *)(a.out + ((i64)n * C2 + 32 * ob) * HW);
-            const int nv = 64 * HW / 8;
+            const int nv = 32 * NB2 * HW / 8;
 #pragma unroll
             for (int i = 0; i < CH_PIX * CH_PIX / 8 / 64; ++i) {
                 const int vi = lane + 64 * i;
@@ -644,6 +652,18 @@ int launch_conv_chain(hipStream_t s, const char *name, const ChainArgs &a, int N
     const dim3 grid(N), block(256);
     const int hw = (a.H == 8 && a.W == 8) ? 8 : (a.H == 7 && a.W == 7) ? 7 : 0;
     const bool ep = a.ep_scale || a.ep_shift || a.ep_add || a.ep_mask || a.ep_relu;
+    // a batch that fills at most half the chip: two workgroups per image where the second stage is the long one
+    if (!ep && k1 == 1 && k2 == 3 && hw == 8 && 2 * N <= 256 && a.C2 % 64 == 0) {
+        const dim3 grid2(N, 2);
+        if (R == 64) {
+            PF_LAUNCH(st, name, (conv_chain_kernel<1, 3, 64, 8, 8, false, false, 2>), grid2, block, s, a);
+            return st;
+        }
+        if (R == 128) {
+            PF_LAUNCH(st, name, (conv_chain_kernel<1, 3, 128, 8, 8, false, false, 2>), grid2, block, s, a);
+            return st;
+        }
+    }
 #define PF_CHAIN_CASE(K1, K2, RR)                                                                    \
     if (k1 == K1 && k2 == K2 && R == RR) {                                                           \
         if (hw == 8 && ep) {                                                                         \
