@@ -278,6 +278,13 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const int npair = (nb2 / NB2 + NVW - 1 - vw) / NVW; // output-block pairs (blocks) of this wavefront: NB2 vw, NB2 (vw + NVW), ...
     const int ngroups2 = npair * T2;
     const int rot2 = (int)((n >> 3) % T2);
+    // ... and the workgroups that share an L2 start at different pairs, so that they do not all ask it for the same
+    // lines of the second-stage weights at the same time
+    const int rotp = npair > 0 ? (int)((n >> 3) % npair) : 0;
+    auto pair_of = [&](int q) __attribute__((always_inline)) { // which of this wavefront's pairs group q works on
+        const int j = q / T2 + rotp;
+        return j >= npair ? j - npair : j;
+    };
     auto tap_of = [&](int q) __attribute__((always_inline)) { // taps of a pair are visited in a rotated order
         const int t = q % T2 + rot2;
         return t >= T2 ? t - T2 : t;
@@ -288,7 +295,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     const i64 w2bb = w2nat ? 4 * R : (i64)S2 * 64, w2k = w2nat ? 2 : 64; // strides in 16-byte units
     auto w2src = [&](int q) __attribute__((always_inline)) {
         const int qq = q < ngroups2 ? q : ngroups2 - 1;
-        const int ob = NB2 * (vw + NVW * (qq / T2)), tap = tap_of(qq);
+        const int ob = NB2 * (vw + NVW * pair_of(qq)), tap = tap_of(qq);
         if (w2nat) return (const uint4 *)(a.W2nat + ((i64)(32 * ob + col) * R + 8 * half));
         return a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
     };
@@ -383,7 +390,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     auto run_group2 = [&](const uint4(&cur)[NB2][R16], uint4(&nxt)[NB2][R16], int q) __attribute__((always_inline)) {
         const int tap = tap_of(q);
         if (EP && !CL && q % T2 == 0 && (a.ep_add || a.ep_mask)) {
-            const i64 blk = ((i64)n * C2 + 32 * NB2 * (vw + NVW * (q / T2))) * HW;
+            const i64 blk = ((i64)n * C2 + 32 * NB2 * (vw + NVW * pair_of(q))) * HW;
 #pragma unroll
             for (int i = 0; i < NOV; ++i) {
                 const int vi = min(lane + 64 * i, 32 * NB2 * HW / 8 - 1);
@@ -418,7 +425,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             // The 64 output channels x HW pixels of the pair are one contiguous block of `out`.  Round to
             // bf16 into this wavefront's (now idle) input tile laid out exactly like that block, then
             // copy it out with 16-byte stores.
-            const int ob = NB2 * (vw + NVW * (q / T2));
+            const int ob = NB2 * (vw + NVW * pair_of(q));
             if (CL) {
                 // Row-major output: a lane holds 4 consecutive output channels of one row per accumulator
                 // quad.  Stage the 64 rows x 64 channels of the pair in the idle input tile ([row][channel],
