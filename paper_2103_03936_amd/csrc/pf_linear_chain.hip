@@ -12,6 +12,8 @@
 //            per-wavefront LDS patch and leaves as 16-byte stores.
 #include "pf_linear_chain.h"
 
+#include <type_traits>
+
 namespace pf {
 
 // native vectors (plain SSA values for the compiler, unlike the uint4 struct)
@@ -54,9 +56,9 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
     struct VR { // a chunk of W1 in flight
         u32x4_t r[8];
     };
-    struct UR { // W2 fragments of a pair of output blocks, and their bias values
-        u32x2_t b[2][4];
+    struct UR { // W2 fragments of a pair of output blocks, and the bias of this lane's row of each block
         u32x4_t r[2][8];
+        uint32_t b[2];
     };
 
     // ---- copy roles: thread -> (row or k, 16-byte column) of a chunk
@@ -105,15 +107,22 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
         c = min(c, nch - 1) + rot1;
         return c >= nch ? c - nch : c;
     };
+    // (one 16-byte piece at a time, so that the requests can be dealt out between the MFMAs: the memory pipeline
+    // takes one such instruction per 16 to 20 cycles from the whole workgroup, and a wavefront that issues a burst
+    // of them stands still until the last one has been accepted)
+    auto load_x1 = [&](XR &x, int c, int i) __attribute__((always_inline)) {
+        x.r[i] = *(const uint4_alias *)(xsrc[i] + chunk_of(c) * LC_KC);
+    };
+    auto load_v1 = [&](VR &v, int c, int i) __attribute__((always_inline)) {
+        v.r[i] = *(const uint4_alias *)(vsrc + ((i64)chunk_of(c) * LC_KC + 16 * i) * LC_R);
+    };
     auto load_x = [&](XR &x, int c) __attribute__((always_inline)) {
-        c = chunk_of(c);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) x.r[i] = *(const uint4_alias *)(xsrc[i] + c * LC_KC);
+        for (int i = 0; i < 2; ++i) load_x1(x, c, i);
     };
     auto load_v = [&](VR &v, int c) __attribute__((always_inline)) {
-        c = chunk_of(c);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v.r[i] = *(const uint4_alias *)(vsrc + ((i64)c * LC_KC + 16 * i) * LC_R);
+        for (int i = 0; i < 8; ++i) load_v1(v, c, i);
     };
 
     // ---- stage 2 operands: W2 fragments of a pair of output blocks, straight from global memory
@@ -123,25 +132,26 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
         g = min(g, obw / 2 - 1) + rot2;
         return g >= obw / 2 ? g - obw / 2 : g;
     };
+    // W2 rows as they lie in memory: 16 lanes fetch one 256-byte row, an instruction four rows (a lane per
+    // row, which is what the MFMA wants, would touch 64 cache lines per instruction instead of 8)
+    auto load_u1 = [&](UR &u, int g, int bi, int j) __attribute__((always_inline)) {
+        const uint16_t *p = a.W2 + (i64)(32 * (w * obw + 2 * pair_of(g) + bi) + (lane >> 4)) * LC_R + 8 * (lane & 15);
+        u.r[bi][j] = *(const uint4_alias *)(p + (i64)4 * j * LC_R);
+    };
+    // The bias enters as one more k-step of the second product, [T 1] [W2 b]^T: the lane that holds row o of a block
+    // (in the lower half of the wavefront: k = 0..7) carries b[o] at k = 0.  Two small requests per pair instead of
+    // vector arithmetic on every output.  (No bias: any readable address; the value is masked to zero.)
+    auto load_ub = [&](UR &u, int g, int bi) __attribute__((always_inline)) {
+        const uint16_t *p = a.bias ? a.bias + 32 * (w * obw + 2 * pair_of(g) + bi) + col : a.W2;
+        const uint32_t v = *p;
+        u.b[bi] = (a.bias && half == 0) ? v : 0u;
+    };
     auto load_u = [&](UR &u, int g) __attribute__((always_inline)) {
-        g = pair_of(g);
-        // bias first: it is needed first, and loads return in order (no bias: any 8 readable bytes, masked below)
-        const uint16_t *bsrc = a.bias ? a.bias + 32 * (w * obw + 2 * g) + 4 * half : a.W2;
-        const unsigned bmask = a.bias ? 0xffffffffu : 0u;
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const u32x2_t t = *(const uint2_alias *)(a.bias ? bsrc + 32 * bi + 8 * q : bsrc);
-                u.b[bi][q] = u32x2_t{t.x & bmask, t.y & bmask};
-            }
-        // W2 rows as they lie in memory: 16 lanes fetch one 256-byte row, an instruction four rows (a lane per
-        // row, which is what the MFMA wants, would touch 64 cache lines per instruction instead of 8)
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi) {
-            const uint16_t *p = a.W2 + (i64)(32 * (w * obw + 2 * g + bi) + (lane >> 4)) * LC_R + 8 * (lane & 15);
+            load_ub(u, g, bi);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) u.r[bi][j] = *(const uint4_alias *)(p + (i64)4 * j * LC_R);
+            for (int j = 0; j < 8; ++j) load_u1(u, g, bi, j);
         }
     };
 
@@ -159,59 +169,114 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
 
-    auto step = [&](XR &xr, VR &vr, int c, int buf, auto extra) __attribute__((always_inline)) {
+    auto write_x = [&](const XR &xr, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) *(uint4_alias *)&Xs[buf][(cr + 16 * i) * LC_XP + 8 * co] = xr.r[i];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(uint4_alias *)&Vs[buf][(cr + 16 * i) * LC_VP + 8 * co] = vr.r[i];
-        extra(0);
-        load_x(xr, c + 4);
-        load_v(vr, c + 2);
-        extra(1);
-        __syncthreads(); // one barrier per chunk: the buffer rewritten next was last read two chunks ago
-        if (c >= nch) return; // uniform; past the end only the copies above ran
+    };
+    auto write_v = [&](const VR &vr, int buf, int i) __attribute__((always_inline)) {
+        *(uint4_alias *)&Vs[buf][(cr + 16 * i) * LC_VP + 8 * co] = vr.r[i];
+    };
+    // Chunk c (already in buffer c & 1) is multiplied while chunk c + 1, which has arrived in the registers xn / vn,
+    // is written to the other buffer, one piece per k-step between the MFMAs, and each register is refilled as soon
+    // as it has been written (chunks c + 5 / c + 3); the fragments of a k-step are read one k-step ahead.  One
+    // barrier closes the chunk: after it the written buffer is complete and the buffer just read may be rewritten.
+    // `refill`: whether chunks c + 3 (W1) and c + 5 (rows) are to be requested (std::true_type / std::false_type)
+    auto step = [&](XR &xn, VR &vn, int c, auto refill, auto extra) __attribute__((always_inline)) {
+        if (c >= nch) return; // uniform
+        const int buf = c & 1;
         if (a.colsum) { // column sums of the valid rows of this chunk (bias gradient): 16 rows per thread
             const i64 left = a.rows - row0;
             const int nr = left < LC_ROWS ? (int)left : LC_ROWS;
             const int cc = tid & (LC_KC - 1), hr = tid >> 7;
+            uint16_t e[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) e[r] = Xs[buf][(16 * hr + r) * LC_XP + cc];
             float s = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float v = bf16_bits_to_float(Xs[buf][(16 * hr + r) * LC_XP + cc]);
-                s += 16 * hr + r < nr ? v : 0.f;
-            }
+            for (int r = 0; r < 16; ++r) s += 16 * hr + r < nr ? bf16_bits_to_float(e[r]) : 0.f;
             a.colsum[((i64)2 * blockIdx.x + hr) * C1 + chunk_of(c) * LC_KC + cc] = s;
         }
+        auto body = [&](auto more) __attribute__((always_inline)) {
+            u32x4_t xf[2];
+            bf16x8_t vf[2];
+            xf[0] = *(const uint4_alias *)&Xs[buf][col * LC_XP + 8 * half];
+            vf[0] = lds_frag_tr(&Vs[buf][0], LC_VP, 0, 32 * w, lane);
 #pragma unroll
-        for (int ks = 0; ks < LC_KC / 16; ++ks) {
-            const bf16x8_t xf = lc_as_bf16x8(*(const uint4_alias *)&Xs[buf][col * LC_XP + 16 * ks + 8 * half]);
-            const bf16x8_t vf = lds_frag_tr(&Vs[buf][0], LC_VP, 16 * ks, 32 * w, lane);
-            if (ks & 1)
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, xf, acc1, 0, 0, 0);
-            else
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, xf, acc0, 0, 0, 0);
-        }
+            for (int ks = 0; ks < LC_KC / 16; ++ks) {
+                if (ks + 1 < LC_KC / 16) {
+                    xf[(ks + 1) & 1] = *(const uint4_alias *)&Xs[buf][col * LC_XP + 16 * (ks + 1) + 8 * half];
+                    vf[(ks + 1) & 1] = lds_frag_tr(&Vs[buf][0], LC_VP, 16 * (ks + 1), 32 * w, lane);
+                }
+                if (decltype(more)::value) {
+                    if (ks == 0) write_x(xn, buf ^ 1);
+                    write_v(vn, buf ^ 1, ks);
+                }
+                if (decltype(refill)::value) {
+                    if (ks == 1 || ks == 2) load_x1(xn, c + 5, ks - 1);
+                    load_v1(vn, c + 3, ks);
+                }
+                extra(ks);
+                if (ks & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1], lc_as_bf16x8(xf[ks & 1]), acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks & 1], lc_as_bf16x8(xf[ks & 1]), acc0, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (c + 1 < nch) // uniform
+            body(std::true_type{});
+        else
+            body(std::false_type{});
+        __syncthreads();
     };
     auto none = [](int) __attribute__((always_inline)) {};
-    // first round: the remaining start-up requests are slipped in (stage-2 operands last: they are needed last)
-    step(x0, v0, 0, 0, [&](int when) __attribute__((always_inline)) {
-        if (when == 0) {
-            load_x(x2, 2);
-            load_x(x3, 3);
-        } else {
-            load_u(ur[0], 0);
+    auto want_u0 = [&](int ks) __attribute__((always_inline)) { // the stage-2 operands of the first pair ...
+        if (ks < 2) load_ub(ur[0], 0, ks);
+        load_u1(ur[0], 0, 0, ks);
+        load_u1(ur[0], 0, 1, ks);
+    };
+    auto want_u1 = [&](int ks) __attribute__((always_inline)) { // ... and of the second
+        if (NP != 1) {
+            if (ks < 2) load_ub(ur[1], 1, ks);
+            load_u1(ur[1], 1, 0, ks);
+            load_u1(ur[1], 1, 1, ks);
         }
-    });
-    step(x1, v1, 1, 1, [&](int when) __attribute__((always_inline)) {
-        if (when == 1 && NP != 1) load_u(ur[1], 1);
-    });
-    step(x2, v0, 2, 0, none);
-    step(x3, v1, 3, 1, none);
-    for (int c = 4; c < nch; c += 4) {
-        step(x0, v0, c, 0, none);
-        step(x1, v1, c + 1, 1, none);
-        step(x2, v0, c + 2, 0, none);
-        step(x3, v1, c + 3, 1, none);
+    };
+    const std::true_type yes;
+    const std::false_type no;
+    // chunk 0 goes to LDS by itself
+    write_x(x0, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) write_v(v0, 0, i);
+    if (!MULTI && nch == 4) {
+        // The common short contraction (512), spelled out: every chunk is requested exactly once, and the stage-2
+        // operands follow in the last two chunks, when nothing else is left to ask for.
+        load_x(x2, 2);
+        load_x(x3, 3);
+        load_v(v0, 2);
+        __syncthreads();
+        step(x1, v1, 0, no, [&](int ks) __attribute__((always_inline)) { load_v1(v1, 3, ks); });
+        step(x2, v0, 1, no, none);
+        step(x3, v1, 2, no, want_u0);
+        step(x0, v0, 3, no, want_u1);
+    } else {
+        // Any length: requests are unconditional (a chunk past the end repeats the last one, and what it brings is
+        // never multiplied), the stage-2 operands are asked for early.
+        load_x(x2, 2);
+        load_x(x3, 3);
+        load_x(x0, 4);
+        load_v(v0, 2);
+        __syncthreads();
+        step(x1, v1, 0, yes, want_u0);
+        step(x2, v0, 1, yes, want_u1);
+        step(x3, v1, 2, yes, none);
+        step(x0, v0, 3, yes, none);
+        for (int c = 4; c < nch; c += 4) {
+            step(x1, v1, c, yes, none);
+            step(x2, v0, c + 1, yes, none);
+            step(x3, v1, c + 2, yes, none);
+            step(x0, v0, c + 3, yes, none);
+        }
     }
 
     // ---- intermediate -> LDS (bf16, row-major): lane holds row `col`, rho = 32 w + 8 q + 4 half + 0..3
@@ -238,65 +303,63 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
     // ---- stage 2: pairs of output blocks
     uint16_t *Us = &Vs[0][0] + w * (64 * LC_TP); // 64 rows of W2 per wavefront
     static_assert(4 * 64 * LC_TP <= 2 * LC_KC * LC_VP, "the W2 patches must fit in the W1 buffers");
-    auto pair = [&](const UR &u, int g) __attribute__((always_inline)) {
-        if (2 * g >= obw) return;
-        const int ob0 = w * obw + 2 * pair_of(g);
-        // epilogue operands of this patch, requested before the products so that they have arrived at the store
-        u32x4_t ea[4], em[4];
+    // rows of W2 -> MFMA fragments through this wavefront's patch of LDS (the W1 buffers are free by now): rows
+    // 0..31 of the patch hold the first block of a pair, rows 32..63 the second.  While one half is multiplied the
+    // other half is rewritten with the block that comes next (a wavefront's LDS accesses are performed in the order
+    // it issues them, and the patch is its own: no barrier).
+    auto write_u = [&](const UR &u, int bi, int j) __attribute__((always_inline)) {
+        *(uint4_alias *)&Us[(32 * bi + 4 * j + (lane >> 4)) * LC_TP + 8 * (lane & 15)] = u.r[bi][j];
+    };
+    const u32x4_t one_k0 = {half == 0 ? 0x3f80u : 0u, 0u, 0u, 0u}; // the row [1 0 0 ...] that multiplies the bias
+    auto mma_block = [&](const UR &u, int bi, f32x16_t &y, auto during) __attribute__((always_inline)) {
+        u32x4_t uf[2];
+        uf[0] = *(const uint4_alias *)&Us[(32 * bi + col) * LC_TP + 8 * half];
+        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lc_as_bf16x8(u32x4_t{u.b[bi], 0u, 0u, 0u}), lc_as_bf16x8(one_k0), y, 0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            if (ks + 1 < 8) uf[(ks + 1) & 1] = *(const uint4_alias *)&Us[(32 * bi + col) * LC_TP + 16 * (ks + 1) + 8 * half];
+            during(ks);
+            y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lc_as_bf16x8(uf[ks & 1]), tf[ks], y, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // The finished sums of a pair do not leave at once: they are kept (yp) and turned into bf16, row-major through a
+    // per-wavefront LDS patch, and stored, piece by piece between the MFMAs of the pair that follows (the conversion
+    // is some 150 vector instructions of 4 cycles each, as long as the 16 MFMAs themselves), or in flush() at the end.
+    f32x16_t yp[2];
+    int obp = 0; // first output block of the pair held in yp
+    u32x4_t ea[4], em[4], ov[4];
+    // epilogue operands of the held pair: requested when the following pair starts, used 9 or more MFMAs later
+    auto epi_operands = [&]() __attribute__((always_inline)) {
         if (EP && (a.ep_add || a.ep_mask)) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
                 const i64 row = row0 + r < a.rows ? row0 + r : a.rows - 1;
-                if (a.ep_add) ea[i] = *(const uint4_alias *)(a.ep_add + row * C2 + 32 * ob0 + 8 * ch);
-                if (a.ep_mask) em[i] = *(const uint4_alias *)(a.ep_mask + row * C2 + 32 * ob0 + 8 * ch);
+                if (a.ep_add) ea[i] = *(const uint4_alias *)(a.ep_add + row * C2 + 32 * obp + 8 * ch);
+                if (a.ep_mask) em[i] = *(const uint4_alias *)(a.ep_mask + row * C2 + 32 * obp + 8 * ch);
             }
         }
-        f32x16_t y[2];
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) y[bi][v] = summing ? ysum[g < NSUM ? g : 0][bi][v] : 0.f;
-        // rows -> MFMA fragments through this wavefront's patch of LDS (the W1 buffers are free by now)
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                *(uint4_alias *)&Us[(32 * bi + 4 * j + (lane >> 4)) * LC_TP + 8 * (lane & 15)] = u.r[bi][j];
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-            for (int bi = 0; bi < 2; ++bi) { // two independent accumulators, alternating
-                const bf16x8_t uf = lc_as_bf16x8(*(const uint4_alias *)&Us[(32 * bi + col) * LC_TP + 16 * ks + 8 * half]);
-                y[bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(uf, tf[ks], y[bi], 0, 0, 0);
-            }
-        __builtin_amdgcn_wave_barrier();
-        if (summing && gi + 1 < G) { // (uniform) not the last group: keep the sums, nothing leaves yet
-#pragma unroll
-            for (int bi = 0; bi < 2; ++bi) ysum[g < NSUM ? g : 0][bi] = y[bi];
+    };
+    // piece s = 0..13 of the held pair's way out
+    auto epi_slot = [&](int s) __attribute__((always_inline)) {
+        if (s < 8) { // lane holds row `col`, outputs o = 32 (obp + bi) + 8 q + 4 half + 0..3
+            const int bi = s >> 2, q = s & 3;
+            u32x2_t pk;
+            pk.x = pack_bf16x2(yp[bi][4 * q], yp[bi][4 * q + 1]);
+            pk.y = pack_bf16x2(yp[bi][4 * q + 2], yp[bi][4 * q + 3]);
+            *(uint2_alias *)&Ys[w][col * LC_YP + 32 * bi + 8 * q + 4 * half] = pk;
             return;
         }
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi) {
-            // lane holds row `col`, outputs o = 32 (ob0 + bi) + 8 q + 4 half + 0..3
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const u32x2_t bb = u.b[bi][q];
-                const float b[4] = {__uint_as_float(bb.x << 16), __uint_as_float(bb.x & 0xffff0000u),
-                                    __uint_as_float(bb.y << 16), __uint_as_float(bb.y & 0xffff0000u)};
-                u32x2_t pk;
-                pk.x = pack_bf16x2(y[bi][4 * q] + b[0], y[bi][4 * q + 1] + b[1]);
-                pk.y = pack_bf16x2(y[bi][4 * q + 2] + b[2], y[bi][4 * q + 3] + b[3]);
-                *(uint2_alias *)&Ys[w][col * LC_YP + 32 * bi + 8 * q + 4 * half] = pk;
-            }
+        if (s == 8) __builtin_amdgcn_wave_barrier();
+        // the patch [32 rows][64 outputs] leaves as 16-byte stores, 8 lanes per row: read in one slot, stored in the next
+        if (s >= 9 && s <= 12) {
+            const int i = s - 9, idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
+            ov[i] = *(const uint4_alias *)&Ys[w][r * LC_YP + 8 * ch];
         }
-        __builtin_amdgcn_wave_barrier();
-        // the patch [32 rows][64 outputs] leaves as 16-byte stores: 8 lanes per row
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
-            u32x4_t v = *(const uint4_alias *)&Ys[w][r * LC_YP + 8 * ch];
+        if (s >= 10 && s <= 13) {
+            const int i = s - 10, idx = lane + 64 * i, r = idx >> 3, ch = idx & 7;
+            u32x4_t v = ov[i];
             if (EP && (a.ep_add || a.ep_mask || a.ep_relu)) { // (uniform)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -316,24 +379,64 @@ __global__ __launch_bounds__(256, 1) void linear_chain2_kernel(LinChainArgs args
                     v[e] = pack_bf16x2(lo, hi);
                 }
             }
-            if (row0 + r < a.rows) *(uint4_alias *)(a.out + (row0 + r) * C2 + 32 * ob0 + 8 * ch) = v;
+            if (row0 + r < a.rows) *(uint4_alias *)(a.out + (row0 + r) * C2 + 32 * obp + 8 * ch) = v;
         }
-        __builtin_amdgcn_wave_barrier();
+        if (s == 13) __builtin_amdgcn_wave_barrier();
     };
+    auto flush = [&]() __attribute__((always_inline)) {
+        epi_operands();
+#pragma unroll
+        for (int s = 0; s < 14; ++s) epi_slot(s);
+    };
+    // u: the pair in work (its first block is in the patch already); un: the pair after it; uf / gf: registers to
+    // refill and the pair to request into them, one piece per MFMA (gf < 0: nothing); held: yp holds a pair
+    auto pair = [&](const UR &u, const UR &un, UR &uf, int gf, int g, bool held) __attribute__((always_inline)) {
+        const int ob0 = w * obw + 2 * pair_of(g);
+        f32x16_t y[2];
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) y[bi][v] = summing ? ysum[g < NSUM ? g : 0][bi][v] : 0.f;
+        if (held) epi_operands();
+        mma_block(u, 0, y[0], [&](int ks) __attribute__((always_inline)) {
+            write_u(u, 1, ks);
+            if (gf >= 0 && ks == 0) load_ub(uf, gf, 0);
+            if (gf >= 0) load_u1(uf, gf, 0, ks);
+            if (held) epi_slot(ks);
+        });
+        // (past the last pair `un` holds a repeat of it: written, never read)
+        mma_block(u, 1, y[1], [&](int ks) __attribute__((always_inline)) {
+            write_u(un, 0, ks);
+            if (gf >= 0 && ks == 0) load_ub(uf, gf, 1);
+            if (gf >= 0) load_u1(uf, gf, 1, ks);
+            if (held) epi_slot(8 + ks);
+        });
+        if (summing && gi + 1 < G) { // (uniform) not the last group: keep the sums, nothing leaves yet
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi) ysum[g < NSUM ? g : 0][bi] = y[bi];
+            return;
+        }
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi) yp[bi] = y[bi];
+        obp = ob0;
+        if (summing) flush(); // (the sums over the groups take the registers a held pair would need)
+    };
+#pragma unroll
+    for (int j = 0; j < 8; ++j) write_u(ur[0], 0, j);
     if (NP > 0) {
 #pragma unroll
-        for (int g = 0; g < NP; ++g) {
-            if (g + 2 < NP) load_u(ur[(g + 2) % 3], g + 2);
-            pair(ur[g % 3], g);
-        }
+        for (int g = 0; g < NP; ++g)
+            pair(ur[g % 3], ur[(g + 1 < NP ? g + 1 : g) % 3], ur[(g + 2) % 3], g + 2 < NP ? g + 2 : -1, g,
+                 g > 0 && !summing);
     } else { // any number of pairs: one pair ahead, requests past the end repeat the last pair
         for (int g = 0; 2 * g < obw; g += 2) {
-            pair(ur[0], g);
+            pair(ur[0], ur[1], ur[2], -1, g, g > 0);
             load_u(ur[0], g + 2);
-            pair(ur[1], g + 1);
+            if (2 * (g + 1) < obw) pair(ur[1], ur[0], ur[2], -1, g + 1, true);
             load_u(ur[1], g + 3);
         }
     }
+    if (!summing) flush();
     } // groups
 }
 
