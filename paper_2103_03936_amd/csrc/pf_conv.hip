@@ -311,11 +311,11 @@ static int conv_fwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
     // both factors the way the backward pass wants them (W_save), which saves that pass a launch of its own.
     uint16_t *s1 = (uint16_t *)W_save, *s2 = W_save ? (uint16_t *)((char *)W_save + align_up(p.n_w1b * 2)) : nullptr;
     int st = launch_pack_chain(
-        s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1),
+        s, make_pack_w1((const uint16_t *)Uk, (uint4 *)w1, g.C, g.r, g.k, (i64)g.C * T, T, 1, g.H, g.W),
         make_pack_w2(W_save ? (const uint16_t *)Uk : nullptr, (uint4 *)s2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1),
         // (kept for a backward call that is given the same scale: its first stage runs on scale * Vp)
         [&] {
-            PackW1 q = make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0);
+            PackW1 q = make_pack_w1(W_save ? (const uint16_t *)Vp : nullptr, (uint4 *)s1, g.Cout, g.r, 1, 1, g.r, 0, g.H, g.W);
             q.cscale = ep.scale;
             return q;
         }(),
@@ -351,7 +351,7 @@ static int conv_bwd_chain(const ConvGeom &g, const ConvPlan &p, const bf16_t *X,
     }
     // stage 1: dT = Vp^T dY (1x1); stage 2: dX = flipped-Uk * dT (k x k)
     if (!W_saved) {
-        PackW1 q = make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0);
+        PackW1 q = make_pack_w1((const uint16_t *)Vp, (uint4 *)w1, g.Cout, g.r, 1, 1, g.r, 0, g.H, g.W);
         q.cscale = ep.scale; // dT = Vp^T (scale dZ) = (scale Vp)^T dZ
         st = launch_pack_chain(s, q, make_pack_w2((const uint16_t *)Uk, (uint4 *)w2, g.C, g.r, g.k, T - 1, T, (i64)g.C * T, -1));
     }

@@ -54,7 +54,12 @@ struct PackW1 {
     int n, RB, T; // n = number of 16-byte fragment slots
     i64 s_rho, s_c, s_tap;
     const float *cscale; // nullable: W1(rho, c, tap) is multiplied by cscale[c] (rounded to bf16 once more)
+    // 0, or C1 / 4: the order the kernel wants for a 1x1 first stage of 7 x 7 images (chain_w1_interleaved): slot
+    // s belongs to wavefront w = s / (C1 / 64), and k-step t of its round `sub` holds the channels
+    // c = 256 sub + 4 (16 t + 8 (lane / 32) + e) + w instead of 16 s + 8 (lane / 32) + e.
+    int il_cw;
 };
+bool chain_w1_interleaved(int k, int H, int W);
 // W2p[ob][s2][lane][e] = W2(o = 32 ob + lane % 32, tap = s2 / (R / 16), rho = 16 (s2 % (R / 16)) + 8 (lane / 32) + e)
 // with W2(o, tap, rho) = src[base + o * s_o + rho * s_rho + tap * s_tap].
 struct PackW2 {
@@ -63,7 +68,8 @@ struct PackW2 {
     int n, S2, R16;
     i64 base, s_o, s_rho, s_tap;
 };
-PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap);
+// H, W: image size of the chain kernel that will read the weights (0, 0 for the fully connected mode)
+PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap, int H = 0, int W = 0);
 PackW2 make_pack_w2(const uint16_t *src, uint4 *dst, int C2, int R, int k, i64 base, i64 s_o, i64 s_rho, i64 s_tap);
 int launch_pack_chain(hipStream_t s, const PackW1 &p1, const PackW2 &p2, const PackW1 &p3 = PackW1{},
                       const PackW2 &p4 = PackW2{});

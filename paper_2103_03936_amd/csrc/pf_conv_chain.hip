@@ -10,7 +10,8 @@ constexpr int CH_XLD = CH_SUB + 8;   // row stride (elements) of the staged inpu
 constexpr int CH_PLD = 64 + 4;        // stride (floats) between the pixels of a partial-sum tile [pixel][64 rows of rho]
 
 typedef uint4 __attribute__((may_alias)) uint4_alias;
-typedef uint32_t X16a2 __attribute__((ext_vector_type(4), aligned(2))); // 16 bytes at any 2-byte aligned address
+typedef uint32_t xvec_t __attribute__((ext_vector_type(4))); // native vector: stays in registers inside an array
+typedef xvec_t __attribute__((may_alias)) xvec_alias;
 
 // 16-byte LDS fragment read that may alias the 2-byte stores which filled the tile
 __device__ __forceinline__ uint4 lds_read16(const uint16_t *p) { return *(const uint4_alias *)p; }
@@ -75,9 +76,24 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     // in the plane.  (Aligned loads of the planes laid end to end, written to their slots with 16-byte LDS
     // stores at 2-byte aligned addresses, were measured: the misaligned LDS stores cost more than the
     // misaligned global loads, 3.8 k against 2.8 k cycles per 64-channel round.)
-    constexpr bool XT = !CL && KS1 == 1 && ((HC == 8 && WC == 8) || (HC == 7 && WC == 7));
-    constexpr int XG = HC == 8 ? 8 : 7; // 16-byte items per plane
-    uint4 xv[NXV];
+    constexpr bool XT = !CL && KS1 == 1 && HC == 8 && WC == 8;
+    constexpr int XG = 8; // 16-byte items per plane
+    // XF: a 1x1 first stage of a 7 x 7 image.  A plane is 98 bytes, so neither the planes nor 8-pixel pieces of them
+    // are aligned, and a 16-byte request at a 2-byte aligned address costs the memory pipeline three aligned ones.
+    // But 256 consecutive planes are 1568 aligned 16-byte pieces: the workgroup copies them to LDS as they are
+    // (two buffers, one barrier per round), and wavefront w multiplies the channels 4 i + w of the block (the
+    // packed weights are ordered to match).  Its rows then start 392 bytes apart at 98 w bytes, which is 2 w past a
+    // multiple of 8: it reads them from w elements earlier, so that the transposing read gets aligned addresses,
+    // and its pixel p stands in slot p + w.  The slots before and after the 49 pixels hold neighbouring planes'
+    // pixels; their columns of the product are never looked at, and the partial sums are lined up when the four
+    // wavefronts' tiles are added.
+    constexpr bool XF = !CL && KS1 == 1 && HC == 7 && WC == 7;
+    constexpr int XF_VEC = 256 * 49 / 8;       // 16-byte pieces of a block of 256 planes
+    constexpr int XF_ELEMS = 256 * 49 + 16;    // elements of one buffer (the last row is read 11 elements past the block)
+    static_assert(!XF || 2 * XF_ELEMS <= 4 * CH_PP * CH_XLD, "two flat buffers fit in the input tiles");
+    uint16_t *const xf0 = &Xs[0][0];
+    int xf_buf = 0; // buffer the MFMAs read
+    xvec_t xv[NXV];
     const int nitem = 8 * HW;
     auto load_x = [&](int sub) __attribute__((always_inline)) {
         if (CL) { // item = (row m, channel octet o): 16 contiguous bytes of X; rows past the end re-read the last row
@@ -86,8 +102,14 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                 const int it = lane + 64 * i, m = it >> 3, o = it & 7;
                 i64 row = (i64)n * CH_PIX + m;
                 row = row < a.rows ? row : a.rows - 1;
-                xv[i] = *(const uint4 *)(a.in + row * C1 + w * cw + sub * CH_SUB + 8 * o);
+                xv[i] = *(const xvec_t *)(a.in + row * C1 + w * cw + sub * CH_SUB + 8 * o);
             }
+            return;
+        }
+        if (XF) { // round `sub` = planes 256 sub .. 256 sub + 255 of the image, piece tid + 256 i to this thread
+            const uint16_t *blk = a.in + ((i64)n * C1 + sub * 256) * 49;
+#pragma unroll
+            for (int i = 0; i < 7; ++i) xv[i] = *(const xvec_t *)(blk + 8 * min(tid + 256 * i, XF_VEC - 1));
             return;
         }
         const uint16_t *src = a.in + ((i64)n * C1 + w * cw + sub * CH_SUB) * HW;
@@ -95,12 +117,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int i = 0; i < NXV; ++i) {
                 const int it = min(lane + 64 * i, CH_SUB * XG - 1), ch = it / XG, j = it - ch * XG;
-                if (XG == 8) {
-                    xv[i] = *(const uint4 *)(src + ch * 64 + 8 * j);
-                } else {
-                    const X16a2 t = *(const X16a2 *)(src + ch * 49 + 8 * j - (j == 6 ? 7 : 0));
-                    xv[i] = make_uint4(t.x, t.y, t.z, t.w);
-                }
+                xv[i] = *(const xvec_t *)(src + ch * 64 + 8 * j);
             }
             return;
         }
@@ -117,7 +134,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) e[k] = 0;
             }
-            xv[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+            xv[i] = xvec_t{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
         }
     };
     auto store_x = [&]() __attribute__((always_inline)) {
@@ -125,7 +142,16 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int i = 0; i < NXV; ++i) {
                 const int it = lane + 64 * i, m = it >> 3, o = it & 7;
-                *(uint4_alias *)&xs[m * CH_XLD + 8 * o] = xv[i];
+                *(xvec_alias *)&xs[m * CH_XLD + 8 * o] = xv[i];
+            }
+            return;
+        }
+        if (XF) { // into the buffer that is not being read
+            uint16_t *dstb = xf0 + (xf_buf ^ 1) * XF_ELEMS;
+#pragma unroll
+            for (int i = 0; i < 7; ++i) {
+                const int vi = tid + 256 * i;
+                if (vi < XF_VEC) *(xvec_alias *)&dstb[8 * vi] = xv[i];
             }
             return;
         }
@@ -133,11 +159,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int i = 0; i < NXV; ++i) {
                 const int it = lane + 64 * i, ch = it / XG, j = it - ch * XG;
-                if (it < CH_SUB * XG) {
-                    uint4 v = xv[i];
-                    if (XG == 7 && j == 6) v = make_uint4(v.w >> 16, 0u, 0u, 0u); // pixel 48, then empty slots
-                    *(uint4_alias *)&xs[ch * CH_XLD + 8 * j] = v;
-                }
+                if (it < CH_SUB * XG) *(xvec_alias *)&xs[ch * CH_XLD + 8 * j] = xv[i];
             }
             return;
         }
@@ -148,7 +170,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                 const int o = it / HW, p = it - o * HW;
                 const int y = p / W, x = p - y * W;
                 const int pos = KS1 == 3 ? (y + 1) * Wp1 + x + 1 : p;
-                *(uint4_alias *)&xs[pos * CH_XLD + 8 * o] = xv[i];
+                *(xvec_alias *)&xs[pos * CH_XLD + 8 * o] = xv[i];
             }
         }
     };
@@ -174,7 +196,8 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     {
         const uint4 z = make_uint4(0, 0, 0, 0);
         uint4_alias *x4 = (uint4_alias *)&Xs[0][0];
-        for (int i = tid; i < 4 * CH_PP * CH_XLD / 8; i += 256) x4[i] = z;
+        if (!XF) // (the flat copy needs no zeros)
+            for (int i = tid; i < 4 * CH_PP * CH_XLD / 8; i += 256) x4[i] = z;
         uint4_alias *t4 = (uint4_alias *)&Ts[0];
         for (int i = tid; i < CH_PP * TLD / 8; i += 256) t4[i] = z;
     }
@@ -210,6 +233,14 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
     };
     // input fragment of pixel block pb: 8 consecutive channels of this lane's pixel
     auto xfrag = [&](int pb, int gi, int t) __attribute__((always_inline)) {
+        if (XF) {
+            union {
+                bf16x8_t b;
+                uint4 u;
+            } c;
+            c.b = lds_frag_tr(xf0 + xf_buf * XF_ELEMS + 48 * w, 4 * 49, 16 * t, 32 * pb, lane);
+            return c.u;
+        }
         if (XT) { // (slots past the image hold zeros)
             union {
                 bf16x8_t b;
@@ -254,13 +285,22 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             __builtin_amdgcn_wave_barrier();
             store_x();
             if (g + 1 + GPS < ngroups) load_x(grp(g + 1 + GPS) / GPS);
+            if (XF) { // the buffers are shared: the round just written becomes the one that is read
+                __syncthreads();
+                xf_buf ^= 1;
+            }
             __builtin_amdgcn_wave_barrier();
         }
     };
 
+    if (XF) xf_buf = 1; // (store_x fills the other buffer: the first round goes to buffer 0)
     store_x();
     if (nsub > 1) load_x(grp(GPS) / GPS);
-    // (the tile is this wavefront's own: no workgroup barrier, which would also wait for the loads just issued)
+    if (XF) {
+        __syncthreads();
+        xf_buf = 0;
+    }
+    // (otherwise the tile is this wavefront's own: no workgroup barrier)
     __builtin_amdgcn_wave_barrier();
     for (int g = 0; g < ngroups; g += 2) {
         run_group(afA, afB, grp(g), grp(g + 1));
@@ -334,9 +374,10 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             float f[8];
 #pragma unroll
             for (int h4 = 0; h4 < 2; ++h4) {
-                const int idx = pix * CH_PLD + r0 + 4 * h4;
-                const float4 p0 = *(const float4 *)&P[0][idx], p1 = *(const float4 *)&P[1][idx];
-                const float4 p2 = *(const float4 *)&P[2][idx], p3 = *(const float4 *)&P[3][idx];
+                // (XF: wavefront k holds pixel p in slot p + k)
+                const int idx = pix * CH_PLD + r0 + 4 * h4, sh = XF ? (pix < 61 ? CH_PLD : 0) : 0;
+                const float4 p0 = *(const float4 *)&P[0][idx], p1 = *(const float4 *)&P[1][idx + sh];
+                const float4 p2 = *(const float4 *)&P[2][idx + 2 * sh], p3 = *(const float4 *)&P[3][idx + 3 * sh];
                 f[4 * h4 + 0] = (p0.x + p1.x) + (p2.x + p3.x);
                 f[4 * h4 + 1] = (p0.y + p1.y) + (p2.y + p3.y);
                 f[4 * h4 + 2] = (p0.z + p1.z) + (p2.z + p3.z);
@@ -544,13 +585,19 @@ __device__ __forceinline__ void pack_w1_item(const PackW1 &p, int g)
 {
     // one 16-byte fragment slot: ((s * RB + b) * 64 + lane)
     const int lane = g & 63, fb = g >> 6, b = fb % p.RB, s = fb / p.RB;
-    const int rho = 32 * b + (lane & 31), c0 = 16 * (s / p.T) + 8 * (lane >> 5), tap = s % p.T;
+    const int rho = 32 * b + (lane & 31), tap = s % p.T;
+    int c0 = 16 * (s / p.T) + 8 * (lane >> 5), cs = 1; // first channel of the slot and the step between its channels
+    if (p.il_cw) { // k-step S of wavefront w = S / (cw / 16): channels 256 sub + 4 (16 t + 8 (lane / 32) + i) + w
+        const int S = s / p.T, per = p.il_cw / 16, wv = S / per, rem = S - wv * per;
+        c0 = 256 * (rem >> 2) + 4 * (16 * (rem & 3) + 8 * (lane >> 5)) + wv;
+        cs = 4;
+    }
     uint32_t e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = p.src[rho * p.s_rho + (c0 + i) * p.s_c + tap * p.s_tap];
+    for (int i = 0; i < 8; ++i) e[i] = p.src[rho * p.s_rho + (c0 + cs * i) * p.s_c + tap * p.s_tap];
     if (p.cscale) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) e[i] = float_to_bf16_bits(bf16_bits_to_float((uint16_t)e[i]) * p.cscale[c0 + i]);
+        for (int i = 0; i < 8; ++i) e[i] = float_to_bf16_bits(bf16_bits_to_float((uint16_t)e[i]) * p.cscale[c0 + cs * i]);
     }
     p.dst[g] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
 }
@@ -593,7 +640,9 @@ bool chain_supported(int C1, int C2, int R, int H, int W, int k, int stride, int
 size_t chain_w1_elems(int C1, int R, int k) { return (size_t)k * k * C1 * R; }
 size_t chain_w2_elems(int C2, int R, int k) { return (size_t)k * k * C2 * R; }
 
-PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap)
+bool chain_w1_interleaved(int k, int H, int W) { return k == 1 && H == 7 && W == 7; }
+
+PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s_rho, i64 s_c, i64 s_tap, int H, int W)
 {
     PackW1 p;
     p.src = src;
@@ -605,6 +654,7 @@ PackW1 make_pack_w1(const uint16_t *src, uint4 *dst, int C1, int R, int k, i64 s
     p.s_c = s_c;
     p.s_tap = s_tap;
     p.cscale = nullptr;
+    p.il_cw = chain_w1_interleaved(k, H, W) ? C1 / 4 : 0;
     return p;
 }
 
