@@ -107,7 +107,7 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
     const int n0 = bx * NCH; // first B channel of this workgroup
     const int img0 = g * a.imgs_per_group;
     const int img1 = min(a.N_img, img0 + a.imgs_per_group);
-    constexpr bool SQ7 = HC == 7 && WC == 7;
+    constexpr bool SQ7 = HC == 7 && WC == 7 && TAPS == 9;
     // 16-byte items of the A block / the B slab of one image (7x7: one per 8-pixel slot group of a plane)
     const int apieces = SQ7 ? M * 7 : M * HW / 8, bpieces = SQ7 ? NCH * 7 : NCH * HW / 8;
     constexpr int NT = WG_THREADS;
@@ -178,6 +178,20 @@ __device__ __forceinline__ void conv_wgrad_body(const WgradArgs &a, const int bx
             const int plane = pc / 7, c = pc - 7 * plane;
             const u32x4 fixed = TAPS == 9 ? row_fix<7>(v, c, 7) : c == 6 ? u32x4{v.w >> 16, 0u, 0u, 0u} : v;
             *(u32x4_alias *)(dst + plane * 144 + c * 16) = fixed;
+            return;
+        }
+        if (HC == 7 && WC == 7 && TAPS == 1) {
+            // 49-pixel planes laid end to end: the piece starts at pixel px0 of a plane and may run on into the
+            // next one, whose pixel 0 stands 144 - 98 bytes further on in LDS than in memory.  (A 7 x 7 plane is 98
+            // bytes, so a 16-byte request for 8 pixels of one plane is never aligned, and a misaligned request
+            // costs the memory pipeline three aligned ones: aligned pieces, taken apart here, are cheaper.)
+            const int f0 = 8 * pc, plane = f0 / 49, px0 = f0 - 49 * plane, j = 49 - px0; // elements e >= j: next plane
+            unsigned char *b0 = dst + plane * 144 + px0 * 2, *b1 = b0 + 46;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t word = v[e >> 1];
+                *(uint16_t *)((e < j ? b0 : b1) + 2 * e) = (uint16_t)((e & 1) ? (word >> 16) : word);
+            }
             return;
         }
         const int e = 8 * pc;
