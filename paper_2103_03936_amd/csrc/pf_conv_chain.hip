@@ -182,6 +182,16 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         const int r = (g < ngroups ? g : ngroups - 1) + rot1;
         return r >= ngroups ? r - ngroups : r;
     };
+    // ---- zero the tiles (borders and the spare row stay zero for the whole kernel): first, because these stores need
+    // nothing from memory, while the requests below keep the wavefront at the memory pipeline's door for a while ----
+    {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        uint4_alias *x4 = (uint4_alias *)&Xs[0][0];
+        if (!XF) // (the flat copy needs no zeros)
+            for (int i = tid; i < 4 * CH_PP * CH_XLD / 8; i += 256) x4[i] = z;
+        uint4_alias *t4 = (uint4_alias *)&Ts[0];
+        for (int i = tid; i < CH_PP * TLD / 8; i += 256) t4[i] = z;
+    }
     uint4 afA[GS1][RB], afB[GS1][RB];
     load_x(grp(0) / GPS);
     {
@@ -192,16 +202,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
             for (int b = 0; b < RB; ++b) afA[t][b] = src[(t * RB + b) * 64];
     }
 
-    // ---- zero the tiles (borders and the spare row stay zero for the whole kernel) ----
-    {
-        const uint4 z = make_uint4(0, 0, 0, 0);
-        uint4_alias *x4 = (uint4_alias *)&Xs[0][0];
-        if (!XF) // (the flat copy needs no zeros)
-            for (int i = tid; i < 4 * CH_PP * CH_XLD / 8; i += 256) x4[i] = z;
-        uint4_alias *t4 = (uint4_alias *)&Ts[0];
-        for (int i = tid; i < CH_PP * TLD / 8; i += 256) t4[i] = z;
-    }
-    __syncthreads();
+    if (!XF) __syncthreads(); // (the flat copy's first round ends with a barrier of its own, and it writes no zeroed tile)
 
     // top-left padded position of this lane's two pixels (pixel blocks 0 and 1), both stages,
     // as element offsets into the tiles; lanes without a pixel read the all-zero row

@@ -76,6 +76,8 @@ FUSED_SHAPES = [
     (37, 256, 8, 8, 256, 64, 3, 1, 1),   # image groups of unequal length
     (29, 512, 7, 7, 512, 128, 3, 1, 1),
     (45, 1024, 7, 7, 256, 128, 1, 1, 0),
+    (11, 768, 7, 7, 256, 64, 1, 1, 0),   # 7 x 7 planes copied flat, rank 64, three rounds of 256 channels
+    (3, 256, 8, 8, 768, 64, 1, 1, 0),
 ]
 
 
