@@ -341,13 +341,18 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
         return a.W2p + ((i64)ob * S2 + tap * R16) * 64 + lane;
     };
     uint4 bwA[NB2][R16], bwB[NB2][R16];
-    if (ngroups2 > 0) {
-        const uint4 *src = w2src(0);
+    // The first group's fragments are requested a few at a time between the phases of the exchange below (pieces
+    // [lo, hi) of the NB2 * R16): issued in one go they keep the wavefront at the memory pipeline's door for over a
+    // thousand cycles in which the exchange, which only needs LDS, could run.
+    constexpr int W2N = NB2 * R16, W2SLOTS = 3 * (R / 64), W2PER = (W2N + W2SLOTS - 1) / W2SLOTS;
+    const uint4 *const w2first = w2src(0);
+    auto w2_request = [&](int slot) __attribute__((always_inline)) {
+        if (ngroups2 > 0) { // (uniform)
 #pragma unroll
-        for (int bb = 0; bb < NB2; ++bb)
-#pragma unroll
-            for (int k = 0; k < R16; ++k) bwA[bb][k] = src[bb * w2bb + k * w2k];
-    }
+            for (int i = slot * W2PER; i < (slot + 1) * W2PER && i < W2N; ++i)
+                bwA[i / R16][i % R16] = w2first[(i / R16) * w2bb + (i % R16) * w2k];
+        }
+    };
 
     // ---------------- sum the four partial tiles, 64 rows of rho at a time ----------------
 #pragma unroll
@@ -365,6 +370,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                     *(float4 *)&pw[32 * pb * CH_PLD + 32 * bb + 8 * q] =
                         make_float4(acc[2 * rh + bb][pb][4 * q], acc[2 * rh + bb][pb][4 * q + 1],
                                     acc[2 * rh + bb][pb][4 * q + 2], acc[2 * rh + bb][pb][4 * q + 3]);
+        w2_request(3 * rh);
         __syncthreads();
         const int pix = tid & 63;
         const int py = pix / W, px = pix - py * W;
@@ -402,6 +408,7 @@ __global__ __launch_bounds__(256, 1) void conv_chain_kernel(ChainArgs a)
                     for (int e = 0; e < 8; ++e) ms[e * HW] = (uint16_t)(d[e >> 1] >> (16 * (e & 1)));
                 }
             }
+            w2_request(3 * rh + 1 + it);
         }
     }
     __syncthreads();
