@@ -23,6 +23,7 @@ SHAPES = [
     (257, 512, 256, 128),
     (1000, 256, 256, 128),
     (100, 768, 1024, 128),  # fused kernel: four output-block pairs per wavefront forward, three backward
+    (65, 1280, 1280, 128),  # fused kernel: ten chunks of the contraction, five pairs (the loop for any count), ragged rows
 ]
 
 
